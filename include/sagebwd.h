@@ -1,0 +1,156 @@
+/*
+ * sagebwd.h -- C ABI of the SageBwd hot path on one MI355X (gfx950).
+ *
+ * SageBwd is a trainable INT8 attention: the forward computes
+ * O = softmax(sm_scale * Q K^T) V with Q K^T and P V on INT8 with per-block
+ * scales (paper Sec. 3 "SageBwd", Algorithm 1); the backward recomputes P and
+ * forms dV, dP, dS, dQ, dK with every matmul on INT8 except dP = dO V^T
+ * (paper Sec. 3 gradient equations, Algorithm 2).
+ *
+ * Conventions shared by every entry point
+ *   - All tensor pointers are DEVICE pointers owned by the caller.  The library
+ *     allocates and frees no device memory; scratch lives in a caller-owned
+ *     workspace of sagebwd_workspace_bytes() bytes (256-byte aligned).
+ *   - Tensors are dense and contiguous: Q, K, V, O, dO, dQ, dK, dV are bf16
+ *     [B, H, N, d]; LSE is float32 [B, H, N].
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Work
+ *     is enqueued on it and the call returns without synchronising.
+ *   - Return value: SAGEBWD_OK (0) or a negative sagebwd_status.  Arguments are
+ *     validated on the host before anything is launched; on error nothing runs.
+ *   - Numerics blocks are B_q = B_kv = 64 (one FP32 scale per 64 rows x d channels).
+ *   - Supported shapes: d in {64, 128}; N a positive multiple of 64 (the paper
+ *     assumes N/B_q and N/B_kv integral, Algorithm 1 line 2); B*H*N*d < 2^40.
+ */
+#ifndef SAGEBWD_H
+#define SAGEBWD_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum sagebwd_status {
+  SAGEBWD_OK = 0,
+  SAGEBWD_INVALID_ARG = -1,        /* null pointer, non-positive size, unknown selector */
+  SAGEBWD_UNSUPPORTED_SHAPE = -2,  /* d not in {64,128}, N not a multiple of 64, ...  */
+  SAGEBWD_WORKSPACE_TOO_SMALL = -3,
+  SAGEBWD_HIP_ERROR = -4           /* a HIP runtime call or launch failed */
+} sagebwd_status;
+
+/* Smoothing flags (paper Sec. 3 "Q and K Smoothing"). */
+#define SAGEBWD_SMOOTH_K 1 /* subtract the token mean of K of each head before quantising */
+#define SAGEBWD_SMOOTH_Q 2 /* subtract the mean of each 64-row Q block; logits get the bias back */
+
+typedef struct sagebwd_params {
+  int32_t B, H, N, d;
+  int32_t causal;  /* 0 / 1: key index <= query index (square self-attention) */
+  int32_t smooth;  /* OR of SAGEBWD_SMOOTH_* ; the paper's default is SAGEBWD_SMOOTH_K */
+  float sm_scale;  /* logit scale; 0 selects 1/sqrt(d) (paper Sec. 4: S = Q K^T / sqrt(d)) */
+  int32_t reserved; /* must be 0 */
+} sagebwd_params;
+
+/* Which quantised tensor sagebwd_export_quantized() copies out. */
+typedef enum sagebwd_tensor {
+  SAGEBWD_TENSOR_Q = 0,
+  SAGEBWD_TENSOR_K = 1,
+  SAGEBWD_TENSOR_V = 2,
+  SAGEBWD_TENSOR_DO = 3
+} sagebwd_tensor;
+
+/* Kernels whose device time sagebwd_read_timing() reports. */
+typedef enum sagebwd_kernel {
+  SAGEBWD_KERNEL_PREPASS_FWD = 0, /* smoothing + psi(Q), psi(K), psi(V)            */
+  SAGEBWD_KERNEL_FWD = 1,         /* fused forward (Algorithm 1 loop)              */
+  SAGEBWD_KERNEL_PREPASS_BWD = 2, /* psi(dO), delta, and the backward's operand layouts */
+  SAGEBWD_KERNEL_BWD = 3,         /* fused backward (Algorithm 2 loop)             */
+  SAGEBWD_KERNEL_BWD_EPILOGUE = 4,/* dQ accumulator -> bf16                        */
+  SAGEBWD_KERNEL_COUNT = 5
+} sagebwd_kernel;
+
+/* Bytes of workspace that sagebwd_fwd / sagebwd_bwd / sagebwd_quantize need for
+ * these params (host computation only).  *bytes is the larger of the forward's
+ * and the backward's need, so one buffer serves both calls. */
+int sagebwd_workspace_bytes(const sagebwd_params* params, size_t* bytes);
+
+/*
+ * Pre-pass (paper Sec. 3 smoothing equations; Algorithm 1 "Quantization" line;
+ * Algorithm 2 line 2 and the psi(dO_i) of its line 6).
+ *   mu_K = mean over the N tokens of K[b,h] (only with SAGEBWD_SMOOTH_K), K_sm = K - mu_K;
+ *   psi per 64-row block of Q (or Q - mu_Qi), K_sm, V:  a = max|x|, s = a/127,
+ *   q = rne(x * (127/a)) in FP32, clamped to [-127,127]; a == 0 gives s = 0, q = 0.
+ *   If dO is non-NULL: psi(dO) per 64-row block; if O is also non-NULL,
+ *   delta = rowsum(dO o O) in FP32.
+ * Results are left in `workspace` in the library's internal operand layouts; use
+ * sagebwd_export_quantized() to read them in row-major form.  dO and O may be NULL.
+ */
+int sagebwd_quantize(const void* Q, const void* K, const void* V, const void* dO, const void* O,
+                     const sagebwd_params* params, void* workspace, size_t workspace_bytes,
+                     void* stream);
+
+/*
+ * Copy one quantised tensor out of a workspace filled by sagebwd_quantize (or by
+ * sagebwd_fwd / sagebwd_bwd, which run the same pre-pass) into row-major form:
+ *   q_out      int8    [B, H, N, d]
+ *   scale_out  float32 [B, H, N/64]
+ * Either output may be NULL.  SAGEBWD_TENSOR_DO requires that dO was given.
+ * This is a test / inspection hook for the bit-exact part of the contract.
+ */
+int sagebwd_export_quantized(const sagebwd_params* params, const void* workspace,
+                             size_t workspace_bytes, int which /* sagebwd_tensor */,
+                             int8_t* q_out, float* scale_out, void* stream);
+
+/* Copy the smoothing means out of the workspace: mu_K float32 [B, H, d] (zeros when
+ * K-smoothing is off), mu_Q float32 [B, H, N/64, d] (only written with
+ * SAGEBWD_SMOOTH_Q), delta float32 [B, H, N] (only after a pre-pass that had dO and O).
+ * Any pointer may be NULL. */
+int sagebwd_export_stats(const sagebwd_params* params, const void* workspace,
+                         size_t workspace_bytes, float* mu_K, float* mu_Q, float* delta,
+                         void* stream);
+
+/*
+ * Forward (paper Algorithm 1 with K-smoothing applied before psi(K), Sec. 3):
+ *   S_ij = (Q^_i K^_j^T) * s_Q * s_K * sm_scale  [+ mu_Qi K_sm_j^T * sm_scale with Q-smoothing],
+ *   online softmax over the KV blocks, per-token quantisation of P~ relative to the
+ *   row max of the tile, O_i += (P^_ij V^_j) * s_P * s_V, O = O / l, L = m + log l.
+ * Writes O bf16 [B,H,N,d] and LSE float32 [B,H,N].  LSE is the log-sum-exp of the
+ * SMOOTHED logits (it differs from the unsmoothed one by a per-row constant) and is
+ * meant to be handed back to sagebwd_bwd unchanged.
+ */
+int sagebwd_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE,
+                const sagebwd_params* params, void* workspace, size_t workspace_bytes,
+                void* stream);
+
+/*
+ * Backward (paper Algorithm 2; gradient equations of Sec. 3):
+ *   delta = rowsum(dO o O);  P_ij = exp(S_ij - L_i);
+ *   dV_j += psi(P_ij)^T psi(dO_i) * s_P * s_dO                      (INT8)
+ *   dP_ij = dO_i V_j^T                                              (bf16, unquantised)
+ *   dS_ij = P_ij o (dP_ij - delta_i)
+ *   dQ_i += psi(dS_ij) K^_j * s_dS * s_K * sm_scale                 (INT8)
+ *   dK_j += psi(dS_ij)^T Q^_i * s_dS * s_Q * sm_scale [+ bias branch with Q-smoothing] (INT8)
+ * Inputs are the caller's bf16 Q, K, V, O, dO and the LSE of sagebwd_fwd run with the
+ * same params; the pre-pass is re-run inside, so the workspace need not survive
+ * between the two calls.  dQ, dK, dV (bf16 [B,H,N,d]) are overwritten.
+ * dQ is accumulated across KV blocks with FP32 atomics, so its last bits may vary
+ * from run to run.
+ */
+int sagebwd_bwd(const void* Q, const void* K, const void* V, const void* O, const void* dO,
+                const float* LSE, void* dQ, void* dK, void* dV, const sagebwd_params* params,
+                void* workspace, size_t workspace_bytes, void* stream);
+
+/* Per-kernel device timing.  When enabled, every entry point brackets each kernel
+ * it launches with HIP events on the caller's stream.  sagebwd_read_timing waits for
+ * the recorded events of `kernel`, returns their summed milliseconds and the launch
+ * count since the last read, and resets both.  Not thread-safe; meant for benchmarks. */
+int sagebwd_set_timing(int enable);
+int sagebwd_read_timing(int kernel /* sagebwd_kernel */, double* total_ms, int* launches);
+
+/* Static description of a status code. */
+const char* sagebwd_strerror(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SAGEBWD_H */

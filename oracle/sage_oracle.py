@@ -1,0 +1,311 @@
+"""Plain NumPy oracle of SageBwd: the INT8 attention forward (Algorithm 1) and
+backward (Algorithm 2) of the paper, written in a non-tiled form.
+
+TEST INFRASTRUCTURE ONLY -- never imported by the product package.
+
+The method is an approximation of exact attention (INT8 noise), so the oracle
+is the method itself, taken step by step in the paper's notation:
+
+  psi      per-block INT8 quantiser, delta_X = max|X| / 127      (Sec. 3, "Quantization")
+  smoothing  K minus its token mean; optional per-block Q mean    (Sec. 3, "Q and K Smoothing")
+  forward  S = psi(Q) psi(K)^T, online softmax, per-token psi(P~),
+           O = sum_j P^_ij V^_j, L = m + log l                   (Algorithm 1)
+  backward D = rowsum(dO o O); P = exp(S - L); dV, dS, dQ, dK with
+           per-block psi(P), psi(dO), psi(dS); dP kept unquantised (Algorithm 2, Sec. 3 "SageBwd")
+
+"Non-tiled" means: the running max / running sum of Algorithm 1 are replaced
+by the row max and row sum over all visible keys, which is what the online
+recurrence evaluates to (only the floating-point order differs).  The pieces
+that the paper defines per tile (the quantisers and their scales) are taken
+per tile exactly as written.
+
+Precision: the quantisers take their decisions (absmax, scale, round) in
+float32, because the stored INT8 tensors and scales are part of the bit-exact
+contract; every other quantity is float64.  Inputs are float32 arrays holding
+bf16-representable values; outputs O, dQ, dK, dV are rounded to bf16 (returned
+as float32 arrays), L is float32.
+
+Readings taken where the paper's text is silent or garbled are listed next to
+the code that uses them (R1..R17).
+"""
+from __future__ import annotations
+
+import numpy as np
+
+BLOCK = 64  # B_q = B_kv = 64: the FlashAttention tile that psi's scale is shared over
+
+_F32 = np.float32
+_F64 = np.float64
+
+
+# --------------------------------------------------------------------------
+# small helpers
+# --------------------------------------------------------------------------
+def round_to_bf16(x) -> np.ndarray:
+    """Round float values to the nearest bf16 (ties to even); result as float32."""
+    a = np.ascontiguousarray(np.asarray(x, dtype=_F32))
+    u = a.view(np.uint32).astype(np.uint64)
+    lsb = (u >> np.uint64(16)) & np.uint64(1)
+    r = (u + np.uint64(0x7FFF) + lsb) >> np.uint64(16)
+    out = (r << np.uint64(16)).astype(np.uint32).view(_F32)
+    nan = np.isnan(a)
+    if nan.any():
+        out = out.copy()
+        out[nan] = np.nan
+    return out.reshape(a.shape)
+
+
+def key_mean(K: np.ndarray) -> np.ndarray:
+    """mu_K = mean_row(K) over ALL N tokens of the head (Sec. 3, smoothing eq.).
+
+    R6/R9: summed in float64 (exact for bf16 data of ordinary dynamic range,
+    hence independent of summation order), divided by N, rounded once to f32.
+    """
+    K = np.asarray(K, dtype=_F32)
+    return (K.astype(_F64).sum(axis=0) / _F64(K.shape[0])).astype(_F32)
+
+
+def block_mean(Q: np.ndarray) -> np.ndarray:
+    """mu_{Q_i} = mean_row(Q_i) for every 64-row block (R17: per block, the
+    Sec. 3 definition). Returns [N/64, d] float32 (float64 sum, one rounding)."""
+    Q = np.asarray(Q, dtype=_F32)
+    n, d = Q.shape
+    return (Q.astype(_F64).reshape(n // BLOCK, BLOCK, d).sum(axis=1) / _F64(BLOCK)).astype(_F32)
+
+
+def quantize_blocks(X: np.ndarray):
+    """psi applied to every 64-row block of X [N, d] (R8: one scale per block of
+    64 rows x all d channels).
+
+    Sec. 3: X^ = round(X / delta_X), delta_X = max|X| / 127, delta in FP32.
+    R5: round = nearest-even; result clamped to [-127, 127].
+    R6: all in float32: a = max|x|, s = a / 127, r = 127 / a, q = rne(x * r).
+    R7: an all-zero block has s = 0 and q = 0.
+    Returns (q int8 [N, d], s float32 [N/64]).
+    """
+    X = np.ascontiguousarray(np.asarray(X, dtype=_F32))
+    n, d = X.shape
+    assert n % BLOCK == 0
+    xb = X.reshape(n // BLOCK, BLOCK * d)
+    a = np.abs(xb).max(axis=1).astype(_F32)
+    nz = a > 0
+    safe = np.where(nz, a, _F32(1))
+    s = np.where(nz, a / _F32(127.0), _F32(0)).astype(_F32)
+    r = np.where(nz, _F32(127.0) / safe, _F32(0)).astype(_F32)
+    y = (xb * r[:, None]).astype(_F32)          # one f32 rounding of the product
+    q = np.clip(np.rint(y), -127, 127).astype(np.int8)
+    return q.reshape(n, d), s
+
+
+def _quantize_tile_f32(x64: np.ndarray):
+    """psi on ONE tile whose values are float64 intermediates (P_ij or dS_ij,
+    Algorithm 2): the decision is taken in float32 like every other quantiser.
+    Returns (q as float64 integers, scale float32); a zero tile gives (0, 0)."""
+    x = x64.astype(_F32)
+    a = np.abs(x).max() if x.size else _F32(0)
+    a = _F32(a)
+    if not a > 0:
+        return np.zeros(x.shape, dtype=_F64), _F32(0)
+    r = _F32(127.0) / a
+    q = np.clip(np.rint((x * r).astype(_F32)), -127, 127)
+    return q.astype(_F64), _F32(a / _F32(127.0))
+
+
+# --------------------------------------------------------------------------
+# pre-pass: smoothing + psi for Q, K, V (and dO in the backward)
+# --------------------------------------------------------------------------
+def prepass_head(Q, K, V, k_smooth: bool = True, q_smooth: bool = False):
+    """Smoothing and per-block quantisation of one head (Algorithm 1, the
+    "Quantization" step, preceded by the smoothing of Sec. 3).
+
+    Returns a dict with Qh, sQ, Kh, sK, Vh, sV (int8 / float32), muK [d],
+    muQ [N/64, d] (zeros when the smoothing is off) and Ksm (float32 K - mu_K).
+    """
+    Q = np.asarray(Q, dtype=_F32)
+    K = np.asarray(K, dtype=_F32)
+    V = np.asarray(V, dtype=_F32)
+    n, d = Q.shape
+    muK = key_mean(K) if k_smooth else np.zeros(d, dtype=_F32)
+    Ksm = (K - muK[None, :]).astype(_F32)       # f32 subtraction, R6
+    if q_smooth:
+        muQ = block_mean(Q)
+        Qsm = (Q.reshape(n // BLOCK, BLOCK, d) - muQ[:, None, :]).astype(_F32).reshape(n, d)
+    else:
+        muQ = np.zeros((n // BLOCK, d), dtype=_F32)
+        Qsm = Q
+    Qh, sQ = quantize_blocks(Qsm)
+    Kh, sK = quantize_blocks(Ksm)
+    Vh, sV = quantize_blocks(V)
+    return dict(Qh=Qh, sQ=sQ, Kh=Kh, sK=sK, Vh=Vh, sV=sV, muK=muK, muQ=muQ, Ksm=Ksm)
+
+
+def delta_rows(dO, O) -> np.ndarray:
+    """delta = rowsum(dO o O) (Sec. 3 "SageBwd"; "D" in Algorithm 2), float64
+    from the bf16 values the caller holds (R16), returned as float64 [N]."""
+    return (np.asarray(dO, dtype=_F64) * np.asarray(O, dtype=_F64)).sum(axis=1)
+
+
+def _logits_block(pp, i0: int, n_keys: int, sm_scale: float, q_smooth: bool) -> np.ndarray:
+    """S for the 64 queries starting at i0 against keys [0, n_keys):
+    S = (Q^ K^^T) * s_Q * s_K * sm_scale (Algorithm 1, the S_ij line; R1: the
+    1/sqrt(d) of Sec. 4 is applied in the dequantisation factor) plus the
+    Q-smoothing bias mu_Qi K^sm^T when that smoothing is on (Sec. 3 decomposition;
+    the mu_K terms are row constants and are dropped, so S lives in the smoothed
+    frame, R10)."""
+    I = i0 // BLOCK
+    qi = pp["Qh"][i0:i0 + BLOCK].astype(_F64)
+    kj = pp["Kh"][:n_keys].astype(_F64)
+    acc = qi @ kj.T                                           # exact integers
+    sk_per_key = np.repeat(pp["sK"].astype(_F64), BLOCK)[:n_keys]
+    S = acc * (_F64(pp["sQ"][I]) * _F64(sm_scale)) * sk_per_key[None, :]
+    if q_smooth:
+        bias = pp["Ksm"][:n_keys].astype(_F64) @ pp["muQ"][I].astype(_F64)
+        S = S + _F64(sm_scale) * bias[None, :]
+    return S
+
+
+# --------------------------------------------------------------------------
+# forward (Algorithm 1)
+# --------------------------------------------------------------------------
+def forward_head(Q, K, V, causal: bool = True, k_smooth: bool = True, q_smooth: bool = False,
+                 sm_scale: float | None = None, return_raw: bool = False):
+    """INT8 attention forward of one head.  Q, K, V: [N, d] float32 (bf16 values).
+
+    Returns (O [N, d] bf16-rounded float32, L [N] float32); with return_raw the
+    unrounded float64 O and L come too.
+    """
+    Q = np.asarray(Q, dtype=_F32)
+    n, d = Q.shape
+    assert n % BLOCK == 0
+    if sm_scale is None:
+        sm_scale = 1.0 / np.sqrt(d)
+    pp = prepass_head(Q, K, V, k_smooth, q_smooth)
+    Vh = pp["Vh"].astype(_F64).reshape(n // BLOCK, BLOCK, d)
+    sV = pp["sV"].astype(_F64)
+    O = np.zeros((n, d), dtype=_F64)
+    L = np.zeros(n, dtype=_F64)
+    rows = np.arange(BLOCK)
+    for i0 in range(0, n, BLOCK):
+        n_keys = i0 + BLOCK if causal else n          # R13: keys k <= i only
+        tj = n_keys // BLOCK
+        S = _logits_block(pp, i0, n_keys, sm_scale, q_smooth)
+        if causal:
+            kk = np.arange(n_keys)
+            S = np.where(kk[None, :] > (i0 + rows)[:, None], -np.inf, S)
+        # softmax statistics over the whole row: what m_{i,Tn}, l_{i,Tn} evaluate to (R2, R3)
+        m = S.max(axis=1)
+        l = np.exp(S - m[:, None]).sum(axis=1)        # unquantised P~ feeds l
+        L[i0:i0 + BLOCK] = m + np.log(l)
+        # per KV block j: per-token quantisation of P~ (the s_P line of Algorithm 1).
+        # R12: P~/s_P = exp(S - m) * 127 / exp(rowmax(S_ij) - m) = 127 exp(S - rowmax(S_ij)),
+        # rounded to nearest; the value is decided in float32.
+        St = S.reshape(BLOCK, tj, BLOCK)
+        Mloc = St.max(axis=2)                         # rowmax(S_ij), [64, tj]
+        e = np.exp(St - Mloc[:, :, None]).astype(_F32)
+        Ph = np.rint((e * _F32(127.0)).astype(_F32)).astype(_F64)      # integers 0..127
+        w = np.exp(Mloc - m[:, None]) / 127.0         # s_P relative to the final max
+        PV = np.einsum("qjk,jkc->qjc", Ph, Vh[:tj])   # exact integers
+        acc = np.einsum("qj,qjc->qc", w * sV[None, :tj], PV)
+        O[i0:i0 + BLOCK] = acc / l[:, None]           # R4: O_i = diag(l)^-1 O_i
+    Ob = round_to_bf16(O)
+    Lf = L.astype(_F32)
+    if return_raw:
+        return Ob, Lf, O, L
+    return Ob, Lf
+
+
+# --------------------------------------------------------------------------
+# backward (Algorithm 2)
+# --------------------------------------------------------------------------
+def backward_head(Q, K, V, O, dO, L, causal: bool = True, k_smooth: bool = True,
+                  q_smooth: bool = False, sm_scale: float | None = None,
+                  return_raw: bool = False, intermediates: dict | None = None):
+    """INT8 attention backward of one head.
+
+    Inputs as the caller holds them: Q, K, V, O, dO [N, d] (bf16 values as
+    float32) and L [N] float32 from the forward.  Returns bf16-rounded
+    (dQ, dK, dV); with return_raw the float64 values instead.
+
+    If `intermediates` is a dict it receives the unquantised float64 P, dP, dS
+    of the whole head (tiny inputs only; used by the invariant tests).
+    """
+    Q = np.asarray(Q, dtype=_F32)
+    n, d = Q.shape
+    assert n % BLOCK == 0
+    if sm_scale is None:
+        sm_scale = 1.0 / np.sqrt(d)
+    pp = prepass_head(Q, K, V, k_smooth, q_smooth)            # same blocks and scales as forward
+    dOh, sdO = quantize_blocks(np.asarray(dO, dtype=_F32))    # psi(dO_i), per 64-row block
+    delta = delta_rows(dO, O)
+    V64 = np.asarray(V, dtype=_F64)
+    dO64 = np.asarray(dO, dtype=_F64)
+    L64 = np.asarray(L, dtype=_F64)
+    Kh = pp["Kh"].astype(_F64)
+    Qh = pp["Qh"].astype(_F64)
+    dQ = np.zeros((n, d), dtype=_F64)
+    dK = np.zeros((n, d), dtype=_F64)
+    dV = np.zeros((n, d), dtype=_F64)
+    if intermediates is not None:
+        intermediates["P"] = np.zeros((n, n))
+        intermediates["dP"] = np.zeros((n, n))
+        intermediates["dS"] = np.zeros((n, n))
+    rows = np.arange(BLOCK)
+    for i0 in range(0, n, BLOCK):
+        I = i0 // BLOCK
+        n_keys = i0 + BLOCK if causal else n
+        S = _logits_block(pp, i0, n_keys, sm_scale, q_smooth)
+        P = np.exp(S - L64[i0:i0 + BLOCK, None])              # P_ij = exp(S_ij - L_i)
+        if causal:
+            kk = np.arange(n_keys)
+            P = np.where(kk[None, :] > (i0 + rows)[:, None], 0.0, P)   # R13: masked entries are 0
+        dP = dO64[i0:i0 + BLOCK] @ V64[:n_keys].T             # unquantised matmul (R15)
+        dS = P * (dP - delta[i0:i0 + BLOCK, None])
+        if intermediates is not None:
+            intermediates["P"][i0:i0 + BLOCK, :n_keys] = P
+            intermediates["dP"][i0:i0 + BLOCK, :n_keys] = dP
+            intermediates["dS"][i0:i0 + BLOCK, :n_keys] = dS
+        dOh_i = dOh[i0:i0 + BLOCK].astype(_F64)
+        Qh_i = Qh[i0:i0 + BLOCK]
+        for J in range(n_keys // BLOCK):
+            j0 = J * BLOCK
+            # dV_j += psi(P_ij)^T psi(dO_i) * s_P * s_dO   (R14: dynamic per-tile scale)
+            Ph, sP = _quantize_tile_f32(P[:, j0:j0 + BLOCK])
+            dV[j0:j0 + BLOCK] += (_F64(sP) * _F64(sdO[I])) * (Ph.T @ dOh_i)
+            # psi(dS_ij); dQ_i += dS^ K^_j * s_dS * s_K ; dK_j += dS^^T Q^_i * s_dS * s_Q
+            dSh, sdS = _quantize_tile_f32(dS[:, j0:j0 + BLOCK])
+            dQ[i0:i0 + BLOCK] += (_F64(sm_scale) * _F64(sdS) * _F64(pp["sK"][J])) * (dSh @ Kh[j0:j0 + BLOCK])
+            dK[j0:j0 + BLOCK] += (_F64(sm_scale) * _F64(sdS) * _F64(pp["sQ"][I])) * (dSh.T @ Qh_i)
+            if q_smooth:
+                # dK_bias = (dS^T 1) mu_Q^T (ablation section); R17: from the unquantised dS
+                colsum = dS[:, j0:j0 + BLOCK].sum(axis=0)
+                dK[j0:j0 + BLOCK] += _F64(sm_scale) * colsum[:, None] * pp["muQ"][I].astype(_F64)[None, :]
+    if return_raw:
+        return dQ, dK, dV
+    return round_to_bf16(dQ), round_to_bf16(dK), round_to_bf16(dV)
+
+
+# --------------------------------------------------------------------------
+# batched wrappers: [B, H, N, d]
+# --------------------------------------------------------------------------
+def forward(Q, K, V, causal=True, k_smooth=True, q_smooth=False, sm_scale=None):
+    Q = np.asarray(Q, dtype=_F32)
+    B, H, N, d = Q.shape
+    O = np.zeros((B, H, N, d), dtype=_F32)
+    L = np.zeros((B, H, N), dtype=_F32)
+    for b in range(B):
+        for h in range(H):
+            O[b, h], L[b, h] = forward_head(Q[b, h], K[b, h], V[b, h], causal, k_smooth, q_smooth, sm_scale)
+    return O, L
+
+
+def backward(Q, K, V, O, dO, L, causal=True, k_smooth=True, q_smooth=False, sm_scale=None):
+    Q = np.asarray(Q, dtype=_F32)
+    B, H, N, d = Q.shape
+    dQ = np.zeros((B, H, N, d), dtype=_F32)
+    dK = np.zeros_like(dQ)
+    dV = np.zeros_like(dQ)
+    for b in range(B):
+        for h in range(H):
+            dQ[b, h], dK[b, h], dV[b, h] = backward_head(
+                Q[b, h], K[b, h], V[b, h], O[b, h], dO[b, h], L[b, h], causal, k_smooth, q_smooth, sm_scale)
+    return dQ, dK, dV
