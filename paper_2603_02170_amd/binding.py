@@ -1,0 +1,206 @@
+"""Thin ctypes binding of libsagebwd.so: argument marshalling only.
+
+Every step of the path runs in the HIP library; PyTorch is used for device
+memory and the current stream.  There is no CPU fallback: if the library is
+missing or a call fails, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB = None
+
+SMOOTH_K = 1
+SMOOTH_Q = 2
+
+TENSOR_Q, TENSOR_K, TENSOR_V, TENSOR_DO = 0, 1, 2, 3
+KERNEL_PREPASS_FWD, KERNEL_FWD, KERNEL_PREPASS_BWD, KERNEL_BWD, KERNEL_BWD_EPILOGUE = range(5)
+
+EXPORTS = (
+    "sagebwd_workspace_bytes", "sagebwd_quantize", "sagebwd_export_quantized", "sagebwd_export_stats",
+    "sagebwd_fwd", "sagebwd_bwd", "sagebwd_set_timing", "sagebwd_read_timing", "sagebwd_strerror",
+)
+
+
+class _CParams(ctypes.Structure):
+    _fields_ = [("B", ctypes.c_int32), ("H", ctypes.c_int32), ("N", ctypes.c_int32), ("d", ctypes.c_int32),
+                ("causal", ctypes.c_int32), ("smooth", ctypes.c_int32), ("sm_scale", ctypes.c_float),
+                ("reserved", ctypes.c_int32)]
+
+
+@dataclass
+class SageParams:
+    B: int
+    H: int
+    N: int
+    d: int
+    causal: bool = True
+    k_smooth: bool = True
+    q_smooth: bool = False
+    sm_scale: float = 0.0   # 0 selects 1/sqrt(d)
+
+    def c(self) -> _CParams:
+        return _CParams(self.B, self.H, self.N, self.d, int(self.causal),
+                        (SMOOTH_K if self.k_smooth else 0) | (SMOOTH_Q if self.q_smooth else 0),
+                        float(self.sm_scale), 0)
+
+
+def lib_path() -> str:
+    return os.path.join(_HERE, "libsagebwd.so")
+
+
+def load_library():
+    """dlopen the in-tree library (built by paper_2603_02170_amd.build); raises if absent."""
+    global _LIB
+    if _LIB is not None:
+        return _LIB
+    path = lib_path()
+    if not os.path.exists(path):
+        raise RuntimeError(f"{path} not found: build it with `python -m paper_2603_02170_amd.build` "
+                           "(there is no fallback path)")
+    lib = ctypes.CDLL(path)
+    vp, sz, i32 = ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int
+    pp = ctypes.POINTER(_CParams)
+    lib.sagebwd_workspace_bytes.argtypes = [pp, ctypes.POINTER(sz)]
+    lib.sagebwd_quantize.argtypes = [vp, vp, vp, vp, vp, pp, vp, sz, vp]
+    lib.sagebwd_export_quantized.argtypes = [pp, vp, sz, i32, vp, vp, vp]
+    lib.sagebwd_export_stats.argtypes = [pp, vp, sz, vp, vp, vp, vp]
+    lib.sagebwd_fwd.argtypes = [vp, vp, vp, vp, vp, pp, vp, sz, vp]
+    lib.sagebwd_bwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, pp, vp, sz, vp]
+    lib.sagebwd_set_timing.argtypes = [i32]
+    lib.sagebwd_read_timing.argtypes = [i32, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i32)]
+    lib.sagebwd_strerror.argtypes = [i32]
+    lib.sagebwd_strerror.restype = ctypes.c_char_p
+    for name in EXPORTS:
+        if name != "sagebwd_strerror":
+            getattr(lib, name).restype = i32
+    _LIB = lib
+    return lib
+
+
+def sagebwd_strerror(status: int) -> str:
+    return load_library().sagebwd_strerror(int(status)).decode()
+
+
+class SageError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {sagebwd_strerror(status)} ({status})")
+
+
+def _check(status: int, where: str):
+    if status != 0:
+        raise SageError(status, where)
+
+
+def _ptr(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _expect(t, dtype, shape, name):
+    if t.dtype != dtype or tuple(t.shape) != tuple(shape) or not t.is_contiguous() or not t.is_cuda:
+        raise ValueError(f"{name}: need contiguous cuda {dtype} {tuple(shape)}, got {t.dtype} {tuple(t.shape)}")
+
+
+def workspace_bytes(p: SageParams) -> int:
+    out = ctypes.c_size_t(0)
+    cp = p.c()
+    _check(load_library().sagebwd_workspace_bytes(ctypes.byref(cp), ctypes.byref(out)), "sagebwd_workspace_bytes")
+    return int(out.value)
+
+
+def alloc_workspace(p: SageParams, device="cuda"):
+    return torch.empty(workspace_bytes(p), dtype=torch.uint8, device=device)
+
+
+def sagebwd_quantize(Q, K, V, p: SageParams, workspace, dO=None, O=None):
+    shp = (p.B, p.H, p.N, p.d)
+    for t, n in ((Q, "Q"), (K, "K"), (V, "V")):
+        _expect(t, torch.bfloat16, shp, n)
+    for t, n in ((dO, "dO"), (O, "O")):
+        if t is not None:
+            _expect(t, torch.bfloat16, shp, n)
+    cp = p.c()
+    _check(load_library().sagebwd_quantize(_ptr(Q), _ptr(K), _ptr(V), _ptr(dO), _ptr(O), ctypes.byref(cp),
+                                           _ptr(workspace), workspace.numel(), _stream()), "sagebwd_quantize")
+
+
+def sagebwd_export_quantized(p: SageParams, workspace, which: int):
+    """Row-major int8 [B,H,N,d] codes and float32 [B,H,N/64] scales of one quantised tensor."""
+    q = torch.empty((p.B, p.H, p.N, p.d), dtype=torch.int8, device=workspace.device)
+    s = torch.empty((p.B, p.H, p.N // 64), dtype=torch.float32, device=workspace.device)
+    cp = p.c()
+    _check(load_library().sagebwd_export_quantized(ctypes.byref(cp), _ptr(workspace), workspace.numel(), which,
+                                                   _ptr(q), _ptr(s), _stream()), "sagebwd_export_quantized")
+    return q, s
+
+
+def sagebwd_export_stats(p: SageParams, workspace, want_delta=False):
+    dev = workspace.device
+    muK = torch.empty((p.B, p.H, p.d), dtype=torch.float32, device=dev)
+    muQ = torch.empty((p.B, p.H, p.N // 64, p.d), dtype=torch.float32, device=dev) if p.q_smooth else None
+    delta = torch.empty((p.B, p.H, p.N), dtype=torch.float32, device=dev) if want_delta else None
+    cp = p.c()
+    _check(load_library().sagebwd_export_stats(ctypes.byref(cp), _ptr(workspace), workspace.numel(), _ptr(muK),
+                                               _ptr(muQ), _ptr(delta), _stream()), "sagebwd_export_stats")
+    return muK, muQ, delta
+
+
+def sagebwd_fwd(Q, K, V, p: SageParams, workspace=None, O=None, LSE=None):
+    """O, LSE = INT8 attention forward.  Allocates outputs / workspace when not given."""
+    shp = (p.B, p.H, p.N, p.d)
+    for t, n in ((Q, "Q"), (K, "K"), (V, "V")):
+        _expect(t, torch.bfloat16, shp, n)
+    if workspace is None:
+        workspace = alloc_workspace(p, Q.device)
+    if O is None:
+        O = torch.empty(shp, dtype=torch.bfloat16, device=Q.device)
+    if LSE is None:
+        LSE = torch.empty(shp[:3], dtype=torch.float32, device=Q.device)
+    _expect(O, torch.bfloat16, shp, "O")
+    _expect(LSE, torch.float32, shp[:3], "LSE")
+    cp = p.c()
+    _check(load_library().sagebwd_fwd(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(LSE), ctypes.byref(cp),
+                                      _ptr(workspace), workspace.numel(), _stream()), "sagebwd_fwd")
+    return O, LSE
+
+
+def sagebwd_bwd(Q, K, V, O, dO, LSE, p: SageParams, workspace=None, dQ=None, dK=None, dV=None):
+    """dQ, dK, dV = INT8 attention backward."""
+    shp = (p.B, p.H, p.N, p.d)
+    for t, n in ((Q, "Q"), (K, "K"), (V, "V"), (O, "O"), (dO, "dO")):
+        _expect(t, torch.bfloat16, shp, n)
+    _expect(LSE, torch.float32, shp[:3], "LSE")
+    if workspace is None:
+        workspace = alloc_workspace(p, Q.device)
+    outs = []
+    for t, n in ((dQ, "dQ"), (dK, "dK"), (dV, "dV")):
+        if t is None:
+            t = torch.empty(shp, dtype=torch.bfloat16, device=Q.device)
+        _expect(t, torch.bfloat16, shp, n)
+        outs.append(t)
+    cp = p.c()
+    _check(load_library().sagebwd_bwd(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(dO), _ptr(LSE), _ptr(outs[0]),
+                                      _ptr(outs[1]), _ptr(outs[2]), ctypes.byref(cp), _ptr(workspace),
+                                      workspace.numel(), _stream()), "sagebwd_bwd")
+    return tuple(outs)
+
+
+def set_timing(enable: bool):
+    _check(load_library().sagebwd_set_timing(int(enable)), "sagebwd_set_timing")
+
+
+def read_timing(kernel: int):
+    ms = ctypes.c_double(0)
+    n = ctypes.c_int(0)
+    _check(load_library().sagebwd_read_timing(kernel, ctypes.byref(ms), ctypes.byref(n)), "sagebwd_read_timing")
+    return float(ms.value), int(n.value)

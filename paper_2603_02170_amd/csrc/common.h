@@ -1,0 +1,71 @@
+// Shared device-side types and helpers for the SageBwd kernels (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace sage {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v2i __attribute__((ext_vector_type(2)));
+typedef int v16i __attribute__((ext_vector_type(16)));
+typedef float v16f __attribute__((ext_vector_type(16)));
+typedef float v4f __attribute__((ext_vector_type(4)));
+typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
+typedef unsigned short v8us __attribute__((ext_vector_type(8)));
+typedef unsigned short v4us __attribute__((ext_vector_type(4)));
+
+constexpr int kBlock = 64;  // B_q = B_kv: rows that share one quantisation scale
+
+// ---------------------------------------------------------------------------
+// Operand layouts written by the pre-pass.  Both cover a tensor X^ [N, d] of one
+// head as consecutive 1 KiB fragments of 64 lanes x 16 bytes, so that a wave loads
+// an MFMA operand with one 16-byte access per lane at `lane * 16`.
+//
+// F  ("row fragments", contraction over d):
+//    fragment (rb, s), rb = 32-row block, s = 32-channel step; lane (r, h), r = lane % 32,
+//    h = lane / 32, byte t:   X^[32 rb + r][32 s + 16 h + t]
+// TF ("transposed fragments", contraction over rows):
+//    fragment (rb, cb), cb = 32-channel block; lane (c, h), byte t = 4a + b:
+//    X^[32 rb + 8a + 4h + b][32 cb + c]
+//    The row order 8a + 4h + b is the order in which a 32x32 MFMA accumulator holds
+//    its rows (register 4a + b of lane half h), so a quantised accumulator tile is
+//    directly the matching operand of the next MFMA.
+// Fragment index within a head: rb * (d / 32) + (s or cb).
+// ---------------------------------------------------------------------------
+
+__device__ __forceinline__ float bf16_bits_to_float(unsigned short u) {
+  return __uint_as_float(((unsigned)u) << 16);
+}
+
+// round-to-nearest-even float -> bf16 bits (finite inputs; NaN kept quiet)
+__device__ __forceinline__ unsigned short float_to_bf16_bits(float f) {
+  unsigned u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (unsigned short)((u >> 16) | 0x40);
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (unsigned short)(u >> 16);
+}
+
+// max over the two 32-lane halves of a wave, result in every lane
+__device__ __forceinline__ int half_swap_max_i32(int v) {
+  auto r = __builtin_amdgcn_permlane32_swap((unsigned)v, (unsigned)v, false, false);
+  int a = (int)r[0], b = (int)r[1];
+  return a > b ? a : b;
+}
+__device__ __forceinline__ float half_swap_max_f32(float v) {
+  auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ __forceinline__ float half_swap_sum_f32(float v) {
+  auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
+// max over all 64 lanes (result in every lane)
+__device__ __forceinline__ float wave_max_f32(float v) {
+#pragma unroll
+  for (int off = 1; off < 32; off <<= 1) v = fmaxf(v, __shfl_xor(v, off, 64));
+  return half_swap_max_f32(v);
+}
+
+}  // namespace sage

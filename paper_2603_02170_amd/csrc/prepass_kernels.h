@@ -1,0 +1,307 @@
+// Pre-pass kernels: K-smoothing mean, optional Q-smoothing block mean, the per-block
+// INT8 quantiser psi, delta = rowsum(dO o O), and the export (inspection) kernels.
+//
+// Paper: Sec. 3 "Quantization" (X^ = round(X / delta_X), delta_X = max|X| / 127),
+// Sec. 3 "Q and K Smoothing" (mu_K over the whole key tensor, mu_Qi per block),
+// Algorithm 1 "Quantization" line, Algorithm 2 line 2 (D) and line 6 (psi(dO_i)).
+//
+// The stored INT8 codes and FP32 scales are a bit-exact contract, so the arithmetic
+// here is fixed: mean = (float64 sum) / N rounded once to FP32; x - mu in FP32;
+// a = max|x|; s = a / 127 and r = 127 / a as IEEE FP32 divisions; q = rne(x * r).
+#pragma once
+
+#include "common.h"
+
+namespace sage {
+
+#pragma clang fp contract(off)
+
+constexpr int kMeanChunkRows = 256;
+
+// ---- K mean, stage 1: float64 column sums of a 256-row chunk ----------------------
+template <int D>
+__global__ void __launch_bounds__(256) kmean_partial_kernel(const unsigned short* __restrict__ K,
+                                                            double* __restrict__ kpart, int N,
+                                                            int nchunk) {
+  constexpr int TPR = D / 8;          // threads per row, 8 channels (16 bytes) each
+  constexpr int RPP = 256 / TPR;      // rows per pass
+  __shared__ double red[256][8];
+  const int t = threadIdx.x;
+  const int chunk = blockIdx.x, bh = blockIdx.y;
+  const int row0 = chunk * kMeanChunkRows;
+  const int rows = min(kMeanChunkRows, N - row0);
+  const unsigned short* base = K + ((size_t)bh * N + row0) * D;
+  double acc[8];
+#pragma unroll
+  for (int e = 0; e < 8; e++) acc[e] = 0.0;
+  const int tr = t / TPR, tc = t % TPR;
+  for (int r = tr; r < rows; r += RPP) {
+    v8us v = *(const v8us*)(base + (size_t)r * D + tc * 8);
+#pragma unroll
+    for (int e = 0; e < 8; e++) acc[e] += (double)bf16_bits_to_float(v[e]);
+  }
+#pragma unroll
+  for (int e = 0; e < 8; e++) red[t][e] = acc[e];
+  __syncthreads();
+  if (t < D) {
+    double s = 0.0;
+    for (int g = 0; g < RPP; g++) s += red[g * TPR + t / 8][t % 8];
+    kpart[((size_t)bh * nchunk + chunk) * D + t] = s;
+  }
+}
+
+// ---- K mean, stage 2: sum the chunks, divide by N, round once to FP32 -------------
+__global__ void kmean_final_kernel(const double* __restrict__ kpart, float* __restrict__ muK, int N,
+                                   int nchunk, int D) {
+  const int bh = blockIdx.x, c = threadIdx.x;
+  if (c >= D) return;
+  double s = 0.0;
+  for (int k = 0; k < nchunk; k++) s += kpart[((size_t)bh * nchunk + k) * D + c];
+  muK[(size_t)bh * D + c] = (float)(s / (double)N);
+}
+
+__global__ void fill_zero_f32_kernel(float* __restrict__ p, size_t n) {
+  size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x;
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  for (; i < n; i += stride) p[i] = 0.f;
+}
+
+// ---- psi on one 64-row block ---------------------------------------------------
+struct QuantJob {
+  const unsigned short* src;   // bf16 [BH, N, D]
+  int8_t* outF;                // F layout or nullptr
+  int8_t* outTF;               // TF layout or nullptr
+  float* scale;                // [BH, N/64]
+  const float* mu_head;        // [BH, D] subtracted from every row (K-smoothing) or nullptr
+  float* mu_block_out;         // [BH, N/64, D]: if set, the block mean is computed, stored and subtracted
+  const unsigned short* O;     // bf16 [BH, N, D] or nullptr: delta = rowsum(src o O)
+  float* delta;                // [BH, N]
+};
+struct QuantJobs {
+  QuantJob job[4];
+};
+
+template <int D>
+__global__ void __launch_bounds__(256) prepass_quant_kernel(QuantJobs jobs, int N) {
+  constexpr int CPR = D / 16;            // 16-channel chunks per row
+  constexpr int NCH = 64 * CPR / 256;    // chunks per thread (1 for D=64, 2 for D=128)
+  constexpr int NTF = 4 * D / 256;       // TF chunks per thread
+  __shared__ __attribute__((aligned(16))) int8_t tile[64 * D];
+  __shared__ float colbuf[64 * D / 4];   // used by the block mean only (16 rows at a time)
+  __shared__ float mu_s[D];
+  __shared__ float wmax[4];
+
+  const QuantJob jb = jobs.job[blockIdx.z];
+  const int t = threadIdx.x;
+  const int blk = blockIdx.x, bh = blockIdx.y;
+  const int nblk = N / kBlock;
+  const size_t tile_off = ((size_t)bh * N + (size_t)blk * kBlock) * D;
+
+  float x[NCH][16];
+#pragma unroll
+  for (int it = 0; it < NCH; it++) {
+    const int c = t + 256 * it;
+    const int row = c / CPR, ch = c % CPR;
+    const unsigned short* p = jb.src + tile_off + (size_t)row * D + ch * 16;
+    v8us lo = *(const v8us*)p;
+    v8us hi = *(const v8us*)(p + 8);
+#pragma unroll
+    for (int e = 0; e < 8; e++) {
+      x[it][e] = bf16_bits_to_float(lo[e]);
+      x[it][8 + e] = bf16_bits_to_float(hi[e]);
+    }
+  }
+
+  // delta = rowsum(dO o O), FP32 (not part of the bit-exact contract)
+  if (jb.O != nullptr) {
+#pragma unroll
+    for (int it = 0; it < NCH; it++) {
+      const int c = t + 256 * it;
+      const int row = c / CPR, ch = c % CPR;
+      const unsigned short* p = jb.O + tile_off + (size_t)row * D + ch * 16;
+      v8us lo = *(const v8us*)p;
+      v8us hi = *(const v8us*)(p + 8);
+      float acc = 0.f;
+#pragma unroll
+      for (int e = 0; e < 8; e++) {
+        acc += x[it][e] * bf16_bits_to_float(lo[e]);
+        acc += x[it][8 + e] * bf16_bits_to_float(hi[e]);
+      }
+#pragma unroll
+      for (int off = 1; off < CPR; off <<= 1) acc += __shfl_xor(acc, off, 64);
+      if (ch == 0) jb.delta[(size_t)bh * N + (size_t)blk * kBlock + row] = acc;
+    }
+  }
+
+  if (jb.mu_head != nullptr) {
+#pragma unroll
+    for (int it = 0; it < NCH; it++) {
+      const int ch = (t + 256 * it) % CPR;
+      const float* mu = jb.mu_head + (size_t)bh * D + ch * 16;
+#pragma unroll
+      for (int e = 0; e < 16; e++) x[it][e] = x[it][e] - mu[e];
+    }
+  }
+
+  if (jb.mu_block_out != nullptr) {
+    // block mean over the 64 rows: float64 sum (exact for bf16 data), one rounding.
+    // Done in 4 passes of 16 rows through `colbuf` to bound LDS.
+    double part = 0.0;   // thread t < D accumulates channel t
+    for (int pass = 0; pass < 4; pass++) {
+      __syncthreads();
+#pragma unroll
+      for (int it = 0; it < NCH; it++) {
+        const int c = t + 256 * it;
+        const int row = c / CPR, ch = c % CPR;
+        if (row / 16 == pass) {
+#pragma unroll
+          for (int e = 0; e < 16; e++) colbuf[(row % 16) * D + ch * 16 + e] = x[it][e];
+        }
+      }
+      __syncthreads();
+      if (t < D) {
+        for (int r = 0; r < 16; r++) part += (double)colbuf[r * D + t];
+      }
+    }
+    if (t < D) {
+      const float m = (float)(part / 64.0);
+      mu_s[t] = m;
+      jb.mu_block_out[((size_t)bh * nblk + blk) * D + t] = m;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int it = 0; it < NCH; it++) {
+      const int ch = (t + 256 * it) % CPR;
+#pragma unroll
+      for (int e = 0; e < 16; e++) x[it][e] = x[it][e] - mu_s[ch * 16 + e];
+    }
+  }
+
+  // block absmax
+  float a = 0.f;
+#pragma unroll
+  for (int it = 0; it < NCH; it++)
+#pragma unroll
+    for (int e = 0; e < 16; e++) a = fmaxf(a, fabsf(x[it][e]));
+  a = wave_max_f32(a);
+  if ((t & 63) == 0) wmax[t >> 6] = a;
+  __syncthreads();
+  a = fmaxf(fmaxf(wmax[0], wmax[1]), fmaxf(wmax[2], wmax[3]));
+  const bool nz = a > 0.f;
+  const float s = nz ? a / 127.0f : 0.f;
+  const float r = nz ? 127.0f / a : 0.f;
+  if (t == 0) jb.scale[(size_t)bh * nblk + blk] = s;
+
+  const size_t frag_base = ((size_t)bh * (N / 32) + (size_t)blk * 2) * (D / 32) * 1024;
+#pragma unroll
+  for (int it = 0; it < NCH; it++) {
+    const int c = t + 256 * it;
+    const int row = c / CPR, ch = c % CPR;
+    v4i packed;
+#pragma unroll
+    for (int w = 0; w < 4; w++) {
+      unsigned u = 0;
+#pragma unroll
+      for (int e = 0; e < 4; e++) {
+        float y = __builtin_rintf(x[it][4 * w + e] * r);
+        y = fminf(fmaxf(y, -127.f), 127.f);
+        u |= ((unsigned)((int)y) & 0xffu) << (8 * e);
+      }
+      packed[w] = (int)u;
+    }
+    if (jb.outTF != nullptr) *(v4i*)(tile + row * D + ch * 16) = packed;
+    if (jb.outF != nullptr) {
+      const int rb = row / 32, sstep = ch / 2, h = ch % 2;
+      const int lane = (row % 32) + 32 * h;
+      *(v4i*)(jb.outF + frag_base + ((size_t)(rb * (D / 32) + sstep) * 64 + lane) * 16) = packed;
+    }
+  }
+  if (jb.outTF != nullptr) {
+    __syncthreads();
+#pragma unroll
+    for (int it = 0; it < NTF; it++) {
+      const int c = t + 256 * it;            // (rb, cb, lane)
+      const int lane = c % 64, cb = (c / 64) % (D / 32), rb = c / (64 * (D / 32));
+      const int col = 32 * cb + (lane % 32), h = lane / 32;
+      v4i packed;
+#pragma unroll
+      for (int aa = 0; aa < 4; aa++) {
+        unsigned u = 0;
+#pragma unroll
+        for (int b = 0; b < 4; b++) {
+          const int row = 32 * rb + 8 * aa + 4 * h + b;
+          u |= ((unsigned)(unsigned char)tile[row * D + col]) << (8 * b);
+        }
+        packed[aa] = (int)u;
+      }
+      *(v4i*)(jb.outTF + frag_base + ((size_t)(rb * (D / 32) + cb) * 64 + lane) * 16) = packed;
+    }
+  }
+}
+
+// ---- inspection: fragment layouts back to row-major -----------------------------
+// One thread per 16-byte fragment chunk.  transposed = 0: F layout, 1: TF layout.
+__global__ void export_fragments_kernel(const int8_t* __restrict__ frag, int8_t* __restrict__ out,
+                                        size_t n_chunks, int N, int D, int transposed) {
+  size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x;
+  if (i >= n_chunks) return;
+  const int fpr = D / 32;                     // fragments per 32-row block
+  const int lane = (int)(i % 64);
+  const size_t f = i / 64;                    // global fragment index
+  const int sc = (int)(f % fpr);
+  const size_t rbg = f / fpr;                 // 32-row block over all heads (N % 32 == 0)
+  const size_t head = rbg / (N / 32);
+  const int rb = (int)(rbg % (N / 32));
+  v4i v = *(const v4i*)(frag + i * 16);
+  const int r = lane % 32, h = lane / 32;
+  int8_t* obase = out + head * (size_t)N * D;
+  if (!transposed) {
+    *(v4i*)(obase + (size_t)(32 * rb + r) * D + 32 * sc + 16 * h) = v;
+  } else {
+#pragma unroll
+    for (int aa = 0; aa < 4; aa++)
+#pragma unroll
+      for (int b = 0; b < 4; b++)
+        obase[(size_t)(32 * rb + 8 * aa + 4 * h + b) * D + 32 * sc + r] = (int8_t)((v[aa] >> (8 * b)) & 0xff);
+  }
+}
+
+__global__ void copy_f32_kernel(const float* __restrict__ in, float* __restrict__ out, size_t n) {
+  size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x;
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  for (; i < n; i += stride) out[i] = in[i];
+}
+
+// ---- Q-smoothing: logit bias table -------------------------------------------------
+// bias[bh][I][k] = sm_scale*log2(e) * mu_Q[I] . K_sm[k]  (the mu_Qi K_sm^T term of the
+// Sec. 3 decomposition; the two mu_K terms are constant along a softmax row and dropped).
+// FP32 from the unquantised K - mu_K.  Causal: blocks I < block(k) are never read.
+template <int D>
+__global__ void __launch_bounds__(256) qsmooth_bias_kernel(const unsigned short* __restrict__ K,
+                                                           const float* __restrict__ muK,
+                                                           const float* __restrict__ muQ,
+                                                           float* __restrict__ bias, int N, int causal,
+                                                           float scale_log2e) {
+  __shared__ float ks[64][D + 1];
+  const int t = threadIdx.x;
+  const int kblk = blockIdx.x, bh = blockIdx.y;
+  const int nblk = N / kBlock;
+  const unsigned short* src = K + ((size_t)bh * N + (size_t)kblk * kBlock) * D;
+  const float* mk = muK + (size_t)bh * D;
+  for (int i = t; i < 64 * D; i += 256) {
+    const int row = i / D, c = i % D;
+    ks[row][c] = bf16_bits_to_float(src[i]) - mk[c];
+  }
+  __syncthreads();
+  const int key = t % 64, grp = t / 64;
+  const int first = causal ? kblk : 0;
+  for (int I = first + grp; I < nblk; I += 4) {
+    const float* mq = muQ + ((size_t)bh * nblk + I) * D;
+    float acc = 0.f;
+#pragma unroll 8
+    for (int c = 0; c < D; c++) acc = __builtin_fmaf(mq[c], ks[key][c], acc);
+    bias[((size_t)bh * nblk + I) * N + (size_t)kblk * kBlock + key] = acc * scale_log2e;
+  }
+}
+
+}  // namespace sage

@@ -1,0 +1,388 @@
+// C-ABI host side of the SageBwd library: argument validation, workspace layout,
+// kernel launches.  See include/sagebwd.h for the contract of every entry point.
+#include "sagebwd.h"
+
+#include <hip/hip_runtime.h>
+#include <math.h>
+#include <string.h>
+
+#include <vector>
+
+#include "common.h"
+#include "prepass_kernels.h"
+#include "fwd_kernel.h"
+#include "bwd_kernel.h"
+
+namespace {
+
+using namespace sage;
+
+inline size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
+
+// Byte offsets of every buffer inside the caller's workspace.
+struct Workspace {
+  size_t kpart, muK, muQ, sQ, sK, sV, sdO, delta;
+  size_t QF, KF, VT;        // forward operands (QF, KF also feed the backward's S recompute)
+  size_t QT, KT, dOT;       // backward operands (TF layouts)
+  size_t dQacc;             // FP32 dQ accumulator [BH, N, d]
+  size_t bias;              // Q-smoothing: logit bias table [BH, N/64, N]
+  size_t colsum;            // Q-smoothing backward: colsum(dS) per (Q block, key) [BH, N/64, N]
+  size_t total;
+  int nchunk;
+};
+
+Workspace make_layout(const sagebwd_params& p) {
+  Workspace w;
+  const size_t BH = (size_t)p.B * p.H, N = p.N, d = p.d, nblk = N / 64;
+  const bool qs = (p.smooth & SAGEBWD_SMOOTH_Q) != 0;
+  w.nchunk = (int)((N + kMeanChunkRows - 1) / kMeanChunkRows);
+  size_t off = 0;
+  auto take = [&](size_t bytes) { size_t o = off; off += align_up(bytes); return o; };
+  w.kpart = take(BH * w.nchunk * d * sizeof(double));
+  w.muK = take(BH * d * 4);
+  w.muQ = take(qs ? BH * nblk * d * 4 : 0);
+  w.sQ = take(BH * nblk * 4);
+  w.sK = take(BH * nblk * 4);
+  w.sV = take(BH * nblk * 4);
+  w.sdO = take(BH * nblk * 4);
+  w.delta = take(BH * N * 4);
+  w.QF = take(BH * N * d);
+  w.KF = take(BH * N * d);
+  w.VT = take(BH * N * d);
+  w.QT = take(BH * N * d);
+  w.KT = take(BH * N * d);
+  w.dOT = take(BH * N * d);
+  w.dQacc = take(BH * N * d * 4);
+  w.bias = take(qs ? BH * nblk * N * 4 : 0);
+  w.colsum = take(qs ? BH * nblk * N * 4 : 0);
+  w.total = off;
+  return w;
+}
+
+int check_params(const sagebwd_params* p) {
+  if (p == nullptr) return SAGEBWD_INVALID_ARG;
+  if (p->B <= 0 || p->H <= 0 || p->N <= 0 || p->d <= 0) return SAGEBWD_INVALID_ARG;
+  if (p->reserved != 0) return SAGEBWD_INVALID_ARG;
+  if ((p->smooth & ~(SAGEBWD_SMOOTH_K | SAGEBWD_SMOOTH_Q)) != 0) return SAGEBWD_INVALID_ARG;
+  if (p->causal != 0 && p->causal != 1) return SAGEBWD_INVALID_ARG;
+  if (!(p->sm_scale >= 0.f) || isinf(p->sm_scale)) return SAGEBWD_INVALID_ARG;
+  if (p->d != 64 && p->d != 128) return SAGEBWD_UNSUPPORTED_SHAPE;
+  if (p->N % 64 != 0) return SAGEBWD_UNSUPPORTED_SHAPE;
+  const double elems = (double)p->B * p->H * (double)p->N * p->d;
+  if (elems >= 1099511627776.0) return SAGEBWD_UNSUPPORTED_SHAPE;
+  if ((double)p->B * p->H > 65535.0) return SAGEBWD_UNSUPPORTED_SHAPE;   // grid.y limit
+  return SAGEBWD_OK;
+}
+
+float logit_scale(const sagebwd_params& p) {
+  return p.sm_scale > 0.f ? p.sm_scale : (float)(1.0 / sqrt((double)p.d));
+}
+
+// ---- timing -----------------------------------------------------------------
+struct TimedSpan {
+  hipEvent_t a, b;
+};
+bool g_timing = false;
+std::vector<TimedSpan> g_spans[SAGEBWD_KERNEL_COUNT];
+std::vector<TimedSpan> g_pool;
+
+struct ScopedTimer {
+  int k;
+  hipStream_t st;
+  TimedSpan span;
+  bool on;
+  ScopedTimer(int kernel, hipStream_t s) : k(kernel), st(s), on(g_timing) {
+    if (!on) return;
+    if (!g_pool.empty()) {
+      span = g_pool.back();
+      g_pool.pop_back();
+    } else if (hipEventCreate(&span.a) != hipSuccess || hipEventCreate(&span.b) != hipSuccess) {
+      on = false;
+      return;
+    }
+    (void)hipEventRecord(span.a, st);
+  }
+  ~ScopedTimer() {
+    if (!on) return;
+    (void)hipEventRecord(span.b, st);
+    g_spans[k].push_back(span);
+  }
+};
+
+#define SAGE_LAUNCH_CHECK()                                   \
+  do {                                                        \
+    if (hipGetLastError() != hipSuccess) return SAGEBWD_HIP_ERROR; \
+  } while (0)
+
+// ---- pre-pass ---------------------------------------------------------------
+template <int D>
+int run_prepass(const void* Q, const void* K, const void* V, const void* dO, const void* O,
+                const sagebwd_params& p, char* ws, const Workspace& w, bool for_bwd, hipStream_t st) {
+  const int BH = p.B * p.H, N = p.N, nblk = N / 64;
+  const bool ks = (p.smooth & SAGEBWD_SMOOTH_K) != 0;
+  const bool qs = (p.smooth & SAGEBWD_SMOOTH_Q) != 0;
+  float* muK = (float*)(ws + w.muK);
+  if (ks) {
+    kmean_partial_kernel<D><<<dim3(w.nchunk, BH), 256, 0, st>>>((const unsigned short*)K,
+                                                                 (double*)(ws + w.kpart), N, w.nchunk);
+    SAGE_LAUNCH_CHECK();
+    kmean_final_kernel<<<BH, 128, 0, st>>>((const double*)(ws + w.kpart), muK, N, w.nchunk, D);
+    SAGE_LAUNCH_CHECK();
+  } else {
+    fill_zero_f32_kernel<<<(BH * D + 255) / 256, 256, 0, st>>>(muK, (size_t)BH * D);
+    SAGE_LAUNCH_CHECK();
+  }
+  QuantJobs jobs;
+  memset(&jobs, 0, sizeof(jobs));
+  int nj = 0;
+  // Q: F layout (S = Q^ K^^T in both passes) and, for the backward, TF layout (dK = dS^^T Q^)
+  jobs.job[nj].src = (const unsigned short*)Q;
+  jobs.job[nj].outF = (int8_t*)(ws + w.QF);
+  jobs.job[nj].outTF = for_bwd ? (int8_t*)(ws + w.QT) : nullptr;
+  jobs.job[nj].scale = (float*)(ws + w.sQ);
+  jobs.job[nj].mu_block_out = qs ? (float*)(ws + w.muQ) : nullptr;
+  nj++;
+  // K: F layout, and TF layout for the backward (dQ = dS^ K^)
+  jobs.job[nj].src = (const unsigned short*)K;
+  jobs.job[nj].outF = (int8_t*)(ws + w.KF);
+  jobs.job[nj].outTF = for_bwd ? (int8_t*)(ws + w.KT) : nullptr;
+  jobs.job[nj].scale = (float*)(ws + w.sK);
+  jobs.job[nj].mu_head = ks ? muK : nullptr;
+  nj++;
+  if (V != nullptr && !for_bwd) {
+    // V: TF layout (O = P^ V^ contracts over keys); the backward uses the bf16 V only
+    jobs.job[nj].src = (const unsigned short*)V;
+    jobs.job[nj].outTF = (int8_t*)(ws + w.VT);
+    jobs.job[nj].scale = (float*)(ws + w.sV);
+    nj++;
+  }
+  if (dO != nullptr) {
+    // dO: TF layout (dV = P^^T dO^ contracts over queries), plus delta when O is given
+    jobs.job[nj].src = (const unsigned short*)dO;
+    jobs.job[nj].outTF = (int8_t*)(ws + w.dOT);
+    jobs.job[nj].scale = (float*)(ws + w.sdO);
+    jobs.job[nj].O = (const unsigned short*)O;
+    jobs.job[nj].delta = (float*)(ws + w.delta);
+    nj++;
+  }
+  prepass_quant_kernel<D><<<dim3(nblk, BH, nj), 256, 0, st>>>(jobs, N);
+  SAGE_LAUNCH_CHECK();
+  if (qs) {
+    const float sl2 = logit_scale(p) * 1.4426950408889634f;
+    qsmooth_bias_kernel<D><<<dim3(nblk, BH), 256, 0, st>>>(
+        (const unsigned short*)K, muK, (const float*)(ws + w.muQ), (float*)(ws + w.bias), N,
+        p.causal, sl2);
+    SAGE_LAUNCH_CHECK();
+  }
+  return SAGEBWD_OK;
+}
+
+int pick_fwd_waves(int N) {
+  if (N % 256 == 0) return 8;
+  if (N % 128 == 0) return 4;
+  return 2;
+}
+
+template <int D, bool CAUSAL, bool QS>
+int launch_fwd_nw(const FwdArgs& a, int nw, hipStream_t st) {
+  FwdArgs args = a;
+  args.n_qtiles = a.N / (32 * nw);
+  const int heads8 = (a.BH + 7) / 8;
+  const int grid = 8 * heads8 * args.n_qtiles;
+  if (nw == 8) sage_fwd_kernel<D, CAUSAL, QS, 8><<<grid, 512, 0, st>>>(args);
+  else if (nw == 4) sage_fwd_kernel<D, CAUSAL, QS, 4><<<grid, 256, 0, st>>>(args);
+  else sage_fwd_kernel<D, CAUSAL, QS, 2><<<grid, 128, 0, st>>>(args);
+  SAGE_LAUNCH_CHECK();
+  return SAGEBWD_OK;
+}
+
+template <int D>
+int launch_fwd(const FwdArgs& a, bool causal, bool qs, hipStream_t st) {
+  const int nw = pick_fwd_waves(a.N);
+  if (causal) return qs ? launch_fwd_nw<D, true, true>(a, nw, st) : launch_fwd_nw<D, true, false>(a, nw, st);
+  return qs ? launch_fwd_nw<D, false, true>(a, nw, st) : launch_fwd_nw<D, false, false>(a, nw, st);
+}
+
+}  // namespace
+
+extern "C" {
+
+int sagebwd_workspace_bytes(const sagebwd_params* params, size_t* bytes) {
+  int rc = check_params(params);
+  if (rc != SAGEBWD_OK) return rc;
+  if (bytes == nullptr) return SAGEBWD_INVALID_ARG;
+  *bytes = make_layout(*params).total;
+  return SAGEBWD_OK;
+}
+
+int sagebwd_quantize(const void* Q, const void* K, const void* V, const void* dO, const void* O,
+                     const sagebwd_params* params, void* workspace, size_t workspace_bytes,
+                     void* stream) {
+  int rc = check_params(params);
+  if (rc != SAGEBWD_OK) return rc;
+  if (Q == nullptr || K == nullptr || V == nullptr || workspace == nullptr) return SAGEBWD_INVALID_ARG;
+  if (O != nullptr && dO == nullptr) return SAGEBWD_INVALID_ARG;
+  const Workspace w = make_layout(*params);
+  if (workspace_bytes < w.total) return SAGEBWD_WORKSPACE_TOO_SMALL;
+  hipStream_t st = (hipStream_t)stream;
+  char* ws = (char*)workspace;
+  // the inspection pre-pass fills every layout: forward operands first, then the backward's
+  {
+    ScopedTimer tm(SAGEBWD_KERNEL_PREPASS_FWD, st);
+    rc = params->d == 64 ? run_prepass<64>(Q, K, V, nullptr, nullptr, *params, ws, w, false, st)
+                         : run_prepass<128>(Q, K, V, nullptr, nullptr, *params, ws, w, false, st);
+  }
+  if (rc != SAGEBWD_OK || dO == nullptr) return rc;
+  {
+    ScopedTimer tm(SAGEBWD_KERNEL_PREPASS_BWD, st);
+    rc = params->d == 64 ? run_prepass<64>(Q, K, V, dO, O, *params, ws, w, true, st)
+                         : run_prepass<128>(Q, K, V, dO, O, *params, ws, w, true, st);
+  }
+  return rc;
+}
+
+int sagebwd_export_quantized(const sagebwd_params* params, const void* workspace,
+                             size_t workspace_bytes, int which, int8_t* q_out, float* scale_out,
+                             void* stream) {
+  int rc = check_params(params);
+  if (rc != SAGEBWD_OK) return rc;
+  if (workspace == nullptr) return SAGEBWD_INVALID_ARG;
+  const Workspace w = make_layout(*params);
+  if (workspace_bytes < w.total) return SAGEBWD_WORKSPACE_TOO_SMALL;
+  size_t qoff, soff;
+  int transposed;
+  switch (which) {
+    case SAGEBWD_TENSOR_Q: qoff = w.QF; soff = w.sQ; transposed = 0; break;
+    case SAGEBWD_TENSOR_K: qoff = w.KF; soff = w.sK; transposed = 0; break;
+    case SAGEBWD_TENSOR_V: qoff = w.VT; soff = w.sV; transposed = 1; break;
+    case SAGEBWD_TENSOR_DO: qoff = w.dOT; soff = w.sdO; transposed = 1; break;
+    default: return SAGEBWD_INVALID_ARG;
+  }
+  hipStream_t st = (hipStream_t)stream;
+  const char* ws = (const char*)workspace;
+  const size_t BH = (size_t)params->B * params->H;
+  if (q_out != nullptr) {
+    const size_t n_chunks = BH * params->N * params->d / 16;
+    export_fragments_kernel<<<(unsigned)((n_chunks + 255) / 256), 256, 0, st>>>(
+        (const int8_t*)(ws + qoff), q_out, n_chunks, params->N, params->d, transposed);
+    SAGE_LAUNCH_CHECK();
+  }
+  if (scale_out != nullptr) {
+    const size_t n = BH * (params->N / 64);
+    copy_f32_kernel<<<(unsigned)((n + 255) / 256), 256, 0, st>>>((const float*)(ws + soff), scale_out, n);
+    SAGE_LAUNCH_CHECK();
+  }
+  return SAGEBWD_OK;
+}
+
+int sagebwd_export_stats(const sagebwd_params* params, const void* workspace, size_t workspace_bytes,
+                         float* mu_K, float* mu_Q, float* delta, void* stream) {
+  int rc = check_params(params);
+  if (rc != SAGEBWD_OK) return rc;
+  if (workspace == nullptr) return SAGEBWD_INVALID_ARG;
+  const Workspace w = make_layout(*params);
+  if (workspace_bytes < w.total) return SAGEBWD_WORKSPACE_TOO_SMALL;
+  if (mu_Q != nullptr && !(params->smooth & SAGEBWD_SMOOTH_Q)) return SAGEBWD_INVALID_ARG;
+  hipStream_t st = (hipStream_t)stream;
+  const char* ws = (const char*)workspace;
+  const size_t BH = (size_t)params->B * params->H;
+  auto copy = [&](size_t off, float* out, size_t n) {
+    unsigned grid = (unsigned)((n + 255) / 256);
+    if (grid > 65535u * 16u) grid = 65535u * 16u;
+    copy_f32_kernel<<<grid, 256, 0, st>>>((const float*)(ws + off), out, n);
+  };
+  if (mu_K != nullptr) { copy(w.muK, mu_K, BH * params->d); SAGE_LAUNCH_CHECK(); }
+  if (mu_Q != nullptr) { copy(w.muQ, mu_Q, BH * (params->N / 64) * params->d); SAGE_LAUNCH_CHECK(); }
+  if (delta != nullptr) { copy(w.delta, delta, BH * params->N); SAGE_LAUNCH_CHECK(); }
+  return SAGEBWD_OK;
+}
+
+int sagebwd_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE,
+                const sagebwd_params* params, void* workspace, size_t workspace_bytes, void* stream) {
+  int rc = check_params(params);
+  if (rc != SAGEBWD_OK) return rc;
+  if (Q == nullptr || K == nullptr || V == nullptr || O == nullptr || LSE == nullptr || workspace == nullptr)
+    return SAGEBWD_INVALID_ARG;
+  const Workspace w = make_layout(*params);
+  if (workspace_bytes < w.total) return SAGEBWD_WORKSPACE_TOO_SMALL;
+  hipStream_t st = (hipStream_t)stream;
+  char* ws = (char*)workspace;
+  {
+    ScopedTimer tm(SAGEBWD_KERNEL_PREPASS_FWD, st);
+    rc = params->d == 64 ? run_prepass<64>(Q, K, V, nullptr, nullptr, *params, ws, w, false, st)
+                         : run_prepass<128>(Q, K, V, nullptr, nullptr, *params, ws, w, false, st);
+  }
+  if (rc != SAGEBWD_OK) return rc;
+  FwdArgs a;
+  a.QF = (const int8_t*)(ws + w.QF);
+  a.KF = (const int8_t*)(ws + w.KF);
+  a.VT = (const int8_t*)(ws + w.VT);
+  a.sQ = (const float*)(ws + w.sQ);
+  a.sK = (const float*)(ws + w.sK);
+  a.sV = (const float*)(ws + w.sV);
+  const bool qs = (params->smooth & SAGEBWD_SMOOTH_Q) != 0;
+  a.bias = qs ? (const float*)(ws + w.bias) : nullptr;
+  a.O = (unsigned short*)O;
+  a.LSE = LSE;
+  a.BH = params->B * params->H;
+  a.N = params->N;
+  a.n_qtiles = 0;
+  a.scale_log2e = logit_scale(*params) * 1.4426950408889634f;
+  {
+    ScopedTimer tm(SAGEBWD_KERNEL_FWD, st);
+    rc = params->d == 64 ? launch_fwd<64>(a, params->causal != 0, qs, st)
+                         : launch_fwd<128>(a, params->causal != 0, qs, st);
+  }
+  return rc;
+}
+
+int sagebwd_bwd(const void* Q, const void* K, const void* V, const void* O, const void* dO,
+                const float* LSE, void* dQ, void* dK, void* dV, const sagebwd_params* params,
+                void* workspace, size_t workspace_bytes, void* stream) {
+  int rc = check_params(params);
+  if (rc != SAGEBWD_OK) return rc;
+  if (Q == nullptr || K == nullptr || V == nullptr || O == nullptr || dO == nullptr || LSE == nullptr ||
+      dQ == nullptr || dK == nullptr || dV == nullptr || workspace == nullptr)
+    return SAGEBWD_INVALID_ARG;
+  const Workspace w = make_layout(*params);
+  if (workspace_bytes < w.total) return SAGEBWD_WORKSPACE_TOO_SMALL;
+  (void)stream;
+  return SAGEBWD_UNSUPPORTED_SHAPE;   // backward kernel not wired yet
+}
+
+int sagebwd_set_timing(int enable) {
+  g_timing = enable != 0;
+  return SAGEBWD_OK;
+}
+
+int sagebwd_read_timing(int kernel, double* total_ms, int* launches) {
+  if (kernel < 0 || kernel >= SAGEBWD_KERNEL_COUNT || total_ms == nullptr || launches == nullptr)
+    return SAGEBWD_INVALID_ARG;
+  double tot = 0.0;
+  int n = 0;
+  for (TimedSpan& s : g_spans[kernel]) {
+    if (hipEventSynchronize(s.b) != hipSuccess) return SAGEBWD_HIP_ERROR;
+    float ms = 0.f;
+    if (hipEventElapsedTime(&ms, s.a, s.b) != hipSuccess) return SAGEBWD_HIP_ERROR;
+    tot += ms;
+    n++;
+    g_pool.push_back(s);
+  }
+  g_spans[kernel].clear();
+  *total_ms = tot;
+  *launches = n;
+  return SAGEBWD_OK;
+}
+
+const char* sagebwd_strerror(int status) {
+  switch (status) {
+    case SAGEBWD_OK: return "ok";
+    case SAGEBWD_INVALID_ARG: return "invalid argument (null pointer, bad flag or size)";
+    case SAGEBWD_UNSUPPORTED_SHAPE: return "unsupported shape (need d in {64,128}, N a multiple of 64)";
+    case SAGEBWD_WORKSPACE_TOO_SMALL: return "workspace too small (see sagebwd_workspace_bytes)";
+    case SAGEBWD_HIP_ERROR: return "HIP runtime error";
+    default: return "unknown status";
+  }
+}
+
+}  // extern "C"

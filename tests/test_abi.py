@@ -1,0 +1,74 @@
+"""Host-side checks of the C-ABI library: it loads, exports every symbol the header
+declares, and rejects bad arguments before touching the GPU (no compute calls)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2603_02170_amd import binding
+from paper_2603_02170_amd.binding import SageParams
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(binding.lib_path()):
+        from paper_2603_02170_amd import build
+        build.build(verbose=False)
+    return binding.load_library()
+
+
+def _declared_functions():
+    text = open(os.path.join(ROOT, "include", "sagebwd.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(sagebwd_[a-z_]+)\s*\(", text)))
+
+
+def test_exports_every_declared_symbol(lib):
+    names = _declared_functions()
+    assert set(names) == set(binding.EXPORTS)
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+def test_strerror(lib):
+    assert binding.sagebwd_strerror(0) == "ok"
+    for code in (-1, -2, -3, -4):
+        assert binding.sagebwd_strerror(code) not in ("ok", "unknown status")
+    assert binding.sagebwd_strerror(-99) == "unknown status"
+
+
+def test_workspace_bytes_and_shape_validation(lib):
+    p = SageParams(2, 32, 8192, 128)
+    n = binding.workspace_bytes(p)
+    elems = 2 * 32 * 8192 * 128
+    assert n >= 6 * elems + 4 * elems          # six INT8 operand tensors + the FP32 dQ accumulator
+    assert n < 12 * elems
+    assert binding.workspace_bytes(SageParams(2, 32, 8192, 128, q_smooth=True)) > n
+    for bad in (SageParams(1, 1, 100, 64), SageParams(1, 1, 128, 96), SageParams(1, 1, 64, 256)):
+        with pytest.raises(binding.SageError) as e:
+            binding.workspace_bytes(bad)
+        assert e.value.status == -2
+    for bad in (SageParams(0, 1, 128, 64), SageParams(1, -1, 128, 64), SageParams(1, 1, 128, 64, sm_scale=-1.0)):
+        with pytest.raises(binding.SageError) as e:
+            binding.workspace_bytes(bad)
+        assert e.value.status == -1
+
+
+def test_entry_points_reject_bad_arguments_on_the_host(lib):
+    cp = SageParams(1, 2, 128, 64).c()
+    null = ctypes.c_void_p(None)
+    one = ctypes.c_void_p(256)   # never dereferenced: validation fails first
+    assert lib.sagebwd_fwd(null, one, one, one, one, ctypes.byref(cp), one, 1 << 30, null) == -1
+    assert lib.sagebwd_fwd(one, one, one, one, one, ctypes.byref(cp), one, 16, null) == -3
+    assert lib.sagebwd_bwd(one, one, one, one, one, one, one, one, null, ctypes.byref(cp), one, 1 << 30, null) == -1
+    assert lib.sagebwd_quantize(one, one, one, null, one, ctypes.byref(cp), one, 1 << 30, null) == -1
+    assert lib.sagebwd_export_quantized(ctypes.byref(cp), one, 1 << 30, 7, one, one, null) == -1
+    assert lib.sagebwd_fwd(one, one, one, one, one, None, one, 1 << 30, null) == -1
+    bad = SageParams(1, 2, 128, 64).c()
+    bad.smooth = 8
+    assert lib.sagebwd_fwd(one, one, one, one, one, ctypes.byref(bad), one, 1 << 30, null) == -1
+    tot, cnt = ctypes.c_double(0), ctypes.c_int(0)
+    assert lib.sagebwd_read_timing(99, ctypes.byref(tot), ctypes.byref(cnt)) == -1

@@ -1,0 +1,80 @@
+"""GPU parity of the pre-pass: INT8 codes, scales and smoothing means must equal the
+oracle's bit for bit (through the C ABI)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2603_02170_amd import binding, synth
+from gpu_common import params_for, to_np
+
+pytestmark = pytest.mark.gpu
+
+
+def _oracle_prepass(Q, K, V, dO, p):
+    B, H, N, d = Q.shape
+    out = {k: np.zeros((B, H, N, d), np.int8) for k in ("Qh", "Kh", "Vh", "dOh")}
+    out.update({k: np.zeros((B, H, N // 64), np.float32) for k in ("sQ", "sK", "sV", "sdO")})
+    out["muK"] = np.zeros((B, H, d), np.float32)
+    out["muQ"] = np.zeros((B, H, N // 64, d), np.float32)
+    for b in range(B):
+        for h in range(H):
+            pp = oracle.prepass_head(Q[b, h], K[b, h], V[b, h], p.k_smooth, p.q_smooth)
+            for k in ("Qh", "Kh", "Vh", "sQ", "sK", "sV", "muK", "muQ"):
+                out[k][b, h] = pp[k]
+            out["dOh"][b, h], out["sdO"][b, h] = oracle.quantize_blocks(dO[b, h])
+    return out
+
+
+def _run_case(Q, K, V, dO, p):
+    dev = "cuda"
+    Qd, Kd, Vd, dOd = (t.to(dev) for t in (Q, K, V, dO))
+    ws = binding.alloc_workspace(p, dev)
+    ws.fill_(0x5A)
+    Od = torch.randn(Q.shape, device=dev).to(torch.bfloat16)
+    binding.sagebwd_quantize(Qd, Kd, Vd, p, ws, dO=dOd, O=Od)
+    ref = _oracle_prepass(*(to_np(t) for t in (Q, K, V, dO)), p)
+    for which, qn, sn in ((binding.TENSOR_Q, "Qh", "sQ"), (binding.TENSOR_K, "Kh", "sK"),
+                          (binding.TENSOR_V, "Vh", "sV"), (binding.TENSOR_DO, "dOh", "sdO")):
+        q, s = binding.sagebwd_export_quantized(p, ws, which)
+        assert np.array_equal(q.cpu().numpy(), ref[qn]), qn
+        assert np.array_equal(s.cpu().numpy().view(np.uint32), ref[sn].view(np.uint32)), sn
+    muK, muQ, delta = binding.sagebwd_export_stats(p, ws, want_delta=True)
+    assert np.array_equal(muK.cpu().numpy().view(np.uint32), ref["muK"].view(np.uint32))
+    if p.q_smooth:
+        assert np.array_equal(muQ.cpu().numpy().view(np.uint32), ref["muQ"].view(np.uint32))
+    dref = (to_np(dO).astype(np.float64) * to_np(Od).astype(np.float64)).sum(-1)
+    assert np.allclose(delta.cpu().numpy(), dref, rtol=1e-4, atol=1e-4)
+
+
+@pytest.mark.parametrize("k_smooth,q_smooth", [(True, False), (False, False), (True, True)])
+def test_prepass_bit_exact_tiny(k_smooth, q_smooth):
+    w = synth.WORKLOADS["tiny"]
+    Q, K, V, dO = synth.make_inputs(w)
+    _run_case(Q, K, V, dO, params_for(w, k_smooth=k_smooth, q_smooth=q_smooth))
+
+
+def test_prepass_bit_exact_d128_ragged_chunks():
+    # N = 320 is not a multiple of the 256-row chunks of the mean reduction
+    g = torch.Generator().manual_seed(5)
+    Q, K, V, dO = (torch.randn(1, 3, 320, 128, generator=g).to(torch.bfloat16) for _ in range(4))
+    K = (K.float() + torch.randn(1, 3, 1, 128, generator=g) * 4).to(torch.bfloat16)
+    _run_case(Q, K, V, dO, binding.SageParams(1, 3, 320, 128, causal=True))
+
+
+def test_prepass_ties_zero_blocks_and_outliers():
+    g = torch.Generator().manual_seed(6)
+    Q = torch.randint(-254, 255, (1, 2, 128, 64), generator=g).float() * 0.5   # many exact .5 ties
+    Q[0, 0, 0, 0] = 127.0
+    Q[0, 1, 64:] = 0.0                                                         # an all-zero block
+    K = torch.randn(1, 2, 128, 64, generator=g) * 30
+    V = torch.randn(1, 2, 128, 64, generator=g) * 1e-3
+    dO = torch.randn(1, 2, 128, 64, generator=g) * 1e3
+    Q, K, V, dO = (t.to(torch.bfloat16) for t in (Q, K, V, dO))
+    _run_case(Q, K, V, dO, binding.SageParams(1, 2, 128, 64, causal=True, k_smooth=False))
+
+
+def test_prepass_bit_exact_sampled_heads_of_pretrain_shape():
+    w = synth.WORKLOADS["pretrain"]
+    Q, K, V, dO = synth.make_inputs(w, heads=[0, 17, 63])
+    _run_case(Q, K, V, dO, params_for(w, B=3, H=1))
