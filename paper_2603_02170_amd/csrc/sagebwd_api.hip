@@ -203,6 +203,21 @@ int launch_fwd(const FwdArgs& a, bool causal, bool qs, hipStream_t st) {
   return qs ? launch_fwd_nw<D, false, true>(a, nw, st) : launch_fwd_nw<D, false, false>(a, nw, st);
 }
 
+template <int D>
+int launch_bwd(const BwdArgs& a, bool causal, bool qs, hipStream_t st) {
+  const int nblk = a.N / 64;
+  const int grid = 8 * ((a.BH + 7) / 8) * nblk;
+  if (causal) {
+    if (qs) sage_bwd_kernel<D, true, true><<<grid, 256, 0, st>>>(a);
+    else sage_bwd_kernel<D, true, false><<<grid, 256, 0, st>>>(a);
+  } else {
+    if (qs) sage_bwd_kernel<D, false, true><<<grid, 256, 0, st>>>(a);
+    else sage_bwd_kernel<D, false, false><<<grid, 256, 0, st>>>(a);
+  }
+  SAGE_LAUNCH_CHECK();
+  return SAGEBWD_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -346,8 +361,53 @@ int sagebwd_bwd(const void* Q, const void* K, const void* V, const void* O, cons
     return SAGEBWD_INVALID_ARG;
   const Workspace w = make_layout(*params);
   if (workspace_bytes < w.total) return SAGEBWD_WORKSPACE_TOO_SMALL;
-  (void)stream;
-  return SAGEBWD_UNSUPPORTED_SHAPE;   // backward kernel not wired yet
+  hipStream_t st = (hipStream_t)stream;
+  char* ws = (char*)workspace;
+  const int BH = params->B * params->H, N = params->N, d = params->d;
+  const bool qs = (params->smooth & SAGEBWD_SMOOTH_Q) != 0;
+  const size_t n4 = (size_t)BH * N * d / 4;
+  const unsigned ew_grid = (unsigned)((n4 + 255) / 256 < 256u * 64u ? (n4 + 255) / 256 : 256u * 64u);
+  {
+    ScopedTimer tm(SAGEBWD_KERNEL_PREPASS_BWD, st);
+    rc = d == 64 ? run_prepass<64>(Q, K, V, dO, O, *params, ws, w, true, st)
+                 : run_prepass<128>(Q, K, V, dO, O, *params, ws, w, true, st);
+    if (rc != SAGEBWD_OK) return rc;
+    fill_zero_v4_kernel<<<ew_grid, 256, 0, st>>>((v4f*)(ws + w.dQacc), n4);
+    SAGE_LAUNCH_CHECK();
+  }
+  BwdArgs a;
+  a.QF = (const int8_t*)(ws + w.QF);
+  a.QT = (const int8_t*)(ws + w.QT);
+  a.KF = (const int8_t*)(ws + w.KF);
+  a.KT = (const int8_t*)(ws + w.KT);
+  a.dOT = (const int8_t*)(ws + w.dOT);
+  a.V = (const unsigned short*)V;
+  a.dO = (const unsigned short*)dO;
+  a.sQ = (const float*)(ws + w.sQ);
+  a.sK = (const float*)(ws + w.sK);
+  a.sdO = (const float*)(ws + w.sdO);
+  a.LSE = LSE;
+  a.delta = (const float*)(ws + w.delta);
+  a.bias = qs ? (const float*)(ws + w.bias) : nullptr;
+  a.muQ = qs ? (const float*)(ws + w.muQ) : nullptr;
+  a.dQacc = (float*)(ws + w.dQacc);
+  a.dK = (unsigned short*)dK;
+  a.dV = (unsigned short*)dV;
+  a.BH = BH;
+  a.N = N;
+  a.sm_scale = logit_scale(*params);
+  a.scale_log2e = a.sm_scale * 1.4426950408889634f;
+  {
+    ScopedTimer tm(SAGEBWD_KERNEL_BWD, st);
+    rc = d == 64 ? launch_bwd<64>(a, params->causal != 0, qs, st) : launch_bwd<128>(a, params->causal != 0, qs, st);
+    if (rc != SAGEBWD_OK) return rc;
+  }
+  {
+    ScopedTimer tm(SAGEBWD_KERNEL_BWD_EPILOGUE, st);
+    dq_to_bf16_kernel<<<ew_grid, 256, 0, st>>>((const float*)(ws + w.dQacc), (unsigned short*)dQ, n4);
+    SAGE_LAUNCH_CHECK();
+  }
+  return SAGEBWD_OK;
 }
 
 int sagebwd_set_timing(int enable) {
