@@ -102,7 +102,7 @@ def main():
     kern = {}
     for name, kid in (("prepass_fwd", binding.KERNEL_PREPASS_FWD), ("fwd", binding.KERNEL_FWD),
                       ("prepass_bwd", binding.KERNEL_PREPASS_BWD), ("bwd", binding.KERNEL_BWD),
-                      ("bwd_epilogue", binding.KERNEL_BWD_EPILOGUE)):
+                      ("bwd_dq", binding.KERNEL_BWD_DQ)):
         tot, n = binding.read_timing(kid)
         kern[name] = tot / max(n, 1)
     binding.set_timing(False)

@@ -64,8 +64,8 @@ typedef enum sagebwd_kernel {
   SAGEBWD_KERNEL_PREPASS_FWD = 0, /* smoothing + psi(Q), psi(K), psi(V)            */
   SAGEBWD_KERNEL_FWD = 1,         /* fused forward (Algorithm 1 loop)              */
   SAGEBWD_KERNEL_PREPASS_BWD = 2, /* psi(dO), delta, and the backward's operand layouts */
-  SAGEBWD_KERNEL_BWD = 3,         /* fused backward (Algorithm 2 loop)             */
-  SAGEBWD_KERNEL_BWD_EPILOGUE = 4,/* dQ accumulator -> bf16                        */
+  SAGEBWD_KERNEL_BWD = 3,         /* fused backward (Algorithm 2 loop): dK, dV, psi(dS) */
+  SAGEBWD_KERNEL_BWD_DQ = 4,      /* dQ = sum_j psi(dS_ij) K^_j from the stored tiles */
   SAGEBWD_KERNEL_COUNT = 5
 } sagebwd_kernel;
 
@@ -133,12 +133,19 @@ int sagebwd_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE
  * Inputs are the caller's bf16 Q, K, V, O, dO and the LSE of sagebwd_fwd run with the
  * same params; the pre-pass is re-run inside, so the workspace need not survive
  * between the two calls.  dQ, dK, dV (bf16 [B,H,N,d]) are overwritten.
- * dQ is accumulated across KV blocks with FP32 atomics, so its last bits may vary
- * from run to run.
+ * The quantised dS tiles are staged in the workspace (N*N bytes per head, at most 8 GiB
+ * at a time: larger problems are processed in groups of heads) and dQ is formed from
+ * them by a second kernel, so all three gradients are deterministic (no atomics).
  */
 int sagebwd_bwd(const void* Q, const void* K, const void* V, const void* O, const void* dO,
                 const float* LSE, void* dQ, void* dK, void* dV, const sagebwd_params* params,
                 void* workspace, size_t workspace_bytes, void* stream);
+
+/* Upper bound, in bytes, on the INT8 dS scratch that sagebwd_bwd holds at once (default
+ * 8 GiB).  The backward needs N*N bytes per head and processes the heads in groups that fit
+ * the bound (at least one head per group).  Process-wide setting: call it before
+ * sagebwd_workspace_bytes, and use the same value for the calls that share a workspace. */
+int sagebwd_set_scratch_budget(size_t bytes);
 
 /* Per-kernel device timing.  When enabled, every entry point brackets each kernel
  * it launches with HIP events on the caller's stream.  sagebwd_read_timing waits for

@@ -168,11 +168,13 @@ def _logits_block(pp, i0: int, n_keys: int, sm_scale: float, q_smooth: bool) -> 
 # forward (Algorithm 1)
 # --------------------------------------------------------------------------
 def forward_head(Q, K, V, causal: bool = True, k_smooth: bool = True, q_smooth: bool = False,
-                 sm_scale: float | None = None, return_raw: bool = False):
+                 sm_scale: float | None = None, return_raw: bool = False, q_blocks=None):
     """INT8 attention forward of one head.  Q, K, V: [N, d] float32 (bf16 values).
 
     Returns (O [N, d] bf16-rounded float32, L [N] float32); with return_raw the
-    unrounded float64 O and L come too.
+    unrounded float64 O and L come too.  `q_blocks` (iterable of 64-row block
+    indices) restricts the work to those query blocks -- rows are independent --
+    and leaves the other rows zero (sampling for large N).
     """
     Q = np.asarray(Q, dtype=_F32)
     n, d = Q.shape
@@ -185,7 +187,8 @@ def forward_head(Q, K, V, causal: bool = True, k_smooth: bool = True, q_smooth: 
     O = np.zeros((n, d), dtype=_F64)
     L = np.zeros(n, dtype=_F64)
     rows = np.arange(BLOCK)
-    for i0 in range(0, n, BLOCK):
+    todo = range(n // BLOCK) if q_blocks is None else sorted(set(int(b) for b in q_blocks))
+    for i0 in (BLOCK * b for b in todo):
         n_keys = i0 + BLOCK if causal else n          # R13: keys k <= i only
         tj = n_keys // BLOCK
         S = _logits_block(pp, i0, n_keys, sm_scale, q_smooth)
@@ -219,7 +222,8 @@ def forward_head(Q, K, V, causal: bool = True, k_smooth: bool = True, q_smooth: 
 # --------------------------------------------------------------------------
 def backward_head(Q, K, V, O, dO, L, causal: bool = True, k_smooth: bool = True,
                   q_smooth: bool = False, sm_scale: float | None = None,
-                  return_raw: bool = False, intermediates: dict | None = None):
+                  return_raw: bool = False, intermediates: dict | None = None,
+                  q_blocks=None, kv_blocks=None):
     """INT8 attention backward of one head.
 
     Inputs as the caller holds them: Q, K, V, O, dO [N, d] (bf16 values as
@@ -228,6 +232,11 @@ def backward_head(Q, K, V, O, dO, L, causal: bool = True, k_smooth: bool = True,
 
     If `intermediates` is a dict it receives the unquantised float64 P, dP, dS
     of the whole head (tiny inputs only; used by the invariant tests).
+
+    Sampling for large N (tiles are independent given L and delta):
+    `q_blocks` keeps only those Q blocks -- the rows of dQ that belong to them are
+    then complete, dK and dV are partial; `kv_blocks` keeps only those KV blocks --
+    the rows of dK and dV that belong to them are complete, dQ is partial.
     """
     Q = np.asarray(Q, dtype=_F32)
     n, d = Q.shape
@@ -250,9 +259,13 @@ def backward_head(Q, K, V, O, dO, L, causal: bool = True, k_smooth: bool = True,
         intermediates["dP"] = np.zeros((n, n))
         intermediates["dS"] = np.zeros((n, n))
     rows = np.arange(BLOCK)
-    for i0 in range(0, n, BLOCK):
+    q_todo = range(n // BLOCK) if q_blocks is None else sorted(set(int(b) for b in q_blocks))
+    kv_keep = None if kv_blocks is None else set(int(b) for b in kv_blocks)
+    for i0 in (BLOCK * b for b in q_todo):
         I = i0 // BLOCK
         n_keys = i0 + BLOCK if causal else n
+        if kv_keep is not None and not any(J in kv_keep for J in range(n_keys // BLOCK)):
+            continue
         S = _logits_block(pp, i0, n_keys, sm_scale, q_smooth)
         P = np.exp(S - L64[i0:i0 + BLOCK, None])              # P_ij = exp(S_ij - L_i)
         if causal:
@@ -267,6 +280,8 @@ def backward_head(Q, K, V, O, dO, L, causal: bool = True, k_smooth: bool = True,
         dOh_i = dOh[i0:i0 + BLOCK].astype(_F64)
         Qh_i = Qh[i0:i0 + BLOCK]
         for J in range(n_keys // BLOCK):
+            if kv_keep is not None and J not in kv_keep:
+                continue
             j0 = J * BLOCK
             # dV_j += psi(P_ij)^T psi(dO_i) * s_P * s_dO   (R14: dynamic per-tile scale)
             Ph, sP = _quantize_tile_f32(P[:, j0:j0 + BLOCK])

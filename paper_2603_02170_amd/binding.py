@@ -19,11 +19,11 @@ SMOOTH_K = 1
 SMOOTH_Q = 2
 
 TENSOR_Q, TENSOR_K, TENSOR_V, TENSOR_DO = 0, 1, 2, 3
-KERNEL_PREPASS_FWD, KERNEL_FWD, KERNEL_PREPASS_BWD, KERNEL_BWD, KERNEL_BWD_EPILOGUE = range(5)
+KERNEL_PREPASS_FWD, KERNEL_FWD, KERNEL_PREPASS_BWD, KERNEL_BWD, KERNEL_BWD_DQ = range(5)
 
 EXPORTS = (
     "sagebwd_workspace_bytes", "sagebwd_quantize", "sagebwd_export_quantized", "sagebwd_export_stats",
-    "sagebwd_fwd", "sagebwd_bwd", "sagebwd_set_timing", "sagebwd_read_timing", "sagebwd_strerror",
+    "sagebwd_fwd", "sagebwd_bwd", "sagebwd_set_scratch_budget", "sagebwd_set_timing", "sagebwd_read_timing", "sagebwd_strerror",
 )
 
 
@@ -73,6 +73,7 @@ def load_library():
     lib.sagebwd_fwd.argtypes = [vp, vp, vp, vp, vp, pp, vp, sz, vp]
     lib.sagebwd_bwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, pp, vp, sz, vp]
     lib.sagebwd_set_timing.argtypes = [i32]
+    lib.sagebwd_set_scratch_budget.argtypes = [sz]
     lib.sagebwd_read_timing.argtypes = [i32, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i32)]
     lib.sagebwd_strerror.argtypes = [i32]
     lib.sagebwd_strerror.restype = ctypes.c_char_p
@@ -193,6 +194,10 @@ def sagebwd_bwd(Q, K, V, O, dO, LSE, p: SageParams, workspace=None, dQ=None, dK=
                                       _ptr(outs[1]), _ptr(outs[2]), ctypes.byref(cp), _ptr(workspace),
                                       workspace.numel(), _stream()), "sagebwd_bwd")
     return tuple(outs)
+
+
+def set_scratch_budget(nbytes: int):
+    _check(load_library().sagebwd_set_scratch_budget(int(nbytes)), "sagebwd_set_scratch_budget")
 
 
 def set_timing(enable: bool):

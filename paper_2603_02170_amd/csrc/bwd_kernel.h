@@ -8,12 +8,18 @@
 //            through LDS; psi(P), psi(dS) are written to LDS as MFMA operand fragments.
 //   phase B  each wave takes one 32-channel slice of the outputs and contracts over the whole
 //            tile: dV^T += dO^^T P^, dK^T += Q^^T dS^ (accumulated in FP32 registers with the
-//            per-tile scales), dQ += dS^ K^ (scaled and added to an FP32 buffer with atomics).
+//            per-tile scales).  psi(dS_ij) and its scale are also stored to a scratch buffer.
+// A second kernel (sage_bwd_dq_kernel) owns one Q block per workgroup and forms
+//   dQ_i = sum_j s_dS(i,j) s_K(j) sm_scale * (dS^_ij K^_j)
+// from the stored INT8 tiles: a plain scaled INT8 GEMM with no atomics, so dQ is
+// deterministic.  (A first version added dQ with FP32 atomics from the first kernel; at
+// N=8192 the 4.3e9 atomic adds alone took 13 ms.)
 //
 // S is formed untransposed (queries x keys): an accumulator lane then holds one key and 16
 // queries, which is the B-operand form of the two contractions over queries (dV, dK).  The
 // contraction over keys (dQ) needs dS^ with one query per lane; that copy is scattered to
-// LDS bytewise (no VALU work) in the key order of the TF layout of K^.
+// LDS bytewise (no VALU work) in the key order of the TF layout of K^, and copied out from
+// there in 16-byte pieces.
 #pragma once
 
 #include "common.h"
@@ -24,7 +30,6 @@ struct BwdArgs {
   const int8_t* QF;    // F layout   (S recompute, A operand)
   const int8_t* QT;    // TF layout  (dK, A operand)
   const int8_t* KF;    // F layout   (S recompute, B operand)
-  const int8_t* KT;    // TF layout  (dQ, B operand)
   const int8_t* dOT;   // TF layout  (dV, A operand)
   const unsigned short* V;    // bf16 [BH, N, D]
   const unsigned short* dO;   // bf16 [BH, N, D]
@@ -35,7 +40,9 @@ struct BwdArgs {
   const float* delta;  // [BH, N]
   const float* bias;   // Q-smoothing logit bias [BH, N/64, N] (log2 domain) or nullptr
   const float* muQ;    // Q-smoothing block means [BH, N/64, D] or nullptr
-  float* dQacc;        // FP32 [BH, N, D], zero-filled
+  int8_t* dSq;         // psi(dS) tiles [heads, N/64, N/64, 4096], A fragments (q block, key step)
+  float* sdS;          // their scales [heads, N/64, N/64]
+  int bh0;             // first head of this launch (the scratch above is indexed from it)
   unsigned short* dK;  // bf16 [BH, N, D]
   unsigned short* dV;
   int BH, N;
@@ -70,8 +77,9 @@ __global__ void __launch_bounds__(256, 2) sage_bwd_kernel(BwdArgs args) {
   const int xcd = g & 7, slot = g >> 3;
   const int N = args.N;
   const int nblk = N / kBlock;
-  const int bh = xcd + 8 * (slot / nblk);
-  if (bh >= args.BH) return;
+  const int hl = xcd + 8 * (slot / nblk);   // head within this launch
+  if (hl >= args.BH) return;
+  const int bh = args.bh0 + hl;
   const int j = slot % nblk;          // small j = most Q blocks under the causal mask: scheduled first
 
   const int tid = threadIdx.x;
@@ -97,11 +105,6 @@ __global__ void __launch_bounds__(256, 2) sage_bwd_kernel(BwdArgs args) {
 #pragma unroll
     for (int s = 0; s < KB; s++) vfr[s] = *(const v8bf*)(p + 16 * s);
   }
-  v4i ktr[2];
-#pragma unroll
-  for (int ks = 0; ks < 2; ks++)
-    ktr[ks] = *(const v4i*)(args.KT + head + ((size_t)(2 * j + ks) * KS + cb) * 1024 + lane * 16);
-
   v16f dvacc[NPB], dkacc[NPB], dkbias[QSMOOTH ? NPB : 1];
 #pragma unroll
   for (int t = 0; t < NPB; t++)
@@ -229,10 +232,16 @@ __global__ void __launch_bounds__(256, 2) sage_bwd_kernel(BwdArgs args) {
     }
     __syncthreads();
 
+    // psi(dS_ij) and its scale go to the scratch buffer for the dQ kernel
+    {
+      const size_t tile = ((size_t)hl * nblk + i) * nblk + j;
+      *(v4i*)(args.dSq + tile * 4096 + tid * 16) = *(const v4i*)(s_dst + tid * 16);
+      if (tid == 0) args.sdS[tile] = sS;
+    }
+
     // ---------------- phase B: channel block cb ----------------
     const float w_dv = sP * args.sdO[(size_t)bh * nblk + i];
     const float w_dk = sS * sQi * args.sm_scale;
-    const float w_dq = sS * sKj * args.sm_scale;
 #pragma unroll
     for (int t = 0; t < NPB; t++) {
       const int kbo = blk0 + t;
@@ -267,24 +276,6 @@ __global__ void __launch_bounds__(256, 2) sage_bwd_kernel(BwdArgs args) {
         }
       }
     }
-#pragma unroll
-    for (int t = 0; t < NPB; t++) {
-      const int qbo = blk0 + t;
-      v16i aq;
-#pragma unroll
-      for (int r = 0; r < 16; r++) aq[r] = 0;
-#pragma unroll
-      for (int ks = 0; ks < 2; ks++) {
-        const v4i a = *(const v4i*)(s_dst + ((qbo * 2 + ks) * 64 + lane) * 16);
-        aq = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, ktr[ks], aq, 0, 0, 0);
-      }
-      float* dst = args.dQacc + head + (size_t)(64 * i + 32 * qbo + 4 * h) * D + 32 * cb + ll;
-#pragma unroll
-      for (int aa = 0; aa < 4; aa++)
-#pragma unroll
-        for (int b = 0; b < 4; b++)
-          unsafeAtomicAdd(dst + (size_t)(8 * aa + b) * D, (float)aq[4 * aa + b] * w_dq);
-    }
   }
 
   // ---- write dV, dK (bf16) ----
@@ -309,24 +300,94 @@ __global__ void __launch_bounds__(256, 2) sage_bwd_kernel(BwdArgs args) {
   }
 }
 
-// dQ accumulator (FP32) -> bf16
-__global__ void dq_to_bf16_kernel(const float* __restrict__ acc, unsigned short* __restrict__ out, size_t n4) {
-  size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x;
-  const size_t stride = (size_t)gridDim.x * blockDim.x;
-  for (; i < n4; i += stride) {
-    const v4f v = *(const v4f*)(acc + 4 * i);
-    v4us o;
-#pragma unroll
-    for (int b = 0; b < 4; b++) o[b] = float_to_bf16_bits(v[b]);
-    *(v4us*)(out + 4 * i) = o;
-  }
-}
+// ---------------------------------------------------------------------------------
+// dQ_i = sum_j (dS^_ij K^_j) * s_dS(i,j) * s_K(j) * sm_scale        (Algorithm 2, the dQ line)
+// One workgroup per Q block; each wave owns a 32-channel slice and streams its operands
+// straight from global memory / L2 (no LDS, no barriers): A = stored psi(dS) fragments,
+// B = K^ in TF layout.
+struct DqArgs {
+  const int8_t* dSq;
+  const float* sdS;
+  const int8_t* KT;
+  const float* sK;
+  unsigned short* dQ;   // bf16 [BH, N, D]
+  int BH, N, bh0;
+  float sm_scale;
+};
 
-__global__ void fill_zero_v4_kernel(v4f* __restrict__ p, size_t n4) {
-  size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x;
-  const size_t stride = (size_t)gridDim.x * blockDim.x;
-  const v4f z = {0.f, 0.f, 0.f, 0.f};
-  for (; i < n4; i += stride) p[i] = z;
+template <int D, bool CAUSAL>
+__global__ void __launch_bounds__(256, 2) sage_bwd_dq_kernel(DqArgs args) {
+  constexpr int KS = D / 32;
+  constexpr int NPB = KS / 2;
+  const int g = blockIdx.x;
+  const int xcd = g & 7, slot = g >> 3;
+  const int N = args.N;
+  const int nblk = N / kBlock;
+  const int hl = xcd + 8 * (slot / nblk);
+  if (hl >= args.BH) return;
+  const int bh = args.bh0 + hl;
+  const int i = nblk - 1 - (slot % nblk);      // longest rows first under the causal mask
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, wave = tid >> 6;
+  const int ll = lane & 31, h = lane >> 5;
+  const int cb = (D == 128) ? wave : (wave & 1);
+  const int blk0 = (D == 128) ? 0 : (wave >> 1);
+  const size_t head = (size_t)bh * N * D;
+  const int n_j = CAUSAL ? i + 1 : nblk;
+
+  const int8_t* ds_row = args.dSq + ((size_t)hl * nblk + i) * nblk * 4096 + lane * 16;
+  const float* sc_row = args.sdS + ((size_t)hl * nblk + i) * nblk;
+  const float* sKh = args.sK + (size_t)bh * nblk;
+  const int8_t* kt = args.KT + head + (size_t)cb * 1024 + lane * 16;
+
+  v16f acc[NPB];
+#pragma unroll
+  for (int t = 0; t < NPB; t++)
+#pragma unroll
+    for (int r = 0; r < 16; r++) acc[t][r] = 0.f;
+
+  v4i a_cur[NPB][2], b_cur[2];
+  auto load_tile = [&](int j, v4i (&a)[NPB][2], v4i (&b)[2]) {
+#pragma unroll
+    for (int ks = 0; ks < 2; ks++) {
+      b[ks] = *(const v4i*)(kt + (size_t)(2 * j + ks) * KS * 1024);
+#pragma unroll
+      for (int t = 0; t < NPB; t++) a[t][ks] = *(const v4i*)(ds_row + (size_t)j * 4096 + ((blk0 + t) * 2 + ks) * 1024);
+    }
+  };
+  load_tile(0, a_cur, b_cur);
+  for (int j = 0; j < n_j; j++) {
+    v4i a_nxt[NPB][2], b_nxt[2];
+    if (j + 1 < n_j) load_tile(j + 1, a_nxt, b_nxt);
+    const float w = sc_row[j] * sKh[j] * args.sm_scale;
+#pragma unroll
+    for (int t = 0; t < NPB; t++) {
+      v16i q;
+#pragma unroll
+      for (int r = 0; r < 16; r++) q[r] = 0;
+#pragma unroll
+      for (int ks = 0; ks < 2; ks++) q = __builtin_amdgcn_mfma_i32_32x32x32_i8(a_cur[t][ks], b_cur[ks], q, 0, 0, 0);
+#pragma unroll
+      for (int r = 0; r < 16; r++) acc[t][r] = __builtin_fmaf((float)q[r], w, acc[t][r]);
+    }
+    if (j + 1 < n_j) {
+#pragma unroll
+      for (int ks = 0; ks < 2; ks++) {
+        b_cur[ks] = b_nxt[ks];
+#pragma unroll
+        for (int t = 0; t < NPB; t++) a_cur[t][ks] = a_nxt[t][ks];
+      }
+    }
+  }
+  // accumulator lane = channel, registers = query rows 8a + 4h + b of the 32-row block
+#pragma unroll
+  for (int t = 0; t < NPB; t++) {
+    unsigned short* dst = args.dQ + head + (size_t)(64 * i + 32 * (blk0 + t) + 4 * h) * D + 32 * cb + ll;
+#pragma unroll
+    for (int aa = 0; aa < 4; aa++)
+#pragma unroll
+      for (int b = 0; b < 4; b++) dst[(size_t)(8 * aa + b) * D] = float_to_bf16_bits(acc[t][4 * aa + b]);
+  }
 }
 
 }  // namespace sage

@@ -17,6 +17,8 @@ namespace {
 
 using namespace sage;
 
+size_t g_ds_budget = (size_t)8 << 30;   // bytes of INT8 dS scratch the backward may hold at once
+
 inline size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
 
 // Byte offsets of every buffer inside the caller's workspace.
@@ -24,7 +26,9 @@ struct Workspace {
   size_t kpart, muK, muQ, sQ, sK, sV, sdO, delta;
   size_t QF, KF, VT;        // forward operands (QF, KF also feed the backward's S recompute)
   size_t QT, KT, dOT;       // backward operands (TF layouts)
-  size_t dQacc;             // FP32 dQ accumulator [BH, N, d]
+  size_t dSq;               // psi(dS) tiles of one head group [heads_per_group, N/64, N/64, 4096]
+  size_t sdS;               // their scales [heads_per_group, N/64, N/64]
+  int heads_per_group;      // the backward runs in groups of heads that share the dS scratch
   size_t bias;              // Q-smoothing: logit bias table [BH, N/64, N]
   size_t colsum;            // Q-smoothing backward: colsum(dS) per (Q block, key) [BH, N/64, N]
   size_t total;
@@ -52,7 +56,13 @@ Workspace make_layout(const sagebwd_params& p) {
   w.QT = take(BH * N * d);
   w.KT = take(BH * N * d);
   w.dOT = take(BH * N * d);
-  w.dQacc = take(BH * N * d * 4);
+  // dS scratch: N*N bytes per head, capped at kDsBudget by processing the heads in groups
+  size_t hpg = g_ds_budget / (N * N);
+  if (hpg < 1) hpg = 1;
+  if (hpg > BH) hpg = BH;
+  w.heads_per_group = (int)hpg;
+  w.dSq = take(hpg * N * N);
+  w.sdS = take(hpg * nblk * nblk * 4);
   w.bias = take(qs ? BH * nblk * N * 4 : 0);
   w.colsum = take(qs ? BH * nblk * N * 4 : 0);
   w.total = off;
@@ -218,6 +228,16 @@ int launch_bwd(const BwdArgs& a, bool causal, bool qs, hipStream_t st) {
   return SAGEBWD_OK;
 }
 
+template <int D>
+int launch_bwd_dq(const DqArgs& a, bool causal, hipStream_t st) {
+  const int nblk = a.N / 64;
+  const int grid = 8 * ((a.BH + 7) / 8) * nblk;
+  if (causal) sage_bwd_dq_kernel<D, true><<<grid, 256, 0, st>>>(a);
+  else sage_bwd_dq_kernel<D, false><<<grid, 256, 0, st>>>(a);
+  SAGE_LAUNCH_CHECK();
+  return SAGEBWD_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -365,21 +385,16 @@ int sagebwd_bwd(const void* Q, const void* K, const void* V, const void* O, cons
   char* ws = (char*)workspace;
   const int BH = params->B * params->H, N = params->N, d = params->d;
   const bool qs = (params->smooth & SAGEBWD_SMOOTH_Q) != 0;
-  const size_t n4 = (size_t)BH * N * d / 4;
-  const unsigned ew_grid = (unsigned)((n4 + 255) / 256 < 256u * 64u ? (n4 + 255) / 256 : 256u * 64u);
   {
     ScopedTimer tm(SAGEBWD_KERNEL_PREPASS_BWD, st);
     rc = d == 64 ? run_prepass<64>(Q, K, V, dO, O, *params, ws, w, true, st)
                  : run_prepass<128>(Q, K, V, dO, O, *params, ws, w, true, st);
     if (rc != SAGEBWD_OK) return rc;
-    fill_zero_v4_kernel<<<ew_grid, 256, 0, st>>>((v4f*)(ws + w.dQacc), n4);
-    SAGE_LAUNCH_CHECK();
   }
   BwdArgs a;
   a.QF = (const int8_t*)(ws + w.QF);
   a.QT = (const int8_t*)(ws + w.QT);
   a.KF = (const int8_t*)(ws + w.KF);
-  a.KT = (const int8_t*)(ws + w.KT);
   a.dOT = (const int8_t*)(ws + w.dOT);
   a.V = (const unsigned short*)V;
   a.dO = (const unsigned short*)dO;
@@ -390,23 +405,42 @@ int sagebwd_bwd(const void* Q, const void* K, const void* V, const void* O, cons
   a.delta = (const float*)(ws + w.delta);
   a.bias = qs ? (const float*)(ws + w.bias) : nullptr;
   a.muQ = qs ? (const float*)(ws + w.muQ) : nullptr;
-  a.dQacc = (float*)(ws + w.dQacc);
+  a.dSq = (int8_t*)(ws + w.dSq);
+  a.sdS = (float*)(ws + w.sdS);
   a.dK = (unsigned short*)dK;
   a.dV = (unsigned short*)dV;
-  a.BH = BH;
   a.N = N;
   a.sm_scale = logit_scale(*params);
   a.scale_log2e = a.sm_scale * 1.4426950408889634f;
-  {
-    ScopedTimer tm(SAGEBWD_KERNEL_BWD, st);
-    rc = d == 64 ? launch_bwd<64>(a, params->causal != 0, qs, st) : launch_bwd<128>(a, params->causal != 0, qs, st);
-    if (rc != SAGEBWD_OK) return rc;
+  DqArgs q;
+  q.dSq = a.dSq;
+  q.sdS = a.sdS;
+  q.KT = (const int8_t*)(ws + w.KT);
+  q.sK = a.sK;
+  q.dQ = (unsigned short*)dQ;
+  q.N = N;
+  q.sm_scale = a.sm_scale;
+  for (int h0 = 0; h0 < BH; h0 += w.heads_per_group) {
+    const int nh = BH - h0 < w.heads_per_group ? BH - h0 : w.heads_per_group;
+    a.bh0 = q.bh0 = h0;
+    a.BH = q.BH = nh;
+    {
+      ScopedTimer tm(SAGEBWD_KERNEL_BWD, st);
+      rc = d == 64 ? launch_bwd<64>(a, params->causal != 0, qs, st) : launch_bwd<128>(a, params->causal != 0, qs, st);
+      if (rc != SAGEBWD_OK) return rc;
+    }
+    {
+      ScopedTimer tm(SAGEBWD_KERNEL_BWD_DQ, st);
+      rc = d == 64 ? launch_bwd_dq<64>(q, params->causal != 0, st) : launch_bwd_dq<128>(q, params->causal != 0, st);
+      if (rc != SAGEBWD_OK) return rc;
+    }
   }
-  {
-    ScopedTimer tm(SAGEBWD_KERNEL_BWD_EPILOGUE, st);
-    dq_to_bf16_kernel<<<ew_grid, 256, 0, st>>>((const float*)(ws + w.dQacc), (unsigned short*)dQ, n4);
-    SAGE_LAUNCH_CHECK();
-  }
+  return SAGEBWD_OK;
+}
+
+int sagebwd_set_scratch_budget(size_t bytes) {
+  if (bytes == 0) return SAGEBWD_INVALID_ARG;
+  g_ds_budget = bytes;
   return SAGEBWD_OK;
 }
 

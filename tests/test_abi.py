@@ -44,8 +44,10 @@ def test_workspace_bytes_and_shape_validation(lib):
     p = SageParams(2, 32, 8192, 128)
     n = binding.workspace_bytes(p)
     elems = 2 * 32 * 8192 * 128
-    assert n >= 6 * elems + 4 * elems          # six INT8 operand tensors + the FP32 dQ accumulator
-    assert n < 12 * elems
+    assert n >= 6 * elems + 64 * 8192 * 8192   # six INT8 operand tensors + the INT8 dS scratch
+    assert n < 7 * elems + 64 * 8192 * 8192 + (64 << 20)
+    # the dS scratch is capped at 8 GiB: larger problems run in groups of heads
+    assert binding.workspace_bytes(SageParams(1, 32, 32768, 128, causal=False)) < (8 << 30) + 7 * 32 * 32768 * 128 + (64 << 20)
     assert binding.workspace_bytes(SageParams(2, 32, 8192, 128, q_smooth=True)) > n
     for bad in (SageParams(1, 1, 100, 64), SageParams(1, 1, 128, 96), SageParams(1, 1, 64, 256)):
         with pytest.raises(binding.SageError) as e:

@@ -74,3 +74,13 @@ def test_bwd_outlier_shape_with_and_without_k_smoothing():
     Q, K, V, dO = synth.make_inputs(w, heads=[3])
     for ks in (True, False):
         _bwd_case(Q, K, V, dO, params_for(w, B=1, H=1, k_smooth=ks))
+
+
+def test_bwd_head_groups_share_the_ds_scratch():
+    # a scratch budget of two heads' worth of dS forces the 5 heads through 3 groups
+    Q, K, V, dO = synth.gaussian_inputs(256, 64, seed=21, heads=5)
+    binding.set_scratch_budget(2 * 256 * 256)
+    try:
+        _bwd_case(Q, K, V, dO, binding.SageParams(1, 5, 256, 64, causal=True))
+    finally:
+        binding.set_scratch_budget(8 << 30)

@@ -31,7 +31,7 @@ def _run_case(Q, K, V, dO, p):
     Qd, Kd, Vd, dOd = (t.to(dev) for t in (Q, K, V, dO))
     ws = binding.alloc_workspace(p, dev)
     ws.fill_(0x5A)
-    Od = torch.randn(Q.shape, device=dev).to(torch.bfloat16)
+    Od = torch.randn(Q.shape, generator=torch.Generator().manual_seed(11)).to(torch.bfloat16).to(dev)
     binding.sagebwd_quantize(Qd, Kd, Vd, p, ws, dO=dOd, O=Od)
     ref = _oracle_prepass(*(to_np(t) for t in (Q, K, V, dO)), p)
     for which, qn, sn in ((binding.TENSOR_Q, "Qh", "sQ"), (binding.TENSOR_K, "Kh", "sK"),
@@ -43,8 +43,9 @@ def _run_case(Q, K, V, dO, p):
     assert np.array_equal(muK.cpu().numpy().view(np.uint32), ref["muK"].view(np.uint32))
     if p.q_smooth:
         assert np.array_equal(muQ.cpu().numpy().view(np.uint32), ref["muQ"].view(np.uint32))
-    dref = (to_np(dO).astype(np.float64) * to_np(Od).astype(np.float64)).sum(-1)
-    assert np.allclose(delta.cpu().numpy(), dref, rtol=1e-4, atol=1e-4)
+    prod = to_np(dO).astype(np.float64) * to_np(Od).astype(np.float64)
+    # FP32 accumulation of d terms: error bounded relative to the sum of magnitudes
+    assert (np.abs(delta.cpu().numpy() - prod.sum(-1)) <= 1e-5 * np.abs(prod).sum(-1) + 1e-30).all()
 
 
 @pytest.mark.parametrize("k_smooth,q_smooth", [(True, False), (False, False), (True, True)])
