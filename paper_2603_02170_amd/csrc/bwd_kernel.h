@@ -119,35 +119,73 @@ __global__ void __launch_bounds__(256, 2) sage_bwd_kernel(BwdArgs args) {
   // slot of key kappa = lane%32 inside a TF-ordered 32-key step: kappa = 8a + 4h' + b -> (h', 4a + b)
   const int tk_h = (ll >> 2) & 1, tk_t = 4 * (ll >> 3) + (ll & 3);
 
-  for (int i = nblk - 1; i >= i_first; i--) {
-    __syncthreads();   // everyone is done with the previous tile's LDS
-    // ---- stage Q^ (two layouts), dO^, dO (bf16), L, delta of Q block i ----
-    {
-      const size_t toff = head + (size_t)i * TILE;
+  // Staging of one Q block through registers.  Set A feeds phase A (Q^ row fragments, bf16 dO
+  // fragments, L, delta), set B feeds phase B (Q^ and dO^ transposed fragments, mu_Q).
+  constexpr int NI8 = TILE / 16 / 256;        // 16-byte pieces per thread of one INT8 tile
+  constexpr int NBF = 2 * TILE / 16 / 256;    // same for the bf16 dO tile
+  v4i ra_qf[NI8], ra_do[NBF], rb_qt[NI8], rb_dot[NI8];
+  float ra_l = 0.f;
+  v4f rb_muq = {0.f, 0.f, 0.f, 0.f};
+  auto load_a = [&](int i) {
+    const size_t toff = head + (size_t)i * TILE;
 #pragma unroll
-      for (int c = 0; c < TILE / 16 / 256; c++) {
-        const int idx = (tid + 256 * c) * 16;
-        *(v4i*)(s_qf + idx) = *(const v4i*)(args.QF + toff + idx);
-        *(v4i*)(s_qt + idx) = *(const v4i*)(args.QT + toff + idx);
-        *(v4i*)(s_dot + idx) = *(const v4i*)(args.dOT + toff + idx);
-      }
-      // bf16 dO rows -> A fragments (32-row block, 16-channel step), lane = row + 32*(channel half);
-      // the slot inside a fragment is XOR-swizzled with the step so these stores spread over banks
-      const unsigned short* src = args.dO + head + (size_t)i * 64 * D;
+    for (int c = 0; c < NI8; c++) ra_qf[c] = *(const v4i*)(args.QF + toff + (tid + 256 * c) * 16);
+    const unsigned short* src = args.dO + head + (size_t)i * 64 * D;
 #pragma unroll
-      for (int c = 0; c < 2 * TILE / 16 / 256; c++) {
-        const int cidx = tid + 256 * c;
-        const int row = cidx / (D / 8), ch = cidx % (D / 8);
-        const int s = ch >> 1, hh = ch & 1;
-        const int slot_ = ((row & 31) + 32 * hh) ^ (s & 7);
-        *(v4i*)(s_dof + (((row >> 5) * KB + s) * 64 + slot_) * 16) = *(const v4i*)(src + (size_t)row * D + ch * 8);
-      }
-      if (tid < 64) s_l[tid] = args.LSE[(size_t)bh * N + 64 * i + tid] * kLog2e;
-      else if (tid < 128) s_dl[tid - 64] = args.delta[(size_t)bh * N + 64 * i + tid - 64];
-      if (QSMOOTH && tid >= 128 && tid < 128 + D / 4)
-        *(v4f*)(s_muq + 4 * (tid - 128)) = *(const v4f*)(args.muQ + ((size_t)bh * nblk + i) * D + 4 * (tid - 128));
+    for (int c = 0; c < NBF; c++) {
+      const int cidx = tid + 256 * c;
+      ra_do[c] = *(const v4i*)(src + (size_t)(cidx / (D / 8)) * D + (cidx % (D / 8)) * 8);
     }
-    __syncthreads();
+    if (tid < 64) ra_l = args.LSE[(size_t)bh * N + 64 * i + tid] * kLog2e;
+    else if (tid < 128) ra_l = args.delta[(size_t)bh * N + 64 * i + tid - 64];
+  };
+  auto store_a = [&]() {
+#pragma unroll
+    for (int c = 0; c < NI8; c++) *(v4i*)(s_qf + (tid + 256 * c) * 16) = ra_qf[c];
+    // bf16 dO rows -> A fragments (32-row block, 16-channel step), lane = row + 32*(channel half);
+    // the slot inside a fragment is XOR-swizzled with the step so these stores spread over banks
+#pragma unroll
+    for (int c = 0; c < NBF; c++) {
+      const int cidx = tid + 256 * c;
+      const int row = cidx / (D / 8), ch = cidx % (D / 8);
+      const int s = ch >> 1, hh = ch & 1;
+      const int slot_ = ((row & 31) + 32 * hh) ^ (s & 7);
+      *(v4i*)(s_dof + (((row >> 5) * KB + s) * 64 + slot_) * 16) = ra_do[c];
+    }
+    if (tid < 64) s_l[tid] = ra_l;
+    else if (tid < 128) s_dl[tid - 64] = ra_l;
+  };
+  auto load_b = [&](int i) {
+    const size_t toff = head + (size_t)i * TILE;
+#pragma unroll
+    for (int c = 0; c < NI8; c++) {
+      rb_qt[c] = *(const v4i*)(args.QT + toff + (tid + 256 * c) * 16);
+      rb_dot[c] = *(const v4i*)(args.dOT + toff + (tid + 256 * c) * 16);
+    }
+    if constexpr (QSMOOTH) {
+      if (tid < D / 4) rb_muq = *(const v4f*)(args.muQ + ((size_t)bh * nblk + i) * D + 4 * tid);
+    }
+  };
+  auto store_b = [&]() {
+#pragma unroll
+    for (int c = 0; c < NI8; c++) {
+      *(v4i*)(s_qt + (tid + 256 * c) * 16) = rb_qt[c];
+      *(v4i*)(s_dot + (tid + 256 * c) * 16) = rb_dot[c];
+    }
+    if constexpr (QSMOOTH) {
+      if (tid < D / 4) *(v4f*)(s_muq + 4 * tid) = rb_muq;
+    }
+  };
+
+  load_a(nblk - 1);
+  load_b(nblk - 1);
+  store_a();
+  store_b();
+  __syncthreads();
+
+  for (int i = nblk - 1; i >= i_first; i--) {
+    const bool has_next = i > i_first;
+    if (has_next) load_a(i - 1);
 
     // ---------------- phase A: quadrant (qb, kb) ----------------
     v16i sacc;
@@ -167,9 +205,10 @@ __global__ void __launch_bounds__(256, 2) sage_bwd_kernel(BwdArgs args) {
       dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, vfr[s], dp, 0, 0, 0);
     }
     const float sQi = args.sQ[(size_t)bh * nblk + i];
+    const float sdOi = args.sdO[(size_t)bh * nblk + i];
     const float c = sQi * sKj * args.scale_log2e;
     float bias_l = 0.f;
-    if (QSMOOTH) bias_l = args.bias[((size_t)bh * nblk + i) * N + 64 * j + 32 * kb + ll];
+    if constexpr (QSMOOTH) bias_l = args.bias[((size_t)bh * nblk + i) * N + 64 * j + 32 * kb + ll];
     const bool diag = CAUSAL && (i == j);
     float p[16], ds[16];
     float pm = 0.f, dm = 0.f, cs = 0.f;
@@ -180,15 +219,21 @@ __global__ void __launch_bounds__(256, 2) sage_bwd_kernel(BwdArgs args) {
 #pragma unroll
       for (int b = 0; b < 4; b++) {
         const int r = 4 * aa + b;
-        float x = __builtin_fmaf((float)sacc[r], c, bias_l - l4[b]);
-        float pv = __builtin_amdgcn_exp2f(x);
-        if (diag) pv = (32 * qb + 8 * aa + 4 * h + b) < (32 * kb + ll) ? 0.f : pv;
-        const float dsv = pv * (dp[r] - d4[b]);
-        p[r] = pv;
-        ds[r] = dsv;
-        pm = fmaxf(pm, pv);
-        dm = fmaxf(dm, fabsf(dsv));
-        if (QSMOOTH) cs += dsv;
+        const float x = __builtin_fmaf((float)sacc[r], c, bias_l - l4[b]);
+        p[r] = __builtin_amdgcn_exp2f(x);
+      }
+      if (diag) {
+#pragma unroll
+        for (int b = 0; b < 4; b++)
+          if ((32 * qb + 8 * aa + 4 * h + b) < (32 * kb + ll)) p[4 * aa + b] = 0.f;
+      }
+#pragma unroll
+      for (int b = 0; b < 4; b++) {
+        const int r = 4 * aa + b;
+        ds[r] = p[r] * (dp[r] - d4[b]);
+        pm = fmaxf(pm, p[r]);
+        dm = fmaxf(dm, fabsf(ds[r]));
+        if constexpr (QSMOOTH) cs += ds[r];
       }
     }
     pm = wave_max_f32(pm);
@@ -197,11 +242,13 @@ __global__ void __launch_bounds__(256, 2) sage_bwd_kernel(BwdArgs args) {
       s_red[wave][0] = pm;
       s_red[wave][1] = dm;
     }
-    if (QSMOOTH) {
+    if constexpr (QSMOOTH) {
       cs = half_swap_sum_f32(cs);
       if (h == 0) s_cs[qb][32 * kb + ll] = cs;
     }
-    __syncthreads();
+    __syncthreads();   // (1) tile maxima visible; phase A reads of the staging buffers are done
+
+    if (has_next) store_a();
     pm = fmaxf(fmaxf(s_red[0][0], s_red[1][0]), fmaxf(s_red[2][0], s_red[3][0]));
     dm = fmaxf(fmaxf(s_red[0][1], s_red[1][1]), fmaxf(s_red[2][1], s_red[3][1]));
     const float rP = pm > 0.f ? 127.0f / pm : 0.f;
@@ -230,7 +277,8 @@ __global__ void __launch_bounds__(256, 2) sage_bwd_kernel(BwdArgs args) {
       *(v4i*)(s_pb + ((qb * 2 + kb) * 64 + lane) * 16) = pf;
       *(v4i*)(s_dsb + ((qb * 2 + kb) * 64 + lane) * 16) = df;
     }
-    __syncthreads();
+    __syncthreads();   // (2) quantised tiles visible
+    if (has_next) load_b(i - 1);
 
     // psi(dS_ij) and its scale go to the scratch buffer for the dQ kernel
     {
@@ -240,7 +288,7 @@ __global__ void __launch_bounds__(256, 2) sage_bwd_kernel(BwdArgs args) {
     }
 
     // ---------------- phase B: channel block cb ----------------
-    const float w_dv = sP * args.sdO[(size_t)bh * nblk + i];
+    const float w_dv = sP * sdOi;
     const float w_dk = sS * sQi * args.sm_scale;
 #pragma unroll
     for (int t = 0; t < NPB; t++) {
@@ -276,6 +324,8 @@ __global__ void __launch_bounds__(256, 2) sage_bwd_kernel(BwdArgs args) {
         }
       }
     }
+    __syncthreads();   // (3) phase B reads done: the phase-B staging and exchange buffers are free
+    if (has_next) store_b();
   }
 
   // ---- write dV, dK (bf16) ----

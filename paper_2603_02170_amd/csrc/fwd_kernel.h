@@ -43,6 +43,128 @@ constexpr float kTau = 8.0f;
 constexpr float kLog2_127 = 6.98868468677216585f;
 constexpr float kLn2 = 0.69314718055994531f;
 
+// One KV tile for one wave.  MASK = the tile straddles the causal diagonal for this wave
+// (a separate instantiation so the full tiles carry no masking code).
+template <int D, bool QSMOOTH, bool MASK>
+__device__ __forceinline__ void fwd_tile(const int8_t* __restrict__ Kt, const int8_t* __restrict__ Vt,
+                                         const v4i (&qf)[D / 32], v16f (&oacc)[D / 32], float& m_ref,
+                                         float& l_part, const float c, const float sv,
+                                         const float* __restrict__ bias_row, const int k0, const int q,
+                                         const int lane, const int h) {
+  constexpr int KS = D / 32;
+  // ---- S^T = K^ Q^^T : two 32-key blocks, interleaved so consecutive MFMAs are independent ----
+  v16i sacc[2];
+#pragma unroll
+  for (int kb = 0; kb < 2; kb++)
+#pragma unroll
+    for (int r = 0; r < 16; r++) sacc[kb][r] = 0;
+#pragma unroll
+  for (int s = 0; s < KS; s++) {
+#pragma unroll
+    for (int kb = 0; kb < 2; kb++) {
+      const v4i a = *(const v4i*)(Kt + (kb * KS + s) * 1024 + lane * 16);
+      sacc[kb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, qf[s], sacc[kb], 0, 0, 0);
+    }
+  }
+  float x[2][16];
+  float mloc;   // row max of the tile in the log2 domain
+  if constexpr (!QSMOOTH) {
+    // the scale is one positive scalar per tile, so the row max can be taken on the integers
+    int mi = INT_MIN;
+#pragma unroll
+    for (int kb = 0; kb < 2; kb++)
+#pragma unroll
+      for (int r = 0; r < 16; r++) {
+        int v = sacc[kb][r];
+        if constexpr (MASK) {
+          const int key = k0 + 32 * kb + 8 * (r >> 2) + 4 * h + (r & 3);
+          v = key > q ? INT_MIN : v;
+          sacc[kb][r] = v;
+        }
+        mi = max(mi, v);
+      }
+    mi = half_swap_max_i32(mi);
+    mloc = (float)mi * c;
+    const float off = kLog2_127 - mloc;
+#pragma unroll
+    for (int kb = 0; kb < 2; kb++)
+#pragma unroll
+      for (int r = 0; r < 16; r++) {
+        float v = __builtin_fmaf((float)sacc[kb][r], c, off);
+        if constexpr (MASK) v = sacc[kb][r] == INT_MIN ? -INFINITY : v;
+        x[kb][r] = v;
+      }
+  } else {
+    float mf = -INFINITY;
+#pragma unroll
+    for (int kb = 0; kb < 2; kb++)
+#pragma unroll
+      for (int aa = 0; aa < 4; aa++) {
+        const int key = k0 + 32 * kb + 8 * aa + 4 * h;
+        const v4f b4 = *(const v4f*)(bias_row + key);
+#pragma unroll
+        for (int b = 0; b < 4; b++) {
+          float v = __builtin_fmaf((float)sacc[kb][4 * aa + b], c, b4[b]);
+          if constexpr (MASK) v = (key + b) > q ? -INFINITY : v;
+          x[kb][4 * aa + b] = v;
+          mf = fmaxf(mf, v);
+        }
+      }
+    mloc = half_swap_max_f32(mf);
+    const float off = kLog2_127 - mloc;
+#pragma unroll
+    for (int kb = 0; kb < 2; kb++)
+#pragma unroll
+      for (int r = 0; r < 16; r++) x[kb][r] = x[kb][r] + off;
+  }
+  // ---- online softmax reference ----
+  if (__builtin_amdgcn_ballot_w64(mloc > m_ref + kTau) != 0) {
+    const float m_new = fmaxf(m_ref, mloc);
+    const float alpha = __builtin_amdgcn_exp2f(m_ref - m_new);   // 0 on the first tile
+    l_part *= alpha;
+#pragma unroll
+    for (int cb = 0; cb < KS; cb++)
+#pragma unroll
+      for (int r = 0; r < 16; r++) oacc[cb][r] *= alpha;
+    m_ref = m_new;
+  }
+  const float beta = __builtin_amdgcn_exp2f(mloc - m_ref);
+  // ---- P^ = rne(127 exp(S - rowmax)), packed as the B operand; row sum of 127 p ----
+  v4i pf[2];
+  float psum = 0.f;
+#pragma unroll
+  for (int kb = 0; kb < 2; kb++)
+#pragma unroll
+    for (int aa = 0; aa < 4; aa++) {
+      unsigned u = 0;
+#pragma unroll
+      for (int b = 0; b < 4; b++) {
+        const float e = __builtin_amdgcn_exp2f(x[kb][4 * aa + b]);
+        psum += e;
+        u = __builtin_amdgcn_cvt_pk_u8_f32(e, b, u);
+      }
+      pf[kb][aa] = (int)u;
+    }
+  l_part = __builtin_fmaf(beta, psum, l_part);
+  const float w = beta * sv;
+  // ---- O^T += (V^^T P^^T) * w : all MFMAs first, then the conversions ----
+  v16i t[KS];
+#pragma unroll
+  for (int cb = 0; cb < KS; cb++) {
+#pragma unroll
+    for (int r = 0; r < 16; r++) t[cb][r] = 0;
+#pragma unroll
+    for (int kb = 0; kb < 2; kb++) {
+      const v4i a = *(const v4i*)(Vt + (kb * KS + cb) * 1024 + lane * 16);
+      t[cb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, pf[kb], t[cb], 0, 0, 0);
+    }
+  }
+#pragma unroll
+  for (int cb = 0; cb < KS; cb++)
+#pragma unroll
+    for (int r = 0; r < 16; r++) oacc[cb][r] = __builtin_fmaf((float)t[cb][r], w, oacc[cb][r]);
+}
+
 template <int D, bool CAUSAL, bool QSMOOTH, int NW>
 __global__ void __launch_bounds__(64 * NW, (NW == 8 ? 1 : 2)) sage_fwd_kernel(FwdArgs args) {
   constexpr int KS = D / 32;                 // k-steps of Q K^T; also channel blocks of O
@@ -126,115 +248,11 @@ __global__ void __launch_bounds__(64 * NW, (NW == 8 ? 1 : 2)) sage_fwd_kernel(Fw
     if (active) {
       const int8_t* Kt = &lds[buf][0];
       const int8_t* Vt = &lds[buf][TILE_BYTES];
-      // ---- S^T = K^ Q^^T : two 32-key blocks ----
-      v16i sacc[2];
-#pragma unroll
-      for (int kb = 0; kb < 2; kb++) {
-#pragma unroll
-        for (int r = 0; r < 16; r++) sacc[kb][r] = 0;
-#pragma unroll
-        for (int s = 0; s < KS; s++) {
-          v4i a = *(const v4i*)(Kt + (kb * KS + s) * 1024 + lane * 16);
-          sacc[kb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, qf[s], sacc[kb], 0, 0, 0);
-        }
-      }
       const float c = cq * sKh[j];
+      const float sv = sVh[j];
       const bool diag = CAUSAL && (k0 + 63 > q0);   // some key of the tile may exceed some query
-      float x[2][16];
-      float mloc;   // row max of the tile in the log2 domain
-      if (!QSMOOTH) {
-        // scale is one positive scalar per tile, so the row max can be taken on the integers
-        int mi = INT_MIN;
-#pragma unroll
-        for (int kb = 0; kb < 2; kb++)
-#pragma unroll
-          for (int r = 0; r < 16; r++) {
-            int v = sacc[kb][r];
-            if (diag) {
-              const int key = k0 + 32 * kb + 8 * (r >> 2) + 4 * h + (r & 3);
-              v = key > q ? INT_MIN : v;
-              sacc[kb][r] = v;
-            }
-            mi = max(mi, v);
-          }
-        mi = half_swap_max_i32(mi);
-        mloc = (float)mi * c;
-        const float off = kLog2_127 - mloc;
-#pragma unroll
-        for (int kb = 0; kb < 2; kb++)
-#pragma unroll
-          for (int r = 0; r < 16; r++) {
-            float v = __builtin_fmaf((float)sacc[kb][r], c, off);
-            if (diag) v = sacc[kb][r] == INT_MIN ? -INFINITY : v;
-            x[kb][r] = v;
-          }
-      } else {
-        float mf = -INFINITY;
-#pragma unroll
-        for (int kb = 0; kb < 2; kb++)
-#pragma unroll
-          for (int aa = 0; aa < 4; aa++) {
-            const int key = k0 + 32 * kb + 8 * aa + 4 * h;
-            const v4f b4 = *(const v4f*)(bias_row + key);
-#pragma unroll
-            for (int b = 0; b < 4; b++) {
-              float v = __builtin_fmaf((float)sacc[kb][4 * aa + b], c, b4[b]);
-              if (diag) v = (key + b) > q ? -INFINITY : v;
-              x[kb][4 * aa + b] = v;
-              mf = fmaxf(mf, v);
-            }
-          }
-        mloc = half_swap_max_f32(mf);
-        const float off = kLog2_127 - mloc;
-#pragma unroll
-        for (int kb = 0; kb < 2; kb++)
-#pragma unroll
-          for (int r = 0; r < 16; r++) x[kb][r] = x[kb][r] + off;
-      }
-      // ---- online softmax reference ----
-      if (__builtin_amdgcn_ballot_w64(mloc > m_ref + kTau) != 0) {
-        const float m_new = fmaxf(m_ref, mloc);
-        const float alpha = __builtin_amdgcn_exp2f(m_ref - m_new);   // 0 on the first tile
-        l_part *= alpha;
-#pragma unroll
-        for (int cb = 0; cb < KS; cb++)
-#pragma unroll
-          for (int r = 0; r < 16; r++) oacc[cb][r] *= alpha;
-        m_ref = m_new;
-      }
-      const float beta = __builtin_amdgcn_exp2f(mloc - m_ref);
-      // ---- P^ = rne(127 exp(S - rowmax)), packed as the B operand; row sum of 127 p ----
-      v4i pf[2];
-      float psum = 0.f;
-#pragma unroll
-      for (int kb = 0; kb < 2; kb++)
-#pragma unroll
-        for (int aa = 0; aa < 4; aa++) {
-          unsigned u = 0;
-#pragma unroll
-          for (int b = 0; b < 4; b++) {
-            const float e = __builtin_amdgcn_exp2f(x[kb][4 * aa + b]);
-            psum += e;
-            u = __builtin_amdgcn_cvt_pk_u8_f32(e, b, u);
-          }
-          pf[kb][aa] = (int)u;
-        }
-      l_part = __builtin_fmaf(beta, psum, l_part);
-      const float w = beta * sVh[j];
-      // ---- O^T += (V^^T P^^T) * w ----
-#pragma unroll
-      for (int cb = 0; cb < KS; cb++) {
-        v16i t;
-#pragma unroll
-        for (int r = 0; r < 16; r++) t[r] = 0;
-#pragma unroll
-        for (int kb = 0; kb < 2; kb++) {
-          v4i a = *(const v4i*)(Vt + (kb * KS + cb) * 1024 + lane * 16);
-          t = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, pf[kb], t, 0, 0, 0);
-        }
-#pragma unroll
-        for (int r = 0; r < 16; r++) oacc[cb][r] = __builtin_fmaf((float)t[r], w, oacc[cb][r]);
-      }
+      if (diag) fwd_tile<D, QSMOOTH, true>(Kt, Vt, qf, oacc, m_ref, l_part, c, sv, bias_row, k0, q, lane, h);
+      else fwd_tile<D, QSMOOTH, false>(Kt, Vt, qf, oacc, m_ref, l_part, c, sv, bias_row, k0, q, lane, h);
     }
 
     if (j + 1 < n_tiles) {
