@@ -28,6 +28,7 @@ def build(verbose: bool = True) -> str:
         "-I", os.path.join(ROOT, "include"), "-I", os.path.join(HERE, "csrc"),
         src, "-o", LIB,
     ]
+    cmd[1:1] = os.environ.get("SAGEBWD_EXTRA_CFLAGS", "").split()   # e.g. -DNAME for kernel experiments
     if verbose:
         print(" ".join(cmd), flush=True)
     res = subprocess.run(cmd, capture_output=True, text=True)

@@ -1,7 +1,9 @@
 // Fused INT8 attention backward (paper Algorithm 2) for gfx950.
 //
-// A workgroup of 4 waves owns one KV block j (64 keys) and walks the Q blocks i.  Per
-// (i, j) tile:
+// sage_bwd_kernel: a workgroup of 8 waves owns two adjacent KV blocks (one per group of 4
+// waves) and walks the Q blocks i from the last one down.  The operands of Q block i - 1 are
+// copied global -> LDS asynchronously (LDS-DMA loads) into the second half of a double buffer
+// while block i is processed.  Per (i, j) tile and group:
 //   phase A  each wave takes one 32x32 quadrant (qb, kb) of the tile:
 //            S = Q^ K^^T on INT8 MFMA, dP = dO V^T on bf16 MFMA (the one unquantised matmul),
 //            P = exp(S - L), dS = P o (dP - delta); tile-wide max P and max |dS| are exchanged
@@ -36,7 +38,7 @@ struct BwdArgs {
   const float* sQ;
   const float* sK;
   const float* sdO;
-  const float* LSE;    // [BH, N]
+  const float* nL2;    // [BH, N]  -LSE * log2(e)
   const float* delta;  // [BH, N]
   const float* bias;   // Q-smoothing logit bias [BH, N/64, N] (log2 domain) or nullptr
   const float* muQ;    // Q-smoothing block means [BH, N/64, D] or nullptr
@@ -53,58 +55,129 @@ struct BwdArgs {
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kRoundMagic = 12582912.0f;   // 1.5 * 2^23: x + magic has rne(x) in its low mantissa bits
 
+typedef const __attribute__((address_space(1))) void* gptr_t;
+typedef __attribute__((address_space(3))) void* lptr_t;
+
+// One 16-byte piece per lane, global -> LDS, no registers in between.  The LDS address is
+// `lds_base + lane * 16` (the hardware adds the lane offset to the wave-uniform base).
+__device__ __forceinline__ void async_copy_16(const void* gsrc_lane, void* lds_base) {
+  __builtin_amdgcn_global_load_lds((gptr_t)gsrc_lane, (lptr_t)lds_base, 16, 0, 0);
+}
+__device__ __forceinline__ void async_copy_4(const void* gsrc_lane, void* lds_base) {
+  __builtin_amdgcn_global_load_lds((gptr_t)gsrc_lane, (lptr_t)lds_base, 4, 0, 0);
+}
+
+template <int D>
+struct BwdStage {             // operands of one Q block
+  int8_t qf[64 * D];          // Q^  F fragments
+  int8_t qt[64 * D];          // Q^  TF fragments
+  int8_t dot[64 * D];         // dO^ TF fragments
+  int8_t dof[128 * D];        // bf16 dO as A fragments (32-row block, 16-channel step), XOR-swizzled slots
+  float nl2[64];              // -L * log2(e)
+  float dl[64];               // delta
+  float muq[D];               // Q-smoothing block mean
+  float bias[128];            // Q-smoothing logit bias of this Q block for the workgroup's 128 keys
+  float sc[4];                // s_Q[i], s_dO[i]
+};
+struct BwdExchange {          // per group of 4 waves
+  int8_t pb[4096];            // psi(P)  B fragments (q step, key block)
+  int8_t dsb[4096];           // psi(dS) B fragments
+  int8_t dst[4096];           // psi(dS) A fragments (q block, key step)
+  float red[4][2];
+  float cs[2][64];            // Q-smoothing: column sums of dS
+};
+
+// Workgroup barrier that waits for this wave's LDS traffic only.  (__syncthreads() would
+// also drain the asynchronous global->LDS copies that are meant to stay in flight.)
+__device__ __forceinline__ void barrier_lds_only() {
+  asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+// Same, after all of this wave's global-memory operations (the async copies included).
+__device__ __forceinline__ void barrier_all_memory() {
+  __builtin_amdgcn_s_waitcnt(0x0f70);   // vmcnt(0), as a builtin so the compiler's own wait tracking sees it
+  asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
+// phase A element-wise work of one quadrant; MASK = the tile is on the causal diagonal
+template <bool MASK, bool QSMOOTH>
+__device__ __forceinline__ void bwd_quadrant(const v16i& sacc, const v16f& dp, const float* __restrict__ nl2,
+                                             const float* __restrict__ dl, const float c, const float bias_l,
+                                             const int qrow0, const int kcol, float (&p)[16], float (&ds)[16],
+                                             float& pm, float& dm, float& cs) {
+  pm = 0.f;
+  dm = 0.f;
+  cs = 0.f;
+#pragma unroll
+  for (int aa = 0; aa < 4; aa++) {
+    const v4f l4 = *(const v4f*)(nl2 + 8 * aa);
+    const v4f d4 = *(const v4f*)(dl + 8 * aa);
+#pragma unroll
+    for (int b = 0; b < 4; b++) {
+      const int r = 4 * aa + b;
+      const float off = QSMOOTH ? bias_l + l4[b] : l4[b];
+      float pv = __builtin_amdgcn_exp2f(__builtin_fmaf((float)sacc[r], c, off));
+      if constexpr (MASK) pv = (qrow0 + 8 * aa + b) < kcol ? 0.f : pv;
+      const float dsv = pv * (dp[r] - d4[b]);
+      p[r] = pv;
+      ds[r] = dsv;
+      pm = fmaxf(pm, pv);
+      dm = fmaxf(dm, fabsf(dsv));
+      if constexpr (QSMOOTH) cs += dsv;
+    }
+  }
+}
+
 template <int D, bool CAUSAL, bool QSMOOTH>
-__global__ void __launch_bounds__(256, 2) sage_bwd_kernel(BwdArgs args) {
+__global__ void __launch_bounds__(512, 1) sage_bwd_kernel(BwdArgs args) {
   constexpr int KS = D / 32;     // INT8 k-steps over d; channel blocks
   constexpr int KB = D / 16;     // bf16 k-steps over d
   constexpr int NPB = KS / 2;    // 32-row blocks per wave in phase B (2 for D=128, 1 for D=64)
   constexpr int TILE = 64 * D;   // bytes of one INT8 tile
+  constexpr int NF = TILE / 1024;  // 1 KiB fragments per INT8 tile
 
-  __shared__ __attribute__((aligned(16))) int8_t s_qf[TILE];
-  __shared__ __attribute__((aligned(16))) int8_t s_qt[TILE];
-  __shared__ __attribute__((aligned(16))) int8_t s_dot[TILE];
-  __shared__ __attribute__((aligned(16))) int8_t s_dof[2 * TILE];   // bf16 dO as A fragments
-  __shared__ __attribute__((aligned(16))) float s_l[64];            // L * log2(e)
-  __shared__ __attribute__((aligned(16))) float s_dl[64];           // delta
-  __shared__ __attribute__((aligned(16))) int8_t s_pb[4096];        // psi(P)  B fragments (q step, key block)
-  __shared__ __attribute__((aligned(16))) int8_t s_dsb[4096];       // psi(dS) B fragments
-  __shared__ __attribute__((aligned(16))) int8_t s_dst[4096];       // psi(dS) A fragments (q block, key step)
-  __shared__ float s_red[4][2];
-  __shared__ float s_cs[2][64];                                     // Q-smoothing: column sums of dS
-  __shared__ __attribute__((aligned(16))) float s_muq[D];
+  __shared__ __attribute__((aligned(16))) BwdStage<D> stage0;
+  __shared__ __attribute__((aligned(16))) BwdStage<D> stage1;
+  __shared__ __attribute__((aligned(16))) BwdExchange xch[2];
 
-  const int g = blockIdx.x;
-  const int xcd = g & 7, slot = g >> 3;
+  const int gidx = blockIdx.x;
+  const int xcd = gidx & 7, slot = gidx >> 3;
   const int N = args.N;
   const int nblk = N / kBlock;
-  const int hl = xcd + 8 * (slot / nblk);   // head within this launch
+  const int npair = (nblk + 1) / 2;
+  const int hl = xcd + 8 * (slot / npair);   // head within this launch
   if (hl >= args.BH) return;
   const int bh = args.bh0 + hl;
-  const int j = slot % nblk;          // small j = most Q blocks under the causal mask: scheduled first
+  const int jp = slot % npair;        // small jp = most Q blocks under the causal mask: scheduled first
 
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
+  const int grp = wave >> 2, w4 = wave & 3, gtid = tid & 255;
   const int ll = lane & 31, h = lane >> 5;
-  const int qb = wave >> 1, kb = wave & 1;                 // phase A quadrant
-  const int cb = (D == 128) ? wave : (wave & 1);           // phase B channel block
-  const int blk0 = (D == 128) ? 0 : (wave >> 1);           // phase B first 32-row block
+  const int qb = w4 >> 1, kb = w4 & 1;                     // phase A quadrant
+  const int cb = (D == 128) ? w4 : (w4 & 1);               // phase B channel block
+  const int blk0 = (D == 128) ? 0 : (w4 >> 1);             // phase B first 32-row block
+  const int j = 2 * jp + grp;
+  const bool gvalid = j < nblk;
+  const int jc = gvalid ? j : nblk - 1;                    // clamped: an idle group still loads in bounds
 
   const size_t head = (size_t)bh * N * D;
-  const float sKj = args.sK[(size_t)bh * nblk + j];
+  const float sKj = args.sK[(size_t)bh * nblk + jc];
+  BwdExchange& X = xch[grp];
 
   // ---- operands that stay in registers for the whole loop ----
   v4i kfr[KS];
   {
-    const int8_t* p = args.KF + head + ((size_t)(2 * j + kb) * KS) * 1024 + lane * 16;
+    const int8_t* p = args.KF + head + ((size_t)(2 * jc + kb) * KS) * 1024 + lane * 16;
 #pragma unroll
     for (int s = 0; s < KS; s++) kfr[s] = *(const v4i*)(p + s * 1024);
   }
   v8bf vfr[KB];
   {
-    const unsigned short* p = args.V + head + (size_t)(64 * j + 32 * kb + ll) * D + 8 * h;
+    const unsigned short* p = args.V + head + (size_t)(64 * jc + 32 * kb + ll) * D + 8 * h;
 #pragma unroll
     for (int s = 0; s < KB; s++) vfr[s] = *(const v8bf*)(p + 16 * s);
   }
+
   v16f dvacc[NPB], dkacc[NPB], dkbias[QSMOOTH ? NPB : 1];
 #pragma unroll
   for (int t = 0; t < NPB; t++)
@@ -115,149 +188,112 @@ __global__ void __launch_bounds__(256, 2) sage_bwd_kernel(BwdArgs args) {
       if constexpr (QSMOOTH) dkbias[t][r] = 0.f;
     }
 
-  const int i_first = CAUSAL ? j : 0;
+  const int i_first = CAUSAL ? 2 * jp : 0;
   // slot of key kappa = lane%32 inside a TF-ordered 32-key step: kappa = 8a + 4h' + b -> (h', 4a + b)
   const int tk_h = (ll >> 2) & 1, tk_t = 4 * (ll >> 3) + (ll & 3);
 
-  // Staging of one Q block through registers.  Set A feeds phase A (Q^ row fragments, bf16 dO
-  // fragments, L, delta), set B feeds phase B (Q^ and dO^ transposed fragments, mu_Q).
-  constexpr int NI8 = TILE / 16 / 256;        // 16-byte pieces per thread of one INT8 tile
-  constexpr int NBF = 2 * TILE / 16 / 256;    // same for the bf16 dO tile
-  v4i ra_qf[NI8], ra_do[NBF], rb_qt[NI8], rb_dot[NI8];
-  float ra_l = 0.f;
-  v4f rb_muq = {0.f, 0.f, 0.f, 0.f};
-  auto load_a = [&](int i) {
+  // Asynchronous staging of Q block i into `st`: 5*NF one-KiB fragment copies (plus L, delta,
+  // mu_Q) dealt round-robin to the 8 waves.
+  auto stage_load = [&](int i, BwdStage<D>& st) {
     const size_t toff = head + (size_t)i * TILE;
 #pragma unroll
-    for (int c = 0; c < NI8; c++) ra_qf[c] = *(const v4i*)(args.QF + toff + (tid + 256 * c) * 16);
-    const unsigned short* src = args.dO + head + (size_t)i * 64 * D;
-#pragma unroll
-    for (int c = 0; c < NBF; c++) {
-      const int cidx = tid + 256 * c;
-      ra_do[c] = *(const v4i*)(src + (size_t)(cidx / (D / 8)) * D + (cidx % (D / 8)) * 8);
+    for (int k = 0; k < (5 * NF + 7) / 8; k++) {
+      const int o = wave + 8 * k;            // wave-uniform
+      if (o < NF) {
+        async_copy_16(args.QF + toff + o * 1024 + lane * 16, st.qf + o * 1024);
+      } else if (o < 2 * NF) {
+        async_copy_16(args.QT + toff + (o - NF) * 1024 + lane * 16, st.qt + (o - NF) * 1024);
+      } else if (o < 3 * NF) {
+        async_copy_16(args.dOT + toff + (o - 2 * NF) * 1024 + lane * 16, st.dot + (o - 2 * NF) * 1024);
+      } else if (o < 5 * NF) {
+        // bf16 dO fragment f = (32-row block, 16-channel step s); LDS slot l holds the piece of
+        // (row, channel half) = (l ^ (s & 7)) so that the A-operand reads stay conflict-free
+        const int f = o - 3 * NF;
+        const int rb = f / KB, sst = f % KB;
+        const int orig = lane ^ (sst & 7);
+        const int row = 32 * rb + (orig & 31), hh = orig >> 5;
+        async_copy_16(args.dO + head + (size_t)(64 * i + row) * D + 16 * sst + 8 * hh, st.dof + f * 1024);
+      }
     }
-    if (tid < 64) ra_l = args.LSE[(size_t)bh * N + 64 * i + tid] * kLog2e;
-    else if (tid < 128) ra_l = args.delta[(size_t)bh * N + 64 * i + tid - 64];
-  };
-  auto store_a = [&]() {
-#pragma unroll
-    for (int c = 0; c < NI8; c++) *(v4i*)(s_qf + (tid + 256 * c) * 16) = ra_qf[c];
-    // bf16 dO rows -> A fragments (32-row block, 16-channel step), lane = row + 32*(channel half);
-    // the slot inside a fragment is XOR-swizzled with the step so these stores spread over banks
-#pragma unroll
-    for (int c = 0; c < NBF; c++) {
-      const int cidx = tid + 256 * c;
-      const int row = cidx / (D / 8), ch = cidx % (D / 8);
-      const int s = ch >> 1, hh = ch & 1;
-      const int slot_ = ((row & 31) + 32 * hh) ^ (s & 7);
-      *(v4i*)(s_dof + (((row >> 5) * KB + s) * 64 + slot_) * 16) = ra_do[c];
-    }
-    if (tid < 64) s_l[tid] = ra_l;
-    else if (tid < 128) s_dl[tid - 64] = ra_l;
-  };
-  auto load_b = [&](int i) {
-    const size_t toff = head + (size_t)i * TILE;
-#pragma unroll
-    for (int c = 0; c < NI8; c++) {
-      rb_qt[c] = *(const v4i*)(args.QT + toff + (tid + 256 * c) * 16);
-      rb_dot[c] = *(const v4i*)(args.dOT + toff + (tid + 256 * c) * 16);
-    }
+    if (wave == 0) async_copy_4(args.nL2 + (size_t)bh * N + 64 * i + lane, st.nl2);
+    if (wave == 1) async_copy_4(args.delta + (size_t)bh * N + 64 * i + lane, st.dl);
+    if (wave == 2 && lane < 2)
+      async_copy_4((lane == 0 ? args.sQ : args.sdO) + (size_t)bh * nblk + i, st.sc);
     if constexpr (QSMOOTH) {
-      if (tid < D / 4) rb_muq = *(const v4f*)(args.muQ + ((size_t)bh * nblk + i) * D + 4 * tid);
-    }
-  };
-  auto store_b = [&]() {
-#pragma unroll
-    for (int c = 0; c < NI8; c++) {
-      *(v4i*)(s_qt + (tid + 256 * c) * 16) = rb_qt[c];
-      *(v4i*)(s_dot + (tid + 256 * c) * 16) = rb_dot[c];
-    }
-    if constexpr (QSMOOTH) {
-      if (tid < D / 4) *(v4f*)(s_muq + 4 * tid) = rb_muq;
+      if (wave == 3) async_copy_4(args.muQ + ((size_t)bh * nblk + i) * D + lane, st.muq);
+      if (D == 128 && wave == 4) async_copy_4(args.muQ + ((size_t)bh * nblk + i) * D + 64 + lane, st.muq + 64);
+      const float* brow = args.bias + ((size_t)bh * nblk + i) * N + 128 * jp;
+      if (wave == 5) async_copy_4(brow + lane, st.bias);
+      if (wave == 6 && 2 * jp + 1 < nblk) async_copy_4(brow + 64 + lane, st.bias + 64);
     }
   };
 
-  load_a(nblk - 1);
-  load_b(nblk - 1);
-  store_a();
-  store_b();
-  __syncthreads();
+  stage_load(nblk - 1, stage0);
+  barrier_all_memory();
 
-  for (int i = nblk - 1; i >= i_first; i--) {
-    const bool has_next = i > i_first;
-    if (has_next) load_a(i - 1);
+  // One tile row.  `st` holds Q block i; `nx` receives Q block i - 1 meanwhile.  The two are
+  // passed as distinct objects (the loop below alternates them explicitly) so that reads of
+  // `st` are never ordered behind the copies into `nx`.
+  auto tile_row = [&](const int i, BwdStage<D>& st, BwdStage<D>& nx) __attribute__((always_inline)) {
+    if (i > i_first) stage_load(i - 1, nx);
+    const bool active = gvalid && (!CAUSAL || i >= j);
 
-    // ---------------- phase A: quadrant (qb, kb) ----------------
-    v16i sacc;
-#pragma unroll
-    for (int r = 0; r < 16; r++) sacc[r] = 0;
-#pragma unroll
-    for (int s = 0; s < KS; s++) {
-      v4i a = *(const v4i*)(s_qf + ((qb * KS + s) * 64 + lane) * 16);
-      sacc = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, kfr[s], sacc, 0, 0, 0);
-    }
-    v16f dp;
-#pragma unroll
-    for (int r = 0; r < 16; r++) dp[r] = 0.f;
-#pragma unroll
-    for (int s = 0; s < KB; s++) {
-      v8bf a = *(const v8bf*)(s_dof + ((qb * KB + s) * 64 + (lane ^ (s & 7))) * 16);
-      dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, vfr[s], dp, 0, 0, 0);
-    }
-    const float sQi = args.sQ[(size_t)bh * nblk + i];
-    const float sdOi = args.sdO[(size_t)bh * nblk + i];
-    const float c = sQi * sKj * args.scale_log2e;
-    float bias_l = 0.f;
-    if constexpr (QSMOOTH) bias_l = args.bias[((size_t)bh * nblk + i) * N + 64 * j + 32 * kb + ll];
-    const bool diag = CAUSAL && (i == j);
     float p[16], ds[16];
     float pm = 0.f, dm = 0.f, cs = 0.f;
+    float sQi = 0.f, sdOi = 0.f;
+    if (active) {
+      // ---------------- phase A: quadrant (qb, kb) ----------------
+      v16i sacc;
 #pragma unroll
-    for (int aa = 0; aa < 4; aa++) {
-      const v4f l4 = *(const v4f*)(s_l + 32 * qb + 8 * aa + 4 * h);
-      const v4f d4 = *(const v4f*)(s_dl + 32 * qb + 8 * aa + 4 * h);
+      for (int r = 0; r < 16; r++) sacc[r] = 0;
 #pragma unroll
-      for (int b = 0; b < 4; b++) {
-        const int r = 4 * aa + b;
-        const float x = __builtin_fmaf((float)sacc[r], c, bias_l - l4[b]);
-        p[r] = __builtin_amdgcn_exp2f(x);
+      for (int s = 0; s < KS; s++) {
+        v4i a = *(const v4i*)(st.qf + ((qb * KS + s) * 64 + lane) * 16);
+        sacc = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, kfr[s], sacc, 0, 0, 0);
       }
-      if (diag) {
+      v16f dp;
 #pragma unroll
-        for (int b = 0; b < 4; b++)
-          if ((32 * qb + 8 * aa + 4 * h + b) < (32 * kb + ll)) p[4 * aa + b] = 0.f;
+      for (int r = 0; r < 16; r++) dp[r] = 0.f;
+#pragma unroll
+      for (int s = 0; s < KB; s++) {
+        v8bf a = *(const v8bf*)(st.dof + ((qb * KB + s) * 64 + (lane ^ (s & 7))) * 16);
+        dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, vfr[s], dp, 0, 0, 0);
       }
-#pragma unroll
-      for (int b = 0; b < 4; b++) {
-        const int r = 4 * aa + b;
-        ds[r] = p[r] * (dp[r] - d4[b]);
-        pm = fmaxf(pm, p[r]);
-        dm = fmaxf(dm, fabsf(ds[r]));
-        if constexpr (QSMOOTH) cs += ds[r];
+      sQi = st.sc[0];
+      sdOi = st.sc[1];
+      const float c = sQi * sKj * args.scale_log2e;
+      float bias_l = 0.f;
+      if constexpr (QSMOOTH) bias_l = st.bias[64 * grp + 32 * kb + ll];
+      const float* nl2 = st.nl2 + 32 * qb + 4 * h;
+      const float* dl = st.dl + 32 * qb + 4 * h;
+      if (CAUSAL && i == j)
+        bwd_quadrant<true, QSMOOTH>(sacc, dp, nl2, dl, c, bias_l, 32 * qb + 4 * h, 32 * kb + ll, p, ds, pm, dm, cs);
+      else
+        bwd_quadrant<false, QSMOOTH>(sacc, dp, nl2, dl, c, bias_l, 0, 0, p, ds, pm, dm, cs);
+      pm = wave_max_nonneg_f32(pm);
+      dm = wave_max_nonneg_f32(dm);
+      if (lane == 0) {
+        X.red[w4][0] = pm;
+        X.red[w4][1] = dm;
+      }
+      if constexpr (QSMOOTH) {
+        cs = half_swap_sum_f32(cs);
+        if (h == 0) X.cs[qb][32 * kb + ll] = cs;
       }
     }
-    pm = wave_max_f32(pm);
-    dm = wave_max_f32(dm);
-    if (lane == 0) {
-      s_red[wave][0] = pm;
-      s_red[wave][1] = dm;
-    }
-    if constexpr (QSMOOTH) {
-      cs = half_swap_sum_f32(cs);
-      if (h == 0) s_cs[qb][32 * kb + ll] = cs;
-    }
-    __syncthreads();   // (1) tile maxima visible; phase A reads of the staging buffers are done
+    barrier_lds_only();   // (1) tile maxima visible
 
-    if (has_next) store_a();
-    pm = fmaxf(fmaxf(s_red[0][0], s_red[1][0]), fmaxf(s_red[2][0], s_red[3][0]));
-    dm = fmaxf(fmaxf(s_red[0][1], s_red[1][1]), fmaxf(s_red[2][1], s_red[3][1]));
-    const float rP = pm > 0.f ? 127.0f / pm : 0.f;
-    const float sP = pm / 127.0f;
-    const float rS = dm > 0.f ? 127.0f / dm : 0.f;
-    const float sS = dm / 127.0f;
-    {
+    float sP = 0.f, sS = 0.f;
+    if (active) {
+      pm = fmaxf(fmaxf(X.red[0][0], X.red[1][0]), fmaxf(X.red[2][0], X.red[3][0]));
+      dm = fmaxf(fmaxf(X.red[0][1], X.red[1][1]), fmaxf(X.red[2][1], X.red[3][1]));
+      // the per-tile scales of P and dS are internal (never stored bit-exactly): 127/a via rcp
+      const float rP = pm > 0.f ? 127.0f * __builtin_amdgcn_rcpf(pm) : 0.f;
+      const float rS = dm > 0.f ? 127.0f * __builtin_amdgcn_rcpf(dm) : 0.f;
+      sP = pm * (1.0f / 127.0f);
+      sS = dm * (1.0f / 127.0f);
       v4i pf, df;
-      int8_t* tbase = s_dst + ((qb * 2 + kb) * 64 + 32 * tk_h) * 16 + tk_t;
+      int8_t* tbase = X.dst + ((qb * 2 + kb) * 64 + 32 * tk_h) * 16 + tk_t;
 #pragma unroll
       for (int aa = 0; aa < 4; aa++) {
         unsigned up = 0;
@@ -274,59 +310,66 @@ __global__ void __launch_bounds__(256, 2) sage_bwd_kernel(BwdArgs args) {
         const unsigned hi = __builtin_amdgcn_perm(ub[3], ub[2], 0x04000c0cu);
         df[aa] = (int)(lo | hi);
       }
-      *(v4i*)(s_pb + ((qb * 2 + kb) * 64 + lane) * 16) = pf;
-      *(v4i*)(s_dsb + ((qb * 2 + kb) * 64 + lane) * 16) = df;
+      *(v4i*)(X.pb + ((qb * 2 + kb) * 64 + lane) * 16) = pf;
+      *(v4i*)(X.dsb + ((qb * 2 + kb) * 64 + lane) * 16) = df;
     }
-    __syncthreads();   // (2) quantised tiles visible
-    if (has_next) load_b(i - 1);
+    barrier_lds_only();   // (2) quantised tiles visible
 
-    // psi(dS_ij) and its scale go to the scratch buffer for the dQ kernel
-    {
-      const size_t tile = ((size_t)hl * nblk + i) * nblk + j;
-      *(v4i*)(args.dSq + tile * 4096 + tid * 16) = *(const v4i*)(s_dst + tid * 16);
-      if (tid == 0) args.sdS[tile] = sS;
-    }
-
-    // ---------------- phase B: channel block cb ----------------
-    const float w_dv = sP * sdOi;
-    const float w_dk = sS * sQi * args.sm_scale;
-#pragma unroll
-    for (int t = 0; t < NPB; t++) {
-      const int kbo = blk0 + t;
-      v16i av, ak;
-#pragma unroll
-      for (int r = 0; r < 16; r++) {
-        av[r] = 0;
-        ak[r] = 0;
+    if (active) {
+      // psi(dS_ij) and its scale go to the scratch buffer for the dQ kernel
+      {
+        const size_t tile = ((size_t)hl * nblk + i) * nblk + j;
+        *(v4i*)(args.dSq + tile * 4096 + gtid * 16) = *(const v4i*)(X.dst + gtid * 16);
+        if (gtid == 0) args.sdS[tile] = sS;
       }
+      // ---------------- phase B: channel block cb ----------------
+      const float w_dv = sP * sdOi;
+      const float w_dk = sS * sQi * args.sm_scale;
 #pragma unroll
-      for (int qs = 0; qs < 2; qs++) {
-        const v4i a1 = *(const v4i*)(s_dot + ((qs * KS + cb) * 64 + lane) * 16);
-        const v4i b1 = *(const v4i*)(s_pb + ((qs * 2 + kbo) * 64 + lane) * 16);
-        av = __builtin_amdgcn_mfma_i32_32x32x32_i8(a1, b1, av, 0, 0, 0);
-        const v4i a2 = *(const v4i*)(s_qt + ((qs * KS + cb) * 64 + lane) * 16);
-        const v4i b2 = *(const v4i*)(s_dsb + ((qs * 2 + kbo) * 64 + lane) * 16);
-        ak = __builtin_amdgcn_mfma_i32_32x32x32_i8(a2, b2, ak, 0, 0, 0);
-      }
+      for (int t = 0; t < NPB; t++) {
+        const int kbo = blk0 + t;
+        v16i av, ak;
 #pragma unroll
-      for (int r = 0; r < 16; r++) {
-        dvacc[t][r] = __builtin_fmaf((float)av[r], w_dv, dvacc[t][r]);
-        dkacc[t][r] = __builtin_fmaf((float)ak[r], w_dk, dkacc[t][r]);
-      }
-      if constexpr (QSMOOTH) {
-        // dK_bias = (dS^T 1) mu_Q^T with the unquantised column sums of this tile
-        const float csv = s_cs[0][32 * kbo + ll] + s_cs[1][32 * kbo + ll];
+        for (int r = 0; r < 16; r++) {
+          av[r] = 0;
+          ak[r] = 0;
+        }
 #pragma unroll
-        for (int aa = 0; aa < 4; aa++) {
-          const v4f m4 = *(const v4f*)(s_muq + 32 * cb + 8 * aa + 4 * h);
+        for (int qs = 0; qs < 2; qs++) {
+          const v4i a1 = *(const v4i*)(st.dot + ((qs * KS + cb) * 64 + lane) * 16);
+          const v4i b1 = *(const v4i*)(X.pb + ((qs * 2 + kbo) * 64 + lane) * 16);
+          av = __builtin_amdgcn_mfma_i32_32x32x32_i8(a1, b1, av, 0, 0, 0);
+          const v4i a2 = *(const v4i*)(st.qt + ((qs * KS + cb) * 64 + lane) * 16);
+          const v4i b2 = *(const v4i*)(X.dsb + ((qs * 2 + kbo) * 64 + lane) * 16);
+          ak = __builtin_amdgcn_mfma_i32_32x32x32_i8(a2, b2, ak, 0, 0, 0);
+        }
 #pragma unroll
-          for (int b = 0; b < 4; b++) dkbias[t][4 * aa + b] = __builtin_fmaf(csv, m4[b], dkbias[t][4 * aa + b]);
+        for (int r = 0; r < 16; r++) {
+          dvacc[t][r] = __builtin_fmaf((float)av[r], w_dv, dvacc[t][r]);
+          dkacc[t][r] = __builtin_fmaf((float)ak[r], w_dk, dkacc[t][r]);
+        }
+        if constexpr (QSMOOTH) {
+          // dK_bias = (dS^T 1) mu_Q^T with the unquantised column sums of this tile
+          const float csv = X.cs[0][32 * kbo + ll] + X.cs[1][32 * kbo + ll];
+#pragma unroll
+          for (int aa = 0; aa < 4; aa++) {
+            const v4f m4 = *(const v4f*)(st.muq + 32 * cb + 8 * aa + 4 * h);
+#pragma unroll
+            for (int b = 0; b < 4; b++) dkbias[t][4 * aa + b] = __builtin_fmaf(csv, m4[b], dkbias[t][4 * aa + b]);
+          }
         }
       }
     }
-    __syncthreads();   // (3) phase B reads done: the phase-B staging and exchange buffers are free
-    if (has_next) store_b();
+    barrier_all_memory();   // (3) next stage has landed; this tile's buffers are free
+  };
+  for (int i = nblk - 1;;) {
+    tile_row(i, stage0, stage1);
+    if (--i < i_first) break;
+    tile_row(i, stage1, stage0);
+    if (--i < i_first) break;
   }
+
+  if (!gvalid) return;
 
   // ---- write dV, dK (bf16) ----
 #pragma unroll

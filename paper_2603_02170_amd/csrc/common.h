@@ -61,11 +61,25 @@ __device__ __forceinline__ float half_swap_sum_f32(float v) {
   return __uint_as_float(r[0]) + __uint_as_float(r[1]);
 }
 
-// max over all 64 lanes (result in every lane)
-__device__ __forceinline__ float wave_max_f32(float v) {
-#pragma unroll
-  for (int off = 1; off < 32; off <<= 1) v = fmaxf(v, __shfl_xor(v, off, 64));
-  return half_swap_max_f32(v);
+// max over all 64 lanes of a NON-NEGATIVE float (result in every lane).  Non-negative floats
+// order like their bit patterns, so the reduction runs on unsigned integers: four DPP steps
+// inside each row of 16 lanes, then the row and half-wave swaps of gfx950.  No LDS traffic.
+__device__ __forceinline__ float wave_max_nonneg_f32(float v) {
+  unsigned u = __float_as_uint(v);
+  unsigned t;
+  t = (unsigned)__builtin_amdgcn_update_dpp((int)u, (int)u, 0xB1, 0xf, 0xf, false);   // quad_perm [1,0,3,2]
+  u = u > t ? u : t;
+  t = (unsigned)__builtin_amdgcn_update_dpp((int)u, (int)u, 0x4E, 0xf, 0xf, false);   // quad_perm [2,3,0,1]
+  u = u > t ? u : t;
+  t = (unsigned)__builtin_amdgcn_update_dpp((int)u, (int)u, 0x141, 0xf, 0xf, false);  // row_half_mirror
+  u = u > t ? u : t;
+  t = (unsigned)__builtin_amdgcn_update_dpp((int)u, (int)u, 0x140, 0xf, 0xf, false);  // row_mirror
+  u = u > t ? u : t;
+  auto r16 = __builtin_amdgcn_permlane16_swap(u, u, false, false);
+  u = r16[0] > r16[1] ? r16[0] : r16[1];
+  auto r32 = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+  u = r32[0] > r32[1] ? r32[0] : r32[1];
+  return __uint_as_float(u);
 }
 
 }  // namespace sage

@@ -76,6 +76,8 @@ struct QuantJob {
   float* mu_block_out;         // [BH, N/64, D]: if set, the block mean is computed, stored and subtracted
   const unsigned short* O;     // bf16 [BH, N, D] or nullptr: delta = rowsum(src o O)
   float* delta;                // [BH, N]
+  const float* lse;            // [BH, N] or nullptr: nl2 = -lse * log2(e) for the backward
+  float* nl2;                  // [BH, N]
 };
 struct QuantJobs {
   QuantJob job[4];
@@ -133,6 +135,11 @@ __global__ void __launch_bounds__(256) prepass_quant_kernel(QuantJobs jobs, int 
     }
   }
 
+  if (jb.lse != nullptr && t < 64) {
+    const size_t row = (size_t)bh * N + (size_t)blk * kBlock + t;
+    jb.nl2[row] = -jb.lse[row] * 1.4426950408889634f;
+  }
+
   if (jb.mu_head != nullptr) {
 #pragma unroll
     for (int it = 0; it < NCH; it++) {
@@ -183,7 +190,7 @@ __global__ void __launch_bounds__(256) prepass_quant_kernel(QuantJobs jobs, int 
   for (int it = 0; it < NCH; it++)
 #pragma unroll
     for (int e = 0; e < 16; e++) a = fmaxf(a, fabsf(x[it][e]));
-  a = wave_max_f32(a);
+  a = wave_max_nonneg_f32(a);
   if ((t & 63) == 0) wmax[t >> 6] = a;
   __syncthreads();
   a = fmaxf(fmaxf(wmax[0], wmax[1]), fmaxf(wmax[2], wmax[3]));

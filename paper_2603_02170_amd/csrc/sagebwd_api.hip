@@ -23,7 +23,7 @@ inline size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
 
 // Byte offsets of every buffer inside the caller's workspace.
 struct Workspace {
-  size_t kpart, muK, muQ, sQ, sK, sV, sdO, delta;
+  size_t kpart, muK, muQ, sQ, sK, sV, sdO, delta, nl2;
   size_t QF, KF, VT;        // forward operands (QF, KF also feed the backward's S recompute)
   size_t QT, KT, dOT;       // backward operands (TF layouts)
   size_t dSq;               // psi(dS) tiles of one head group [heads_per_group, N/64, N/64, 4096]
@@ -50,6 +50,7 @@ Workspace make_layout(const sagebwd_params& p) {
   w.sV = take(BH * nblk * 4);
   w.sdO = take(BH * nblk * 4);
   w.delta = take(BH * N * 4);
+  w.nl2 = take(BH * N * 4);
   w.QF = take(BH * N * d);
   w.KF = take(BH * N * d);
   w.VT = take(BH * N * d);
@@ -126,7 +127,7 @@ struct ScopedTimer {
 
 // ---- pre-pass ---------------------------------------------------------------
 template <int D>
-int run_prepass(const void* Q, const void* K, const void* V, const void* dO, const void* O,
+int run_prepass(const void* Q, const void* K, const void* V, const void* dO, const void* O, const float* LSE,
                 const sagebwd_params& p, char* ws, const Workspace& w, bool for_bwd, hipStream_t st) {
   const int BH = p.B * p.H, N = p.N, nblk = N / 64;
   const bool ks = (p.smooth & SAGEBWD_SMOOTH_K) != 0;
@@ -173,6 +174,8 @@ int run_prepass(const void* Q, const void* K, const void* V, const void* dO, con
     jobs.job[nj].scale = (float*)(ws + w.sdO);
     jobs.job[nj].O = (const unsigned short*)O;
     jobs.job[nj].delta = (float*)(ws + w.delta);
+    jobs.job[nj].lse = LSE;
+    jobs.job[nj].nl2 = (float*)(ws + w.nl2);
     nj++;
   }
   prepass_quant_kernel<D><<<dim3(nblk, BH, nj), 256, 0, st>>>(jobs, N);
@@ -215,14 +218,14 @@ int launch_fwd(const FwdArgs& a, bool causal, bool qs, hipStream_t st) {
 
 template <int D>
 int launch_bwd(const BwdArgs& a, bool causal, bool qs, hipStream_t st) {
-  const int nblk = a.N / 64;
-  const int grid = 8 * ((a.BH + 7) / 8) * nblk;
+  const int npair = (a.N / 64 + 1) / 2;     // one workgroup per pair of KV blocks
+  const int grid = 8 * ((a.BH + 7) / 8) * npair;
   if (causal) {
-    if (qs) sage_bwd_kernel<D, true, true><<<grid, 256, 0, st>>>(a);
-    else sage_bwd_kernel<D, true, false><<<grid, 256, 0, st>>>(a);
+    if (qs) sage_bwd_kernel<D, true, true><<<grid, 512, 0, st>>>(a);
+    else sage_bwd_kernel<D, true, false><<<grid, 512, 0, st>>>(a);
   } else {
-    if (qs) sage_bwd_kernel<D, false, true><<<grid, 256, 0, st>>>(a);
-    else sage_bwd_kernel<D, false, false><<<grid, 256, 0, st>>>(a);
+    if (qs) sage_bwd_kernel<D, false, true><<<grid, 512, 0, st>>>(a);
+    else sage_bwd_kernel<D, false, false><<<grid, 512, 0, st>>>(a);
   }
   SAGE_LAUNCH_CHECK();
   return SAGEBWD_OK;
@@ -264,14 +267,14 @@ int sagebwd_quantize(const void* Q, const void* K, const void* V, const void* dO
   // the inspection pre-pass fills every layout: forward operands first, then the backward's
   {
     ScopedTimer tm(SAGEBWD_KERNEL_PREPASS_FWD, st);
-    rc = params->d == 64 ? run_prepass<64>(Q, K, V, nullptr, nullptr, *params, ws, w, false, st)
-                         : run_prepass<128>(Q, K, V, nullptr, nullptr, *params, ws, w, false, st);
+    rc = params->d == 64 ? run_prepass<64>(Q, K, V, nullptr, nullptr, nullptr, *params, ws, w, false, st)
+                         : run_prepass<128>(Q, K, V, nullptr, nullptr, nullptr, *params, ws, w, false, st);
   }
   if (rc != SAGEBWD_OK || dO == nullptr) return rc;
   {
     ScopedTimer tm(SAGEBWD_KERNEL_PREPASS_BWD, st);
-    rc = params->d == 64 ? run_prepass<64>(Q, K, V, dO, O, *params, ws, w, true, st)
-                         : run_prepass<128>(Q, K, V, dO, O, *params, ws, w, true, st);
+    rc = params->d == 64 ? run_prepass<64>(Q, K, V, dO, O, nullptr, *params, ws, w, true, st)
+                         : run_prepass<128>(Q, K, V, dO, O, nullptr, *params, ws, w, true, st);
   }
   return rc;
 }
@@ -344,8 +347,8 @@ int sagebwd_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE
   char* ws = (char*)workspace;
   {
     ScopedTimer tm(SAGEBWD_KERNEL_PREPASS_FWD, st);
-    rc = params->d == 64 ? run_prepass<64>(Q, K, V, nullptr, nullptr, *params, ws, w, false, st)
-                         : run_prepass<128>(Q, K, V, nullptr, nullptr, *params, ws, w, false, st);
+    rc = params->d == 64 ? run_prepass<64>(Q, K, V, nullptr, nullptr, nullptr, *params, ws, w, false, st)
+                         : run_prepass<128>(Q, K, V, nullptr, nullptr, nullptr, *params, ws, w, false, st);
   }
   if (rc != SAGEBWD_OK) return rc;
   FwdArgs a;
@@ -387,8 +390,8 @@ int sagebwd_bwd(const void* Q, const void* K, const void* V, const void* O, cons
   const bool qs = (params->smooth & SAGEBWD_SMOOTH_Q) != 0;
   {
     ScopedTimer tm(SAGEBWD_KERNEL_PREPASS_BWD, st);
-    rc = d == 64 ? run_prepass<64>(Q, K, V, dO, O, *params, ws, w, true, st)
-                 : run_prepass<128>(Q, K, V, dO, O, *params, ws, w, true, st);
+    rc = d == 64 ? run_prepass<64>(Q, K, V, dO, O, LSE, *params, ws, w, true, st)
+                 : run_prepass<128>(Q, K, V, dO, O, LSE, *params, ws, w, true, st);
     if (rc != SAGEBWD_OK) return rc;
   }
   BwdArgs a;
@@ -401,7 +404,7 @@ int sagebwd_bwd(const void* Q, const void* K, const void* V, const void* O, cons
   a.sQ = (const float*)(ws + w.sQ);
   a.sK = (const float*)(ws + w.sK);
   a.sdO = (const float*)(ws + w.sdO);
-  a.LSE = LSE;
+  a.nL2 = (const float*)(ws + w.nl2);
   a.delta = (const float*)(ws + w.delta);
   a.bias = qs ? (const float*)(ws + w.bias) : nullptr;
   a.muQ = qs ? (const float*)(ws + w.muQ) : nullptr;
