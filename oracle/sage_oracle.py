@@ -145,21 +145,23 @@ def delta_rows(dO, O) -> np.ndarray:
     return (np.asarray(dO, dtype=_F64) * np.asarray(O, dtype=_F64)).sum(axis=1)
 
 
-def _logits_block(pp, i0: int, n_keys: int, sm_scale: float, q_smooth: bool) -> np.ndarray:
-    """S for the 64 queries starting at i0 against keys [0, n_keys):
+def _logits_block(pp, i0: int, n_keys: int, sm_scale: float, q_smooth: bool, key_idx=None) -> np.ndarray:
+    """S for the 64 queries starting at i0 against keys [0, n_keys) (or against the
+    keys listed in key_idx, a sampling aid that changes no value):
     S = (Q^ K^^T) * s_Q * s_K * sm_scale (Algorithm 1, the S_ij line; R1: the
     1/sqrt(d) of Sec. 4 is applied in the dequantisation factor) plus the
     Q-smoothing bias mu_Qi K^sm^T when that smoothing is on (Sec. 3 decomposition;
     the mu_K terms are row constants and are dropped, so S lives in the smoothed
     frame, R10)."""
     I = i0 // BLOCK
+    sel = slice(0, n_keys) if key_idx is None else key_idx
     qi = pp["Qh"][i0:i0 + BLOCK].astype(_F64)
-    kj = pp["Kh"][:n_keys].astype(_F64)
+    kj = pp["Kh"][sel].astype(_F64)
     acc = qi @ kj.T                                           # exact integers
-    sk_per_key = np.repeat(pp["sK"].astype(_F64), BLOCK)[:n_keys]
+    sk_per_key = np.repeat(pp["sK"].astype(_F64), BLOCK)[sel]
     S = acc * (_F64(pp["sQ"][I]) * _F64(sm_scale)) * sk_per_key[None, :]
     if q_smooth:
-        bias = pp["Ksm"][:n_keys].astype(_F64) @ pp["muQ"][I].astype(_F64)
+        bias = pp["Ksm"][sel].astype(_F64) @ pp["muQ"][I].astype(_F64)
         S = S + _F64(sm_scale) * bias[None, :]
     return S
 
@@ -264,35 +266,36 @@ def backward_head(Q, K, V, O, dO, L, causal: bool = True, k_smooth: bool = True,
     for i0 in (BLOCK * b for b in q_todo):
         I = i0 // BLOCK
         n_keys = i0 + BLOCK if causal else n
-        if kv_keep is not None and not any(J in kv_keep for J in range(n_keys // BLOCK)):
+        blocks = [J for J in range(n_keys // BLOCK) if kv_keep is None or J in kv_keep]
+        if not blocks:
             continue
-        S = _logits_block(pp, i0, n_keys, sm_scale, q_smooth)
+        # the key columns this row block works on (all visible keys unless KV blocks are sampled)
+        kk = np.concatenate([np.arange(BLOCK * J, BLOCK * J + BLOCK) for J in blocks])
+        S = _logits_block(pp, i0, n_keys, sm_scale, q_smooth, None if kv_keep is None else kk)
         P = np.exp(S - L64[i0:i0 + BLOCK, None])              # P_ij = exp(S_ij - L_i)
         if causal:
-            kk = np.arange(n_keys)
             P = np.where(kk[None, :] > (i0 + rows)[:, None], 0.0, P)   # R13: masked entries are 0
-        dP = dO64[i0:i0 + BLOCK] @ V64[:n_keys].T             # unquantised matmul (R15)
+        dP = dO64[i0:i0 + BLOCK] @ V64[kk].T                  # unquantised matmul (R15)
         dS = P * (dP - delta[i0:i0 + BLOCK, None])
         if intermediates is not None:
-            intermediates["P"][i0:i0 + BLOCK, :n_keys] = P
-            intermediates["dP"][i0:i0 + BLOCK, :n_keys] = dP
-            intermediates["dS"][i0:i0 + BLOCK, :n_keys] = dS
+            intermediates["P"][i0:i0 + BLOCK, kk] = P
+            intermediates["dP"][i0:i0 + BLOCK, kk] = dP
+            intermediates["dS"][i0:i0 + BLOCK, kk] = dS
         dOh_i = dOh[i0:i0 + BLOCK].astype(_F64)
         Qh_i = Qh[i0:i0 + BLOCK]
-        for J in range(n_keys // BLOCK):
-            if kv_keep is not None and J not in kv_keep:
-                continue
+        for t, J in enumerate(blocks):
             j0 = J * BLOCK
+            c0 = t * BLOCK                                    # column offset of block J inside S, P, dS
             # dV_j += psi(P_ij)^T psi(dO_i) * s_P * s_dO   (R14: dynamic per-tile scale)
-            Ph, sP = _quantize_tile_f32(P[:, j0:j0 + BLOCK])
+            Ph, sP = _quantize_tile_f32(P[:, c0:c0 + BLOCK])
             dV[j0:j0 + BLOCK] += (_F64(sP) * _F64(sdO[I])) * (Ph.T @ dOh_i)
             # psi(dS_ij); dQ_i += dS^ K^_j * s_dS * s_K ; dK_j += dS^^T Q^_i * s_dS * s_Q
-            dSh, sdS = _quantize_tile_f32(dS[:, j0:j0 + BLOCK])
+            dSh, sdS = _quantize_tile_f32(dS[:, c0:c0 + BLOCK])
             dQ[i0:i0 + BLOCK] += (_F64(sm_scale) * _F64(sdS) * _F64(pp["sK"][J])) * (dSh @ Kh[j0:j0 + BLOCK])
             dK[j0:j0 + BLOCK] += (_F64(sm_scale) * _F64(sdS) * _F64(pp["sQ"][I])) * (dSh.T @ Qh_i)
             if q_smooth:
                 # dK_bias = (dS^T 1) mu_Q^T (ablation section); R17: from the unquantised dS
-                colsum = dS[:, j0:j0 + BLOCK].sum(axis=0)
+                colsum = dS[:, c0:c0 + BLOCK].sum(axis=0)
                 dK[j0:j0 + BLOCK] += _F64(sm_scale) * colsum[:, None] * pp["muQ"][I].astype(_F64)[None, :]
     if return_raw:
         return dQ, dK, dV
