@@ -21,6 +21,10 @@ if ROOT not in sys.path:
 INT8_PEAK_TOPS = 5000.0     # MI355X dense INT8 MFMA peak (published)
 HBM_PEAK_GBS = 8000.0       # MI355X HBM3E peak (published)
 
+# HBM bytes per launch at the headline workload, from the rocprofv3 FETCH_SIZE / WRITE_SIZE runs
+# summarised in profiles/hbm_traffic_headline_fwd_bwd.txt (scaled by the copy-kernel calibration).
+MEASURED_TRAFFIC_BYTES = {"headline": {"bwd": 3.4625e9, "fwd": 3.384e8, "bwd_dq": 2.4091e9}}
+
 
 def work_ops(w, fwd=True, bwd=True):
     per = (4 if fwd else 0) + (10 if bwd else 0)
@@ -59,6 +63,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="headline")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="run only a plain 1 GiB device copy (known HBM bytes) to calibrate rocprofv3's "
+                         "FETCH_SIZE / WRITE_SIZE counters, then exit")
     a = ap.parse_args()
     if a.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (heads shard with no communication; see DESIGN.md); "
@@ -67,6 +74,16 @@ def main():
 
     import torch
     from paper_2603_02170_amd import binding, synth
+
+    if a.copy_calibration:
+        torch.cuda.set_device(0)
+        src = torch.full((1 << 30,), 7, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)          # reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_bytes_read": 1 << 30, "copy_bytes_written": 1 << 30, "launches": 3}))
+        return
 
     w = synth.WORKLOADS[a.workload]
     binding.load_library()      # fails loudly if the HIP library is missing
@@ -126,12 +143,14 @@ def main():
                      "pct_of_int8_peak": 100.0 * fwd_ops / (fwd_ms * 1e-3) / 1e12 / INT8_PEAK_TOPS},
         "kernel_ms": kern,
         "roofline": {"bound": "mfma", "kernel": "sage_bwd_kernel", "achieved": bwd_tops, "peak": INT8_PEAK_TOPS,
-                     "unit": "TOP/s", "frac": bwd_tops / INT8_PEAK_TOPS, "traffic": None,
+                     "unit": "TOP/s", "frac": bwd_tops / INT8_PEAK_TOPS,
+                     "traffic": MEASURED_TRAFFIC_BYTES.get(w.name, {}).get("bwd"),
                      "note": "algorithmic ops of the five backward matmuls (10*N^2*d per head, x0.5 causal) over "
                              "the kernel's mean HIP-event duration; one of the five runs on bf16 MFMA (half rate), "
                              "so the mixed roof is 5/6 of the INT8 peak"},
         "roofline_fwd": {"bound": "mfma", "kernel": "sage_fwd_kernel", "achieved": fwd_tops, "peak": INT8_PEAK_TOPS,
-                         "unit": "TOP/s", "frac": fwd_tops / INT8_PEAK_TOPS},
+                         "unit": "TOP/s", "frac": fwd_tops / INT8_PEAK_TOPS,
+                         "traffic": MEASURED_TRAFFIC_BYTES.get(w.name, {}).get("fwd")},
         "roofline_prepass": {"bound": "hbm", "kernel": "prepass (forward)",
                              "achieved": pre_fwd_bytes / (kern["prepass_fwd"] * 1e-3) / 1e9, "peak": HBM_PEAK_GBS,
                              "unit": "GB/s", "frac": pre_fwd_bytes / (kern["prepass_fwd"] * 1e-3) / 1e9 / HBM_PEAK_GBS},
