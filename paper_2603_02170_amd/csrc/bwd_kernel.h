@@ -55,18 +55,6 @@ struct BwdArgs {
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kRoundMagic = 12582912.0f;   // 1.5 * 2^23: x + magic has rne(x) in its low mantissa bits
 
-typedef const __attribute__((address_space(1))) void* gptr_t;
-typedef __attribute__((address_space(3))) void* lptr_t;
-
-// One 16-byte piece per lane, global -> LDS, no registers in between.  The LDS address is
-// `lds_base + lane * 16` (the hardware adds the lane offset to the wave-uniform base).
-__device__ __forceinline__ void async_copy_16(const void* gsrc_lane, void* lds_base) {
-  __builtin_amdgcn_global_load_lds((gptr_t)gsrc_lane, (lptr_t)lds_base, 16, 0, 0);
-}
-__device__ __forceinline__ void async_copy_4(const void* gsrc_lane, void* lds_base) {
-  __builtin_amdgcn_global_load_lds((gptr_t)gsrc_lane, (lptr_t)lds_base, 4, 0, 0);
-}
-
 template <int D>
 struct BwdStage {             // operands of one Q block
   int8_t qf[64 * D];          // Q^  F fragments
@@ -86,17 +74,6 @@ struct BwdExchange {          // per group of 4 waves
   float red[4][2];
   float cs[2][64];            // Q-smoothing: column sums of dS
 };
-
-// Workgroup barrier that waits for this wave's LDS traffic only.  (__syncthreads() would
-// also drain the asynchronous global->LDS copies that are meant to stay in flight.)
-__device__ __forceinline__ void barrier_lds_only() {
-  asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-}
-// Same, after all of this wave's global-memory operations (the async copies included).
-__device__ __forceinline__ void barrier_all_memory() {
-  __builtin_amdgcn_s_waitcnt(0x0f70);   // vmcnt(0), as a builtin so the compiler's own wait tracking sees it
-  asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-}
 
 // phase A element-wise work of one quadrant; MASK = the tile is on the causal diagonal
 template <bool MASK, bool QSMOOTH>

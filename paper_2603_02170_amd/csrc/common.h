@@ -11,6 +11,7 @@ typedef int v2i __attribute__((ext_vector_type(2)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 typedef float v16f __attribute__((ext_vector_type(16)));
 typedef float v4f __attribute__((ext_vector_type(4)));
+typedef float v2f __attribute__((ext_vector_type(2)));
 typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
 typedef unsigned short v8us __attribute__((ext_vector_type(8)));
 typedef unsigned short v4us __attribute__((ext_vector_type(4)));
@@ -80,6 +81,29 @@ __device__ __forceinline__ float wave_max_nonneg_f32(float v) {
   auto r32 = __builtin_amdgcn_permlane32_swap(u, u, false, false);
   u = r32[0] > r32[1] ? r32[0] : r32[1];
   return __uint_as_float(u);
+}
+
+typedef const __attribute__((address_space(1))) void* gptr_t;
+typedef __attribute__((address_space(3))) void* lptr_t;
+
+// One 16-byte piece per lane, global -> LDS, no registers in between.  The LDS address is
+// `lds_base + lane * 16` (the hardware adds the lane offset to the wave-uniform base).
+__device__ __forceinline__ void async_copy_16(const void* gsrc_lane, void* lds_base) {
+  __builtin_amdgcn_global_load_lds((gptr_t)gsrc_lane, (lptr_t)lds_base, 16, 0, 0);
+}
+__device__ __forceinline__ void async_copy_4(const void* gsrc_lane, void* lds_base) {
+  __builtin_amdgcn_global_load_lds((gptr_t)gsrc_lane, (lptr_t)lds_base, 4, 0, 0);
+}
+
+// Workgroup barrier that waits for this wave's LDS traffic only.  (__syncthreads() would
+// also drain the asynchronous global->LDS copies that are meant to stay in flight.)
+__device__ __forceinline__ void barrier_lds_only() {
+  asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+// Same, after all of this wave's global-memory operations (the async copies included).
+__device__ __forceinline__ void barrier_all_memory() {
+  __builtin_amdgcn_s_waitcnt(0x0f70);   // vmcnt(0), as a builtin so the compiler's own wait tracking sees it
+  asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
 }
 
 }  // namespace sage

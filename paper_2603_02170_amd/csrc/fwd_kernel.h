@@ -1,7 +1,8 @@
 // Fused INT8 attention forward (paper Algorithm 1) for gfx950.
 //
 // One wave owns 32 queries; a workgroup of NW waves owns 32*NW consecutive queries of
-// one head and walks the KV blocks (64 keys each), staging K^ and V^ fragments in LDS.
+// one head and walks the KV blocks (64 keys each).  K^ and V^ fragments are copied
+// global -> LDS asynchronously into a ring of four tile buffers, one barrier per tile.
 //
 // The logits are formed TRANSPOSED, S^T = K^ Q^^T (keys x queries), with the 32x32x32
 // INT8 MFMA: an accumulator lane then holds one query (column) and 16 keys (rows) per
@@ -12,12 +13,20 @@
 //     is already the B operand of O^T = V^^T P^^T (the TF layout of V^ orders its keys
 //     the way the accumulator holds them), with no trip through LDS.
 //
+// Software pipeline inside a wave: the MFMAs of S_{j+1} are issued before the softmax of
+// tile j, and the MFMAs of one 32-channel block of P^V^ before the FP32 update of the
+// previous block, so that the matrix pipe works underneath the vector work of the same wave.
+//
 // Per-token quantisation: P~/s_P with s_P = exp(rowmax(S_ij) - m_ij)/127 equals
 // 127 * exp(S_ij - rowmax(S_ij)), which does not depend on the running max.  The kernel
 // evaluates that form (never 0/0) and keeps the running reference m only for the FP32
 // accumulators: O += beta * s_V * (P^ V^), l += beta * sum(127 p), beta = exp(rowmax - m).
 // m is raised only when a tile's row max exceeds it by more than kTau (in log2 units); the
 // result is unchanged because O/l and m + log l do not depend on the reference chosen.
+//
+// INT32 -> FP32 without a conversion instruction: the P^V^ accumulators start from the bit
+// pattern of 1.5 * 2^23; adding an integer |a| < 2^22 to it gives the float 1.5 * 2^23 + a
+// exactly, and subtracting the constant (an exact FP32 operation) leaves float(a).
 #pragma once
 
 #include "common.h"
@@ -42,18 +51,19 @@ struct FwdArgs {
 constexpr float kTau = 8.0f;
 constexpr float kLog2_127 = 6.98868468677216585f;
 constexpr float kLn2 = 0.69314718055994531f;
+constexpr float kMagicF = 12582912.0f;        // 1.5 * 2^23
+constexpr int kMagicI = 0x4B400000;           // its bit pattern
 
-// One KV tile for one wave.  MASK = the tile straddles the causal diagonal for this wave
-// (a separate instantiation so the full tiles carry no masking code).
-template <int D, bool QSMOOTH, bool MASK>
-__device__ __forceinline__ void fwd_tile(const int8_t* __restrict__ Kt, const int8_t* __restrict__ Vt,
-                                         const v4i (&qf)[D / 32], v16f (&oacc)[D / 32], float& m_ref,
-                                         float& l_part, const float c, const float sv,
-                                         const float* __restrict__ bias_row, const int k0, const int q,
-                                         const int lane, const int h) {
+// Keeps the computation of `v` where it is written: without a use at this point the compiler
+// sinks the vector work of a chunk past the scheduling barriers into the next basic block.
+__device__ __forceinline__ void pin(float& v) { asm volatile("" : "+v"(v)); }
+
+// S^T accumulators of one 64-key tile (two 32-key blocks), interleaved so that consecutive
+// MFMAs are independent.
+template <int D>
+__device__ __forceinline__ void fwd_s_mfma(const int8_t* __restrict__ Kt, const v4i (&qf)[D / 32], v16i (&sacc)[2],
+                                           const int lane) {
   constexpr int KS = D / 32;
-  // ---- S^T = K^ Q^^T : two 32-key blocks, interleaved so consecutive MFMAs are independent ----
-  v16i sacc[2];
 #pragma unroll
   for (int kb = 0; kb < 2; kb++)
 #pragma unroll
@@ -66,11 +76,40 @@ __device__ __forceinline__ void fwd_tile(const int8_t* __restrict__ Kt, const in
       sacc[kb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, qf[s], sacc[kb], 0, 0, 0);
     }
   }
+}
+
+// One KV tile for one wave: (optionally) the logits of the NEXT tile on the matrix pipe, the
+// softmax and per-token quantisation of THIS tile (`sacc`), then O^T += V^^T P^^T.
+// MASK = the tile straddles the causal diagonal for this wave.
+//
+// The instruction stream is laid out by hand in chunks separated by scheduling barriers: each
+// chunk pairs one MFMA (and the LDS read of an operand two MFMAs ahead) with the vector work of
+// four logits or of sixteen output values, so that the matrix pipe and the LDS latency hide
+// under the vector instructions of the same wave.
+template <int D, bool QSMOOTH, bool MASK, bool NEXT>
+__device__ __forceinline__ void fwd_tile(const int8_t* __restrict__ Knext, const int8_t* __restrict__ Vt,
+                                         const v4i (&qf)[D / 32], v16i (&sacc)[2], v16i (&snext)[2],
+                                         float (&oacc)[D / 32][16], const v16i& magic16, float& m_ref, float& l_part,
+                                         const float c, const float sv, const float* __restrict__ bias_row,
+                                         const int k0, const int q, const int lane, const int h) {
+  constexpr int KS = D / 32;
+  constexpr int NSM = 2 * KS;    // MFMAs of the next tile's logits; MFMA m = (k-step m / 2, key block m % 2)
+  const int8_t* kl = Knext + lane * 16;
+  const int8_t* vl = Vt + lane * 16;
+  auto k_frag = [&](int m) { return *(const v4i*)(kl + ((m & 1) * KS + (m >> 1)) * 1024); };
+  auto v_frag = [&](int m) { return *(const v4i*)(vl + m * 1024); };   // m = kb * KS + cb
+
+  v4i ka[3];
+  if constexpr (NEXT) {
+    ka[0] = k_frag(0);
+    ka[1] = k_frag(1);
+  }
+
   float x[2][16];
   float mloc;   // row max of the tile in the log2 domain
   if constexpr (!QSMOOTH) {
     // the scale is one positive scalar per tile, so the row max can be taken on the integers
-    int mi = INT_MIN;
+    int mi[2] = {INT_MIN, INT_MIN};
 #pragma unroll
     for (int kb = 0; kb < 2; kb++)
 #pragma unroll
@@ -81,19 +120,9 @@ __device__ __forceinline__ void fwd_tile(const int8_t* __restrict__ Kt, const in
           v = key > q ? INT_MIN : v;
           sacc[kb][r] = v;
         }
-        mi = max(mi, v);
+        mi[kb] = max(mi[kb], v);
       }
-    mi = half_swap_max_i32(mi);
-    mloc = (float)mi * c;
-    const float off = kLog2_127 - mloc;
-#pragma unroll
-    for (int kb = 0; kb < 2; kb++)
-#pragma unroll
-      for (int r = 0; r < 16; r++) {
-        float v = __builtin_fmaf((float)sacc[kb][r], c, off);
-        if constexpr (MASK) v = sacc[kb][r] == INT_MIN ? -INFINITY : v;
-        x[kb][r] = v;
-      }
+    mloc = (float)half_swap_max_i32(max(mi[0], mi[1])) * c;
   } else {
     float mf = -INFINITY;
 #pragma unroll
@@ -111,13 +140,8 @@ __device__ __forceinline__ void fwd_tile(const int8_t* __restrict__ Kt, const in
         }
       }
     mloc = half_swap_max_f32(mf);
-    const float off = kLog2_127 - mloc;
-#pragma unroll
-    for (int kb = 0; kb < 2; kb++)
-#pragma unroll
-      for (int r = 0; r < 16; r++) x[kb][r] = x[kb][r] + off;
   }
-  // ---- online softmax reference ----
+  // ---- online softmax reference (rarely raised) ----
   if (__builtin_amdgcn_ballot_w64(mloc > m_ref + kTau) != 0) {
     const float m_new = fmaxf(m_ref, mloc);
     const float alpha = __builtin_amdgcn_exp2f(m_ref - m_new);   // 0 on the first tile
@@ -129,51 +153,92 @@ __device__ __forceinline__ void fwd_tile(const int8_t* __restrict__ Kt, const in
     m_ref = m_new;
   }
   const float beta = __builtin_amdgcn_exp2f(mloc - m_ref);
-  // ---- P^ = rne(127 exp(S - rowmax)), packed as the B operand; row sum of 127 p ----
+  const float off = kLog2_127 - mloc;
+  __builtin_amdgcn_sched_barrier(0);
+
+  // ---- slots 0..7: P^ = rne(127 exp(S - rowmax)) for four logits each, packed as the B operand;
+  //      row sum of 127 p.  Matrix work issued underneath: MFMA m of the next tile's logits in
+  //      slot m; the first half of O^T += V^^T P^^T (key block 0, channel block cb) in slot 4 + cb.
+  // ---- slots 8..: the second half (key block 1) in slot 8 + cb, and the FP32 update of channel
+  //      block cb in slots 10 + 2 cb and 11 + 2 cb.  V^ fragments are read two slots ahead. ----
   v4i pf[2];
-  float psum = 0.f;
+  v4i va[4];
+  v16i t[KS];
+  float psum[4] = {0.f, 0.f, 0.f, 0.f};
+  float w = 0.f;
+  constexpr int NSLOT = 10 + 2 * KS;
+  auto pv_slot = [&](int m) { return m < KS ? 4 + m : 8 + (m - KS); };   // slot of P^V^ MFMA m = (kb, cb)
 #pragma unroll
-  for (int kb = 0; kb < 2; kb++)
+  for (int sl = 0; sl < NSLOT; sl++) {
+    // LDS reads: V^ fragment of the MFMA two slots ahead
 #pragma unroll
-    for (int aa = 0; aa < 4; aa++) {
+    for (int m = 0; m < 2 * KS; m++)
+      if (pv_slot(m) == sl + 2) va[m & 3] = v_frag(m);
+    // matrix work of this slot
+    if constexpr (NEXT) {
+      if (sl < NSM) {
+        if (sl + 2 < NSM) ka[(sl + 2) % 3] = k_frag(sl + 2);
+        if (sl < 2) {
+          v16i z;
+#pragma unroll
+          for (int r = 0; r < 16; r++) z[r] = 0;
+          snext[sl & 1] = __builtin_amdgcn_mfma_i32_32x32x32_i8(ka[sl % 3], qf[sl >> 1], z, 0, 0, 0);
+        } else {
+          snext[sl & 1] = __builtin_amdgcn_mfma_i32_32x32x32_i8(ka[sl % 3], qf[sl >> 1], snext[sl & 1], 0, 0, 0);
+        }
+      }
+    }
+#pragma unroll
+    for (int m = 0; m < 2 * KS; m++)
+      if (pv_slot(m) == sl) {
+        if (m < KS) t[m] = __builtin_amdgcn_mfma_i32_32x32x32_i8(va[m & 3], pf[0], magic16, 0, 0, 0);
+        else t[m - KS] = __builtin_amdgcn_mfma_i32_32x32x32_i8(va[m & 3], pf[1], t[m - KS], 0, 0, 0);
+      }
+    // vector work of this slot
+    if (sl < 8) {
+      const int kb = sl >> 2, aa = sl & 3;
       unsigned u = 0;
 #pragma unroll
       for (int b = 0; b < 4; b++) {
-        const float e = __builtin_amdgcn_exp2f(x[kb][4 * aa + b]);
-        psum += e;
+        float xv;
+        if constexpr (!QSMOOTH) {
+          xv = __builtin_fmaf((float)sacc[kb][4 * aa + b], c, off);
+          if constexpr (MASK) xv = sacc[kb][4 * aa + b] == INT_MIN ? -INFINITY : xv;
+        } else {
+          xv = x[kb][4 * aa + b] + off;
+        }
+        const float e = __builtin_amdgcn_exp2f(xv);
+        psum[b] += e;
+        pin(psum[b]);
         u = __builtin_amdgcn_cvt_pk_u8_f32(e, b, u);
       }
       pf[kb][aa] = (int)u;
+    } else if (sl == 8) {
+      l_part = __builtin_fmaf(beta, (psum[0] + psum[1]) + (psum[2] + psum[3]), l_part);
+      w = beta * sv;
+      pin(l_part);
+      pin(w);
+    } else if (sl >= 10) {
+      const int cb = (sl - 10) >> 1, half = (sl - 10) & 1;
+#pragma unroll
+      for (int r = 8 * half; r < 8 * half + 8; r++) {
+        oacc[cb][r] = __builtin_fmaf(__int_as_float(t[cb][r]) - kMagicF, w, oacc[cb][r]);
+        pin(oacc[cb][r]);
+      }
     }
-  l_part = __builtin_fmaf(beta, psum, l_part);
-  const float w = beta * sv;
-  // ---- O^T += (V^^T P^^T) * w : all MFMAs first, then the conversions ----
-  v16i t[KS];
-#pragma unroll
-  for (int cb = 0; cb < KS; cb++) {
-#pragma unroll
-    for (int r = 0; r < 16; r++) t[cb][r] = 0;
-#pragma unroll
-    for (int kb = 0; kb < 2; kb++) {
-      const v4i a = *(const v4i*)(Vt + (kb * KS + cb) * 1024 + lane * 16);
-      t[cb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, pf[kb], t[cb], 0, 0, 0);
-    }
+    __builtin_amdgcn_sched_barrier(0);
   }
-#pragma unroll
-  for (int cb = 0; cb < KS; cb++)
-#pragma unroll
-    for (int r = 0; r < 16; r++) oacc[cb][r] = __builtin_fmaf((float)t[cb][r], w, oacc[cb][r]);
 }
 
 template <int D, bool CAUSAL, bool QSMOOTH, int NW>
-__global__ void __launch_bounds__(64 * NW, (NW == 8 ? 1 : 2)) sage_fwd_kernel(FwdArgs args) {
+__global__ void __launch_bounds__(64 * NW, (NW == 4 ? 2 : 1)) sage_fwd_kernel(FwdArgs args) {
   constexpr int KS = D / 32;                 // k-steps of Q K^T; also channel blocks of O
   constexpr int TILE_BYTES = 64 * D;         // one K^ or V^ tile of 64 keys
+  constexpr int PAIR = 2 * TILE_BYTES;       // K^ tile | V^ tile
+  constexpr int NFRAG = PAIR / 1024;         // 1 KiB fragments per pair
   constexpr int QT = 32 * NW;                // queries per workgroup
-  constexpr int CHUNKS = 2 * TILE_BYTES / 16 / (64 * NW);  // 16-byte chunks per thread per tile pair
-  static_assert(CHUNKS >= 1, "tile too small for this workgroup");
 
-  __shared__ __attribute__((aligned(16))) int8_t lds[2][2 * TILE_BYTES];   // [buf][K tile | V tile]
+  __shared__ __attribute__((aligned(16))) int8_t lds[4][PAIR + 64];   // K^ | V^ | per-wave (s_K, s_V)
 
   // XCD-aware mapping: consecutive workgroup ids go round-robin over the 8 XCDs, so all
   // query tiles of one head are given ids with the same residue and share one L2.
@@ -185,7 +250,8 @@ __global__ void __launch_bounds__(64 * NW, (NW == 8 ? 1 : 2)) sage_fwd_kernel(Fw
   const int qt = args.n_qtiles - 1 - (slot % args.n_qtiles);
 
   const int tid = threadIdx.x;
-  const int lane = tid & 63, wave = tid >> 6;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int ql = lane & 31, h = lane >> 5;
   const int N = args.N;
   const int q0 = qt * QT + 32 * wave;        // first query of this wave
@@ -207,9 +273,20 @@ __global__ void __launch_bounds__(64 * NW, (NW == 8 ? 1 : 2)) sage_fwd_kernel(Fw
   const float cq = args.sQ[(size_t)bh * nblk + q0 / kBlock] * args.scale_log2e;
   const float* bias_row = QSMOOTH ? args.bias + ((size_t)bh * nblk + q0 / kBlock) * N : nullptr;
 
-  const int n_tiles = CAUSAL ? (qt * QT + QT) / kBlock : nblk;
+  const int n_tiles = CAUSAL ? (qt * QT + QT) / kBlock : nblk;   // barrier count, uniform in the workgroup
+  const int last = CAUSAL ? (q0 + 31) / kBlock : nblk - 1;       // this wave's last tile (masked if causal)
 
-  v16f oacc[KS];
+  // the constant the P^V^ accumulators start from, hidden from the compiler so that it
+  // stays in registers instead of being rebuilt with 16 moves per MFMA chain
+  v16i magic16;
+#pragma unroll
+  for (int r = 0; r < 16; r++) {
+    int mv;
+    asm volatile("v_mov_b32 %0, %1" : "=v"(mv) : "s"(kMagicI));
+    magic16[r] = mv;
+  }
+
+  float oacc[KS][16];
 #pragma unroll
   for (int cb = 0; cb < KS; cb++)
 #pragma unroll
@@ -217,49 +294,89 @@ __global__ void __launch_bounds__(64 * NW, (NW == 8 ? 1 : 2)) sage_fwd_kernel(Fw
   float m_ref = -INFINITY;   // log2 domain
   float l_part = 0.f;        // this lane's share of sum(127 p) relative to m_ref
 
-  // stage tile 0
-  v4i pre[CHUNKS];
-  {
+  // Asynchronous copy of tile j (K^ fragments, then V^ fragments) into a ring slot; the
+  // 1 KiB fragments are dealt round-robin to the waves.
+  auto stage_load = [&](int j, int8_t* dst) {
 #pragma unroll
-    for (int c = 0; c < CHUNKS; c++) {
-      const int idx = (tid + c * 64 * NW) * 16;
-      const int8_t* src = idx < TILE_BYTES ? KFh + idx : VTh + (idx - TILE_BYTES);
-      pre[c] = *(const v4i*)src;
-    }
-#pragma unroll
-    for (int c = 0; c < CHUNKS; c++) *(v4i*)(&lds[0][(tid + c * 64 * NW) * 16]) = pre[c];
-  }
-  __syncthreads();
-
-  for (int j = 0; j < n_tiles; j++) {
-    const int buf = j & 1;
-    if (j + 1 < n_tiles) {
-#pragma unroll
-      for (int c = 0; c < CHUNKS; c++) {
-        const int idx = (tid + c * 64 * NW) * 16;
-        const int8_t* src = idx < TILE_BYTES ? KFh + (size_t)(j + 1) * TILE_BYTES + idx
-                                             : VTh + (size_t)(j + 1) * TILE_BYTES + (idx - TILE_BYTES);
-        pre[c] = *(const v4i*)src;
+    for (int k = 0; k < (NFRAG + NW - 1) / NW; k++) {
+      const int o = wave + NW * k;           // wave-uniform
+      if (o < NFRAG) {
+        const int8_t* src = o < NFRAG / 2 ? KFh + (size_t)j * TILE_BYTES + o * 1024
+                                          : VTh + (size_t)j * TILE_BYTES + (o - NFRAG / 2) * 1024;
+        async_copy_16(src + lane * 16, dst + o * 1024);
       }
     }
+    // the two block scales of the tile, one private copy per wave (lanes 0 and 1 carry them)
+    if (lane < 2) async_copy_4((lane == 0 ? sKh : sVh) + j, dst + PAIR + wave * 8);
+  };
 
-    const int k0 = j * kBlock;
-    const bool active = !CAUSAL || (k0 <= q0 + 31);
-    if (active) {
-      const int8_t* Kt = &lds[buf][0];
-      const int8_t* Vt = &lds[buf][TILE_BYTES];
-      const float c = cq * sKh[j];
-      const float sv = sVh[j];
-      const bool diag = CAUSAL && (k0 + 63 > q0);   // some key of the tile may exceed some query
-      if (diag) fwd_tile<D, QSMOOTH, true>(Kt, Vt, qf, oacc, m_ref, l_part, c, sv, bias_row, k0, q, lane, h);
-      else fwd_tile<D, QSMOOTH, false>(Kt, Vt, qf, oacc, m_ref, l_part, c, sv, bias_row, k0, q, lane, h);
+  int8_t* cur = &lds[0][0];
+  int8_t* nxt = &lds[1][0];
+  int8_t* nx2 = &lds[2][0];
+  int8_t* nx3 = &lds[3][0];
+  stage_load(0, cur);
+  if (n_tiles > 1) stage_load(1, nxt);
+  if (n_tiles > 2) stage_load(2, nx2);
+  barrier_all_memory();
+
+  v16i sA[2], sB[2];
+  fwd_s_mfma<D>(cur, qf, sA, lane);
+
+  // Iteration j: tile j + 3 starts to load into the slot that tile j - 1 occupied (every wave is
+  // past the barrier that ended iteration j - 1, so nobody reads it any more); this wave forms
+  // S_{j+1} from slot `nxt` and finishes tile j with V^ from slot `cur`; before the barrier at
+  // the end it waits for the copies of tile j + 2 (issued one iteration earlier), while its copies
+  // of tile j + 3 stay in flight.  The block scales travel with the tiles, so the loop has no
+  // register-returning global loads whose waits would also drain the copies.  Every wave of
+  // the workgroup runs n_tiles iterations (the barriers must match): its unmasked tiles, its last
+  // tile, then iterations that only keep the ring moving.
+  constexpr int CPW = (NFRAG + NW - 1) / NW;   // copies per wave and tile (every wave issues all of them)
+  static_assert(NFRAG % NW == 0, "every wave must issue the same number of copies");
+  auto end_iter = [&](const bool issued) {
+    if (issued) {
+      __builtin_amdgcn_s_waitcnt(0x0F70 | (CPW + 1));   // vmcnt: all but this iteration's copies
+      barrier_lds_only();
+    } else {
+      barrier_all_memory();
     }
-
-    if (j + 1 < n_tiles) {
+    int8_t* t = cur;
+    cur = nxt;
+    nxt = nx2;
+    nx2 = nx3;
+    nx3 = t;
+  };
+  auto full_iter = [&](const int j, v16i (&sc)[2], v16i (&sn)[2]) __attribute__((always_inline)) {
+    const bool issue = j + 3 < n_tiles;
+    if (issue) stage_load(j + 3, nx3);
+    const v2f sc2 = *(const v2f*)(cur + PAIR + wave * 8);
+    fwd_tile<D, QSMOOTH, false, true>(nxt, cur + TILE_BYTES, qf, sc, sn, oacc, magic16, m_ref, l_part,
+                                      cq * sc2[0], sc2[1], bias_row, j * kBlock, q, lane, h);
+    end_iter(issue);
+  };
+  int j = 0;
+  for (; j + 1 < last; j += 2) {
+    full_iter(j, sA, sB);
+    full_iter(j + 1, sB, sA);
+  }
+  if (j < last) {
+    full_iter(j, sA, sB);
 #pragma unroll
-      for (int c = 0; c < CHUNKS; c++) *(v4i*)(&lds[buf ^ 1][(tid + c * 64 * NW) * 16]) = pre[c];
-    }
-    __syncthreads();
+    for (int kb = 0; kb < 2; kb++) sA[kb] = sB[kb];
+    j++;
+  }
+  {
+    const bool issue = j + 3 < n_tiles;
+    if (issue) stage_load(j + 3, nx3);
+    const v2f sc2 = *(const v2f*)(cur + PAIR + wave * 8);
+    fwd_tile<D, QSMOOTH, CAUSAL, false>(nxt, cur + TILE_BYTES, qf, sA, sB, oacc, magic16, m_ref, l_part,
+                                        cq * sc2[0], sc2[1], bias_row, j * kBlock, q, lane, h);
+    end_iter(issue);
+    j++;
+  }
+  for (; j < n_tiles; j++) {
+    const bool issue = j + 3 < n_tiles;
+    if (issue) stage_load(j + 3, nx3);
+    end_iter(issue);
   }
 
   // ---- epilogue: O = O / l, L = m + log(l) (l carries a factor 127) ----
