@@ -1,16 +1,19 @@
 // Fused INT8 attention backward (paper Algorithm 2) for gfx950.
 //
 // sage_bwd_kernel: a workgroup of 8 waves owns two adjacent KV blocks (one per group of 4
-// waves) and walks the Q blocks i from the last one down.  The operands of Q block i - 1 are
-// copied global -> LDS asynchronously (LDS-DMA loads) into the second half of a double buffer
-// while block i is processed.  Per (i, j) tile and group:
+// waves) and walks the Q blocks i from the last one down.  The operands of the coming Q blocks
+// are copied global -> LDS asynchronously (LDS-DMA loads) into double buffers.  Per (i, j) tile
+// and group there are three phases:
 //   phase A  each wave takes one 32x32 quadrant (qb, kb) of the tile:
 //            S = Q^ K^^T on INT8 MFMA, dP = dO V^T on bf16 MFMA (the one unquantised matmul),
-//            P = exp(S - L), dS = P o (dP - delta); tile-wide max P and max |dS| are exchanged
-//            through LDS; psi(P), psi(dS) are written to LDS as MFMA operand fragments.
+//            P = exp(S - L), dS = P o (dP - delta), kept in registers; the wave maxima of P and
+//            |dS| go to LDS.
+//   phase Q  with the tile-wide maxima: psi(P), psi(dS) to LDS as MFMA operand fragments, and
+//            psi(dS) transposed (one MFMA against a permutation matrix) to the scratch buffer.
 //   phase B  each wave takes one 32-channel slice of the outputs and contracts over the whole
 //            tile: dV^T += dO^^T P^, dK^T += Q^^T dS^ (accumulated in FP32 registers with the
-//            per-tile scales).  psi(dS_ij) and its scale are also stored to a scratch buffer.
+//            per-tile scales).
+// The phases are software-pipelined over ONE workgroup barrier per tile (see the kernel).
 // A second kernel (sage_bwd_dq_kernel) owns one Q block per workgroup and forms
 //   dQ_i = sum_j s_dS(i,j) s_K(j) sm_scale * (dS^_ij K^_j)
 // from the stored INT8 tiles: a plain scaled INT8 GEMM with no atomics, so dQ is
@@ -19,10 +22,11 @@
 //
 // S is formed untransposed (queries x keys): an accumulator lane then holds one key and 16
 // queries, which is the B-operand form of the two contractions over queries (dV, dK).  The
-// contraction over keys (dQ) needs dS^ with one query per lane; that copy is scattered to
-// LDS bytewise (no VALU work) in the key order of the TF layout of K^, and copied out from
-// there in 16-byte pieces.
+// contraction over keys (dQ) needs dS^ with one query per lane; scattering it bytewise through
+// LDS cost more LDS time than all operand reads together, hence the transposing MFMA.
 #pragma once
+
+#include <type_traits>
 
 #include "common.h"
 
@@ -54,25 +58,27 @@ struct BwdArgs {
 
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kRoundMagic = 12582912.0f;   // 1.5 * 2^23: x + magic has rne(x) in its low mantissa bits
+constexpr int kMagicBits = 0x4B400000;       // its bit pattern
 
 template <int D>
-struct BwdStage {             // operands of one Q block
+struct BwdStageA {            // operands of phase A for one Q block
   int8_t qf[64 * D];          // Q^  F fragments
-  int8_t qt[64 * D];          // Q^  TF fragments
-  int8_t dot[64 * D];         // dO^ TF fragments
   int8_t dof[128 * D];        // bf16 dO as A fragments (32-row block, 16-channel step), XOR-swizzled slots
   float nl2[64];              // -L * log2(e)
   float dl[64];               // delta
-  float muq[D];               // Q-smoothing block mean
   float bias[128];            // Q-smoothing logit bias of this Q block for the workgroup's 128 keys
+  float sc[4];                // s_Q[i]
+};
+template <int D>
+struct BwdStageB {            // operands of phase B for one Q block
+  int8_t qt[64 * D];          // Q^  TF fragments
+  int8_t dot[64 * D];         // dO^ TF fragments
+  float muq[D];               // Q-smoothing block mean
   float sc[4];                // s_Q[i], s_dO[i]
 };
-struct BwdExchange {          // per group of 4 waves
+struct BwdExchange {          // per group of 4 waves and tile parity
   int8_t pb[4096];            // psi(P)  B fragments (q step, key block)
   int8_t dsb[4096];           // psi(dS) B fragments
-  int8_t dst[4096];           // psi(dS) A fragments (q block, key step)
-  float red[4][2];
-  float cs[2][64];            // Q-smoothing: column sums of dS
 };
 
 // phase A element-wise work of one quadrant; MASK = the tile is on the causal diagonal
@@ -81,8 +87,7 @@ __device__ __forceinline__ void bwd_quadrant(const v16i& sacc, const v16f& dp, c
                                              const float* __restrict__ dl, const float c, const float bias_l,
                                              const int qrow0, const int kcol, float (&p)[16], float (&ds)[16],
                                              float& pm, float& dm, float& cs) {
-  pm = 0.f;
-  dm = 0.f;
+  float pm2[2] = {0.f, 0.f}, dm2[2] = {0.f, 0.f};
   cs = 0.f;
 #pragma unroll
   for (int aa = 0; aa < 4; aa++) {
@@ -97,13 +102,23 @@ __device__ __forceinline__ void bwd_quadrant(const v16i& sacc, const v16f& dp, c
       const float dsv = pv * (dp[r] - d4[b]);
       p[r] = pv;
       ds[r] = dsv;
-      pm = fmaxf(pm, pv);
-      dm = fmaxf(dm, fabsf(dsv));
+      pm2[aa & 1] = fmaxf(pm2[aa & 1], pv);
+      dm2[aa & 1] = fmaxf(dm2[aa & 1], fabsf(dsv));
       if constexpr (QSMOOTH) cs += dsv;
     }
   }
+  pm = fmaxf(pm2[0], pm2[1]);
+  dm = fmaxf(dm2[0], dm2[1]);
 }
 
+// Schedule.  The tiles of a group (Q blocks i = nblk-1 .. i_first against its KV block) go
+// through three phases,
+//   A  S = Q^K^^T (INT8), dP = dO V^T (bf16), P, dS in registers, wave maxima to LDS,
+//   Q  psi(P), psi(dS) with the tile maxima -> LDS operand fragments,
+//   B  dV^T += dO^^T P^, dK^T += Q^^T dS^ (INT8) with FP32 accumulation,
+// software-pipelined over the workgroup's ONE barrier per tile: interval t runs Q of tile t-1,
+// A of tile t and B of tile t-2, so every phase finds its cross-wave inputs complete and the
+// matrix work of one tile runs under the vector work of its neighbours.
 template <int D, bool CAUSAL, bool QSMOOTH>
 __global__ void __launch_bounds__(512, 1) sage_bwd_kernel(BwdArgs args) {
   constexpr int KS = D / 32;     // INT8 k-steps over d; channel blocks
@@ -112,9 +127,11 @@ __global__ void __launch_bounds__(512, 1) sage_bwd_kernel(BwdArgs args) {
   constexpr int TILE = 64 * D;   // bytes of one INT8 tile
   constexpr int NF = TILE / 1024;  // 1 KiB fragments per INT8 tile
 
-  __shared__ __attribute__((aligned(16))) BwdStage<D> stage0;
-  __shared__ __attribute__((aligned(16))) BwdStage<D> stage1;
-  __shared__ __attribute__((aligned(16))) BwdExchange xch[2];
+  __shared__ __attribute__((aligned(16))) BwdStageA<D> stA[2];
+  __shared__ __attribute__((aligned(16))) BwdStageB<D> stB[2];
+  __shared__ __attribute__((aligned(16))) BwdExchange xch[2][2];      // [group][tile parity]
+  __shared__ float red[2][2][4][2];                                  // [group][tile parity][wave][max P, max |dS|]
+  __shared__ float csum[QSMOOTH ? 2 * 3 * 2 * 64 : 1];                // [group][tile % 3][q half][key]: column sums of dS
 
   const int gidx = blockIdx.x;
   const int xcd = gidx & 7, slot = gidx >> 3;
@@ -127,7 +144,8 @@ __global__ void __launch_bounds__(512, 1) sage_bwd_kernel(BwdArgs args) {
   const int jp = slot % npair;        // small jp = most Q blocks under the causal mask: scheduled first
 
   const int tid = threadIdx.x;
-  const int lane = tid & 63, wave = tid >> 6;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int grp = wave >> 2, w4 = wave & 3, gtid = tid & 255;
   const int ll = lane & 31, h = lane >> 5;
   const int qb = w4 >> 1, kb = w4 & 1;                     // phase A quadrant
@@ -139,7 +157,6 @@ __global__ void __launch_bounds__(512, 1) sage_bwd_kernel(BwdArgs args) {
 
   const size_t head = (size_t)bh * N * D;
   const float sKj = args.sK[(size_t)bh * nblk + jc];
-  BwdExchange& X = xch[grp];
 
   // ---- operands that stay in registers for the whole loop ----
   v4i kfr[KS];
@@ -166,26 +183,31 @@ __global__ void __launch_bounds__(512, 1) sage_bwd_kernel(BwdArgs args) {
     }
 
   const int i_first = CAUSAL ? 2 * jp : 0;
-  // slot of key kappa = lane%32 inside a TF-ordered 32-key step: kappa = 8a + 4h' + b -> (h', 4a + b)
-  const int tk_h = (ll >> 2) & 1, tk_t = 4 * (ll >> 3) + (ll & 3);
+  const int T = nblk - i_first;                 // tile rows of this workgroup; tile t is Q block nblk-1-t
+  // B operand of the transposing MFMA of phase Q: a quantised quadrant, read as an A operand, has
+  // contraction index k = 16h + 4a + b for the query 8a + 4h + b; column n of the permutation
+  // matrix picks the k that stands for query n.  Lane (n, hh) holds k = 16hh + t in byte t.
+  v4i tperm;
+#pragma unroll
+  for (int aa = 0; aa < 4; aa++) {
+    unsigned u = 0;
+#pragma unroll
+    for (int b = 0; b < 4; b++) u |= (unsigned)((8 * aa + 4 * h + b) == ll) << (8 * b);
+    tperm[aa] = (int)u;
+  }
 
-  // Asynchronous staging of Q block i into `st`: 5*NF one-KiB fragment copies (plus L, delta,
-  // mu_Q) dealt round-robin to the 8 waves.
-  auto stage_load = [&](int i, BwdStage<D>& st) {
+  // Asynchronous staging (global -> LDS, no registers) of the phase-A operands of Q block i.
+  auto load_A = [&](int i, BwdStageA<D>& st) {
     const size_t toff = head + (size_t)i * TILE;
 #pragma unroll
-    for (int k = 0; k < (5 * NF + 7) / 8; k++) {
+    for (int k = 0; k < (3 * NF + 7) / 8; k++) {
       const int o = wave + 8 * k;            // wave-uniform
       if (o < NF) {
         async_copy_16(args.QF + toff + o * 1024 + lane * 16, st.qf + o * 1024);
-      } else if (o < 2 * NF) {
-        async_copy_16(args.QT + toff + (o - NF) * 1024 + lane * 16, st.qt + (o - NF) * 1024);
       } else if (o < 3 * NF) {
-        async_copy_16(args.dOT + toff + (o - 2 * NF) * 1024 + lane * 16, st.dot + (o - 2 * NF) * 1024);
-      } else if (o < 5 * NF) {
         // bf16 dO fragment f = (32-row block, 16-channel step s); LDS slot l holds the piece of
         // (row, channel half) = (l ^ (s & 7)) so that the A-operand reads stay conflict-free
-        const int f = o - 3 * NF;
+        const int f = o - NF;
         const int rb = f / KB, sst = f % KB;
         const int orig = lane ^ (sst & 7);
         const int row = 32 * rb + (orig & 31), hh = orig >> 5;
@@ -194,83 +216,63 @@ __global__ void __launch_bounds__(512, 1) sage_bwd_kernel(BwdArgs args) {
     }
     if (wave == 0) async_copy_4(args.nL2 + (size_t)bh * N + 64 * i + lane, st.nl2);
     if (wave == 1) async_copy_4(args.delta + (size_t)bh * N + 64 * i + lane, st.dl);
-    if (wave == 2 && lane < 2)
-      async_copy_4((lane == 0 ? args.sQ : args.sdO) + (size_t)bh * nblk + i, st.sc);
+    if (wave == 2 && lane < 1) async_copy_4(args.sQ + (size_t)bh * nblk + i, st.sc);
     if constexpr (QSMOOTH) {
-      if (wave == 3) async_copy_4(args.muQ + ((size_t)bh * nblk + i) * D + lane, st.muq);
-      if (D == 128 && wave == 4) async_copy_4(args.muQ + ((size_t)bh * nblk + i) * D + 64 + lane, st.muq + 64);
       const float* brow = args.bias + ((size_t)bh * nblk + i) * N + 128 * jp;
       if (wave == 5) async_copy_4(brow + lane, st.bias);
       if (wave == 6 && 2 * jp + 1 < nblk) async_copy_4(brow + 64 + lane, st.bias + 64);
     }
   };
+  // ... and of its phase-B operands.
+  auto load_B = [&](int i, BwdStageB<D>& st) {
+    const size_t toff = head + (size_t)i * TILE;
+#pragma unroll
+    for (int k = 0; k < (2 * NF + 7) / 8; k++) {
+      const int o = wave + 8 * k;
+      if (o < NF) async_copy_16(args.QT + toff + o * 1024 + lane * 16, st.qt + o * 1024);
+      else if (o < 2 * NF) async_copy_16(args.dOT + toff + (o - NF) * 1024 + lane * 16, st.dot + (o - NF) * 1024);
+    }
+    if (wave == 7 && lane < 2) async_copy_4((lane == 0 ? args.sQ : args.sdO) + (size_t)bh * nblk + i, st.sc);
+    if constexpr (QSMOOTH) {
+      if (wave == 3) async_copy_4(args.muQ + ((size_t)bh * nblk + i) * D + lane, st.muq);
+      if (D == 128 && wave == 4) async_copy_4(args.muQ + ((size_t)bh * nblk + i) * D + 64 + lane, st.muq + 64);
+    }
+  };
 
-  stage_load(nblk - 1, stage0);
+  load_A(nblk - 1, stA[0]);
   barrier_all_memory();
 
-  // One tile row.  `st` holds Q block i; `nx` receives Q block i - 1 meanwhile.  The two are
-  // passed as distinct objects (the loop below alternates them explicitly) so that reads of
-  // `st` are never ordered behind the copies into `nx`.
-  auto tile_row = [&](const int i, BwdStage<D>& st, BwdStage<D>& nx) __attribute__((always_inline)) {
-    if (i > i_first) stage_load(i - 1, nx);
-    const bool active = gvalid && (!CAUSAL || i >= j);
+  float p[16], ds[16];           // P and dS of the tile between its phases A and Q
+  float sP_q = 0.f, sS_q = 0.f;  // tile scales found by the last phase Q
+  // One interval.  STEADY = all three phases are active and tile t is not on the diagonal: the
+  // body is then free of branches, one basic block in which the compiler interleaves the three
+  // independent phases (the LDS and MFMA latencies of one hide under the vector work of the others).
+  auto interval = [&](const int t, auto steady_tag) __attribute__((always_inline)) {
+    constexpr bool STEADY = decltype(steady_tag)::value;
+    const float sP_b = sP_q, sS_b = sS_q;      // scales of tile t - 2 (its phase Q ran in the last interval)
+    const int ib = nblk - 1 - (t - 2);         // Q blocks of the three tiles in flight
+    const int iq = nblk - 1 - (t - 1);
+    const int ia = nblk - 1 - t;
+    const bool act_b = STEADY || (t >= 2 && gvalid && (!CAUSAL || ib >= j));
+    const bool act_q = STEADY || (t >= 1 && t - 1 < T && gvalid && (!CAUSAL || iq >= j));
+    const bool act_a = STEADY || (t < T && gvalid && (!CAUSAL || ia >= j));
 
-    float p[16], ds[16];
-    float pm = 0.f, dm = 0.f, cs = 0.f;
-    float sQi = 0.f, sdOi = 0.f;
-    if (active) {
-      // ---------------- phase A: quadrant (qb, kb) ----------------
-      v16i sacc;
-#pragma unroll
-      for (int r = 0; r < 16; r++) sacc[r] = 0;
-#pragma unroll
-      for (int s = 0; s < KS; s++) {
-        v4i a = *(const v4i*)(st.qf + ((qb * KS + s) * 64 + lane) * 16);
-        sacc = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, kfr[s], sacc, 0, 0, 0);
-      }
-      v16f dp;
-#pragma unroll
-      for (int r = 0; r < 16; r++) dp[r] = 0.f;
-#pragma unroll
-      for (int s = 0; s < KB; s++) {
-        v8bf a = *(const v8bf*)(st.dof + ((qb * KB + s) * 64 + (lane ^ (s & 7))) * 16);
-        dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, vfr[s], dp, 0, 0, 0);
-      }
-      sQi = st.sc[0];
-      sdOi = st.sc[1];
-      const float c = sQi * sKj * args.scale_log2e;
-      float bias_l = 0.f;
-      if constexpr (QSMOOTH) bias_l = st.bias[64 * grp + 32 * kb + ll];
-      const float* nl2 = st.nl2 + 32 * qb + 4 * h;
-      const float* dl = st.dl + 32 * qb + 4 * h;
-      if (CAUSAL && i == j)
-        bwd_quadrant<true, QSMOOTH>(sacc, dp, nl2, dl, c, bias_l, 32 * qb + 4 * h, 32 * kb + ll, p, ds, pm, dm, cs);
-      else
-        bwd_quadrant<false, QSMOOTH>(sacc, dp, nl2, dl, c, bias_l, 0, 0, p, ds, pm, dm, cs);
-      pm = wave_max_nonneg_f32(pm);
-      dm = wave_max_nonneg_f32(dm);
-      if (lane == 0) {
-        X.red[w4][0] = pm;
-        X.red[w4][1] = dm;
-      }
-      if constexpr (QSMOOTH) {
-        cs = half_swap_sum_f32(cs);
-        if (h == 0) X.cs[qb][32 * kb + ll] = cs;
-      }
-    }
-    barrier_lds_only();   // (1) tile maxima visible
+    // operands of the coming intervals; the copies are issued in two batches so that the eight
+    // waves do not queue up behind each other at the memory pipeline
+    if (STEADY || t + 1 < T) load_A(ia - 1, stA[(t + 1) & 1]);
 
-    float sP = 0.f, sS = 0.f;
-    if (active) {
-      pm = fmaxf(fmaxf(X.red[0][0], X.red[1][0]), fmaxf(X.red[2][0], X.red[3][0]));
-      dm = fmaxf(fmaxf(X.red[0][1], X.red[1][1]), fmaxf(X.red[2][1], X.red[3][1]));
+    // ---------------- phase Q of tile t - 1 ----------------
+    if (act_q) {
+      BwdExchange& X = xch[grp][(t - 1) & 1];
+      const float(&R)[4][2] = red[grp][(t - 1) & 1];
+      const float pm = fmaxf(fmaxf(R[0][0], R[1][0]), fmaxf(R[2][0], R[3][0]));
+      const float dm = fmaxf(fmaxf(R[0][1], R[1][1]), fmaxf(R[2][1], R[3][1]));
       // the per-tile scales of P and dS are internal (never stored bit-exactly): 127/a via rcp
       const float rP = pm > 0.f ? 127.0f * __builtin_amdgcn_rcpf(pm) : 0.f;
       const float rS = dm > 0.f ? 127.0f * __builtin_amdgcn_rcpf(dm) : 0.f;
-      sP = pm * (1.0f / 127.0f);
-      sS = dm * (1.0f / 127.0f);
+      sP_q = pm * (1.0f / 127.0f);
+      sS_q = dm * (1.0f / 127.0f);
       v4i pf, df;
-      int8_t* tbase = X.dst + ((qb * 2 + kb) * 64 + 32 * tk_h) * 16 + tk_t;
 #pragma unroll
       for (int aa = 0; aa < 4; aa++) {
         unsigned up = 0;
@@ -280,7 +282,6 @@ __global__ void __launch_bounds__(512, 1) sage_bwd_kernel(BwdArgs args) {
           const int r = 4 * aa + b;
           up = __builtin_amdgcn_cvt_pk_u8_f32(p[r] * rP, b, up);
           ub[b] = __float_as_uint(__builtin_fmaf(ds[r], rS, kRoundMagic));
-          tbase[(8 * aa + 4 * h + b) * 16] = (int8_t)ub[b];
         }
         pf[aa] = (int)up;
         const unsigned lo = __builtin_amdgcn_perm(ub[1], ub[0], 0x0c0c0400u);
@@ -289,22 +290,79 @@ __global__ void __launch_bounds__(512, 1) sage_bwd_kernel(BwdArgs args) {
       }
       *(v4i*)(X.pb + ((qb * 2 + kb) * 64 + lane) * 16) = pf;
       *(v4i*)(X.dsb + ((qb * 2 + kb) * 64 + lane) * 16) = df;
-    }
-    barrier_lds_only();   // (2) quantised tiles visible
-
-    if (active) {
-      // psi(dS_ij) and its scale go to the scratch buffer for the dQ kernel
+      // The dQ kernel contracts over keys and needs this quadrant with one QUERY per lane.  Taken as
+      // an A operand, `df` is the matrix (key, permuted query); one MFMA against the matching
+      // permutation matrix returns it transposed in the accumulator: lane = query, registers =
+      // keys in the order of the TF layout of K^.  The low bytes of the INT32 results are the codes.
       {
-        const size_t tile = ((size_t)hl * nblk + i) * nblk + j;
-        *(v4i*)(args.dSq + tile * 4096 + gtid * 16) = *(const v4i*)(X.dst + gtid * 16);
-        if (gtid == 0) args.sdS[tile] = sS;
-      }
-      // ---------------- phase B: channel block cb ----------------
-      const float w_dv = sP * sdOi;
-      const float w_dk = sS * sQi * args.sm_scale;
+        v16i z;
 #pragma unroll
-      for (int t = 0; t < NPB; t++) {
-        const int kbo = blk0 + t;
+        for (int r = 0; r < 16; r++) z[r] = 0;
+        const v16i tr = __builtin_amdgcn_mfma_i32_32x32x32_i8(df, tperm, z, 0, 0, 0);
+        v4i o;
+#pragma unroll
+        for (int aa = 0; aa < 4; aa++) {
+          const unsigned lo = __builtin_amdgcn_perm((unsigned)tr[4 * aa + 1], (unsigned)tr[4 * aa], 0x0c0c0400u);
+          const unsigned hi = __builtin_amdgcn_perm((unsigned)tr[4 * aa + 3], (unsigned)tr[4 * aa + 2], 0x04000c0cu);
+          o[aa] = (int)(lo | hi);
+        }
+        const size_t tile = ((size_t)hl * nblk + iq) * nblk + j;
+        *(v4i*)(args.dSq + tile * 4096 + ((qb * 2 + kb) * 64 + lane) * 16) = o;
+        if (gtid == 0) args.sdS[tile] = sS_q;
+      }
+    }
+    if (STEADY || (t >= 1 && t - 1 < T)) load_B(iq, stB[(t - 1) & 1]);
+
+    // ---------------- phase A of tile t: quadrant (qb, kb) ----------------
+    if (act_a) {
+      const BwdStageA<D>& st = stA[t & 1];
+      v16i sacc;
+      v16f dp;
+#pragma unroll
+      for (int r = 0; r < 16; r++) {
+        sacc[r] = 0;
+        dp[r] = 0.f;
+      }
+#pragma unroll
+      for (int s = 0; s < KB; s++) {
+        if (s % 2 == 0) {
+          const v4i a = *(const v4i*)(st.qf + ((qb * KS + s / 2) * 64 + lane) * 16);
+          sacc = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, kfr[s / 2], sacc, 0, 0, 0);
+        }
+        const v8bf a = *(const v8bf*)(st.dof + ((qb * KB + s) * 64 + (lane ^ (s & 7))) * 16);
+        dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, vfr[s], dp, 0, 0, 0);
+      }
+      const float c = st.sc[0] * sKj * args.scale_log2e;
+      float bias_l = 0.f;
+      if constexpr (QSMOOTH) bias_l = st.bias[64 * grp + 32 * kb + ll];
+      const float* nl2 = st.nl2 + 32 * qb + 4 * h;
+      const float* dl = st.dl + 32 * qb + 4 * h;
+      float pm, dm, cs;
+      if (!STEADY && CAUSAL && ia == j)
+        bwd_quadrant<true, QSMOOTH>(sacc, dp, nl2, dl, c, bias_l, 32 * qb + 4 * h, 32 * kb + ll, p, ds, pm, dm, cs);
+      else
+        bwd_quadrant<false, QSMOOTH>(sacc, dp, nl2, dl, c, bias_l, 0, 0, p, ds, pm, dm, cs);
+      pm = wave_max_nonneg_f32(pm);
+      dm = wave_max_nonneg_f32(dm);
+      if (lane == 0) {
+        red[grp][t & 1][w4][0] = pm;
+        red[grp][t & 1][w4][1] = dm;
+      }
+      if constexpr (QSMOOTH) {
+        cs = half_swap_sum_f32(cs);
+        if (h == 0) csum[((grp * 3 + t % 3) * 2 + qb) * 64 + 32 * kb + ll] = cs;
+      }
+    }
+
+    // ---------------- phase B of tile t - 2: channel block cb ----------------
+    if (act_b) {
+      const BwdStageB<D>& st = stB[t & 1];
+      const BwdExchange& X = xch[grp][t & 1];
+      const float w_dv = sP_b * st.sc[1];
+      const float w_dk = sS_b * st.sc[0] * args.sm_scale;
+#pragma unroll
+      for (int tt = 0; tt < NPB; tt++) {
+        const int kbo = blk0 + tt;
         v16i av, ak;
 #pragma unroll
         for (int r = 0; r < 16; r++) {
@@ -322,29 +380,30 @@ __global__ void __launch_bounds__(512, 1) sage_bwd_kernel(BwdArgs args) {
         }
 #pragma unroll
         for (int r = 0; r < 16; r++) {
-          dvacc[t][r] = __builtin_fmaf((float)av[r], w_dv, dvacc[t][r]);
-          dkacc[t][r] = __builtin_fmaf((float)ak[r], w_dk, dkacc[t][r]);
+          dvacc[tt][r] = __builtin_fmaf((float)av[r], w_dv, dvacc[tt][r]);
+          dkacc[tt][r] = __builtin_fmaf((float)ak[r], w_dk, dkacc[tt][r]);
         }
         if constexpr (QSMOOTH) {
           // dK_bias = (dS^T 1) mu_Q^T with the unquantised column sums of this tile
-          const float csv = X.cs[0][32 * kbo + ll] + X.cs[1][32 * kbo + ll];
+          const float* cs2 = csum + ((grp * 3 + (t - 2) % 3) * 2) * 64;
+          const float csv = cs2[32 * kbo + ll] + cs2[64 + 32 * kbo + ll];
 #pragma unroll
           for (int aa = 0; aa < 4; aa++) {
             const v4f m4 = *(const v4f*)(st.muq + 32 * cb + 8 * aa + 4 * h);
 #pragma unroll
-            for (int b = 0; b < 4; b++) dkbias[t][4 * aa + b] = __builtin_fmaf(csv, m4[b], dkbias[t][4 * aa + b]);
+            for (int b = 0; b < 4; b++) dkbias[tt][4 * aa + b] = __builtin_fmaf(csv, m4[b], dkbias[tt][4 * aa + b]);
           }
         }
       }
     }
-    barrier_all_memory();   // (3) next stage has landed; this tile's buffers are free
+    barrier_all_memory();   // the interval's LDS traffic, copies and stores are complete
   };
-  for (int i = nblk - 1;;) {
-    tile_row(i, stage0, stage1);
-    if (--i < i_first) break;
-    tile_row(i, stage1, stage0);
-    if (--i < i_first) break;
-  }
+  // steady intervals: t >= 2 (all three tiles exist), tile t above the diagonal and not the last row
+  const int t_steady_end = !gvalid ? 0 : (CAUSAL ? nblk - 1 - j : T - 1);
+  int t = 0;
+  for (; t < 2 && t < T + 2; t++) interval(t, std::false_type{});
+  for (; t < t_steady_end; t++) interval(t, std::true_type{});
+  for (; t < T + 2; t++) interval(t, std::false_type{});
 
   if (!gvalid) return;
 

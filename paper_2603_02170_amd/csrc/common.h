@@ -64,17 +64,19 @@ __device__ __forceinline__ float half_swap_sum_f32(float v) {
 
 // max over all 64 lanes of a NON-NEGATIVE float (result in every lane).  Non-negative floats
 // order like their bit patterns, so the reduction runs on unsigned integers: four DPP steps
-// inside each row of 16 lanes, then the row and half-wave swaps of gfx950.  No LDS traffic.
+// inside each row of 16 lanes (the `old` value 0 is the identity of an unsigned max, which lets the
+// compiler fold each lane permutation into the max instruction), then the row and half-wave swaps
+// of gfx950.  No LDS traffic.
 __device__ __forceinline__ float wave_max_nonneg_f32(float v) {
   unsigned u = __float_as_uint(v);
   unsigned t;
-  t = (unsigned)__builtin_amdgcn_update_dpp((int)u, (int)u, 0xB1, 0xf, 0xf, false);   // quad_perm [1,0,3,2]
+  t = (unsigned)__builtin_amdgcn_update_dpp(0, (int)u, 0xB1, 0xf, 0xf, false);   // quad_perm [1,0,3,2]
   u = u > t ? u : t;
-  t = (unsigned)__builtin_amdgcn_update_dpp((int)u, (int)u, 0x4E, 0xf, 0xf, false);   // quad_perm [2,3,0,1]
+  t = (unsigned)__builtin_amdgcn_update_dpp(0, (int)u, 0x4E, 0xf, 0xf, false);   // quad_perm [2,3,0,1]
   u = u > t ? u : t;
-  t = (unsigned)__builtin_amdgcn_update_dpp((int)u, (int)u, 0x141, 0xf, 0xf, false);  // row_half_mirror
+  t = (unsigned)__builtin_amdgcn_update_dpp(0, (int)u, 0x141, 0xf, 0xf, false);  // row_half_mirror
   u = u > t ? u : t;
-  t = (unsigned)__builtin_amdgcn_update_dpp((int)u, (int)u, 0x140, 0xf, 0xf, false);  // row_mirror
+  t = (unsigned)__builtin_amdgcn_update_dpp(0, (int)u, 0x140, 0xf, 0xf, false);  // row_mirror
   u = u > t ? u : t;
   auto r16 = __builtin_amdgcn_permlane16_swap(u, u, false, false);
   u = r16[0] > r16[1] ? r16[0] : r16[1];

@@ -191,9 +191,6 @@ int run_prepass(const void* Q, const void* K, const void* V, const void* dO, con
 }
 
 int pick_fwd_waves(int N) {
-#ifdef FWD_FORCE_NW4
-  if (N % 128 == 0) return 4;
-#endif
   if (N % 256 == 0) return 8;
   if (N % 128 == 0) return 4;
   return 2;
