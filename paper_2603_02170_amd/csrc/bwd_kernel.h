@@ -67,14 +67,14 @@ struct BwdStageA {            // operands of phase A for one Q block
   float nl2[64];              // -L * log2(e)
   float dl[64];               // delta
   float bias[128];            // Q-smoothing logit bias of this Q block for the workgroup's 128 keys
-  float sc[4];                // s_Q[i]
+  float sc[64];               // s_Q[i] in every entry
 };
 template <int D>
 struct BwdStageB {            // operands of phase B for one Q block
   int8_t qt[64 * D];          // Q^  TF fragments
   int8_t dot[64 * D];         // dO^ TF fragments
   float muq[D];               // Q-smoothing block mean
-  float sc[4];                // s_Q[i], s_dO[i]
+  float sc[64];               // s_Q[i] in the even entries, s_dO[i] in the odd ones
 };
 struct BwdExchange {          // per group of 4 waves and tile parity
   int8_t pb[4096];            // psi(P)  B fragments (q step, key block)
@@ -130,6 +130,7 @@ __global__ void __launch_bounds__(512, 1) sage_bwd_kernel(BwdArgs args) {
   __shared__ __attribute__((aligned(16))) BwdStageA<D> stA[2];
   __shared__ __attribute__((aligned(16))) BwdStageB<D> stB[2];
   __shared__ __attribute__((aligned(16))) BwdExchange xch[2][2];      // [group][tile parity]
+  __shared__ __attribute__((aligned(16))) int8_t vst[2][2 * D * 64];   // [group]: bf16 V_j as B fragments (key block, 16-channel step)
   __shared__ float red[2][2][4][2];                                  // [group][tile parity][wave][max P, max |dS|]
   __shared__ float csum[QSMOOTH ? 2 * 3 * 2 * 64 : 1];                // [group][tile % 3][q half][key]: column sums of dS
 
@@ -165,11 +166,18 @@ __global__ void __launch_bounds__(512, 1) sage_bwd_kernel(BwdArgs args) {
 #pragma unroll
     for (int s = 0; s < KS; s++) kfr[s] = *(const v4i*)(p + s * 1024);
   }
-  v8bf vfr[KB];
-  {
-    const unsigned short* p = args.V + head + (size_t)(64 * jc + 32 * kb + ll) * D + 8 * h;
+  // bf16 V_j (B operand of dP): staged once in LDS as 1 KiB fragments (key block kb, 16-channel
+  // step s), lane (key, half) holding V[key][16 s + 8 half .. + 8]; 16 fragments (d = 128) dealt
+  // to the group's 4 waves.  Keeping it in registers instead would cost 32 of them, which the
+  // prefetch of the streamed operands needs more.
 #pragma unroll
-    for (int s = 0; s < KB; s++) vfr[s] = *(const v8bf*)(p + 16 * s);
+  for (int k = 0; k < (2 * KB + 3) / 4; k++) {
+    const int f = w4 + 4 * k;
+    if (f < 2 * KB) {
+      const int fkb = f / KB, fs = f % KB;
+      async_copy_16((const char*)(args.V + head + (size_t)(64 * jc + 32 * fkb) * D + 16 * fs) + ll * (2 * D) + h * 16,
+                    vst[grp] + f * 1024);
+    }
   }
 
   v16f dvacc[NPB], dkacc[NPB], dkbias[QSMOOTH ? NPB : 1];
@@ -216,7 +224,7 @@ __global__ void __launch_bounds__(512, 1) sage_bwd_kernel(BwdArgs args) {
     }
     if (wave == 0) async_copy_4(args.nL2 + (size_t)bh * N + 64 * i + lane, st.nl2);
     if (wave == 1) async_copy_4(args.delta + (size_t)bh * N + 64 * i + lane, st.dl);
-    if (wave == 2 && lane < 1) async_copy_4(args.sQ + (size_t)bh * nblk + i, st.sc);
+    if (wave == 2) async_copy_4(args.sQ + (size_t)bh * nblk + i, st.sc);   // all 64 lanes: s_Q[i] in every entry
     if constexpr (QSMOOTH) {
       const float* brow = args.bias + ((size_t)bh * nblk + i) * N + 128 * jp;
       if (wave == 5) async_copy_4(brow + lane, st.bias);
@@ -232,7 +240,7 @@ __global__ void __launch_bounds__(512, 1) sage_bwd_kernel(BwdArgs args) {
       if (o < NF) async_copy_16(args.QT + toff + o * 1024 + lane * 16, st.qt + o * 1024);
       else if (o < 2 * NF) async_copy_16(args.dOT + toff + (o - NF) * 1024 + lane * 16, st.dot + (o - NF) * 1024);
     }
-    if (wave == 7 && lane < 2) async_copy_4((lane == 0 ? args.sQ : args.sdO) + (size_t)bh * nblk + i, st.sc);
+    if (wave == 7) async_copy_4(((lane & 1) ? args.sdO : args.sQ) + (size_t)bh * nblk + i, st.sc);
     if constexpr (QSMOOTH) {
       if (wave == 3) async_copy_4(args.muQ + ((size_t)bh * nblk + i) * D + lane, st.muq);
       if (D == 128 && wave == 4) async_copy_4(args.muQ + ((size_t)bh * nblk + i) * D + 64 + lane, st.muq + 64);
@@ -261,6 +269,7 @@ __global__ void __launch_bounds__(512, 1) sage_bwd_kernel(BwdArgs args) {
     // waves do not queue up behind each other at the memory pipeline
     if (STEADY || t + 1 < T) load_A(ia - 1, stA[(t + 1) & 1]);
 
+    __builtin_amdgcn_sched_barrier(0);
     // ---------------- phase Q of tile t - 1 ----------------
     if (act_q) {
       BwdExchange& X = xch[grp][(t - 1) & 1];
@@ -308,14 +317,28 @@ __global__ void __launch_bounds__(512, 1) sage_bwd_kernel(BwdArgs args) {
         }
         const size_t tile = ((size_t)hl * nblk + iq) * nblk + j;
         *(v4i*)(args.dSq + tile * 4096 + ((qb * 2 + kb) * 64 + lane) * 16) = o;
-        if (gtid == 0) args.sdS[tile] = sS_q;
+        args.sdS[tile] = sS_q;   // the same value from every lane: no branch
       }
     }
     if (STEADY || (t >= 1 && t - 1 < T)) load_B(iq, stB[(t - 1) & 1]);
 
+    __builtin_amdgcn_sched_barrier(0);
     // ---------------- phase A of tile t: quadrant (qb, kb) ----------------
     if (act_a) {
       const BwdStageA<D>& st = stA[t & 1];
+      // The two MFMA chains (S over INT8 steps, dP over bf16 steps) are interleaved, and the LDS
+      // reads of their operands run two bf16 steps ahead of the MFMAs that consume them.
+      v4i qa[KS];
+      v8bf da[KB], vb[KB];
+      const int8_t* qfp = st.qf + (qb * KS * 64 + lane) * 16;
+      const int8_t* vbp = vst[grp] + (kb * KB * 64 + lane) * 16;
+      auto ld = [&](int s) {
+        if (s % 2 == 0) qa[s / 2] = *(const v4i*)(qfp + (s / 2) * 1024);
+        da[s] = *(const v8bf*)(st.dof + ((qb * KB + s) * 64 + (lane ^ (s & 7))) * 16);
+        vb[s] = *(const v8bf*)(vbp + s * 1024);
+      };
+      ld(0);
+      ld(1);
       v16i sacc;
       v16f dp;
 #pragma unroll
@@ -323,14 +346,13 @@ __global__ void __launch_bounds__(512, 1) sage_bwd_kernel(BwdArgs args) {
         sacc[r] = 0;
         dp[r] = 0.f;
       }
+      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int s = 0; s < KB; s++) {
-        if (s % 2 == 0) {
-          const v4i a = *(const v4i*)(st.qf + ((qb * KS + s / 2) * 64 + lane) * 16);
-          sacc = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, kfr[s / 2], sacc, 0, 0, 0);
-        }
-        const v8bf a = *(const v8bf*)(st.dof + ((qb * KB + s) * 64 + (lane ^ (s & 7))) * 16);
-        dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, vfr[s], dp, 0, 0, 0);
+        if (s + 2 < KB) ld(s + 2);
+        if (s % 2 == 0) sacc = __builtin_amdgcn_mfma_i32_32x32x32_i8(qa[s / 2], kfr[s / 2], sacc, 0, 0, 0);
+        dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(da[s], vb[s], dp, 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
       }
       const float c = st.sc[0] * sKj * args.scale_log2e;
       float bias_l = 0.f;
@@ -344,16 +366,16 @@ __global__ void __launch_bounds__(512, 1) sage_bwd_kernel(BwdArgs args) {
         bwd_quadrant<false, QSMOOTH>(sacc, dp, nl2, dl, c, bias_l, 0, 0, p, ds, pm, dm, cs);
       pm = wave_max_nonneg_f32(pm);
       dm = wave_max_nonneg_f32(dm);
-      if (lane == 0) {
-        red[grp][t & 1][w4][0] = pm;
-        red[grp][t & 1][w4][1] = dm;
-      }
+      // every lane stores the same pair (one LDS write, no branch)
+      red[grp][t & 1][w4][0] = pm;
+      red[grp][t & 1][w4][1] = dm;
       if constexpr (QSMOOTH) {
         cs = half_swap_sum_f32(cs);
         if (h == 0) csum[((grp * 3 + t % 3) * 2 + qb) * 64 + 32 * kb + ll] = cs;
       }
     }
 
+    __builtin_amdgcn_sched_barrier(0);
     // ---------------- phase B of tile t - 2: channel block cb ----------------
     if (act_b) {
       const BwdStageB<D>& st = stB[t & 1];
