@@ -453,9 +453,7 @@ __global__ void __launch_bounds__(512, 1) sage_bwd_kernel(BwdArgs args) {
 
 // ---------------------------------------------------------------------------------
 // dQ_i = sum_j (dS^_ij K^_j) * s_dS(i,j) * s_K(j) * sm_scale        (Algorithm 2, the dQ line)
-// One workgroup per Q block; each wave owns a 32-channel slice and streams its operands
-// straight from global memory / L2 (no LDS, no barriers): A = stored psi(dS) fragments,
-// B = K^ in TF layout.
+// A = stored psi(dS) fragments, B = K^ in TF layout.
 struct DqArgs {
   const int8_t* dSq;
   const float* sdS;
@@ -466,30 +464,63 @@ struct DqArgs {
   float sm_scale;
 };
 
+// A workgroup of 8 waves owns TWO Q blocks (128 queries) and walks the KV blocks j.  Per j, the two
+// psi(dS) tiles and the K^ tile (TF layout) are copied global -> LDS asynchronously into a ring of
+// four stages (one barrier per j), so that each byte crosses the memory pipeline once per
+// workgroup; wave (q block, channel block) reads its operands from LDS.
 template <int D, bool CAUSAL>
-__global__ void __launch_bounds__(256, 2) sage_bwd_dq_kernel(DqArgs args) {
+__global__ void __launch_bounds__(512, 2) sage_bwd_dq_kernel(DqArgs args) {
   constexpr int KS = D / 32;
-  constexpr int NPB = KS / 2;
+  constexpr int NPB = KS / 2;              // 32-row blocks per wave (2 for d = 128, 1 for d = 64)
+  constexpr int TILE = 64 * D;             // bytes of one K^ tile
+  constexpr int DSB = 4096;                // bytes of one psi(dS) tile
+  constexpr int NFRAG = (2 * DSB + TILE) / 1024;
+  constexpr int STAGE = 2 * DSB + TILE + 64;   // dS tile of Q block 0 | of Q block 1 | K^ tile | per-wave (s_dS, s_K)
+  constexpr int CPW_MIN = NFRAG / 8 + 1;   // copies every wave issues per stage (fragments + its scale pair)
+
+  __shared__ __attribute__((aligned(16))) int8_t lds[4][STAGE];
+
   const int g = blockIdx.x;
   const int xcd = g & 7, slot = g >> 3;
   const int N = args.N;
   const int nblk = N / kBlock;
-  const int hl = xcd + 8 * (slot / nblk);
+  const int npair = (nblk + 1) / 2;
+  const int hl = xcd + 8 * (slot / npair);
   if (hl >= args.BH) return;
   const int bh = args.bh0 + hl;
-  const int i = nblk - 1 - (slot % nblk);      // longest rows first under the causal mask
+  const int i0 = 2 * (npair - 1 - (slot % npair));     // longest rows first under the causal mask
   const int tid = threadIdx.x;
-  const int lane = tid & 63, wave = tid >> 6;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int ll = lane & 31, h = lane >> 5;
-  const int cb = (D == 128) ? wave : (wave & 1);
-  const int blk0 = (D == 128) ? 0 : (wave >> 1);
+  const int iq = wave >> 2, w4 = wave & 3;
+  const int cb = (D == 128) ? w4 : (w4 & 1);
+  const int blk0 = (D == 128) ? 0 : (w4 >> 1);
+  const bool valid = i0 + iq < nblk;
+  const int i = valid ? i0 + iq : i0;                  // clamped: an idle wave still copies in bounds
+  const int i1 = i0 + 1 < nblk ? i0 + 1 : i0;
   const size_t head = (size_t)bh * N * D;
-  const int n_j = CAUSAL ? i + 1 : nblk;
+  const int n_j = CAUSAL ? (i0 + 2 < nblk ? i0 + 2 : nblk) : nblk;
 
-  const int8_t* ds_row = args.dSq + ((size_t)hl * nblk + i) * nblk * 4096 + lane * 16;
+  const int8_t* ds0 = args.dSq + ((size_t)hl * nblk + i0) * nblk * DSB;
+  const int8_t* ds1 = args.dSq + ((size_t)hl * nblk + i1) * nblk * DSB;
+  const int8_t* kth = args.KT + head;
   const float* sc_row = args.sdS + ((size_t)hl * nblk + i) * nblk;
   const float* sKh = args.sK + (size_t)bh * nblk;
-  const int8_t* kt = args.KT + head + (size_t)cb * 1024 + lane * 16;
+
+  auto stage_load = [&](int j, int8_t* dst) {
+#pragma unroll
+    for (int k = 0; k < (NFRAG + 7) / 8; k++) {
+      const int o = wave + 8 * k;          // wave-uniform
+      if (o < NFRAG) {
+        const int8_t* src = o < 4 ? ds0 + (size_t)j * DSB + o * 1024
+                          : o < 8 ? ds1 + (size_t)j * DSB + (o - 4) * 1024
+                                  : kth + (size_t)j * TILE + (o - 8) * 1024;
+        async_copy_16(src + lane * 16, dst + o * 1024);
+      }
+    }
+    if (lane < 2) async_copy_4((lane == 0 ? sc_row : sKh) + j, dst + 2 * DSB + TILE + wave * 8);
+  };
 
   v16f acc[NPB];
 #pragma unroll
@@ -497,39 +528,56 @@ __global__ void __launch_bounds__(256, 2) sage_bwd_dq_kernel(DqArgs args) {
 #pragma unroll
     for (int r = 0; r < 16; r++) acc[t][r] = 0.f;
 
-  v4i a_cur[NPB][2], b_cur[2];
-  auto load_tile = [&](int j, v4i (&a)[NPB][2], v4i (&b)[2]) {
-#pragma unroll
-    for (int ks = 0; ks < 2; ks++) {
-      b[ks] = *(const v4i*)(kt + (size_t)(2 * j + ks) * KS * 1024);
-#pragma unroll
-      for (int t = 0; t < NPB; t++) a[t][ks] = *(const v4i*)(ds_row + (size_t)j * 4096 + ((blk0 + t) * 2 + ks) * 1024);
-    }
-  };
-  load_tile(0, a_cur, b_cur);
+  int8_t* cur = &lds[0][0];
+  int8_t* nxt = &lds[1][0];
+  int8_t* nx2 = &lds[2][0];
+  int8_t* nx3 = &lds[3][0];
+  stage_load(0, cur);
+  if (n_j > 1) stage_load(1, nxt);
+  if (n_j > 2) stage_load(2, nx2);
+  barrier_all_memory();
+
+  // Iteration j: stage j + 3 starts to load into the slot that stage j - 1 occupied; before the
+  // barrier at the end the wave waits until at most the copies of stages j + 2 and j + 3 are
+  // still in flight, i.e. stage j + 1 has landed.
+  bool issued_prev = n_j > 2;
   for (int j = 0; j < n_j; j++) {
-    v4i a_nxt[NPB][2], b_nxt[2];
-    if (j + 1 < n_j) load_tile(j + 1, a_nxt, b_nxt);
-    const float w = sc_row[j] * sKh[j] * args.sm_scale;
+    const bool issue = j + 3 < n_j;
+    if (issue) stage_load(j + 3, nx3);
+    if (valid && (!CAUSAL || j <= i)) {
+      const int8_t* ap = cur + iq * DSB + lane * 16;
+      const int8_t* bp = cur + 2 * DSB + cb * 1024 + lane * 16;
+      const v2f sc2 = *(const v2f*)(cur + 2 * DSB + TILE + wave * 8);
+      const float w = sc2[0] * sc2[1] * args.sm_scale;
+      const v4i b0 = *(const v4i*)(bp);
+      const v4i b1 = *(const v4i*)(bp + KS * 1024);
 #pragma unroll
-    for (int t = 0; t < NPB; t++) {
-      v16i q;
+      for (int t = 0; t < NPB; t++) {
+        const v4i a0 = *(const v4i*)(ap + ((blk0 + t) * 2 + 0) * 1024);
+        const v4i a1 = *(const v4i*)(ap + ((blk0 + t) * 2 + 1) * 1024);
+        v16i q;
 #pragma unroll
-      for (int r = 0; r < 16; r++) q[r] = 0;
+        for (int r = 0; r < 16; r++) q[r] = 0;
+        q = __builtin_amdgcn_mfma_i32_32x32x32_i8(a0, b0, q, 0, 0, 0);
+        q = __builtin_amdgcn_mfma_i32_32x32x32_i8(a1, b1, q, 0, 0, 0);
 #pragma unroll
-      for (int ks = 0; ks < 2; ks++) q = __builtin_amdgcn_mfma_i32_32x32x32_i8(a_cur[t][ks], b_cur[ks], q, 0, 0, 0);
-#pragma unroll
-      for (int r = 0; r < 16; r++) acc[t][r] = __builtin_fmaf((float)q[r], w, acc[t][r]);
-    }
-    if (j + 1 < n_j) {
-#pragma unroll
-      for (int ks = 0; ks < 2; ks++) {
-        b_cur[ks] = b_nxt[ks];
-#pragma unroll
-        for (int t = 0; t < NPB; t++) a_cur[t][ks] = a_nxt[t][ks];
+        for (int r = 0; r < 16; r++) acc[t][r] = __builtin_fmaf((float)q[r], w, acc[t][r]);
       }
     }
+    if (issue && issued_prev) {
+      __builtin_amdgcn_s_waitcnt(0x0F70 | (2 * CPW_MIN));
+      barrier_lds_only();
+    } else {
+      barrier_all_memory();
+    }
+    issued_prev = issue;
+    int8_t* tmp = cur;
+    cur = nxt;
+    nxt = nx2;
+    nx2 = nx3;
+    nx3 = tmp;
   }
+  if (!valid) return;
   // accumulator lane = channel, registers = query rows 8a + 4h + b of the 32-row block
 #pragma unroll
   for (int t = 0; t < NPB; t++) {

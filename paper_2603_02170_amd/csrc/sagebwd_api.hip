@@ -233,10 +233,10 @@ int launch_bwd(const BwdArgs& a, bool causal, bool qs, hipStream_t st) {
 
 template <int D>
 int launch_bwd_dq(const DqArgs& a, bool causal, hipStream_t st) {
-  const int nblk = a.N / 64;
-  const int grid = 8 * ((a.BH + 7) / 8) * nblk;
-  if (causal) sage_bwd_dq_kernel<D, true><<<grid, 256, 0, st>>>(a);
-  else sage_bwd_dq_kernel<D, false><<<grid, 256, 0, st>>>(a);
+  const int npair = (a.N / 64 + 1) / 2;     // one workgroup per pair of Q blocks
+  const int grid = 8 * ((a.BH + 7) / 8) * npair;
+  if (causal) sage_bwd_dq_kernel<D, true><<<grid, 512, 0, st>>>(a);
+  else sage_bwd_dq_kernel<D, false><<<grid, 512, 0, st>>>(a);
   SAGE_LAUNCH_CHECK();
   return SAGEBWD_OK;
 }
