@@ -23,7 +23,7 @@ HBM_PEAK_GBS = 8000.0       # MI355X HBM3E peak (published)
 
 # HBM bytes per launch at the headline workload, from the rocprofv3 FETCH_SIZE / WRITE_SIZE runs
 # summarised in profiles/hbm_traffic_headline_fwd_bwd.txt (scaled by the copy-kernel calibration).
-MEASURED_TRAFFIC_BYTES = {"headline": {"bwd": 3.4625e9, "fwd": 3.384e8, "bwd_dq": 2.4091e9}}
+MEASURED_TRAFFIC_BYTES = {"headline": {"bwd": 3.4719e9, "fwd": 3.381e8, "bwd_dq": 2.4403e9}}
 
 
 def work_ops(w, fwd=True, bwd=True):
@@ -59,8 +59,8 @@ def cpu_baseline(w, seconds_hint=20.0):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=10)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="headline")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
