@@ -84,3 +84,28 @@ def test_bwd_head_groups_share_the_ds_scratch():
         _bwd_case(Q, K, V, dO, binding.SageParams(1, 5, 256, 64, causal=True))
     finally:
         binding.set_scratch_budget(8 << 30)
+
+
+def test_bwd_q_smoothing_head_dim_64_odd_block_count():
+    # d = 64 with Q-smoothing; 5 blocks, so the last workgroup has an idle second group
+    Q, K, V, dO = synth.gaussian_inputs(320, 64, sigma_qk=1.0, seed=5, heads=2)
+    Q = (Q.float() + torch.linspace(-2, 2, 64)).to(torch.bfloat16)
+    _bwd_case(Q, K, V, dO, binding.SageParams(1, 2, 320, 64, causal=True, q_smooth=True))
+
+
+def test_bwd_zero_upstream_gradient_gives_zero_gradients():
+    # dO = 0: delta = 0, every dS tile is all-zero (scale 0, codes 0), all three gradients vanish
+    Q, K, V, dO = synth.gaussian_inputs(256, 128, seed=11, heads=1)
+    Z = torch.zeros_like(dO)
+    O, L = binding.sagebwd_fwd(Q.cuda(), K.cuda(), V.cuda(), binding.SageParams(1, 1, 256, 128, causal=True))
+    dQ, dK, dV = binding.sagebwd_bwd(Q.cuda(), K.cuda(), V.cuda(), O, Z.cuda(), L,
+                                     binding.SageParams(1, 1, 256, 128, causal=True))
+    torch.cuda.synchronize()
+    for name, g in (("dQ", dQ), ("dK", dK), ("dV", dV)):
+        assert torch.count_nonzero(g).item() == 0, name
+
+
+def test_bwd_two_steady_intervals_only():
+    # N = 256 non-causal: 4 tile rows, the shortest loop that reaches the branch-free interval
+    Q, K, V, dO = synth.gaussian_inputs(256, 128, seed=13, heads=2)
+    _bwd_case(Q, K, V, dO, binding.SageParams(1, 2, 256, 128, causal=False))

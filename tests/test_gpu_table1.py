@@ -1,0 +1,57 @@
+"""Accuracy of the GPU path against exact FP64 attention on the paper's sigma sweep.
+
+Paper Table 1 (Sec. 4, "Effect of QK Standard Deviation on Quantization Error") prints the
+cosine similarity and relative L2 error of O, dQ, dK, dV against full-precision attention
+for Gaussian Q, K of standard deviation 1, 3, 5, 8, 10 (sigma_V = sigma_dO = 1).  The CPU
+pins hold the oracle to those printed values; this test holds the HIP kernels, called through
+the C ABI, to the same values with the same bands: N = 1024, d = 64, non-causal, K-smoothing on,
+four seeds averaged (the table does not state its shape; see the oracle pin for that reading).
+"""
+import math
+import os
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2603_02170_amd import binding, synth
+from fpa_ref import cos_sim, fpa_backward, rel_l2
+from gpu_common import to_np
+
+pytestmark = pytest.mark.gpu
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def test_table1_sigma_sweep_on_the_gpu_path():
+    rows = [l.split() for l in open(os.path.join(GOLDEN, "table1_qk_sigma.txt")) if l.strip() and not l.startswith("#")]
+    N, d, seeds = 1024, 64, 4
+    names = ("O", "dQ", "dK", "dV")
+    p = binding.SageParams(1, seeds, N, d, causal=False)
+    for row in rows:
+        sigma = float(row[0])
+        paper = dict(zip(names, [(float(row[1 + 2 * i]), float(row[2 + 2 * i])) for i in range(4)]))
+        # one launch per sigma: the four seeds are four heads
+        Q, K, V, dO = synth.gaussian_inputs(N, d, sigma_qk=sigma, seed=1000 + int(sigma), heads=seeds)
+        Qd, Kd, Vd, dOd = (t.cuda() for t in (Q, K, V, dO))
+        O, L = binding.sagebwd_fwd(Qd, Kd, Vd, p)
+        dQ, dK, dV = binding.sagebwd_bwd(Qd, Kd, Vd, O, dOd, L, p)
+        torch.cuda.synchronize()
+        got = dict(O=to_np(O), dQ=to_np(dQ), dK=to_np(dK), dV=to_np(dV))
+        acc = {n: [] for n in names}
+        for h in range(seeds):
+            ref = fpa_backward(to_np(Q)[0, h], to_np(K)[0, h], to_np(V)[0, h], to_np(dO)[0, h], False, 1 / math.sqrt(d))
+            for n in names:
+                acc[n].append((cos_sim(got[n][0, h], ref[n]), rel_l2(got[n][0, h], ref[n])))
+        for n in names:
+            c, e = np.mean(acc[n], axis=0)
+            pc, pe = paper[n]
+            if sigma == 1:
+                # bf16 outputs add a rounding error of about 2^-9 relative, visible at this level only
+                if n == "O":
+                    assert abs(e - pe) < 0.3 * pe and c > 0.9997, (sigma, n, c, e)
+                else:
+                    assert pe * 0.8 < e < pe * 3.2 and c > 0.998, (sigma, n, c, e)
+            else:
+                band = 0.15 if sigma < 8 or n in ("O", "dV") else 0.2
+                assert abs(e - pe) < band * pe, (sigma, n, e, pe)
+                assert abs(c - pc) < max(0.001, 0.25 * (1 - pc)), (sigma, n, c, pc)
