@@ -35,7 +35,11 @@
 // one part in 10^4 of a typical tile's contribution.  Measured at N = 8192 against the CPU oracle:
 // relative L1 of O 2.5e-4 (6e-5 when the bias is subtracted after every tile, 4e-4 with a period
 // of 16), an order of magnitude below the rounding of the bf16 output and the 1e-2 tolerance.
+// The logits' accumulators use the same start where the tile scales allow it (SBIAS in fwd_tile;
+// |s| <= 128 * 127 * 127 still fits the binade): O then sits 5e-4 from the oracle, L 4e-5.
 #pragma once
+
+#include <type_traits>
 
 #include "common.h"
 
@@ -70,14 +74,14 @@ __device__ __forceinline__ void pin(float& v) { asm volatile("" : "+v"(v)); }
 
 // S^T accumulators of one 64-key tile (two 32-key blocks), interleaved so that consecutive
 // MFMAs are independent.
-template <int D>
+template <int D, bool SBIAS>
 __device__ __forceinline__ void fwd_s_mfma(const int8_t* __restrict__ Kt, const v4i (&qf)[D / 32], v16i (&sacc)[2],
                                            const int lane) {
   constexpr int KS = D / 32;
 #pragma unroll
   for (int kb = 0; kb < 2; kb++)
 #pragma unroll
-    for (int r = 0; r < 16; r++) sacc[kb][r] = 0;
+    for (int r = 0; r < 16; r++) sacc[kb][r] = SBIAS ? kBiasBits : 0;
 #pragma unroll
   for (int s = 0; s < KS; s++) {
 #pragma unroll
@@ -96,7 +100,7 @@ __device__ __forceinline__ void fwd_s_mfma(const int8_t* __restrict__ Kt, const 
 // chunk pairs one MFMA (and the LDS read of an operand two MFMAs ahead) with the vector work of
 // four logits or of sixteen output values, so that the matrix pipe and the LDS latency hide
 // under the vector instructions of the same wave.
-template <int D, bool QSMOOTH, bool MASK, bool NEXT>
+template <int D, bool QSMOOTH, bool MASK, bool NEXT, bool SBIAS>
 __device__ __forceinline__ void fwd_tile(const int8_t* __restrict__ Knext, const int8_t* __restrict__ Vt,
                                          const v4i (&qf)[D / 32], v16i (&sacc)[2], v16i (&snext)[2],
                                          float (&oacc)[D / 32][16], float& w_bias, float& m_ref, float& l_part,
@@ -117,6 +121,7 @@ __device__ __forceinline__ void fwd_tile(const int8_t* __restrict__ Knext, const
 
   float x[2][16];
   float mloc;   // row max of the tile in the log2 domain
+  float bmax_f = 0.f;   // SBIAS: the row max as the float its bits spell
   if constexpr (!QSMOOTH) {
     // the scale is one positive scalar per tile, so the row max can be taken on the integers
     int mi[2] = {INT_MIN, INT_MIN};
@@ -132,7 +137,10 @@ __device__ __forceinline__ void fwd_tile(const int8_t* __restrict__ Knext, const
         }
         mi[kb] = max(mi[kb], v);
       }
-    mloc = (float)half_swap_max_i32(max(mi[0], mi[1])) * c;
+    // (with SBIAS the accumulators hold B0 + s: the same order, and B0 + s never is INT_MIN)
+    const int mrow = half_swap_max_i32(max(mi[0], mi[1]));
+    mloc = (float)(mrow - (SBIAS ? kBiasBits : 0)) * c;
+    if constexpr (SBIAS) bmax_f = __int_as_float(mrow);
   } else {
     float mf = -INFINITY;
 #pragma unroll
@@ -164,7 +172,13 @@ __device__ __forceinline__ void fwd_tile(const int8_t* __restrict__ Knext, const
     m_ref = m_new;
   }
   const float beta = __builtin_amdgcn_exp2f(mloc - m_ref);
-  const float off = kLog2_127 - mloc;
+  // SBIAS: the logits' accumulators started from the bits of C0, so they read as the floats
+  // C0 + s * 2^-26 and x = s * c + off becomes one FMA on those floats, without a conversion; the
+  // offset is formed from the row max taken the same way, so the largest logit of the row still
+  // lands on log2(127) up to the rounding of the product C0 * 2^26 * c (the caller admits only
+  // scales c for which that is far below the half code that would carry 127 to 128).
+  const float c_eff = SBIAS ? c * kTwo26 : c;
+  const float off = SBIAS ? __builtin_fmaf(-bmax_f, c_eff, kLog2_127) : kLog2_127 - mloc;
   __builtin_amdgcn_sched_barrier(0);
 
   // ---- slots 0..7: P^ = rne(127 exp(S - rowmax)) for four logits each, packed as the B operand;
@@ -192,7 +206,7 @@ __device__ __forceinline__ void fwd_tile(const int8_t* __restrict__ Knext, const
         if (sl < 2) {
           v16i z;
 #pragma unroll
-          for (int r = 0; r < 16; r++) z[r] = 0;
+          for (int r = 0; r < 16; r++) z[r] = SBIAS ? kBiasBits : 0;
           snext[sl & 1] = __builtin_amdgcn_mfma_i32_32x32x32_i8(ka[sl % 3], qf[sl >> 1], z, 0, 0, 0);
         } else {
           snext[sl & 1] = __builtin_amdgcn_mfma_i32_32x32x32_i8(ka[sl % 3], qf[sl >> 1], snext[sl & 1], 0, 0, 0);
@@ -218,7 +232,8 @@ __device__ __forceinline__ void fwd_tile(const int8_t* __restrict__ Knext, const
       for (int b = 0; b < 4; b++) {
         float xv;
         if constexpr (!QSMOOTH) {
-          xv = __builtin_fmaf((float)sacc[kb][4 * aa + b], c, off);
+          if constexpr (SBIAS) xv = __builtin_fmaf(__int_as_float(sacc[kb][4 * aa + b]), c_eff, off);
+          else xv = __builtin_fmaf((float)sacc[kb][4 * aa + b], c, off);
           if constexpr (MASK) xv = sacc[kb][4 * aa + b] == INT_MIN ? -INFINITY : xv;
         } else {
           xv = x[kb][4 * aa + b] + off;
@@ -328,8 +343,6 @@ __global__ void __launch_bounds__(64 * NW, (NW == 4 ? 2 : 1)) sage_fwd_kernel(Fw
   if (n_tiles > 2) stage_load(2, nx2);
   barrier_all_memory();
 
-  v16i sA[2], sB[2];
-  fwd_s_mfma<D>(cur, qf, sA, lane);
 
   // Iteration j: tile j + 3 starts to load into the slot that tile j - 1 occupied (every wave is
   // past the barrier that ended iteration j - 1, so nobody reads it any more); this wave forms
@@ -363,56 +376,73 @@ __global__ void __launch_bounds__(64 * NW, (NW == 4 ? 2 : 1)) sage_fwd_kernel(Fw
       for (int r = 0; r < 16; r++) oacc[cb][r] -= corr;
     w_bias = 0.f;
   };
-  auto full_iter = [&](const int j, v16i (&sc)[2], v16i (&sn)[2]) __attribute__((always_inline)) {
-    const bool issue = j + 3 < n_tiles;
-    if (issue) stage_load(j + 3, nx3);
-    const v2f sc2 = *(const v2f*)(cur + PAIR + wave * 8);
-    fwd_tile<D, QSMOOTH, false, true>(nxt, cur + TILE_BYTES, qf, sc, sn, oacc, w_bias, m_ref, l_part,
-                                      cq * sc2[0], sc2[1], bias_row, j * kBlock, q, lane, h);
-    if ((j & (kBiasPeriod - 1)) == kBiasPeriod - 1) unbias();
-    end_iter(issue);
-  };
-  int j = 0;
-  for (; j + 1 < last; j += 2) {
-    full_iter(j, sA, sB);
-    full_iter(j + 1, sB, sA);
+  // The logits' accumulators can start from the bits of C0 as well (SBIAS, see fwd_tile), which
+  // saves the INT32 -> FP32 conversion of every logit; that needs C0 * 2^26 * c, about 1e7 c, to
+  // stay small against the half code between 127 and 128 in the log2 domain, so the wave takes
+  // that path only if its largest tile scale c is below 1e-3 (QK-normed inputs sit near 1e-4).
+  bool use_sbias = false;
+  if constexpr (!QSMOOTH) {
+    float smax = 0.f;
+    for (int jj = lane; jj < n_tiles; jj += 64) smax = fmaxf(smax, sKh[jj]);
+    use_sbias = cq * wave_max_nonneg_f32(smax) < 1e-3f;
   }
-  if (j < last) {
-    full_iter(j, sA, sB);
-#pragma unroll
-    for (int kb = 0; kb < 2; kb++) sA[kb] = sB[kb];
-    j++;
-  }
-  {
-    const bool issue = j + 3 < n_tiles;
-    if (issue) stage_load(j + 3, nx3);
-    const v2f sc2 = *(const v2f*)(cur + PAIR + wave * 8);
-    fwd_tile<D, QSMOOTH, CAUSAL, false>(nxt, cur + TILE_BYTES, qf, sA, sB, oacc, w_bias, m_ref, l_part,
+  auto run = [&](auto sbias_tag) __attribute__((always_inline)) {
+    constexpr bool SBIAS = decltype(sbias_tag)::value;
+    v16i sA[2], sB[2];
+    fwd_s_mfma<D, SBIAS>(cur, qf, sA, lane);
+    auto full_iter = [&](const int j, v16i (&sc)[2], v16i (&sn)[2]) __attribute__((always_inline)) {
+      const bool issue = j + 3 < n_tiles;
+      if (issue) stage_load(j + 3, nx3);
+      const v2f sc2 = *(const v2f*)(cur + PAIR + wave * 8);
+      fwd_tile<D, QSMOOTH, false, true, SBIAS>(nxt, cur + TILE_BYTES, qf, sc, sn, oacc, w_bias, m_ref, l_part,
                                         cq * sc2[0], sc2[1], bias_row, j * kBlock, q, lane, h);
-    end_iter(issue);
-    j++;
-  }
-  for (; j < n_tiles; j++) {
-    const bool issue = j + 3 < n_tiles;
-    if (issue) stage_load(j + 3, nx3);
-    end_iter(issue);
-  }
-
-  unbias();
-  // ---- epilogue: O = O / l, L = m + log(l) (l carries a factor 127) ----
-  const float l_tot = half_swap_sum_f32(l_part);
-  const float inv_l = 1.0f / l_tot;
-  unsigned short* Oh = args.O + ((size_t)bh * N + q) * D;
-#pragma unroll
-  for (int cb = 0; cb < KS; cb++)
-#pragma unroll
-    for (int aa = 0; aa < 4; aa++) {
-      v4us o;
-#pragma unroll
-      for (int b = 0; b < 4; b++) o[b] = float_to_bf16_bits(oacc[cb][4 * aa + b] * inv_l);
-      *(v4us*)(Oh + 32 * cb + 8 * aa + 4 * h) = o;
+      if ((j & (kBiasPeriod - 1)) == kBiasPeriod - 1) unbias();
+      end_iter(issue);
+    };
+    int j = 0;
+    for (; j + 1 < last; j += 2) {
+      full_iter(j, sA, sB);
+      full_iter(j + 1, sB, sA);
     }
-  if (h == 0) args.LSE[(size_t)bh * N + q] = (m_ref + __builtin_amdgcn_logf(l_tot) - kLog2_127) * kLn2;
+    if (j < last) {
+      full_iter(j, sA, sB);
+#pragma unroll
+      for (int kb = 0; kb < 2; kb++) sA[kb] = sB[kb];
+      j++;
+    }
+    {
+      const bool issue = j + 3 < n_tiles;
+      if (issue) stage_load(j + 3, nx3);
+      const v2f sc2 = *(const v2f*)(cur + PAIR + wave * 8);
+      fwd_tile<D, QSMOOTH, CAUSAL, false, SBIAS>(nxt, cur + TILE_BYTES, qf, sA, sB, oacc, w_bias, m_ref, l_part,
+                                          cq * sc2[0], sc2[1], bias_row, j * kBlock, q, lane, h);
+      end_iter(issue);
+      j++;
+    }
+    for (; j < n_tiles; j++) {
+      const bool issue = j + 3 < n_tiles;
+      if (issue) stage_load(j + 3, nx3);
+      end_iter(issue);
+    }
+    unbias();
+    // ---- epilogue: O = O / l, L = m + log(l) (l carries a factor 127) ----
+    const float l_tot = half_swap_sum_f32(l_part);
+    const float inv_l = 1.0f / l_tot;
+    unsigned short* Oh = args.O + ((size_t)bh * N + q) * D;
+#pragma unroll
+    for (int cb = 0; cb < KS; cb++)
+#pragma unroll
+      for (int aa = 0; aa < 4; aa++) {
+        v4us o;
+#pragma unroll
+        for (int b = 0; b < 4; b++) o[b] = float_to_bf16_bits(oacc[cb][4 * aa + b] * inv_l);
+        *(v4us*)(Oh + 32 * cb + 8 * aa + 4 * h) = o;
+      }
+    if (h == 0) args.LSE[(size_t)bh * N + q] = (m_ref + __builtin_amdgcn_logf(l_tot) - kLog2_127) * kLn2;
+  };
+  // (each path runs to the end of the kernel, so that no register state has to be merged)
+  if (__builtin_amdgcn_readfirstlane((int)use_sbias)) run(std::true_type{});
+  else run(std::false_type{});
 }
 
 }  // namespace sage
