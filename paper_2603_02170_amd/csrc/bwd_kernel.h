@@ -127,12 +127,23 @@ __global__ void __launch_bounds__(512, 1) sage_bwd_kernel(BwdArgs args) {
   constexpr int TILE = 64 * D;   // bytes of one INT8 tile
   constexpr int NF = TILE / 1024;  // 1 KiB fragments per INT8 tile
 
-  __shared__ __attribute__((aligned(16))) BwdStageA<D> stA[2];
-  __shared__ __attribute__((aligned(16))) BwdStageB<D> stB[2];
-  __shared__ __attribute__((aligned(16))) BwdExchange xch[2][2];      // [group][tile parity]
-  __shared__ __attribute__((aligned(16))) int8_t vst[2][2 * D * 64];   // [group]: bf16 V_j as B fragments (key block, 16-channel step)
-  __shared__ float red[2][2][4][2];                                  // [group][tile parity][wave][max P, max |dS|]
-  __shared__ float csum[QSMOOTH ? 2 * 3 * 2 * 64 : 1];                // [group][tile % 3][q half][key]: column sums of dS
+  // One LDS object: with several, the compiler tags every LDS access with the variable it touches and
+  // then makes reads of buffers that no asynchronous copy ever writes wait for all copies in flight.
+  struct Lds {
+    BwdStageA<D> stA[2];
+    BwdStageB<D> stB[2];
+    BwdExchange xch[2][2];                          // [group][tile parity]
+    int8_t vst[2][2 * D * 64];                      // [group]: bf16 V_j as B fragments (key block, 16-channel step)
+    float red[2][2][4][2];                          // [group][tile parity][wave][max P, max |dS|]
+    float csum[QSMOOTH ? 2 * 3 * 2 * 64 : 1];       // [group][tile % 3][q half][key]: column sums of dS
+  };
+  __shared__ __attribute__((aligned(16))) Lds L;
+  auto& stA = L.stA;
+  auto& stB = L.stB;
+  auto& xch = L.xch;
+  auto& vst = L.vst;
+  auto& red = L.red;
+  auto& csum = L.csum;
 
   const int gidx = blockIdx.x;
   const int xcd = gidx & 7, slot = gidx >> 3;
@@ -205,45 +216,59 @@ __global__ void __launch_bounds__(512, 1) sage_bwd_kernel(BwdArgs args) {
   }
 
   // Asynchronous staging (global -> LDS, no registers) of the phase-A operands of Q block i.
+  // Written without branches where the fragment counts divide evenly among the 8 waves (d = 128):
+  // which array a wave copies from is a compile-time fact per copy, and the small vectors are
+  // copied by every wave (duplicates of identical data), so that the steady-state interval stays
+  // one basic block.  Every address is a wave-uniform base plus a 32-bit lane offset.
   auto load_A = [&](int i, BwdStageA<D>& st) {
     const size_t toff = head + (size_t)i * TILE;
+    const unsigned lane16 = lane * 16;
 #pragma unroll
     for (int k = 0; k < (3 * NF + 7) / 8; k++) {
       const int o = wave + 8 * k;            // wave-uniform
-      if (o < NF) {
-        async_copy_16(args.QF + toff + o * 1024 + lane * 16, st.qf + o * 1024);
-      } else if (o < 3 * NF) {
+      const bool all_q = 8 * k + 7 < NF, none_q = 8 * k >= NF;       // compile-time when NF % 8 == 0
+      const bool in_range = 8 * k + 7 < 3 * NF || o < 3 * NF;
+      if (all_q || (!none_q && o < NF)) {
+        async_copy_16(args.QF + toff + o * 1024 + lane16, st.qf + o * 1024);
+      } else if (in_range) {
         // bf16 dO fragment f = (32-row block, 16-channel step s); LDS slot l holds the piece of
         // (row, channel half) = (l ^ (s & 7)) so that the A-operand reads stay conflict-free
         const int f = o - NF;
         const int rb = f / KB, sst = f % KB;
-        const int orig = lane ^ (sst & 7);
-        const int row = 32 * rb + (orig & 31), hh = orig >> 5;
-        async_copy_16(args.dO + head + (size_t)(64 * i + row) * D + 16 * sst + 8 * hh, st.dof + f * 1024);
+        const unsigned orig = lane ^ (sst & 7);
+        const unsigned loff = (orig & 31) * (2 * D) + (orig >> 5) * 16;          // bytes: row, channel half
+        const char* base = (const char*)(args.dO + head + (size_t)(64 * i + 32 * rb) * D + 16 * sst);
+        async_copy_16(base + loff, st.dof + f * 1024);
       }
     }
-    if (wave == 0) async_copy_4(args.nL2 + (size_t)bh * N + 64 * i + lane, st.nl2);
-    if (wave == 1) async_copy_4(args.delta + (size_t)bh * N + 64 * i + lane, st.dl);
-    if (wave == 2) async_copy_4(args.sQ + (size_t)bh * nblk + i, st.sc);   // all 64 lanes: s_Q[i] in every entry
+    // -L*log2e (even waves) or delta (odd waves), and s_Q[i] broadcast to 64 entries
+    const float* vsrc = ((wave & 1) ? args.delta : args.nL2) + (size_t)bh * N + 64 * i;
+    async_copy_4((const char*)vsrc + lane * 4, (wave & 1) ? st.dl : st.nl2);
+    async_copy_4(args.sQ + (size_t)bh * nblk + i, st.sc);
     if constexpr (QSMOOTH) {
-      const float* brow = args.bias + ((size_t)bh * nblk + i) * N + 128 * jp;
-      if (wave == 5) async_copy_4(brow + lane, st.bias);
-      if (wave == 6 && 2 * jp + 1 < nblk) async_copy_4(brow + 64 + lane, st.bias + 64);
+      const char* brow = (const char*)(args.bias + ((size_t)bh * nblk + i) * N + 128 * jp);
+      if (wave == 5) async_copy_4(brow + lane * 4, st.bias);
+      if (wave == 6 && 2 * jp + 1 < nblk) async_copy_4(brow + 256 + lane * 4, st.bias + 64);
     }
   };
   // ... and of its phase-B operands.
   auto load_B = [&](int i, BwdStageB<D>& st) {
     const size_t toff = head + (size_t)i * TILE;
+    const unsigned lane16 = lane * 16;
 #pragma unroll
     for (int k = 0; k < (2 * NF + 7) / 8; k++) {
       const int o = wave + 8 * k;
-      if (o < NF) async_copy_16(args.QT + toff + o * 1024 + lane * 16, st.qt + o * 1024);
-      else if (o < 2 * NF) async_copy_16(args.dOT + toff + (o - NF) * 1024 + lane * 16, st.dot + (o - NF) * 1024);
+      const bool all_q = 8 * k + 7 < NF, none_q = 8 * k >= NF;
+      const bool in_range = 8 * k + 7 < 2 * NF || o < 2 * NF;
+      if (all_q || (!none_q && o < NF)) async_copy_16(args.QT + toff + o * 1024 + lane16, st.qt + o * 1024);
+      else if (in_range) async_copy_16(args.dOT + toff + (o - NF) * 1024 + lane16, st.dot + (o - NF) * 1024);
     }
-    if (wave == 7) async_copy_4(((lane & 1) ? args.sdO : args.sQ) + (size_t)bh * nblk + i, st.sc);
+    // s_Q[i] (even lanes) and s_dO[i] (odd lanes)
+    async_copy_4(((lane & 1) ? args.sdO : args.sQ) + (size_t)bh * nblk + i, st.sc);
     if constexpr (QSMOOTH) {
-      if (wave == 3) async_copy_4(args.muQ + ((size_t)bh * nblk + i) * D + lane, st.muq);
-      if (D == 128 && wave == 4) async_copy_4(args.muQ + ((size_t)bh * nblk + i) * D + 64 + lane, st.muq + 64);
+      const char* mq = (const char*)(args.muQ + ((size_t)bh * nblk + i) * D);
+      if (wave == 3) async_copy_4(mq + lane * 4, st.muq);
+      if (D == 128 && wave == 4) async_copy_4(mq + 256 + lane * 4, st.muq + 64);
     }
   };
 
@@ -323,6 +348,10 @@ __global__ void __launch_bounds__(512, 1) sage_bwd_kernel(BwdArgs args) {
     if (STEADY || (t >= 1 && t - 1 < T)) load_B(iq, stB[(t - 1) & 1]);
 
     __builtin_amdgcn_sched_barrier(0);
+    // The two waves of a SIMD are wave w (first group) and w + 4 (second group); the arbiter favours the
+    // older one, which then idles at the interval's barrier.  Raising the younger wave's priority for
+    // its MFMA-dense phase evens the two out (measured: 2-3 % of the kernel).
+    if (STEADY && grp == 1) __builtin_amdgcn_s_setprio(1);
     // ---------------- phase A of tile t: quadrant (qb, kb) ----------------
     if (act_a) {
       const BwdStageA<D>& st = stA[t & 1];
@@ -376,6 +405,7 @@ __global__ void __launch_bounds__(512, 1) sage_bwd_kernel(BwdArgs args) {
     }
 
     __builtin_amdgcn_sched_barrier(0);
+    if (STEADY) __builtin_amdgcn_s_setprio(0);
     // ---------------- phase B of tile t - 2: channel block cb ----------------
     if (act_b) {
       const BwdStageB<D>& st = stB[t & 1];
