@@ -135,8 +135,9 @@ def main():
         "metric": "attention fwd+bwd TOPS and % of INT8 MFMA peak on one MI355X, N=8192 d=128",
         "value": tops, "unit": "TOPS", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": ms,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int8", "data": "synthetic",
-        "config": {"workload": f"{w.name}: B={w.B} H={w.H} N={w.N} d={w.d} causal={w.causal} bf16 N(0,1) with "
-                               f"QK-norm, K-smoothing on, Q-smoothing off, 64x64 blocks",
+        "config": {"workload": f"{w.name}: B={w.B} H={w.H} N={w.N} d={w.d} causal={w.causal} bf16 N(0,1) "
+                               f"{'with' if w.qk_norm else 'without'} QK-norm, K-smoothing {'on' if w.k_smooth else 'off'}, "
+                               f"Q-smoothing {'on' if w.q_smooth else 'off'}, 64x64 blocks",
                    "work_convention": "fwd 4*BH*N^2*d + bwd 10*BH*N^2*d ops, x0.5 causal"},
         "pct_of_int8_peak": 100.0 * tops / INT8_PEAK_TOPS,
         "fwd_only": {"ms": fwd_ms, "TOPS": fwd_ops / (fwd_ms * 1e-3) / 1e12,

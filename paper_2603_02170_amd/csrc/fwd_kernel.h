@@ -148,7 +148,7 @@ __device__ __forceinline__ void fwd_tile(const int8_t* __restrict__ Knext, const
 #pragma unroll
       for (int aa = 0; aa < 4; aa++) {
         const int key = k0 + 32 * kb + 8 * aa + 4 * h;
-        const v4f b4 = *(const v4f*)(bias_row + key);
+        const v4f b4 = *(const v4f*)(bias_row + (key - k0));   // the tile's 64 biases, staged in LDS
 #pragma unroll
         for (int b = 0; b < 4; b++) {
           float v = __builtin_fmaf((float)sacc[kb][4 * aa + b], c, b4[b]);
@@ -271,7 +271,10 @@ __global__ void __launch_bounds__(64 * NW, (NW == 4 ? 2 : 1)) sage_fwd_kernel(Fw
   constexpr int NFRAG = PAIR / 1024;         // 1 KiB fragments per pair
   constexpr int QT = 32 * NW;                // queries per workgroup
 
-  __shared__ __attribute__((aligned(16))) int8_t lds[4][PAIR + 64];   // K^ | V^ | per-wave (s_K, s_V)
+  // Q-smoothing: the 64 logit biases of each wave's Q block and the tile's keys travel with the tile too
+  constexpr int BIAS_OFF = PAIR + 64;
+  constexpr int SLOT = BIAS_OFF + (QSMOOTH ? NW * 256 : 0);
+  __shared__ __attribute__((aligned(16))) int8_t lds[4][SLOT];   // K^ | V^ | per-wave (s_K, s_V) | per-wave bias row
 
   // XCD-aware mapping: consecutive workgroup ids go round-robin over the 8 XCDs, so all
   // query tiles of one head are given ids with the same residue and share one L2.
@@ -332,6 +335,7 @@ __global__ void __launch_bounds__(64 * NW, (NW == 4 ? 2 : 1)) sage_fwd_kernel(Fw
     }
     // the two block scales of the tile, one private copy per wave (lanes 0 and 1 carry them)
     if (lane < 2) async_copy_4((lane == 0 ? sKh : sVh) + j, dst + PAIR + wave * 8);
+    if constexpr (QSMOOTH) async_copy_4(bias_row + j * kBlock + lane, dst + BIAS_OFF + wave * 256);
   };
 
   int8_t* cur = &lds[0][0];
@@ -352,7 +356,7 @@ __global__ void __launch_bounds__(64 * NW, (NW == 4 ? 2 : 1)) sage_fwd_kernel(Fw
   // register-returning global loads whose waits would also drain the copies.  Every wave of
   // the workgroup runs n_tiles iterations (the barriers must match): its unmasked tiles, its last
   // tile, then iterations that only keep the ring moving.
-  constexpr int CPW = (NFRAG + NW - 1) / NW;   // copies per wave and tile (every wave issues all of them)
+  constexpr int CPW = (NFRAG + NW - 1) / NW + (QSMOOTH ? 1 : 0);   // copies per wave and tile (every wave issues all of them)
   static_assert(NFRAG % NW == 0, "every wave must issue the same number of copies");
   auto end_iter = [&](const bool issued) {
     if (issued) {
@@ -395,7 +399,7 @@ __global__ void __launch_bounds__(64 * NW, (NW == 4 ? 2 : 1)) sage_fwd_kernel(Fw
       if (issue) stage_load(j + 3, nx3);
       const v2f sc2 = *(const v2f*)(cur + PAIR + wave * 8);
       fwd_tile<D, QSMOOTH, false, true, SBIAS>(nxt, cur + TILE_BYTES, qf, sc, sn, oacc, w_bias, m_ref, l_part,
-                                        cq * sc2[0], sc2[1], bias_row, j * kBlock, q, lane, h);
+                                        cq * sc2[0], sc2[1], (const float*)(cur + BIAS_OFF + wave * 256), j * kBlock, q, lane, h);
       if ((j & (kBiasPeriod - 1)) == kBiasPeriod - 1) unbias();
       end_iter(issue);
     };
@@ -415,7 +419,7 @@ __global__ void __launch_bounds__(64 * NW, (NW == 4 ? 2 : 1)) sage_fwd_kernel(Fw
       if (issue) stage_load(j + 3, nx3);
       const v2f sc2 = *(const v2f*)(cur + PAIR + wave * 8);
       fwd_tile<D, QSMOOTH, CAUSAL, false, SBIAS>(nxt, cur + TILE_BYTES, qf, sA, sB, oacc, w_bias, m_ref, l_part,
-                                          cq * sc2[0], sc2[1], bias_row, j * kBlock, q, lane, h);
+                                          cq * sc2[0], sc2[1], (const float*)(cur + BIAS_OFF + wave * 256), j * kBlock, q, lane, h);
       end_iter(issue);
       j++;
     }

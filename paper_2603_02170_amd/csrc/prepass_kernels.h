@@ -282,32 +282,80 @@ __global__ void copy_f32_kernel(const float* __restrict__ in, float* __restrict_
 // ---- Q-smoothing: logit bias table -------------------------------------------------
 // bias[bh][I][k] = sm_scale*log2(e) * mu_Q[I] . K_sm[k]  (the mu_Qi K_sm^T term of the
 // Sec. 3 decomposition; the two mu_K terms are constant along a softmax row and dropped).
-// FP32 from the unquantised K - mu_K.  Causal: blocks I < block(k) are never read.
+// FP32 from the unquantised K - mu_K.  Causal: blocks I < block(k) are never read (nor written).
 template <int D>
 __global__ void __launch_bounds__(256) qsmooth_bias_kernel(const unsigned short* __restrict__ K,
                                                            const float* __restrict__ muK,
                                                            const float* __restrict__ muQ,
                                                            float* __restrict__ bias, int N, int causal,
                                                            float scale_log2e) {
-  __shared__ float ks[64][D + 1];
+  // One workgroup per (key block, head): a [Q blocks] x [64 keys] x [D channels] FP32 product on
+  // the FP32 matrix instruction (32x32x2).  The smoothed keys go through LDS once (coalesced
+  // reads); every wave keeps them as B operands in registers and takes 32 Q blocks at a time as
+  // the A operand.  The contraction order is free, so lane (row, half) pairs channel
+  // 8 v + 4 half + e with step (v, e): both operands then come from 16-byte reads.
+  constexpr int LD = D + 4;                      // floats per LDS row (keeps rows 16-byte aligned)
+  __shared__ __attribute__((aligned(16))) float ks[64 * LD];
   const int t = threadIdx.x;
   const int kblk = blockIdx.x, bh = blockIdx.y;
   const int nblk = N / kBlock;
   const unsigned short* src = K + ((size_t)bh * N + (size_t)kblk * kBlock) * D;
   const float* mk = muK + (size_t)bh * D;
-  for (int i = t; i < 64 * D; i += 256) {
-    const int row = i / D, c = i % D;
-    ks[row][c] = bf16_bits_to_float(src[i]) - mk[c];
+  {
+    constexpr int NCH = 64 * D / 8 / 256;        // 16-byte chunks (8 channels) per thread
+    v8us raw[NCH];
+#pragma unroll
+    for (int u = 0; u < NCH; u++) raw[u] = *(const v8us*)(src + 8 * (t + 256 * u));
+#pragma unroll
+    for (int u = 0; u < NCH; u++) {
+      const int ch = t + 256 * u, row = ch / (D / 8), c0 = 8 * (ch % (D / 8));
+      const v4f m0 = *(const v4f*)(mk + c0), m1 = *(const v4f*)(mk + c0 + 4);
+      v4f f0, f1;
+#pragma unroll
+      for (int e = 0; e < 4; e++) {
+        f0[e] = bf16_bits_to_float(raw[u][e]) - m0[e];
+        f1[e] = bf16_bits_to_float(raw[u][4 + e]) - m1[e];
+      }
+      *(v4f*)(ks + row * LD + c0) = f0;
+      *(v4f*)(ks + row * LD + c0 + 4) = f1;
+    }
   }
   __syncthreads();
-  const int key = t % 64, grp = t / 64;
-  const int first = causal ? kblk : 0;
-  for (int I = first + grp; I < nblk; I += 4) {
-    const float* mq = muQ + ((size_t)bh * nblk + I) * D;
-    float acc = 0.f;
-#pragma unroll 8
-    for (int c = 0; c < D; c++) acc = __builtin_fmaf(mq[c], ks[key][c], acc);
-    bias[((size_t)bh * nblk + I) * N + (size_t)kblk * kBlock + key] = acc * scale_log2e;
+  const int lane = t & 63, r = lane & 31, half = lane >> 5;
+  const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
+  v4f kb[2][D / 8];                              // B operands: keys r and 32 + r
+#pragma unroll
+  for (int kt = 0; kt < 2; kt++)
+#pragma unroll
+    for (int v = 0; v < D / 8; v++) kb[kt][v] = *(const v4f*)(ks + (32 * kt + r) * LD + 8 * v + 4 * half);
+  const int first = causal ? kblk : 0;           // Q blocks below the key block are never read
+  for (int it = first / 32 + wave; 32 * it < nblk; it += 4) {
+    const int I = min(32 * it + r, nblk - 1);    // rows past the end repeat the last one (not stored)
+    const float* mq = muQ + ((size_t)bh * nblk + I) * D + 4 * half;
+    v16f acc[2];
+#pragma unroll
+    for (int kt = 0; kt < 2; kt++)
+#pragma unroll
+      for (int e = 0; e < 16; e++) acc[kt][e] = 0.f;
+#pragma unroll
+    for (int v = 0; v < D / 8; v++) {
+      const v4f a4 = *(const v4f*)(mq + 8 * v);
+#pragma unroll
+      for (int e = 0; e < 4; e++) {
+        acc[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a4[e], kb[0][v][e], acc[0], 0, 0, 0);
+        acc[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a4[e], kb[1][v][e], acc[1], 0, 0, 0);
+      }
+    }
+    // accumulator register e of lane (r, half): Q block 32 it + 8 (e / 4) + 4 half + e % 4, key 32 kt + r
+#pragma unroll
+    for (int e = 0; e < 16; e++) {
+      const int Io = 32 * it + 8 * (e >> 2) + 4 * half + (e & 3);
+      if (Io >= first && Io < nblk) {
+        float* dst = bias + ((size_t)bh * nblk + Io) * N + (size_t)kblk * kBlock + r;
+        dst[0] = acc[0][e] * scale_log2e;
+        dst[32] = acc[1][e] * scale_log2e;
+      }
+    }
   }
 }
 

@@ -42,6 +42,10 @@ WORKLOADS = {
     "headline": Workload("headline", 3, 2, 32, 8192, 128, True),
     # Long context, non-causal, small-magnitude upstream gradient (variance 1e-2).
     "long": Workload("long", 4, 1, 32, 32768, 128, False, do_std=0.1),
+    # The headline shape with Q-smoothing on (the paper's Sec. 5.4 ablation), and at the paper's
+    # other benchmarked head dimension (Sec. 5.5).
+    "headline_qsmooth": Workload("headline_qsmooth", 5, 2, 32, 8192, 128, True, q_smooth=True),
+    "headline_d64": Workload("headline_d64", 6, 2, 32, 8192, 64, True),
 }
 
 
