@@ -264,7 +264,7 @@ __device__ __forceinline__ void fwd_tile(const int8_t* __restrict__ Knext, const
 }
 
 template <int D, bool CAUSAL, bool QSMOOTH, int NW>
-__global__ void __launch_bounds__(64 * NW, (NW == 4 ? 2 : 1)) sage_fwd_kernel(FwdArgs args) {
+__global__ void __launch_bounds__(64 * NW, (NW == 4 ? (D == 64 ? 3 : 2) : 1)) sage_fwd_kernel(FwdArgs args) {
   constexpr int KS = D / 32;                 // k-steps of Q K^T; also channel blocks of O
   constexpr int TILE_BYTES = 64 * D;         // one K^ or V^ tile of 64 keys
   constexpr int PAIR = 2 * TILE_BYTES;       // K^ tile | V^ tile

@@ -211,7 +211,10 @@ int launch_fwd_nw(const FwdArgs& a, int nw, hipStream_t st) {
 
 template <int D>
 int launch_fwd(const FwdArgs& a, bool causal, bool qs, hipStream_t st) {
-  const int nw = pick_fwd_waves(a.N);
+  int nw = pick_fwd_waves(a.N);
+  // d = 64 leaves room for three 4-wave workgroups per CU (168 registers per lane), and three waves
+  // per SIMD hide more of the softmax latency than two (measured 0.68 -> 0.56 ms at B2 H32 N8192)
+  if (D == 64 && nw == 8) nw = 4;
   if (causal) return qs ? launch_fwd_nw<D, true, true>(a, nw, st) : launch_fwd_nw<D, true, false>(a, nw, st);
   return qs ? launch_fwd_nw<D, false, true>(a, nw, st) : launch_fwd_nw<D, false, false>(a, nw, st);
 }
