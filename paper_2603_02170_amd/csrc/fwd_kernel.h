@@ -195,6 +195,10 @@ __device__ __forceinline__ void fwd_tile(const int8_t* __restrict__ Knext, const
   auto pv_slot = [&](int m) { return m < KS ? 4 + m : 8 + (m - KS); };   // slot of P^V^ MFMA m = (kb, cb)
 #pragma unroll
   for (int sl = 0; sl < NSLOT; sl++) {
+    // The softmax slots carry the long dependency chains (max, exp2, pack); a wave in them gets issue
+    // priority over its SIMD neighbour, which is mostly in the matrix-heavy second half (measured: 5-7 %).
+    if (sl == 0) __builtin_amdgcn_s_setprio(1);
+    if (sl == 8) __builtin_amdgcn_s_setprio(0);
     // LDS reads: V^ fragment of the MFMA two slots ahead
 #pragma unroll
     for (int m = 0; m < 2 * KS; m++)
