@@ -78,3 +78,39 @@ def test_long_context_shape_sampled_blocks():
     check_close("dV rows", to_np(dV[b, h])[krows], rV[krows])
     for t in (O, dQ, dK, dV):
         assert torch.isfinite(t.float()).all()
+
+
+@pytest.mark.parametrize("name", ["headline_d64", "headline_qsmooth"])
+def test_headline_variants_sampled_blocks(name):
+    """The headline shape at the paper's other head dimension (d = 64: three forward workgroups
+    per CU) and with Q-smoothing on (bias table, staged bias rows, dK bias branch): full GPU run in
+    the benchmark's launch configuration; on one head the oracle checks sampled Q blocks of O, LSE,
+    dQ and sampled KV blocks of dK, dV (first, interior and last blocks of the causal triangle)."""
+    w = synth.WORKLOADS[name]
+    p = params_for(w)
+    Q, K, V, dO = synth.make_inputs(w)
+    Qd, Kd, Vd, dOd = (t.cuda() for t in (Q, K, V, dO))
+    ws = binding.alloc_workspace(p)
+    O, L = binding.sagebwd_fwd(Qd, Kd, Vd, p, ws)
+    torch.cuda.synchronize()
+    b, h = 1, 7
+    q, k, v, do = (to_np(t[b, h]) for t in (Q, K, V, dO))
+    kw = dict(causal=True, k_smooth=w.k_smooth, q_smooth=w.q_smooth)
+    qblocks = [0, 1, 64, 127]
+    Or, Lr = oracle.forward_head(q, k, v, q_blocks=qblocks, **kw)
+    Og, Lg = to_np(O[b, h]), to_np(L[b, h])
+    rows = np.concatenate([np.arange(64 * i, 64 * i + 64) for i in qblocks])
+    check_close("O rows", Og[rows], Or[rows])
+    assert np.abs(Lg[rows] - Lr[rows]).max() < 2e-3
+    # the backward is fed the GPU forward's own O and L on both sides (L was checked above)
+    dQ, dK, dV = binding.sagebwd_bwd(Qd, Kd, Vd, O, dOd, L, p, ws)
+    torch.cuda.synchronize()
+    rQ, _, _ = oracle.backward_head(q, k, v, Og, do, Lg, q_blocks=qblocks, **kw)
+    check_close("dQ rows", to_np(dQ[b, h])[rows], rQ[rows])
+    kvblocks = [0, 63, 126, 127]
+    _, rK, rV = oracle.backward_head(q, k, v, Og, do, Lg, kv_blocks=kvblocks, **kw)
+    krows = np.concatenate([np.arange(64 * i, 64 * i + 64) for i in kvblocks])
+    check_close("dK rows", to_np(dK[b, h])[krows], rK[krows])
+    check_close("dV rows", to_np(dV[b, h])[krows], rV[krows])
+    for t in (O, dQ, dK, dV):
+        assert torch.isfinite(t.float()).all()
