@@ -291,8 +291,8 @@ __global__ void __launch_bounds__(256) qsmooth_bias_kernel(const unsigned short*
                                                            float scale_log2e) {
   // One workgroup per (key block, head): a [Q blocks] x [64 keys] x [D channels] FP32 product on
   // the FP32 matrix instruction (32x32x2).  The smoothed keys go through LDS once (coalesced
-  // reads); every wave keeps them as B operands in registers and takes 32 Q blocks at a time as
-  // the A operand.  The contraction order is free, so lane (row, half) pairs channel
+  // reads); every wave keeps half of them as B operands in registers and takes 32 Q blocks at a
+  // time as the A operand.  The contraction order is free, so lane (row, half) pairs channel
   // 8 v + 4 half + e with step (v, e): both operands then come from 16-byte reads.
   constexpr int LD = D + 4;                      // floats per LDS row (keeps rows 16-byte aligned)
   __shared__ __attribute__((aligned(16))) float ks[64 * LD];
@@ -323,38 +323,33 @@ __global__ void __launch_bounds__(256) qsmooth_bias_kernel(const unsigned short*
   __syncthreads();
   const int lane = t & 63, r = lane & 31, half = lane >> 5;
   const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
-  v4f kb[2][D / 8];                              // B operands: keys r and 32 + r
+  // wave = (Q-block tile parity, key half): each wave keeps one half of the keys as B operands
+  const int kt = wave & 1;
+  v4f kb[D / 8];                                 // B operands: key 32 kt + r
 #pragma unroll
-  for (int kt = 0; kt < 2; kt++)
-#pragma unroll
-    for (int v = 0; v < D / 8; v++) kb[kt][v] = *(const v4f*)(ks + (32 * kt + r) * LD + 8 * v + 4 * half);
+  for (int v = 0; v < D / 8; v++) kb[v] = *(const v4f*)(ks + (32 * kt + r) * LD + 8 * v + 4 * half);
   const int first = causal ? kblk : 0;           // Q blocks below the key block are never read
-  for (int it = first / 32 + wave; 32 * it < nblk; it += 4) {
+  for (int it = first / 32 + (wave >> 1); 32 * it < nblk; it += 2) {
     const int I = min(32 * it + r, nblk - 1);    // rows past the end repeat the last one (not stored)
     const float* mq = muQ + ((size_t)bh * nblk + I) * D + 4 * half;
-    v16f acc[2];
+    v16f acc[2];                                 // two chains over alternate steps, summed at the end
 #pragma unroll
-    for (int kt = 0; kt < 2; kt++)
+    for (int c = 0; c < 2; c++)
 #pragma unroll
-      for (int e = 0; e < 16; e++) acc[kt][e] = 0.f;
+      for (int e = 0; e < 16; e++) acc[c][e] = 0.f;
 #pragma unroll
     for (int v = 0; v < D / 8; v++) {
       const v4f a4 = *(const v4f*)(mq + 8 * v);
 #pragma unroll
-      for (int e = 0; e < 4; e++) {
-        acc[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a4[e], kb[0][v][e], acc[0], 0, 0, 0);
-        acc[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a4[e], kb[1][v][e], acc[1], 0, 0, 0);
-      }
+      for (int e = 0; e < 4; e++)
+        acc[e & 1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a4[e], kb[v][e], acc[e & 1], 0, 0, 0);
     }
     // accumulator register e of lane (r, half): Q block 32 it + 8 (e / 4) + 4 half + e % 4, key 32 kt + r
 #pragma unroll
     for (int e = 0; e < 16; e++) {
       const int Io = 32 * it + 8 * (e >> 2) + 4 * half + (e & 3);
-      if (Io >= first && Io < nblk) {
-        float* dst = bias + ((size_t)bh * nblk + Io) * N + (size_t)kblk * kBlock + r;
-        dst[0] = acc[0][e] * scale_log2e;
-        dst[32] = acc[1][e] * scale_log2e;
-      }
+      if (Io >= first && Io < nblk)
+        bias[((size_t)bh * nblk + Io) * N + (size_t)kblk * kBlock + 32 * kt + r] = (acc[0][e] + acc[1][e]) * scale_log2e;
     }
   }
 }
