@@ -504,11 +504,18 @@ __global__ void __launch_bounds__(512, 2) sage_bwd_dq_kernel(DqArgs args) {
   constexpr int NPB = KS / 2;              // 32-row blocks per wave (2 for d = 128, 1 for d = 64)
   constexpr int TILE = 64 * D;             // bytes of one K^ tile
   constexpr int DSB = 4096;                // bytes of one psi(dS) tile
-  constexpr int NFRAG = (2 * DSB + TILE) / 1024;
-  constexpr int STAGE = 2 * DSB + TILE + 64;   // dS tile of Q block 0 | of Q block 1 | K^ tile | per-wave (s_dS, s_K)
-  constexpr int CPW_MIN = NFRAG / 8 + 1;   // copies every wave issues per stage (fragments + its scale pair)
+  // Two rings in LDS: the psi(dS) tile pairs come from HBM and need many bytes in flight, the K^
+  // tiles (and the scales) come from L2.  Waves 0..3 issue only psi(dS) copies and waves 4..7 only
+  // K^ copies, so each wave's in-order copy counter tracks one ring and the two prefetch distances
+  // are independent: five stages ahead for psi(dS), two for K^.
+  constexpr int ND = 6, NK = 3;                // ring slots (deeper or shallower rings measured the same)
+  constexpr int DSLOT = 2 * DSB;               // dS tile of Q block 0 | of Q block 1
+  constexpr int KSLOT = TILE + 64;             // K^ tile | s_dS of Q block 0, of Q block 1, s_K
+  constexpr int KCOPIES = TILE / 4096 + 1;     // copies a K^ wave issues per stage
 
-  __shared__ __attribute__((aligned(16))) int8_t lds[4][STAGE];
+  __shared__ __attribute__((aligned(16))) int8_t lds[ND * DSLOT + NK * KSLOT];
+  int8_t* const dsr = lds;
+  int8_t* const ktr = lds + ND * DSLOT;
 
   const int g = blockIdx.x;
   const int xcd = g & 7, slot = g >> 3;
@@ -527,29 +534,35 @@ __global__ void __launch_bounds__(512, 2) sage_bwd_dq_kernel(DqArgs args) {
   const int cb = (D == 128) ? w4 : (w4 & 1);
   const int blk0 = (D == 128) ? 0 : (w4 >> 1);
   const bool valid = i0 + iq < nblk;
-  const int i = valid ? i0 + iq : i0;                  // clamped: an idle wave still copies in bounds
-  const int i1 = i0 + 1 < nblk ? i0 + 1 : i0;
+  const int i = valid ? i0 + iq : i0;
+  const int i1 = i0 + 1 < nblk ? i0 + 1 : i0;          // clamped: the copies stay in bounds
   const size_t head = (size_t)bh * N * D;
   const int n_j = CAUSAL ? (i0 + 2 < nblk ? i0 + 2 : nblk) : nblk;
+  const bool ds_wave = wave < 4;
 
   const int8_t* ds0 = args.dSq + ((size_t)hl * nblk + i0) * nblk * DSB;
   const int8_t* ds1 = args.dSq + ((size_t)hl * nblk + i1) * nblk * DSB;
   const int8_t* kth = args.KT + head;
-  const float* sc_row = args.sdS + ((size_t)hl * nblk + i) * nblk;
-  const float* sKh = args.sK + (size_t)bh * nblk;
+  // per stage lanes 0, 1, 2 fetch s_dS of Q block 0, s_dS of Q block 1, s_K
+  const size_t sc_off = lane == 0 ? ((size_t)hl * nblk + i0) * nblk : ((size_t)hl * nblk + i1) * nblk;
+  const float* sc_src = lane < 2 ? args.sdS + sc_off : args.sK + (size_t)bh * nblk;
 
-  auto stage_load = [&](int j, int8_t* dst) {
-#pragma unroll
-    for (int k = 0; k < (NFRAG + 7) / 8; k++) {
-      const int o = wave + 8 * k;          // wave-uniform
-      if (o < NFRAG) {
-        const int8_t* src = o < 4 ? ds0 + (size_t)j * DSB + o * 1024
-                          : o < 8 ? ds1 + (size_t)j * DSB + (o - 4) * 1024
-                                  : kth + (size_t)j * TILE + (o - 8) * 1024;
-        async_copy_16(src + lane * 16, dst + o * 1024);
-      }
-    }
-    if (lane < 2) async_copy_4((lane == 0 ? sc_row : sKh) + j, dst + 2 * DSB + TILE + wave * 8);
+  // Stage indices past the end are clamped: the copy then re-reads the last stage into a slot that
+  // nobody reads any more, and every wave issues the same number of copies in every iteration.
+  auto load_ds = [&](int j, int sl) __attribute__((always_inline)) {   // waves 0..3: two of the eight 1 KiB fragments each
+    const int jc = j < n_j ? j : n_j - 1;
+    const size_t off = (size_t)jc * DSB + w4 * 1024 + lane * 16;
+    int8_t* dst = dsr + sl * DSLOT + w4 * 1024;
+    async_copy_16(ds0 + off, dst);
+    async_copy_16(ds1 + off, dst + DSB);
+  };
+  auto load_k = [&](int j, int sl) __attribute__((always_inline)) {    // waves 4..7: the K^ fragments, and (all four alike) the scales
+    const int jc = j < n_j ? j : n_j - 1;
+    const int8_t* src = kth + (size_t)jc * TILE + w4 * 1024 + lane * 16;
+    int8_t* dst = ktr + sl * KSLOT + w4 * 1024;
+    async_copy_16(src, dst);
+    if constexpr (TILE / 4096 == 2) async_copy_16(src + 4096, dst + 4096);
+    if (lane < 3) async_copy_4(sc_src + jc, ktr + sl * KSLOT + TILE);
   };
 
   v16f acc[NPB];
@@ -558,27 +571,28 @@ __global__ void __launch_bounds__(512, 2) sage_bwd_dq_kernel(DqArgs args) {
 #pragma unroll
     for (int r = 0; r < 16; r++) acc[t][r] = 0.f;
 
-  int8_t* cur = &lds[0][0];
-  int8_t* nxt = &lds[1][0];
-  int8_t* nx2 = &lds[2][0];
-  int8_t* nx3 = &lds[3][0];
-  stage_load(0, cur);
-  if (n_j > 1) stage_load(1, nxt);
-  if (n_j > 2) stage_load(2, nx2);
+  if (ds_wave) {
+#pragma unroll
+    for (int jj = 0; jj < ND - 1; jj++) load_ds(jj, jj);
+  } else {
+#pragma unroll
+    for (int jj = 0; jj < NK - 1; jj++) load_k(jj, jj);
+  }
   barrier_all_memory();
 
-  // Iteration j: stage j + 3 starts to load into the slot that stage j - 1 occupied; before the
-  // barrier at the end the wave waits until at most the copies of stages j + 2 and j + 3 are
-  // still in flight, i.e. stage j + 1 has landed.
-  bool issued_prev = n_j > 2;
+  // Iteration j: the psi(dS) waves start stage j + 5 and the K^ waves stage j + 2, each into the
+  // slot that stage j - 1 occupied; before the barrier at the end each wave waits until its copies
+  // of stage j + 1 have landed and leaves the younger ones in flight.
+  int sd = 0, sk = 0;                      // slots of stage j
   for (int j = 0; j < n_j; j++) {
-    const bool issue = j + 3 < n_j;
-    if (issue) stage_load(j + 3, nx3);
+    if (ds_wave) load_ds(j + ND - 1, sd == 0 ? ND - 1 : sd - 1);
+    else load_k(j + NK - 1, sk == 0 ? NK - 1 : sk - 1);
     if (valid && (!CAUSAL || j <= i)) {
-      const int8_t* ap = cur + iq * DSB + lane * 16;
-      const int8_t* bp = cur + 2 * DSB + cb * 1024 + lane * 16;
-      const v2f sc2 = *(const v2f*)(cur + 2 * DSB + TILE + wave * 8);
-      const float w = sc2[0] * sc2[1] * args.sm_scale;
+      const int8_t* ap = dsr + sd * DSLOT + iq * DSB + lane * 16;
+      const int8_t* kp = ktr + sk * KSLOT;
+      const int8_t* bp = kp + cb * 1024 + lane * 16;
+      const float* sc = (const float*)(kp + TILE);
+      const float w = sc[iq] * sc[2] * args.sm_scale;
       const v4i b0 = *(const v4i*)(bp);
       const v4i b1 = *(const v4i*)(bp + KS * 1024);
 #pragma unroll
@@ -594,28 +608,33 @@ __global__ void __launch_bounds__(512, 2) sage_bwd_dq_kernel(DqArgs args) {
         for (int r = 0; r < 16; r++) acc[t][r] = __builtin_fmaf((float)q[r], w, acc[t][r]);
       }
     }
-    if (issue && issued_prev) {
-      __builtin_amdgcn_s_waitcnt(0x0F70 | (2 * CPW_MIN));
-      barrier_lds_only();
-    } else {
-      barrier_all_memory();
-    }
-    issued_prev = issue;
-    int8_t* tmp = cur;
-    cur = nxt;
-    nxt = nx2;
-    nx2 = nx3;
-    nx3 = tmp;
+    if (ds_wave) __builtin_amdgcn_s_waitcnt(0x0F70 | (2 * (ND - 2)));
+    else __builtin_amdgcn_s_waitcnt(0x0F70 | (KCOPIES * (NK - 2)));
+    barrier_lds_only();
+    sd = sd == ND - 1 ? 0 : sd + 1;
+    sk = sk == NK - 1 ? 0 : sk + 1;
   }
-  if (!valid) return;
-  // accumulator lane = channel, registers = query rows 8a + 4h + b of the 32-row block
+  barrier_all_memory();    // the clamped copies past the last stage have landed before the workgroup leaves
+  // ---- write dQ (bf16): the accumulators hold one channel per lane and 16 query rows in registers, so
+  // the two 64 x D blocks go through LDS (the rings are drained) and leave as 16-byte row pieces ----
+  constexpr int LDQ = D + 8;                                   // padded row, in bf16 elements
+  static_assert(2 * 64 * LDQ * 2 <= ND * DSLOT + NK * KSLOT, "the dQ staging must fit the rings");
+  unsigned short* stg = (unsigned short*)lds;                  // [Q block][row][LDQ]
+  if (valid) {
 #pragma unroll
-  for (int t = 0; t < NPB; t++) {
-    unsigned short* dst = args.dQ + head + (size_t)(64 * i + 32 * (blk0 + t) + 4 * h) * D + 32 * cb + ll;
+    for (int t = 0; t < NPB; t++)
 #pragma unroll
-    for (int aa = 0; aa < 4; aa++)
+      for (int aa = 0; aa < 4; aa++)
 #pragma unroll
-      for (int b = 0; b < 4; b++) dst[(size_t)(8 * aa + b) * D] = float_to_bf16_bits(acc[t][4 * aa + b]);
+        for (int b = 0; b < 4; b++)
+          stg[(iq * 64 + 32 * (blk0 + t) + 8 * aa + 4 * h + b) * LDQ + 32 * cb + ll] = float_to_bf16_bits(acc[t][4 * aa + b]);
+  }
+  barrier_lds_only();
+  constexpr int CPR = D / 8;                                   // 16-byte pieces per row
+  for (int c = tid; c < 2 * 64 * CPR; c += 512) {
+    const int qb = c / (64 * CPR), row = (c / CPR) % 64, pc = c % CPR;
+    if (i0 + qb < nblk)
+      *(v8us*)(args.dQ + head + (size_t)(64 * (i0 + qb) + row) * D + 8 * pc) = *(const v8us*)(stg + (qb * 64 + row) * LDQ + 8 * pc);
   }
 }
 
