@@ -14,10 +14,11 @@
 //            tile: dV^T += dO^^T P^, dK^T += Q^^T dS^ (accumulated in FP32 registers with the
 //            per-tile scales).
 // The phases are software-pipelined over ONE workgroup barrier per tile (see the kernel).
-// A second kernel (sage_bwd_dq_kernel) owns one Q block per workgroup and forms
+// A second kernel (sage_bwd_dq_kernel) owns two Q blocks per workgroup and forms
 //   dQ_i = sum_j s_dS(i,j) s_K(j) sm_scale * (dS^_ij K^_j)
 // from the stored INT8 tiles: a plain scaled INT8 GEMM with no atomics, so dQ is
-// deterministic.  (A first version added dQ with FP32 atomics from the first kernel; at
+// deterministic.  It is bound by the memory pipeline (the tiles are read once, from HBM), so
+// its work goes into how the copies are issued and how dQ leaves, not into its arithmetic.  (A first version added dQ with FP32 atomics from the first kernel; at
 // N=8192 the 4.3e9 atomic adds alone took 13 ms.)
 //
 // S is formed untransposed (queries x keys): an accumulator lane then holds one key and 16
@@ -495,9 +496,9 @@ struct DqArgs {
 };
 
 // A workgroup of 8 waves owns TWO Q blocks (128 queries) and walks the KV blocks j.  Per j, the two
-// psi(dS) tiles and the K^ tile (TF layout) are copied global -> LDS asynchronously into a ring of
-// four stages (one barrier per j), so that each byte crosses the memory pipeline once per
-// workgroup; wave (q block, channel block) reads its operands from LDS.
+// psi(dS) tiles and the K^ tile (TF layout) are copied global -> LDS asynchronously into two rings
+// (one barrier per j), so that each byte crosses the memory pipeline once per workgroup; wave
+// (q block, channel block) reads its operands from LDS.
 template <int D, bool CAUSAL>
 __global__ void __launch_bounds__(512, 2) sage_bwd_dq_kernel(DqArgs args) {
   constexpr int KS = D / 32;
