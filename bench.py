@@ -132,7 +132,7 @@ def main():
     elems = w.B * w.H * w.N * w.d
     pre_fwd_bytes = elems * (4 * 2 + 3 * 1)          # read Q, K (twice), V bf16; write three INT8 tensors
     out = {
-        "metric": "attention fwd+bwd TOPS and % of INT8 MFMA peak on one MI355X, N=8192 d=128",
+        "metric": f"attention fwd+bwd TOPS and % of INT8 MFMA peak on one MI355X, N={w.N} d={w.d}",
         "value": tops, "unit": "TOPS", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": ms,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int8", "data": "synthetic",
         "config": {"workload": f"{w.name}: B={w.B} H={w.H} N={w.N} d={w.d} causal={w.causal} bf16 N(0,1) "
