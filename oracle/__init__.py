@@ -10,6 +10,7 @@ from .sage_oracle import (  # noqa: F401
     round_to_bf16,
     key_mean,
     block_mean,
+    pad_rows,
     quantize_blocks,
     prepass_head,
     delta_rows,

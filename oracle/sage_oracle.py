@@ -27,6 +27,13 @@ as float32 arrays), L is float32.
 
 Readings taken where the paper's text is silent or garbled are listed next to
 the code that uses them (R1..R17).
+
+Sequence lengths that are not a multiple of the block (the paper assumes N/B_q and
+N/B_kv integral, Algorithm 1 line 2): the last block is a partial block whose
+missing rows do not exist.  They enter no mean, no absmax, no sum, no softmax.
+The code below writes that as "append zero rows AFTER the smoothing, mask the
+appended keys, drop the appended query rows", which is the same thing: a zero
+row changes no absmax and no integer sum, and a masked key has P = 0.
 """
 from __future__ import annotations
 
@@ -67,10 +74,26 @@ def key_mean(K: np.ndarray) -> np.ndarray:
 
 def block_mean(Q: np.ndarray) -> np.ndarray:
     """mu_{Q_i} = mean_row(Q_i) for every 64-row block (R17: per block, the
-    Sec. 3 definition). Returns [N/64, d] float32 (float64 sum, one rounding)."""
+    Sec. 3 definition); a partial last block is averaged over the rows it has.
+    Returns [ceil(N/64), d] float32 (float64 sum, one rounding)."""
     Q = np.asarray(Q, dtype=_F32)
     n, d = Q.shape
-    return (Q.astype(_F64).reshape(n // BLOCK, BLOCK, d).sum(axis=1) / _F64(BLOCK)).astype(_F32)
+    nb = -(-n // BLOCK)
+    out = np.zeros((nb, d), dtype=_F32)
+    for b in range(nb):
+        rows = Q[b * BLOCK:(b + 1) * BLOCK].astype(_F64)
+        out[b] = (rows.sum(axis=0) / _F64(rows.shape[0])).astype(_F32)
+    return out
+
+
+def pad_rows(X: np.ndarray, n_pad: int) -> np.ndarray:
+    """X [n, ...] with zero rows appended up to n_pad rows (see the module header)."""
+    X = np.asarray(X)
+    if X.shape[0] == n_pad:
+        return X
+    out = np.zeros((n_pad,) + X.shape[1:], dtype=X.dtype)
+    out[:X.shape[0]] = X
+    return out
 
 
 def quantize_blocks(X: np.ndarray):
@@ -119,24 +142,28 @@ def prepass_head(Q, K, V, k_smooth: bool = True, q_smooth: bool = False):
     "Quantization" step, preceded by the smoothing of Sec. 3).
 
     Returns a dict with Qh, sQ, Kh, sK, Vh, sV (int8 / float32), muK [d],
-    muQ [N/64, d] (zeros when the smoothing is off) and Ksm (float32 K - mu_K).
+    muQ [ceil(N/64), d] (zeros when the smoothing is off) and Ksm (float32 K - mu_K).
+    When N is not a multiple of 64 the row-indexed entries have ceil(N/64)*64 rows,
+    the appended ones zero (module header); "n" is the true N.
     """
     Q = np.asarray(Q, dtype=_F32)
     K = np.asarray(K, dtype=_F32)
     V = np.asarray(V, dtype=_F32)
     n, d = Q.shape
-    muK = key_mean(K) if k_smooth else np.zeros(d, dtype=_F32)
+    nb = -(-n // BLOCK)
+    muK = key_mean(K) if k_smooth else np.zeros(d, dtype=_F32)   # over the N tokens that exist
     Ksm = (K - muK[None, :]).astype(_F32)       # f32 subtraction, R6
     if q_smooth:
         muQ = block_mean(Q)
-        Qsm = (Q.reshape(n // BLOCK, BLOCK, d) - muQ[:, None, :]).astype(_F32).reshape(n, d)
+        Qsm = (Q - np.repeat(muQ, BLOCK, axis=0)[:n]).astype(_F32)
     else:
-        muQ = np.zeros((n // BLOCK, d), dtype=_F32)
+        muQ = np.zeros((nb, d), dtype=_F32)
         Qsm = Q
+    Qsm, Ksm, Vp = (pad_rows(x, nb * BLOCK) for x in (Qsm, Ksm, V))
     Qh, sQ = quantize_blocks(Qsm)
     Kh, sK = quantize_blocks(Ksm)
-    Vh, sV = quantize_blocks(V)
-    return dict(Qh=Qh, sQ=sQ, Kh=Kh, sK=sK, Vh=Vh, sV=sV, muK=muK, muQ=muQ, Ksm=Ksm)
+    Vh, sV = quantize_blocks(Vp)
+    return dict(Qh=Qh, sQ=sQ, Kh=Kh, sK=sK, Vh=Vh, sV=sV, muK=muK, muQ=muQ, Ksm=Ksm, n=n)
 
 
 def delta_rows(dO, O) -> np.ndarray:
@@ -179,8 +206,8 @@ def forward_head(Q, K, V, causal: bool = True, k_smooth: bool = True, q_smooth: 
     and leaves the other rows zero (sampling for large N).
     """
     Q = np.asarray(Q, dtype=_F32)
-    n, d = Q.shape
-    assert n % BLOCK == 0
+    n_true, d = Q.shape
+    n = -(-n_true // BLOCK) * BLOCK                   # rows after appending (module header)
     if sm_scale is None:
         sm_scale = 1.0 / np.sqrt(d)
     pp = prepass_head(Q, K, V, k_smooth, q_smooth)
@@ -194,9 +221,10 @@ def forward_head(Q, K, V, causal: bool = True, k_smooth: bool = True, q_smooth: 
         n_keys = i0 + BLOCK if causal else n          # R13: keys k <= i only
         tj = n_keys // BLOCK
         S = _logits_block(pp, i0, n_keys, sm_scale, q_smooth)
+        kk = np.arange(n_keys)
         if causal:
-            kk = np.arange(n_keys)
             S = np.where(kk[None, :] > (i0 + rows)[:, None], -np.inf, S)
+        S = np.where(kk[None, :] >= n_true, -np.inf, S)           # keys that do not exist
         # softmax statistics over the whole row: what m_{i,Tn}, l_{i,Tn} evaluate to (R2, R3)
         m = S.max(axis=1)
         l = np.exp(S - m[:, None]).sum(axis=1)        # unquantised P~ feeds l
@@ -212,6 +240,7 @@ def forward_head(Q, K, V, causal: bool = True, k_smooth: bool = True, q_smooth: 
         PV = np.einsum("qjk,jkc->qjc", Ph, Vh[:tj])   # exact integers
         acc = np.einsum("qj,qjc->qc", w * sV[None, :tj], PV)
         O[i0:i0 + BLOCK] = acc / l[:, None]           # R4: O_i = diag(l)^-1 O_i
+    O, L = O[:n_true], L[:n_true]                     # query rows that do not exist are dropped
     Ob = round_to_bf16(O)
     Lf = L.astype(_F32)
     if return_raw:
@@ -241,12 +270,16 @@ def backward_head(Q, K, V, O, dO, L, causal: bool = True, k_smooth: bool = True,
     the rows of dK and dV that belong to them are complete, dQ is partial.
     """
     Q = np.asarray(Q, dtype=_F32)
-    n, d = Q.shape
-    assert n % BLOCK == 0
+    n_true, d = Q.shape
+    n = -(-n_true // BLOCK) * BLOCK                           # rows after appending (module header)
     if sm_scale is None:
         sm_scale = 1.0 / np.sqrt(d)
     pp = prepass_head(Q, K, V, k_smooth, q_smooth)            # same blocks and scales as forward
-    dOh, sdO = quantize_blocks(np.asarray(dO, dtype=_F32))    # psi(dO_i), per 64-row block
+    dO = pad_rows(np.asarray(dO, dtype=_F32), n)
+    O = pad_rows(np.asarray(O, dtype=_F32), n)
+    V = pad_rows(np.asarray(V, dtype=_F32), n)
+    L = pad_rows(np.asarray(L, dtype=_F32), n)
+    dOh, sdO = quantize_blocks(dO)                            # psi(dO_i), per 64-row block
     delta = delta_rows(dO, O)
     V64 = np.asarray(V, dtype=_F64)
     dO64 = np.asarray(dO, dtype=_F64)
@@ -275,6 +308,8 @@ def backward_head(Q, K, V, O, dO, L, causal: bool = True, k_smooth: bool = True,
         P = np.exp(S - L64[i0:i0 + BLOCK, None])              # P_ij = exp(S_ij - L_i)
         if causal:
             P = np.where(kk[None, :] > (i0 + rows)[:, None], 0.0, P)   # R13: masked entries are 0
+        # keys and query rows that do not exist
+        P = np.where((kk[None, :] >= n_true) | ((i0 + rows)[:, None] >= n_true), 0.0, P)
         dP = dO64[i0:i0 + BLOCK] @ V64[kk].T                  # unquantised matmul (R15)
         dS = P * (dP - delta[i0:i0 + BLOCK, None])
         if intermediates is not None:
@@ -297,6 +332,7 @@ def backward_head(Q, K, V, O, dO, L, causal: bool = True, k_smooth: bool = True,
                 # dK_bias = (dS^T 1) mu_Q^T (ablation section); R17: from the unquantised dS
                 colsum = dS[:, c0:c0 + BLOCK].sum(axis=0)
                 dK[j0:j0 + BLOCK] += _F64(sm_scale) * colsum[:, None] * pp["muQ"][I].astype(_F64)[None, :]
+    dQ, dK, dV = dQ[:n_true], dK[:n_true], dV[:n_true]
     if return_raw:
         return dQ, dK, dV
     return round_to_bf16(dQ), round_to_bf16(dK), round_to_bf16(dV)

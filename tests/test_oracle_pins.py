@@ -401,3 +401,56 @@ def test_brute_force_scalar_transcription():
     g = oracle.backward_head(Q, K, V, Ob, dO, L, causal=True, return_raw=True)
     for a, b in zip(g, (dQ, dK, dV)):
         assert np.allclose(a, b, rtol=1e-9, atol=1e-12)
+
+
+# ------------------------------------------- sequence lengths that are not a multiple of 64
+@pytest.mark.parametrize("causal", [True, False])
+@pytest.mark.parametrize("N,d", [(100, 64), (37, 64), (200, 128)])
+def test_partial_last_block_close_to_exact_attention(N, d, causal):
+    """A partial last block (its missing rows do not exist) still approximates exact attention
+    on the N tokens that do: a missing key mask, a mean or an absmax taken over appended rows,
+    or gradients leaking into them would leave these bounds."""
+    Q, K, V, dO = _rand(N, d, seed=40 + N + causal, qk_norm=True)
+    sc = 1 / math.sqrt(d)
+    O, L = oracle.forward_head(Q, K, V, causal=causal)
+    dQ, dK, dV = oracle.backward_head(Q, K, V, O, dO, L, causal=causal)
+    assert O.shape == (N, d) and L.shape == (N,) and dQ.shape == dK.shape == dV.shape == (N, d)
+    ref = fpa_backward(Q, K, V, dO, causal, sc)
+    for name, got in (("O", O), ("dQ", dQ), ("dK", dK), ("dV", dV)):
+        assert cos_sim(got, ref[name]) > 0.998, name
+        assert rel_l2(got, ref[name]) < 0.07, name
+    shift = sc * (Q.astype(np.float64) @ oracle.key_mean(K).astype(np.float64))
+    assert np.abs(L + shift - ref["L"]).max() < 0.05
+
+
+@pytest.mark.parametrize("causal", [True, False])
+def test_partial_last_block_zero_queries_closed_form(causal):
+    """Q = 0 with N = 150: L_i = log(#visible keys that exist) and O_i is the mean of the
+    dequantised V rows over exactly those keys (the scale of the partial block comes from its
+    22 rows alone)."""
+    N, d = 150, 16
+    _, K, V, _ = _rand(N, d, seed=41)
+    Q = np.zeros((N, d), dtype=np.float32)
+    O, L, Oraw, Lraw = oracle.forward_head(Q, K, V, causal=causal, return_raw=True)
+    Vh, sV = oracle.quantize_blocks(oracle.pad_rows(V, 192))
+    assert sV[2] == np.float32(np.abs(V[128:]).max()) / np.float32(127.0)
+    Vdq = (Vh.astype(np.float64) * np.repeat(sV.astype(np.float64), 64)[:, None])[:N]
+    for i in (0, 63, 64, 127, 128, 149):
+        nvis = i + 1 if causal else N
+        assert math.isclose(Lraw[i], math.log(nvis), abs_tol=1e-12)
+        assert np.allclose(Oraw[i], Vdq[:nvis].mean(0), atol=1e-12)
+
+
+def test_partial_last_block_means_and_prefix_property():
+    """mu_K runs over the N tokens that exist, mu_Q of the partial block over its own rows; and
+    under the causal mask (K-smoothing off, so that nothing couples the rows) the first 64 query
+    rows of an N = 100 problem equal those of the N = 64 problem on the same leading tokens."""
+    N, d = 100, 32
+    Q, K, V, dO = _rand(N, d, seed=42)
+    pp = oracle.prepass_head(Q, K, V, True, True)
+    assert np.array_equal(pp["muK"], (K.astype(np.float64).sum(0) / 100.0).astype(np.float32))
+    assert np.array_equal(pp["muQ"][1], (Q[64:].astype(np.float64).sum(0) / 36.0).astype(np.float32))
+    assert not pp["Kh"][100:].any() and not pp["Qh"][100:].any() and not pp["Vh"][100:].any()
+    O, L = oracle.forward_head(Q, K, V, causal=True, k_smooth=False)
+    O64, L64 = oracle.forward_head(Q[:64], K[:64], V[:64], causal=True, k_smooth=False)
+    assert np.array_equal(O[:64], O64) and np.array_equal(L[:64], L64)
