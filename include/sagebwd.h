@@ -18,8 +18,13 @@
  *   - Return value: SAGEBWD_OK (0) or a negative sagebwd_status.  Arguments are
  *     validated on the host before anything is launched; on error nothing runs.
  *   - Numerics blocks are B_q = B_kv = 64 (one FP32 scale per 64 rows x d channels).
- *   - Supported shapes: d in {64, 128}; N a positive multiple of 64 (the paper
- *     assumes N/B_q and N/B_kv integral, Algorithm 1 line 2); B*H*N*d < 2^40.
+ *   - Supported shapes: d in {64, 128}; N >= 1; B*H*Np*d < 2^40, where Np is N rounded
+ *     up to a multiple of 64.  The paper assumes N/B_q and N/B_kv integral (Algorithm 1
+ *     line 2); for other N the last block is a partial block whose missing rows do not
+ *     exist: they enter no mean, no block maximum, no softmax and receive no gradient.
+ *     (The kernels then run on Np rows with the missing keys masked, and the library
+ *     moves O, LSE, dQ, dK, dV and the backward's V, dO through row-padded copies in the
+ *     workspace: extra traffic that a multiple of 64 does not pay.)
  */
 #ifndef SAGEBWD_H
 #define SAGEBWD_H
@@ -34,7 +39,7 @@ extern "C" {
 typedef enum sagebwd_status {
   SAGEBWD_OK = 0,
   SAGEBWD_INVALID_ARG = -1,        /* null pointer, non-positive size, unknown selector */
-  SAGEBWD_UNSUPPORTED_SHAPE = -2,  /* d not in {64,128}, N not a multiple of 64, ...  */
+  SAGEBWD_UNSUPPORTED_SHAPE = -2,  /* d not in {64,128}, sizes beyond the stated limits */
   SAGEBWD_WORKSPACE_TOO_SMALL = -3,
   SAGEBWD_HIP_ERROR = -4           /* a HIP runtime call or launch failed */
 } sagebwd_status;
@@ -92,8 +97,8 @@ int sagebwd_quantize(const void* Q, const void* K, const void* V, const void* dO
 /*
  * Copy one quantised tensor out of a workspace filled by sagebwd_quantize (or by
  * sagebwd_fwd / sagebwd_bwd, which run the same pre-pass) into row-major form:
- *   q_out      int8    [B, H, N, d]
- *   scale_out  float32 [B, H, N/64]
+ *   q_out      int8    [B, H, Np, d]     (Np = N rounded up to a multiple of 64; rows N..Np-1 are zero)
+ *   scale_out  float32 [B, H, Np/64]
  * Either output may be NULL.  SAGEBWD_TENSOR_DO requires that dO was given.
  * This is a test / inspection hook for the bit-exact part of the contract.
  */
@@ -102,8 +107,9 @@ int sagebwd_export_quantized(const sagebwd_params* params, const void* workspace
                              int8_t* q_out, float* scale_out, void* stream);
 
 /* Copy the smoothing means out of the workspace: mu_K float32 [B, H, d] (zeros when
- * K-smoothing is off), mu_Q float32 [B, H, N/64, d] (only written with
- * SAGEBWD_SMOOTH_Q), delta float32 [B, H, N] (only after a pre-pass that had dO and O).
+ * K-smoothing is off), mu_Q float32 [B, H, Np/64, d] (only written with
+ * SAGEBWD_SMOOTH_Q), delta float32 [B, H, Np] (only after a pre-pass that had dO and O);
+ * Np = N rounded up to a multiple of 64.
  * Any pointer may be NULL. */
 int sagebwd_export_stats(const sagebwd_params* params, const void* workspace,
                          size_t workspace_bytes, float* mu_K, float* mu_Q, float* delta,

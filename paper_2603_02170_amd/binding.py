@@ -135,10 +135,17 @@ def sagebwd_quantize(Q, K, V, p: SageParams, workspace, dO=None, O=None):
                                            _ptr(workspace), workspace.numel(), _stream()), "sagebwd_quantize")
 
 
+def padded_rows(N: int) -> int:
+    """Rows of the workspace tensors: N rounded up to the 64-row block."""
+    return (N + 63) // 64 * 64
+
+
 def sagebwd_export_quantized(p: SageParams, workspace, which: int):
-    """Row-major int8 [B,H,N,d] codes and float32 [B,H,N/64] scales of one quantised tensor."""
-    q = torch.empty((p.B, p.H, p.N, p.d), dtype=torch.int8, device=workspace.device)
-    s = torch.empty((p.B, p.H, p.N // 64), dtype=torch.float32, device=workspace.device)
+    """Row-major int8 [B,H,Np,d] codes and float32 [B,H,Np/64] scales of one quantised tensor
+    (Np = N rounded up to a multiple of 64; rows N..Np-1 are zero)."""
+    Np = padded_rows(p.N)
+    q = torch.empty((p.B, p.H, Np, p.d), dtype=torch.int8, device=workspace.device)
+    s = torch.empty((p.B, p.H, Np // 64), dtype=torch.float32, device=workspace.device)
     cp = p.c()
     _check(load_library().sagebwd_export_quantized(ctypes.byref(cp), _ptr(workspace), workspace.numel(), which,
                                                    _ptr(q), _ptr(s), _stream()), "sagebwd_export_quantized")
@@ -148,8 +155,9 @@ def sagebwd_export_quantized(p: SageParams, workspace, which: int):
 def sagebwd_export_stats(p: SageParams, workspace, want_delta=False):
     dev = workspace.device
     muK = torch.empty((p.B, p.H, p.d), dtype=torch.float32, device=dev)
-    muQ = torch.empty((p.B, p.H, p.N // 64, p.d), dtype=torch.float32, device=dev) if p.q_smooth else None
-    delta = torch.empty((p.B, p.H, p.N), dtype=torch.float32, device=dev) if want_delta else None
+    Np = padded_rows(p.N)
+    muQ = torch.empty((p.B, p.H, Np // 64, p.d), dtype=torch.float32, device=dev) if p.q_smooth else None
+    delta = torch.empty((p.B, p.H, Np), dtype=torch.float32, device=dev) if want_delta else None
     cp = p.c()
     _check(load_library().sagebwd_export_stats(ctypes.byref(cp), _ptr(workspace), workspace.numel(), _ptr(muK),
                                                _ptr(muQ), _ptr(delta), _stream()), "sagebwd_export_stats")

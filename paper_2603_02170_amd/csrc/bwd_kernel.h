@@ -52,7 +52,8 @@ struct BwdArgs {
   int bh0;             // first head of this launch (the scratch above is indexed from it)
   unsigned short* dK;  // bf16 [BH, N, D]
   unsigned short* dV;
-  int BH, N;
+  int BH, N;           // N = rows of the workspace tensors (a multiple of 64)
+  int nvalid;          // keys >= nvalid do not exist (nvalid = N unless the caller's N is not a multiple of 64)
   float sm_scale;
   float scale_log2e;
 };
@@ -82,12 +83,14 @@ struct BwdExchange {          // per group of 4 waves and tile parity
   int8_t dsb[4096];           // psi(dS) B fragments
 };
 
-// phase A element-wise work of one quadrant; MASK = the tile is on the causal diagonal
+// phase A element-wise work of one quadrant; MASK = some entries of the tile are masked: query row
+// qrow0 + 8 aa + b of the tile sees key column kcol only up to column klim_row (the row itself on
+// the causal diagonal, 63 elsewhere) and only if the key exists (kcol < kvalid)
 template <bool MASK, bool QSMOOTH>
 __device__ __forceinline__ void bwd_quadrant(const v16i& sacc, const v16f& dp, const float* __restrict__ nl2,
                                              const float* __restrict__ dl, const float c, const float bias_l,
-                                             const int qrow0, const int kcol, float (&p)[16], float (&ds)[16],
-                                             float& pm, float& dm, float& cs) {
+                                             const int qrow0, const int kcol, const bool diag, const int kvalid,
+                                             float (&p)[16], float (&ds)[16], float& pm, float& dm, float& cs) {
   float pm2[2] = {0.f, 0.f}, dm2[2] = {0.f, 0.f};
   cs = 0.f;
 #pragma unroll
@@ -99,7 +102,7 @@ __device__ __forceinline__ void bwd_quadrant(const v16i& sacc, const v16f& dp, c
       const int r = 4 * aa + b;
       const float off = QSMOOTH ? bias_l + l4[b] : l4[b];
       float pv = __builtin_amdgcn_exp2f(__builtin_fmaf((float)sacc[r], c, off));
-      if constexpr (MASK) pv = (qrow0 + 8 * aa + b) < kcol ? 0.f : pv;
+      if constexpr (MASK) pv = ((diag && (qrow0 + 8 * aa + b) < kcol) || kcol >= kvalid) ? 0.f : pv;
       const float dsv = pv * (dp[r] - d4[b]);
       p[r] = pv;
       ds[r] = dsv;
@@ -167,6 +170,7 @@ __global__ void __launch_bounds__(512, 1) sage_bwd_kernel(BwdArgs args) {
   const int j = 2 * jp + grp;
   const bool gvalid = j < nblk;
   const int jc = gvalid ? j : nblk - 1;                    // clamped: an idle group still loads in bounds
+  const int kvalid = min(64, args.nvalid - 64 * jc);       // key columns of this group's KV block that exist
 
   const size_t head = (size_t)bh * N * D;
   const float sKj = args.sK[(size_t)bh * nblk + jc];
@@ -390,10 +394,11 @@ __global__ void __launch_bounds__(512, 1) sage_bwd_kernel(BwdArgs args) {
       const float* nl2 = st.nl2 + 32 * qb + 4 * h;
       const float* dl = st.dl + 32 * qb + 4 * h;
       float pm, dm, cs;
-      if (!STEADY && CAUSAL && ia == j)
-        bwd_quadrant<true, QSMOOTH>(sacc, dp, nl2, dl, c, bias_l, 32 * qb + 4 * h, 32 * kb + ll, p, ds, pm, dm, cs);
+      if (!STEADY && ((CAUSAL && ia == j) || kvalid < 64))
+        bwd_quadrant<true, QSMOOTH>(sacc, dp, nl2, dl, c, bias_l, 32 * qb + 4 * h, 32 * kb + ll, CAUSAL && ia == j, kvalid,
+                                    p, ds, pm, dm, cs);
       else
-        bwd_quadrant<false, QSMOOTH>(sacc, dp, nl2, dl, c, bias_l, 0, 0, p, ds, pm, dm, cs);
+        bwd_quadrant<false, QSMOOTH>(sacc, dp, nl2, dl, c, bias_l, 0, 0, false, 64, p, ds, pm, dm, cs);
       pm = wave_max_nonneg_f32(pm);
       dm = wave_max_nonneg_f32(dm);
       // every lane stores the same pair (one LDS write, no branch)
@@ -452,7 +457,8 @@ __global__ void __launch_bounds__(512, 1) sage_bwd_kernel(BwdArgs args) {
     barrier_all_memory();   // the interval's LDS traffic, copies and stores are complete
   };
   // steady intervals: t >= 2 (all three tiles exist), tile t above the diagonal and not the last row
-  const int t_steady_end = !gvalid ? 0 : (CAUSAL ? nblk - 1 - j : T - 1);
+  // (a KV block with keys that do not exist masks them in every tile: no branch-free intervals for its group)
+  const int t_steady_end = (!gvalid || kvalid < 64) ? 0 : (CAUSAL ? nblk - 1 - j : T - 1);
   int t = 0;
   for (; t < 2 && t < T + 2; t++) interval(t, std::false_type{});
   for (; t < t_steady_end; t++) interval(t, std::true_type{});

@@ -55,7 +55,8 @@ struct FwdArgs {
   const float* bias;    // Q-smoothing: [BH, N/64, N] = sm_scale*log2e * mu_Qi . K_sm[k], else nullptr
   unsigned short* O;    // bf16 [BH, N, D]
   float* LSE;           // [BH, N]
-  int BH, N;
+  int BH, N;            // N = rows of the workspace tensors (a multiple of 64)
+  int nvalid;           // keys >= nvalid do not exist (nvalid = N unless the caller's N is not a multiple of 64)
   int n_qtiles;         // workgroups per head
   float scale_log2e;    // sm_scale * log2(e)
 };
@@ -296,6 +297,9 @@ __global__ void __launch_bounds__(64 * NW, (NW == 4 ? (D == 64 ? 3 : 2) : 1)) sa
   const int N = args.N;
   const int q0 = qt * QT + 32 * wave;        // first query of this wave
   const int q = q0 + ql;
+  // last visible key of this lane's query: under the causal mask the query itself (a query row
+  // that does not exist may see keys that do not exist: it is dropped anyway), else the last key
+  const int qlim = CAUSAL ? q : args.nvalid - 1;
   const int nblk = N / kBlock;
 
   const int8_t* KFh = args.KF + (size_t)bh * N * D;
@@ -422,8 +426,9 @@ __global__ void __launch_bounds__(64 * NW, (NW == 4 ? (D == 64 ? 3 : 2) : 1)) sa
       const bool issue = j + 3 < n_tiles;
       if (issue) stage_load(j + 3, nx3);
       const v2f sc2 = *(const v2f*)(cur + PAIR + wave * 8);
-      fwd_tile<D, QSMOOTH, CAUSAL, false, SBIAS>(nxt, cur + TILE_BYTES, qf, sA, sB, oacc, w_bias, m_ref, l_part,
-                                          cq * sc2[0], sc2[1], (const float*)(cur + BIAS_OFF + wave * 256), j * kBlock, q, lane, h);
+      // (the last tile always takes the masked path: without the causal mask it hides the keys past nvalid)
+      fwd_tile<D, QSMOOTH, true, false, SBIAS>(nxt, cur + TILE_BYTES, qf, sA, sB, oacc, w_bias, m_ref, l_part,
+                                        cq * sc2[0], sc2[1], (const float*)(cur + BIAS_OFF + wave * 256), j * kBlock, qlim, lane, h);
       end_iter(issue);
       j++;
     }

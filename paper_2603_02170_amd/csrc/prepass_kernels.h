@@ -83,8 +83,11 @@ struct QuantJobs {
   QuantJob job[4];
 };
 
+// N = rows of the caller's tensors, Np = N rounded up to a multiple of 64 = rows of every workspace
+// tensor.  Rows N .. Np-1 do not exist: they are read as zeros AFTER the smoothing (so they change
+// no absmax), enter no mean, get delta = 0 and -L*log2(e) = -inf (P = 0 in the backward).
 template <int D>
-__global__ void __launch_bounds__(256) prepass_quant_kernel(QuantJobs jobs, int N) {
+__global__ void __launch_bounds__(256) prepass_quant_kernel(QuantJobs jobs, int N, int Np) {
   constexpr int CPR = D / 16;            // 16-channel chunks per row
   constexpr int NCH = 64 * CPR / 256;    // chunks per thread (1 for D=64, 2 for D=128)
   constexpr int NTF = 4 * D / 256;       // TF chunks per thread
@@ -96,17 +99,21 @@ __global__ void __launch_bounds__(256) prepass_quant_kernel(QuantJobs jobs, int 
   const QuantJob jb = jobs.job[blockIdx.z];
   const int t = threadIdx.x;
   const int blk = blockIdx.x, bh = blockIdx.y;
-  const int nblk = N / kBlock;
-  const size_t tile_off = ((size_t)bh * N + (size_t)blk * kBlock) * D;
+  const int nblk = Np / kBlock;
+  const size_t tile_off = ((size_t)bh * N + (size_t)blk * kBlock) * D;      // in the caller's tensors
+  const int rows_here = min(kBlock, N - blk * kBlock);                      // rows of this block that exist
 
   float x[NCH][16];
 #pragma unroll
   for (int it = 0; it < NCH; it++) {
     const int c = t + 256 * it;
     const int row = c / CPR, ch = c % CPR;
-    const unsigned short* p = jb.src + tile_off + (size_t)row * D + ch * 16;
-    v8us lo = *(const v8us*)p;
-    v8us hi = *(const v8us*)(p + 8);
+    v8us lo = {0, 0, 0, 0, 0, 0, 0, 0}, hi = {0, 0, 0, 0, 0, 0, 0, 0};
+    if (row < rows_here) {
+      const unsigned short* p = jb.src + tile_off + (size_t)row * D + ch * 16;
+      lo = *(const v8us*)p;
+      hi = *(const v8us*)(p + 8);
+    }
 #pragma unroll
     for (int e = 0; e < 8; e++) {
       x[it][e] = bf16_bits_to_float(lo[e]);
@@ -120,9 +127,12 @@ __global__ void __launch_bounds__(256) prepass_quant_kernel(QuantJobs jobs, int 
     for (int it = 0; it < NCH; it++) {
       const int c = t + 256 * it;
       const int row = c / CPR, ch = c % CPR;
-      const unsigned short* p = jb.O + tile_off + (size_t)row * D + ch * 16;
-      v8us lo = *(const v8us*)p;
-      v8us hi = *(const v8us*)(p + 8);
+      v8us lo = {0, 0, 0, 0, 0, 0, 0, 0}, hi = {0, 0, 0, 0, 0, 0, 0, 0};
+      if (row < rows_here) {
+        const unsigned short* p = jb.O + tile_off + (size_t)row * D + ch * 16;
+        lo = *(const v8us*)p;
+        hi = *(const v8us*)(p + 8);
+      }
       float acc = 0.f;
 #pragma unroll
       for (int e = 0; e < 8; e++) {
@@ -131,27 +141,29 @@ __global__ void __launch_bounds__(256) prepass_quant_kernel(QuantJobs jobs, int 
       }
 #pragma unroll
       for (int off = 1; off < CPR; off <<= 1) acc += __shfl_xor(acc, off, 64);
-      if (ch == 0) jb.delta[(size_t)bh * N + (size_t)blk * kBlock + row] = acc;
+      if (ch == 0) jb.delta[(size_t)bh * Np + (size_t)blk * kBlock + row] = acc;
     }
   }
 
   if (jb.lse != nullptr && t < 64) {
-    const size_t row = (size_t)bh * N + (size_t)blk * kBlock + t;
-    jb.nl2[row] = -jb.lse[row] * 1.4426950408889634f;
+    const size_t row = (size_t)blk * kBlock + t;
+    jb.nl2[(size_t)bh * Np + row] = t < rows_here ? -jb.lse[(size_t)bh * N + row] * 1.4426950408889634f : -INFINITY;
   }
 
   if (jb.mu_head != nullptr) {
 #pragma unroll
     for (int it = 0; it < NCH; it++) {
-      const int ch = (t + 256 * it) % CPR;
+      const int row = (t + 256 * it) / CPR, ch = (t + 256 * it) % CPR;
       const float* mu = jb.mu_head + (size_t)bh * D + ch * 16;
+      if (row < rows_here) {
 #pragma unroll
-      for (int e = 0; e < 16; e++) x[it][e] = x[it][e] - mu[e];
+        for (int e = 0; e < 16; e++) x[it][e] = x[it][e] - mu[e];
+      }
     }
   }
 
   if (jb.mu_block_out != nullptr) {
-    // block mean over the 64 rows: float64 sum (exact for bf16 data), one rounding.
+    // block mean over the rows of the block that exist: float64 sum (exact for bf16 data), one rounding.
     // Done in 4 passes of 16 rows through `colbuf` to bound LDS.
     double part = 0.0;   // thread t < D accumulates channel t
     for (int pass = 0; pass < 4; pass++) {
@@ -171,16 +183,18 @@ __global__ void __launch_bounds__(256) prepass_quant_kernel(QuantJobs jobs, int 
       }
     }
     if (t < D) {
-      const float m = (float)(part / 64.0);
+      const float m = (float)(part / (double)rows_here);
       mu_s[t] = m;
       jb.mu_block_out[((size_t)bh * nblk + blk) * D + t] = m;
     }
     __syncthreads();
 #pragma unroll
     for (int it = 0; it < NCH; it++) {
-      const int ch = (t + 256 * it) % CPR;
+      const int row = (t + 256 * it) / CPR, ch = (t + 256 * it) % CPR;
+      if (row < rows_here) {
 #pragma unroll
-      for (int e = 0; e < 16; e++) x[it][e] = x[it][e] - mu_s[ch * 16 + e];
+        for (int e = 0; e < 16; e++) x[it][e] = x[it][e] - mu_s[ch * 16 + e];
+      }
     }
   }
 
@@ -199,7 +213,7 @@ __global__ void __launch_bounds__(256) prepass_quant_kernel(QuantJobs jobs, int 
   const float r = nz ? 127.0f / a : 0.f;
   if (t == 0) jb.scale[(size_t)bh * nblk + blk] = s;
 
-  const size_t frag_base = ((size_t)bh * (N / 32) + (size_t)blk * 2) * (D / 32) * 1024;
+  const size_t frag_base = ((size_t)bh * (Np / 32) + (size_t)blk * 2) * (D / 32) * 1024;
 #pragma unroll
   for (int it = 0; it < NCH; it++) {
     const int c = t + 256 * it;
@@ -287,8 +301,9 @@ template <int D>
 __global__ void __launch_bounds__(256) qsmooth_bias_kernel(const unsigned short* __restrict__ K,
                                                            const float* __restrict__ muK,
                                                            const float* __restrict__ muQ,
-                                                           float* __restrict__ bias, int N, int causal,
+                                                           float* __restrict__ bias, int N, int Np, int causal,
                                                            float scale_log2e) {
+  // (N = rows of K as the caller holds it, Np = N rounded up to the block: keys that do not exist count as zero rows.)
   // One workgroup per (key block, head): a [Q blocks] x [64 keys] x [D channels] FP32 product on
   // the FP32 matrix instruction (32x32x2).  The smoothed keys go through LDS once (coalesced
   // reads); every wave keeps half of them as B operands in registers and takes 32 Q blocks at a
@@ -298,23 +313,28 @@ __global__ void __launch_bounds__(256) qsmooth_bias_kernel(const unsigned short*
   __shared__ __attribute__((aligned(16))) float ks[64 * LD];
   const int t = threadIdx.x;
   const int kblk = blockIdx.x, bh = blockIdx.y;
-  const int nblk = N / kBlock;
+  const int nblk = Np / kBlock;
   const unsigned short* src = K + ((size_t)bh * N + (size_t)kblk * kBlock) * D;
+  const int rows_here = min(kBlock, N - kblk * kBlock);
   const float* mk = muK + (size_t)bh * D;
   {
     constexpr int NCH = 64 * D / 8 / 256;        // 16-byte chunks (8 channels) per thread
     v8us raw[NCH];
 #pragma unroll
-    for (int u = 0; u < NCH; u++) raw[u] = *(const v8us*)(src + 8 * (t + 256 * u));
+    for (int u = 0; u < NCH; u++) {
+      raw[u] = v8us{0, 0, 0, 0, 0, 0, 0, 0};
+      if ((t + 256 * u) / (D / 8) < rows_here) raw[u] = *(const v8us*)(src + 8 * (t + 256 * u));
+    }
 #pragma unroll
     for (int u = 0; u < NCH; u++) {
       const int ch = t + 256 * u, row = ch / (D / 8), c0 = 8 * (ch % (D / 8));
+      const bool there = row < rows_here;
       const v4f m0 = *(const v4f*)(mk + c0), m1 = *(const v4f*)(mk + c0 + 4);
       v4f f0, f1;
 #pragma unroll
       for (int e = 0; e < 4; e++) {
-        f0[e] = bf16_bits_to_float(raw[u][e]) - m0[e];
-        f1[e] = bf16_bits_to_float(raw[u][4 + e]) - m1[e];
+        f0[e] = there ? bf16_bits_to_float(raw[u][e]) - m0[e] : 0.f;
+        f1[e] = there ? bf16_bits_to_float(raw[u][4 + e]) - m1[e] : 0.f;
       }
       *(v4f*)(ks + row * LD + c0) = f0;
       *(v4f*)(ks + row * LD + c0 + 4) = f1;
@@ -349,7 +369,33 @@ __global__ void __launch_bounds__(256) qsmooth_bias_kernel(const unsigned short*
     for (int e = 0; e < 16; e++) {
       const int Io = 32 * it + 8 * (e >> 2) + 4 * half + (e & 3);
       if (Io >= first && Io < nblk)
-        bias[((size_t)bh * nblk + Io) * N + (size_t)kblk * kBlock + 32 * kt + r] = (acc[0][e] + acc[1][e]) * scale_log2e;
+        bias[((size_t)bh * nblk + Io) * Np + (size_t)kblk * kBlock + 32 * kt + r] = (acc[0][e] + acc[1][e]) * scale_log2e;
+    }
+  }
+}
+
+// ---- sequence lengths that are not a multiple of the block ---------------------------
+// Rows of `row_bytes` bytes (a multiple of 16, or 4 for the LSE): [BH, n_in, row] -> [BH, n_out, row];
+// n_out > n_in appends zero rows (inputs of the backward), n_out < n_in drops the tail (outputs).
+__global__ void __launch_bounds__(256) resize_rows_kernel(const char* __restrict__ in, char* __restrict__ out,
+                                                          int BH, int n_in, int n_out, int row_bytes) {
+  const int unit = row_bytes % 16 == 0 ? 16 : 4;
+  const size_t per_row = row_bytes / unit;
+  const size_t total = (size_t)BH * n_out * per_row;
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < total; i += stride) {
+    const size_t piece = i % per_row, row = (i / per_row) % n_out, bh = i / (per_row * n_out);
+    const bool there = row < (size_t)n_in;
+    const char* src = in + ((bh * n_in + row) * per_row + piece) * unit;
+    char* dst = out + i * unit;
+    if (unit == 16) {
+      v4i v = {0, 0, 0, 0};
+      if (there) v = *(const v4i*)src;
+      *(v4i*)dst = v;
+    } else {
+      int v = 0;
+      if (there) v = *(const int*)src;
+      *(int*)dst = v;
     }
   }
 }

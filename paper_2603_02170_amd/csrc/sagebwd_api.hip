@@ -21,6 +21,11 @@ size_t g_ds_budget = (size_t)8 << 30;   // bytes of INT8 dS scratch the backward
 
 inline size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
 
+// Rows of every workspace tensor: the caller's N rounded up to the 64-row block.  When the two differ
+// the kernels run on the rounded shape (the rows that do not exist are zero rows behind a key mask)
+// and the library moves the caller's tensors in and out of row-padded copies in the workspace.
+inline int padded_rows(int N) { return (N + 63) / 64 * 64; }
+
 // Byte offsets of every buffer inside the caller's workspace.
 struct Workspace {
   size_t kpart, muK, muQ, sQ, sK, sV, sdO, delta, nl2;
@@ -31,15 +36,20 @@ struct Workspace {
   int heads_per_group;      // the backward runs in groups of heads that share the dS scratch
   size_t bias;              // Q-smoothing: logit bias table [BH, N/64, N]
   size_t colsum;            // Q-smoothing backward: colsum(dS) per (Q block, key) [BH, N/64, N]
+  // only when N is not a multiple of 64: row-padded copies [BH, Np, d] bf16 (and [BH, Np] float)
+  size_t padO, padL;        // forward outputs
+  size_t padV, paddO;       // backward inputs
+  size_t paddQ, paddK, paddV;   // backward outputs
   size_t total;
   int nchunk;
 };
 
 Workspace make_layout(const sagebwd_params& p) {
   Workspace w;
-  const size_t BH = (size_t)p.B * p.H, N = p.N, d = p.d, nblk = N / 64;
+  const size_t BH = (size_t)p.B * p.H, N = padded_rows(p.N), d = p.d, nblk = N / 64;
   const bool qs = (p.smooth & SAGEBWD_SMOOTH_Q) != 0;
-  w.nchunk = (int)((N + kMeanChunkRows - 1) / kMeanChunkRows);
+  const bool ragged = (size_t)p.N != N;
+  w.nchunk = (int)(((size_t)p.N + kMeanChunkRows - 1) / kMeanChunkRows);
   size_t off = 0;
   auto take = [&](size_t bytes) { size_t o = off; off += align_up(bytes); return o; };
   w.kpart = take(BH * w.nchunk * d * sizeof(double));
@@ -66,6 +76,14 @@ Workspace make_layout(const sagebwd_params& p) {
   w.sdS = take(hpg * nblk * nblk * 4);
   w.bias = take(qs ? BH * nblk * N * 4 : 0);
   w.colsum = take(qs ? BH * nblk * N * 4 : 0);
+  const size_t padded = ragged ? BH * N * d * 2 : 0;
+  w.padO = take(padded);
+  w.padL = take(ragged ? BH * N * 4 : 0);
+  w.padV = take(padded);
+  w.paddO = take(padded);
+  w.paddQ = take(padded);
+  w.paddK = take(padded);
+  w.paddV = take(padded);
   w.total = off;
   return w;
 }
@@ -78,8 +96,8 @@ int check_params(const sagebwd_params* p) {
   if (p->causal != 0 && p->causal != 1) return SAGEBWD_INVALID_ARG;
   if (!(p->sm_scale >= 0.f) || isinf(p->sm_scale)) return SAGEBWD_INVALID_ARG;
   if (p->d != 64 && p->d != 128) return SAGEBWD_UNSUPPORTED_SHAPE;
-  if (p->N % 64 != 0) return SAGEBWD_UNSUPPORTED_SHAPE;
-  const double elems = (double)p->B * p->H * (double)p->N * p->d;
+  if (p->N > (1 << 30)) return SAGEBWD_UNSUPPORTED_SHAPE;
+  const double elems = (double)p->B * p->H * (double)padded_rows(p->N) * p->d;
   if (elems >= 1099511627776.0) return SAGEBWD_UNSUPPORTED_SHAPE;
   if ((double)p->B * p->H > 65535.0) return SAGEBWD_UNSUPPORTED_SHAPE;   // grid.y limit
   return SAGEBWD_OK;
@@ -129,7 +147,7 @@ struct ScopedTimer {
 template <int D>
 int run_prepass(const void* Q, const void* K, const void* V, const void* dO, const void* O, const float* LSE,
                 const sagebwd_params& p, char* ws, const Workspace& w, bool for_bwd, hipStream_t st) {
-  const int BH = p.B * p.H, N = p.N, nblk = N / 64;
+  const int BH = p.B * p.H, N = p.N, Np = padded_rows(N), nblk = Np / 64;
   const bool ks = (p.smooth & SAGEBWD_SMOOTH_K) != 0;
   const bool qs = (p.smooth & SAGEBWD_SMOOTH_Q) != 0;
   float* muK = (float*)(ws + w.muK);
@@ -178,12 +196,12 @@ int run_prepass(const void* Q, const void* K, const void* V, const void* dO, con
     jobs.job[nj].nl2 = (float*)(ws + w.nl2);
     nj++;
   }
-  prepass_quant_kernel<D><<<dim3(nblk, BH, nj), 256, 0, st>>>(jobs, N);
+  prepass_quant_kernel<D><<<dim3(nblk, BH, nj), 256, 0, st>>>(jobs, N, Np);
   SAGE_LAUNCH_CHECK();
   if (qs) {
     const float sl2 = logit_scale(p) * 1.4426950408889634f;
     qsmooth_bias_kernel<D><<<dim3(nblk, BH), 256, 0, st>>>(
-        (const unsigned short*)K, muK, (const float*)(ws + w.muQ), (float*)(ws + w.bias), N,
+        (const unsigned short*)K, muK, (const float*)(ws + w.muQ), (float*)(ws + w.bias), N, Np,
         p.causal, sl2);
     SAGE_LAUNCH_CHECK();
   }
@@ -226,6 +244,16 @@ int launch_bwd(const BwdArgs& a, bool causal, bool qs, hipStream_t st) {
     if (qs) sage_bwd_kernel<D, false, true><<<grid, 512, 0, st>>>(a);
     else sage_bwd_kernel<D, false, false><<<grid, 512, 0, st>>>(a);
   }
+  SAGE_LAUNCH_CHECK();
+  return SAGEBWD_OK;
+}
+
+// [BH, n_in, row_bytes] -> [BH, n_out, row_bytes]: appends zero rows or drops the tail
+int resize_rows(const void* in, void* out, int BH, int n_in, int n_out, int row_bytes, hipStream_t st) {
+  const size_t pieces = (size_t)BH * n_out * (row_bytes % 16 == 0 ? row_bytes / 16 : row_bytes / 4);
+  size_t grid = (pieces + 255) / 256;
+  if (grid > 65536) grid = 65536;
+  resize_rows_kernel<<<(unsigned)grid, 256, 0, st>>>((const char*)in, (char*)out, BH, n_in, n_out, row_bytes);
   SAGE_LAUNCH_CHECK();
   return SAGEBWD_OK;
 }
@@ -298,14 +326,15 @@ int sagebwd_export_quantized(const sagebwd_params* params, const void* workspace
   hipStream_t st = (hipStream_t)stream;
   const char* ws = (const char*)workspace;
   const size_t BH = (size_t)params->B * params->H;
+  const int Np = padded_rows(params->N);
   if (q_out != nullptr) {
-    const size_t n_chunks = BH * params->N * params->d / 16;
+    const size_t n_chunks = BH * Np * params->d / 16;
     export_fragments_kernel<<<(unsigned)((n_chunks + 255) / 256), 256, 0, st>>>(
-        (const int8_t*)(ws + qoff), q_out, n_chunks, params->N, params->d, transposed);
+        (const int8_t*)(ws + qoff), q_out, n_chunks, Np, params->d, transposed);
     SAGE_LAUNCH_CHECK();
   }
   if (scale_out != nullptr) {
-    const size_t n = BH * (params->N / 64);
+    const size_t n = BH * (Np / 64);
     copy_f32_kernel<<<(unsigned)((n + 255) / 256), 256, 0, st>>>((const float*)(ws + soff), scale_out, n);
     SAGE_LAUNCH_CHECK();
   }
@@ -329,8 +358,9 @@ int sagebwd_export_stats(const sagebwd_params* params, const void* workspace, si
     copy_f32_kernel<<<grid, 256, 0, st>>>((const float*)(ws + off), out, n);
   };
   if (mu_K != nullptr) { copy(w.muK, mu_K, BH * params->d); SAGE_LAUNCH_CHECK(); }
-  if (mu_Q != nullptr) { copy(w.muQ, mu_Q, BH * (params->N / 64) * params->d); SAGE_LAUNCH_CHECK(); }
-  if (delta != nullptr) { copy(w.delta, delta, BH * params->N); SAGE_LAUNCH_CHECK(); }
+  const size_t Np = padded_rows(params->N);
+  if (mu_Q != nullptr) { copy(w.muQ, mu_Q, BH * (Np / 64) * params->d); SAGE_LAUNCH_CHECK(); }
+  if (delta != nullptr) { copy(w.delta, delta, BH * Np); SAGE_LAUNCH_CHECK(); }
   return SAGEBWD_OK;
 }
 
@@ -359,16 +389,23 @@ int sagebwd_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE
   a.sV = (const float*)(ws + w.sV);
   const bool qs = (params->smooth & SAGEBWD_SMOOTH_Q) != 0;
   a.bias = qs ? (const float*)(ws + w.bias) : nullptr;
-  a.O = (unsigned short*)O;
-  a.LSE = LSE;
+  const int Np = padded_rows(params->N);
+  const bool ragged = Np != params->N;
+  a.O = ragged ? (unsigned short*)(ws + w.padO) : (unsigned short*)O;
+  a.LSE = ragged ? (float*)(ws + w.padL) : LSE;
   a.BH = params->B * params->H;
-  a.N = params->N;
+  a.N = Np;
+  a.nvalid = params->N;
   a.n_qtiles = 0;
   a.scale_log2e = logit_scale(*params) * 1.4426950408889634f;
   {
     ScopedTimer tm(SAGEBWD_KERNEL_FWD, st);
     rc = params->d == 64 ? launch_fwd<64>(a, params->causal != 0, qs, st)
                          : launch_fwd<128>(a, params->causal != 0, qs, st);
+    if (rc == SAGEBWD_OK && ragged) {
+      rc = resize_rows(a.O, O, a.BH, Np, params->N, params->d * 2, st);
+      if (rc == SAGEBWD_OK) rc = resize_rows(a.LSE, LSE, a.BH, Np, params->N, 4, st);
+    }
   }
   return rc;
 }
@@ -385,21 +422,28 @@ int sagebwd_bwd(const void* Q, const void* K, const void* V, const void* O, cons
   if (workspace_bytes < w.total) return SAGEBWD_WORKSPACE_TOO_SMALL;
   hipStream_t st = (hipStream_t)stream;
   char* ws = (char*)workspace;
-  const int BH = params->B * params->H, N = params->N, d = params->d;
+  const int BH = params->B * params->H, N = padded_rows(params->N), d = params->d;
+  const bool ragged = N != params->N;
   const bool qs = (params->smooth & SAGEBWD_SMOOTH_Q) != 0;
   {
     ScopedTimer tm(SAGEBWD_KERNEL_PREPASS_BWD, st);
     rc = d == 64 ? run_prepass<64>(Q, K, V, dO, O, LSE, *params, ws, w, true, st)
                  : run_prepass<128>(Q, K, V, dO, O, LSE, *params, ws, w, true, st);
     if (rc != SAGEBWD_OK) return rc;
+    if (ragged) {
+      // the backward kernel reads bf16 V and dO itself: give it row-padded copies
+      rc = resize_rows(V, ws + w.padV, BH, params->N, N, d * 2, st);
+      if (rc == SAGEBWD_OK) rc = resize_rows(dO, ws + w.paddO, BH, params->N, N, d * 2, st);
+      if (rc != SAGEBWD_OK) return rc;
+    }
   }
   BwdArgs a;
   a.QF = (const int8_t*)(ws + w.QF);
   a.QT = (const int8_t*)(ws + w.QT);
   a.KF = (const int8_t*)(ws + w.KF);
   a.dOT = (const int8_t*)(ws + w.dOT);
-  a.V = (const unsigned short*)V;
-  a.dO = (const unsigned short*)dO;
+  a.V = ragged ? (const unsigned short*)(ws + w.padV) : (const unsigned short*)V;
+  a.dO = ragged ? (const unsigned short*)(ws + w.paddO) : (const unsigned short*)dO;
   a.sQ = (const float*)(ws + w.sQ);
   a.sK = (const float*)(ws + w.sK);
   a.sdO = (const float*)(ws + w.sdO);
@@ -409,9 +453,10 @@ int sagebwd_bwd(const void* Q, const void* K, const void* V, const void* O, cons
   a.muQ = qs ? (const float*)(ws + w.muQ) : nullptr;
   a.dSq = (int8_t*)(ws + w.dSq);
   a.sdS = (float*)(ws + w.sdS);
-  a.dK = (unsigned short*)dK;
-  a.dV = (unsigned short*)dV;
+  a.dK = ragged ? (unsigned short*)(ws + w.paddK) : (unsigned short*)dK;
+  a.dV = ragged ? (unsigned short*)(ws + w.paddV) : (unsigned short*)dV;
   a.N = N;
+  a.nvalid = params->N;
   a.sm_scale = logit_scale(*params);
   a.scale_log2e = a.sm_scale * 1.4426950408889634f;
   DqArgs q;
@@ -419,7 +464,7 @@ int sagebwd_bwd(const void* Q, const void* K, const void* V, const void* O, cons
   q.sdS = a.sdS;
   q.KT = (const int8_t*)(ws + w.KT);
   q.sK = a.sK;
-  q.dQ = (unsigned short*)dQ;
+  q.dQ = ragged ? (unsigned short*)(ws + w.paddQ) : (unsigned short*)dQ;
   q.N = N;
   q.sm_scale = a.sm_scale;
   for (int h0 = 0; h0 < BH; h0 += w.heads_per_group) {
@@ -437,7 +482,13 @@ int sagebwd_bwd(const void* Q, const void* K, const void* V, const void* O, cons
       if (rc != SAGEBWD_OK) return rc;
     }
   }
-  return SAGEBWD_OK;
+  if (ragged) {
+    ScopedTimer tm(SAGEBWD_KERNEL_BWD_DQ, st);
+    rc = resize_rows(q.dQ, dQ, BH, N, params->N, d * 2, st);
+    if (rc == SAGEBWD_OK) rc = resize_rows(a.dK, dK, BH, N, params->N, d * 2, st);
+    if (rc == SAGEBWD_OK) rc = resize_rows(a.dV, dV, BH, N, params->N, d * 2, st);
+  }
+  return rc;
 }
 
 int sagebwd_set_scratch_budget(size_t bytes) {

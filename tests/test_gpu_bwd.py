@@ -50,6 +50,23 @@ def test_bwd_shapes_ragged_tiles(N, d, causal):
     _bwd_case(Q, K, V, dO, binding.SageParams(1, 3, N, d, causal=causal))
 
 
+@pytest.mark.parametrize("N,d,causal", [(100, 64, True), (100, 64, False), (200, 128, True), (333, 128, False),
+                                        (37, 64, False), (65, 64, True), (129, 128, False), (1000, 128, True)])
+def test_bwd_partial_last_block(N, d, causal):
+    """N that is not a multiple of 64: no gradient reaches rows that do not exist, and the keys
+    that do not exist are masked in every tile of the last KV block."""
+    Q, K, V, dO = synth.gaussian_inputs(N, d, sigma_qk=1.5, seed=2 * N + d, heads=3)
+    _bwd_case(Q, K, V, dO, binding.SageParams(1, 3, N, d, causal=causal))
+
+
+def test_bwd_partial_last_block_q_smoothing_and_no_k_smoothing():
+    Q, K, V, dO = synth.gaussian_inputs(300, 128, sigma_qk=1.0, seed=31, heads=2)
+    Q = (Q.float() + torch.linspace(-3, 3, 128)).to(torch.bfloat16)
+    _bwd_case(Q, K, V, dO, binding.SageParams(1, 2, 300, 128, causal=False, q_smooth=True))
+    _bwd_case(Q, K, V, dO, binding.SageParams(1, 2, 300, 128, causal=True, q_smooth=True))
+    _bwd_case(Q, K, V, dO, binding.SageParams(1, 2, 300, 128, causal=False, k_smooth=False))
+
+
 def test_bwd_q_smoothing():
     Q, K, V, dO = synth.gaussian_inputs(512, 128, sigma_qk=1.0, seed=3, heads=2)
     Q = (Q.float() + torch.linspace(-3, 3, 128)).to(torch.bfloat16)

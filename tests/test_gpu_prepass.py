@@ -13,16 +13,17 @@ pytestmark = pytest.mark.gpu
 
 def _oracle_prepass(Q, K, V, dO, p):
     B, H, N, d = Q.shape
-    out = {k: np.zeros((B, H, N, d), np.int8) for k in ("Qh", "Kh", "Vh", "dOh")}
-    out.update({k: np.zeros((B, H, N // 64), np.float32) for k in ("sQ", "sK", "sV", "sdO")})
+    Np = -(-N // 64) * 64      # the exported tensors have N rounded up to the block; the extra rows are zero
+    out = {k: np.zeros((B, H, Np, d), np.int8) for k in ("Qh", "Kh", "Vh", "dOh")}
+    out.update({k: np.zeros((B, H, Np // 64), np.float32) for k in ("sQ", "sK", "sV", "sdO")})
     out["muK"] = np.zeros((B, H, d), np.float32)
-    out["muQ"] = np.zeros((B, H, N // 64, d), np.float32)
+    out["muQ"] = np.zeros((B, H, Np // 64, d), np.float32)
     for b in range(B):
         for h in range(H):
             pp = oracle.prepass_head(Q[b, h], K[b, h], V[b, h], p.k_smooth, p.q_smooth)
             for k in ("Qh", "Kh", "Vh", "sQ", "sK", "sV", "muK", "muQ"):
                 out[k][b, h] = pp[k]
-            out["dOh"][b, h], out["sdO"][b, h] = oracle.quantize_blocks(dO[b, h])
+            out["dOh"][b, h], out["sdO"][b, h] = oracle.quantize_blocks(oracle.pad_rows(dO[b, h], Np))
     return out
 
 
@@ -44,8 +45,11 @@ def _run_case(Q, K, V, dO, p):
     if p.q_smooth:
         assert np.array_equal(muQ.cpu().numpy().view(np.uint32), ref["muQ"].view(np.uint32))
     prod = to_np(dO).astype(np.float64) * to_np(Od).astype(np.float64)
+    N = Q.shape[2]
+    delta = delta.cpu().numpy()
     # FP32 accumulation of d terms: error bounded relative to the sum of magnitudes
-    assert (np.abs(delta.cpu().numpy() - prod.sum(-1)) <= 1e-5 * np.abs(prod).sum(-1) + 1e-30).all()
+    assert (np.abs(delta[:, :, :N] - prod.sum(-1)) <= 1e-5 * np.abs(prod).sum(-1) + 1e-30).all()
+    assert not delta[:, :, N:].any()
 
 
 @pytest.mark.parametrize("k_smooth,q_smooth", [(True, False), (False, False), (True, True)])
@@ -61,6 +65,17 @@ def test_prepass_bit_exact_d128_ragged_chunks():
     Q, K, V, dO = (torch.randn(1, 3, 320, 128, generator=g).to(torch.bfloat16) for _ in range(4))
     K = (K.float() + torch.randn(1, 3, 1, 128, generator=g) * 4).to(torch.bfloat16)
     _run_case(Q, K, V, dO, binding.SageParams(1, 3, 320, 128, causal=True))
+
+
+@pytest.mark.parametrize("N,d,q_smooth", [(100, 64, False), (300, 128, True), (37, 128, True), (257, 64, False)])
+def test_prepass_bit_exact_partial_last_block(N, d, q_smooth):
+    """N not a multiple of 64: the means run over the rows that exist, the partial block's scale comes
+    from its own rows, and the rows that do not exist are zero codes."""
+    g = torch.Generator().manual_seed(N)
+    Q, K, V, dO = (torch.randn(1, 2, N, d, generator=g).to(torch.bfloat16) for _ in range(4))
+    K = (K.float() + torch.randn(1, 2, 1, d, generator=g) * 4).to(torch.bfloat16)
+    Q = (Q.float() + torch.linspace(-2, 2, d)).to(torch.bfloat16)
+    _run_case(Q, K, V, dO, binding.SageParams(1, 2, N, d, causal=True, q_smooth=q_smooth))
 
 
 def test_prepass_ties_zero_blocks_and_outliers():
