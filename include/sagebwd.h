@@ -12,7 +12,7 @@
  *     allocates and frees no device memory; scratch lives in a caller-owned
  *     workspace of sagebwd_workspace_bytes() bytes (256-byte aligned).
  *   - Tensors are dense and contiguous: Q, K, V, O, dO, dQ, dK, dV are bf16
- *     [B, H, N, d]; LSE is float32 [B, H, N].
+ *     [B, H, N, d] (or [B, N, H, d], see sagebwd_params.layout); LSE is float32 [B, H, N].
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Work
  *     is enqueued on it and the call returns without synchronising.
  *   - Return value: SAGEBWD_OK (0) or a negative sagebwd_status.  Arguments are
@@ -48,12 +48,18 @@ typedef enum sagebwd_status {
 #define SAGEBWD_SMOOTH_K 1 /* subtract the token mean of K of each head before quantising */
 #define SAGEBWD_SMOOTH_Q 2 /* subtract the mean of each 64-row Q block; logits get the bias back */
 
+/* Layouts of the bf16 tensors (LSE is float32 [B, H, N] in both). */
+#define SAGEBWD_LAYOUT_BHND 0 /* [B, H, N, d]: what the kernels read and write directly */
+#define SAGEBWD_LAYOUT_BNHD 1 /* [B, N, H, d], token-major as most frameworks hold activations: the
+                                 pre-pass reads it in place; O, dQ, dK, dV and the backward's V, dO pass
+                                 through dense copies in the workspace (extra traffic, more workspace) */
+
 typedef struct sagebwd_params {
   int32_t B, H, N, d;
   int32_t causal;  /* 0 / 1: key index <= query index (square self-attention) */
   int32_t smooth;  /* OR of SAGEBWD_SMOOTH_* ; the paper's default is SAGEBWD_SMOOTH_K */
   float sm_scale;  /* logit scale; 0 selects 1/sqrt(d) (paper Sec. 4: S = Q K^T / sqrt(d)) */
-  int32_t reserved; /* must be 0 */
+  int32_t layout;  /* SAGEBWD_LAYOUT_*: how the caller holds Q, K, V, O, dO, dQ, dK, dV */
 } sagebwd_params;
 
 /* Which quantised tensor sagebwd_export_quantized() copies out. */

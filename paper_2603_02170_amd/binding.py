@@ -17,6 +17,7 @@ _LIB = None
 
 SMOOTH_K = 1
 SMOOTH_Q = 2
+LAYOUT_BHND, LAYOUT_BNHD = 0, 1
 
 TENSOR_Q, TENSOR_K, TENSOR_V, TENSOR_DO = 0, 1, 2, 3
 KERNEL_PREPASS_FWD, KERNEL_FWD, KERNEL_PREPASS_BWD, KERNEL_BWD, KERNEL_BWD_DQ = range(5)
@@ -30,7 +31,7 @@ EXPORTS = (
 class _CParams(ctypes.Structure):
     _fields_ = [("B", ctypes.c_int32), ("H", ctypes.c_int32), ("N", ctypes.c_int32), ("d", ctypes.c_int32),
                 ("causal", ctypes.c_int32), ("smooth", ctypes.c_int32), ("sm_scale", ctypes.c_float),
-                ("reserved", ctypes.c_int32)]
+                ("layout", ctypes.c_int32)]
 
 
 @dataclass
@@ -43,11 +44,16 @@ class SageParams:
     k_smooth: bool = True
     q_smooth: bool = False
     sm_scale: float = 0.0   # 0 selects 1/sqrt(d)
+    token_major: bool = False   # the bf16 tensors are [B, N, H, d] instead of [B, H, N, d]
 
     def c(self) -> _CParams:
         return _CParams(self.B, self.H, self.N, self.d, int(self.causal),
                         (SMOOTH_K if self.k_smooth else 0) | (SMOOTH_Q if self.q_smooth else 0),
-                        float(self.sm_scale), 0)
+                        float(self.sm_scale), LAYOUT_BNHD if self.token_major else LAYOUT_BHND)
+
+    def tensor_shape(self):
+        """Shape of Q, K, V, O, dO, dQ, dK, dV as the caller holds them."""
+        return (self.B, self.N, self.H, self.d) if self.token_major else (self.B, self.H, self.N, self.d)
 
 
 def lib_path() -> str:
@@ -124,7 +130,7 @@ def alloc_workspace(p: SageParams, device="cuda"):
 
 
 def sagebwd_quantize(Q, K, V, p: SageParams, workspace, dO=None, O=None):
-    shp = (p.B, p.H, p.N, p.d)
+    shp = p.tensor_shape()
     for t, n in ((Q, "Q"), (K, "K"), (V, "V")):
         _expect(t, torch.bfloat16, shp, n)
     for t, n in ((dO, "dO"), (O, "O")):
@@ -166,7 +172,8 @@ def sagebwd_export_stats(p: SageParams, workspace, want_delta=False):
 
 def sagebwd_fwd(Q, K, V, p: SageParams, workspace=None, O=None, LSE=None):
     """O, LSE = INT8 attention forward.  Allocates outputs / workspace when not given."""
-    shp = (p.B, p.H, p.N, p.d)
+    shp = p.tensor_shape()
+    lshp = (p.B, p.H, p.N)
     for t, n in ((Q, "Q"), (K, "K"), (V, "V")):
         _expect(t, torch.bfloat16, shp, n)
     if workspace is None:
@@ -174,9 +181,9 @@ def sagebwd_fwd(Q, K, V, p: SageParams, workspace=None, O=None, LSE=None):
     if O is None:
         O = torch.empty(shp, dtype=torch.bfloat16, device=Q.device)
     if LSE is None:
-        LSE = torch.empty(shp[:3], dtype=torch.float32, device=Q.device)
+        LSE = torch.empty(lshp, dtype=torch.float32, device=Q.device)
     _expect(O, torch.bfloat16, shp, "O")
-    _expect(LSE, torch.float32, shp[:3], "LSE")
+    _expect(LSE, torch.float32, lshp, "LSE")
     cp = p.c()
     _check(load_library().sagebwd_fwd(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(LSE), ctypes.byref(cp),
                                       _ptr(workspace), workspace.numel(), _stream()), "sagebwd_fwd")
@@ -185,10 +192,10 @@ def sagebwd_fwd(Q, K, V, p: SageParams, workspace=None, O=None, LSE=None):
 
 def sagebwd_bwd(Q, K, V, O, dO, LSE, p: SageParams, workspace=None, dQ=None, dK=None, dV=None):
     """dQ, dK, dV = INT8 attention backward."""
-    shp = (p.B, p.H, p.N, p.d)
+    shp = p.tensor_shape()
     for t, n in ((Q, "Q"), (K, "K"), (V, "V"), (O, "O"), (dO, "dO")):
         _expect(t, torch.bfloat16, shp, n)
-    _expect(LSE, torch.float32, shp[:3], "LSE")
+    _expect(LSE, torch.float32, (p.B, p.H, p.N), "LSE")
     if workspace is None:
         workspace = alloc_workspace(p, Q.device)
     outs = []

@@ -18,9 +18,19 @@ namespace sage {
 
 constexpr int kMeanChunkRows = 256;
 
+// Where row n of head bh = b * H + h of one of the caller's [.., N, d] tensors starts, in elements:
+// dense [B, H, N, d] has strides (H N d, N d, d), token-major [B, N, H, d] has (N H d, d, H d).
+struct RowView {
+  size_t batch_stride, head_stride, row_stride;
+  int H;
+  __host__ __device__ size_t row(int bh, size_t n) const {
+    return (size_t)(bh / H) * batch_stride + (size_t)(bh % H) * head_stride + n * row_stride;
+  }
+};
+
 // ---- K mean, stage 1: float64 column sums of a 256-row chunk ----------------------
 template <int D>
-__global__ void __launch_bounds__(256) kmean_partial_kernel(const unsigned short* __restrict__ K,
+__global__ void __launch_bounds__(256) kmean_partial_kernel(const unsigned short* __restrict__ K, RowView view,
                                                             double* __restrict__ kpart, int N,
                                                             int nchunk) {
   constexpr int TPR = D / 8;          // threads per row, 8 channels (16 bytes) each
@@ -30,13 +40,13 @@ __global__ void __launch_bounds__(256) kmean_partial_kernel(const unsigned short
   const int chunk = blockIdx.x, bh = blockIdx.y;
   const int row0 = chunk * kMeanChunkRows;
   const int rows = min(kMeanChunkRows, N - row0);
-  const unsigned short* base = K + ((size_t)bh * N + row0) * D;
+  const unsigned short* base = K + view.row(bh, row0);
   double acc[8];
 #pragma unroll
   for (int e = 0; e < 8; e++) acc[e] = 0.0;
   const int tr = t / TPR, tc = t % TPR;
   for (int r = tr; r < rows; r += RPP) {
-    v8us v = *(const v8us*)(base + (size_t)r * D + tc * 8);
+    v8us v = *(const v8us*)(base + (size_t)r * view.row_stride + tc * 8);
 #pragma unroll
     for (int e = 0; e < 8; e++) acc[e] += (double)bf16_bits_to_float(v[e]);
   }
@@ -87,7 +97,7 @@ struct QuantJobs {
 // tensor.  Rows N .. Np-1 do not exist: they are read as zeros AFTER the smoothing (so they change
 // no absmax), enter no mean, get delta = 0 and -L*log2(e) = -inf (P = 0 in the backward).
 template <int D>
-__global__ void __launch_bounds__(256) prepass_quant_kernel(QuantJobs jobs, int N, int Np) {
+__global__ void __launch_bounds__(256) prepass_quant_kernel(QuantJobs jobs, RowView view, int N, int Np) {
   constexpr int CPR = D / 16;            // 16-channel chunks per row
   constexpr int NCH = 64 * CPR / 256;    // chunks per thread (1 for D=64, 2 for D=128)
   constexpr int NTF = 4 * D / 256;       // TF chunks per thread
@@ -100,7 +110,7 @@ __global__ void __launch_bounds__(256) prepass_quant_kernel(QuantJobs jobs, int 
   const int t = threadIdx.x;
   const int blk = blockIdx.x, bh = blockIdx.y;
   const int nblk = Np / kBlock;
-  const size_t tile_off = ((size_t)bh * N + (size_t)blk * kBlock) * D;      // in the caller's tensors
+  const size_t tile_off = view.row(bh, (size_t)blk * kBlock);               // in the caller's tensors
   const int rows_here = min(kBlock, N - blk * kBlock);                      // rows of this block that exist
 
   float x[NCH][16];
@@ -110,7 +120,7 @@ __global__ void __launch_bounds__(256) prepass_quant_kernel(QuantJobs jobs, int 
     const int row = c / CPR, ch = c % CPR;
     v8us lo = {0, 0, 0, 0, 0, 0, 0, 0}, hi = {0, 0, 0, 0, 0, 0, 0, 0};
     if (row < rows_here) {
-      const unsigned short* p = jb.src + tile_off + (size_t)row * D + ch * 16;
+      const unsigned short* p = jb.src + tile_off + (size_t)row * view.row_stride + ch * 16;
       lo = *(const v8us*)p;
       hi = *(const v8us*)(p + 8);
     }
@@ -129,7 +139,7 @@ __global__ void __launch_bounds__(256) prepass_quant_kernel(QuantJobs jobs, int 
       const int row = c / CPR, ch = c % CPR;
       v8us lo = {0, 0, 0, 0, 0, 0, 0, 0}, hi = {0, 0, 0, 0, 0, 0, 0, 0};
       if (row < rows_here) {
-        const unsigned short* p = jb.O + tile_off + (size_t)row * D + ch * 16;
+        const unsigned short* p = jb.O + tile_off + (size_t)row * view.row_stride + ch * 16;
         lo = *(const v8us*)p;
         hi = *(const v8us*)(p + 8);
       }
@@ -298,7 +308,7 @@ __global__ void copy_f32_kernel(const float* __restrict__ in, float* __restrict_
 // Sec. 3 decomposition; the two mu_K terms are constant along a softmax row and dropped).
 // FP32 from the unquantised K - mu_K.  Causal: blocks I < block(k) are never read (nor written).
 template <int D>
-__global__ void __launch_bounds__(256) qsmooth_bias_kernel(const unsigned short* __restrict__ K,
+__global__ void __launch_bounds__(256) qsmooth_bias_kernel(const unsigned short* __restrict__ K, RowView view,
                                                            const float* __restrict__ muK,
                                                            const float* __restrict__ muQ,
                                                            float* __restrict__ bias, int N, int Np, int causal,
@@ -314,7 +324,7 @@ __global__ void __launch_bounds__(256) qsmooth_bias_kernel(const unsigned short*
   const int t = threadIdx.x;
   const int kblk = blockIdx.x, bh = blockIdx.y;
   const int nblk = Np / kBlock;
-  const unsigned short* src = K + ((size_t)bh * N + (size_t)kblk * kBlock) * D;
+  const unsigned short* src = K + view.row(bh, (size_t)kblk * kBlock);
   const int rows_here = min(kBlock, N - kblk * kBlock);
   const float* mk = muK + (size_t)bh * D;
   {
@@ -323,7 +333,8 @@ __global__ void __launch_bounds__(256) qsmooth_bias_kernel(const unsigned short*
 #pragma unroll
     for (int u = 0; u < NCH; u++) {
       raw[u] = v8us{0, 0, 0, 0, 0, 0, 0, 0};
-      if ((t + 256 * u) / (D / 8) < rows_here) raw[u] = *(const v8us*)(src + 8 * (t + 256 * u));
+      const int ch = t + 256 * u;
+      if (ch / (D / 8) < rows_here) raw[u] = *(const v8us*)(src + (size_t)(ch / (D / 8)) * view.row_stride + 8 * (ch % (D / 8)));
     }
 #pragma unroll
     for (int u = 0; u < NCH; u++) {
@@ -374,20 +385,23 @@ __global__ void __launch_bounds__(256) qsmooth_bias_kernel(const unsigned short*
   }
 }
 
-// ---- sequence lengths that are not a multiple of the block ---------------------------
-// Rows of `row_bytes` bytes (a multiple of 16, or 4 for the LSE): [BH, n_in, row] -> [BH, n_out, row];
-// n_out > n_in appends zero rows (inputs of the backward), n_out < n_in drops the tail (outputs).
-__global__ void __launch_bounds__(256) resize_rows_kernel(const char* __restrict__ in, char* __restrict__ out,
-                                                          int BH, int n_in, int n_out, int row_bytes) {
+// ---- row-padded / re-laid-out copies ---------------------------------------------------
+// Copies rows of `row_bytes` bytes (a multiple of 16, or 4 for the LSE) between two views of a
+// [BH, n, row] tensor: rows past n_in are written as zeros (inputs of the backward when N is not a
+// multiple of 64), rows past n_out are dropped (outputs).  Strides of the views are in bytes.
+__global__ void __launch_bounds__(256) resize_rows_kernel(const char* __restrict__ in, RowView vin,
+                                                          char* __restrict__ out, RowView vout, int BH,
+                                                          int n_in, int n_out, int row_bytes) {
   const int unit = row_bytes % 16 == 0 ? 16 : 4;
   const size_t per_row = row_bytes / unit;
   const size_t total = (size_t)BH * n_out * per_row;
   const size_t stride = (size_t)gridDim.x * blockDim.x;
   for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < total; i += stride) {
-    const size_t piece = i % per_row, row = (i / per_row) % n_out, bh = i / (per_row * n_out);
+    const size_t piece = i % per_row, row = (i / per_row) % n_out;
+    const int bh = (int)(i / (per_row * n_out));
     const bool there = row < (size_t)n_in;
-    const char* src = in + ((bh * n_in + row) * per_row + piece) * unit;
-    char* dst = out + i * unit;
+    const char* src = in + vin.row(bh, row) + piece * unit;
+    char* dst = out + vout.row(bh, row) + piece * unit;
     if (unit == 16) {
       v4i v = {0, 0, 0, 0};
       if (there) v = *(const v4i*)src;

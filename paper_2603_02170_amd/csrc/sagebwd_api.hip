@@ -26,6 +26,28 @@ inline size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
 // and the library moves the caller's tensors in and out of row-padded copies in the workspace.
 inline int padded_rows(int N) { return (N + 63) / 64 * 64; }
 
+// The caller's [.., N, d] tensors in elements of `unit` bytes per channel (2 for bf16; pass unit = 2 * 1
+// and scale for byte views), and the dense [BH, rows, d] tensors of the workspace.
+inline RowView caller_view(const sagebwd_params& p, size_t scale) {
+  const size_t N = p.N, H = p.H, d = p.d;
+  RowView v;
+  v.H = p.H;
+  if (p.layout == SAGEBWD_LAYOUT_BNHD) {
+    v.batch_stride = N * H * d * scale; v.head_stride = d * scale; v.row_stride = H * d * scale;
+  } else {
+    v.batch_stride = H * N * d * scale; v.head_stride = N * d * scale; v.row_stride = d * scale;
+  }
+  return v;
+}
+inline RowView dense_view(int H, size_t rows, size_t row_units) {
+  RowView v;
+  v.H = H;
+  v.batch_stride = (size_t)H * rows * row_units; v.head_stride = rows * row_units; v.row_stride = row_units;
+  return v;
+}
+// the kernels work on dense [BH, Np, d] copies in the workspace unless the caller's tensors already are that
+inline bool staged(const sagebwd_params& p) { return padded_rows(p.N) != p.N || p.layout != SAGEBWD_LAYOUT_BHND; }
+
 // Byte offsets of every buffer inside the caller's workspace.
 struct Workspace {
   size_t kpart, muK, muQ, sQ, sK, sV, sdO, delta, nl2;
@@ -36,7 +58,8 @@ struct Workspace {
   int heads_per_group;      // the backward runs in groups of heads that share the dS scratch
   size_t bias;              // Q-smoothing: logit bias table [BH, N/64, N]
   size_t colsum;            // Q-smoothing backward: colsum(dS) per (Q block, key) [BH, N/64, N]
-  // only when N is not a multiple of 64: row-padded copies [BH, Np, d] bf16 (and [BH, Np] float)
+  // only when N is not a multiple of 64 or the caller's layout is token-major: dense row-padded copies
+  // [BH, Np, d] bf16 (and [BH, Np] float)
   size_t padO, padL;        // forward outputs
   size_t padV, paddO;       // backward inputs
   size_t paddQ, paddK, paddV;   // backward outputs
@@ -48,7 +71,7 @@ Workspace make_layout(const sagebwd_params& p) {
   Workspace w;
   const size_t BH = (size_t)p.B * p.H, N = padded_rows(p.N), d = p.d, nblk = N / 64;
   const bool qs = (p.smooth & SAGEBWD_SMOOTH_Q) != 0;
-  const bool ragged = (size_t)p.N != N;
+  const bool ragged = staged(p);
   w.nchunk = (int)(((size_t)p.N + kMeanChunkRows - 1) / kMeanChunkRows);
   size_t off = 0;
   auto take = [&](size_t bytes) { size_t o = off; off += align_up(bytes); return o; };
@@ -91,7 +114,7 @@ Workspace make_layout(const sagebwd_params& p) {
 int check_params(const sagebwd_params* p) {
   if (p == nullptr) return SAGEBWD_INVALID_ARG;
   if (p->B <= 0 || p->H <= 0 || p->N <= 0 || p->d <= 0) return SAGEBWD_INVALID_ARG;
-  if (p->reserved != 0) return SAGEBWD_INVALID_ARG;
+  if (p->layout != SAGEBWD_LAYOUT_BHND && p->layout != SAGEBWD_LAYOUT_BNHD) return SAGEBWD_INVALID_ARG;
   if ((p->smooth & ~(SAGEBWD_SMOOTH_K | SAGEBWD_SMOOTH_Q)) != 0) return SAGEBWD_INVALID_ARG;
   if (p->causal != 0 && p->causal != 1) return SAGEBWD_INVALID_ARG;
   if (!(p->sm_scale >= 0.f) || isinf(p->sm_scale)) return SAGEBWD_INVALID_ARG;
@@ -150,9 +173,10 @@ int run_prepass(const void* Q, const void* K, const void* V, const void* dO, con
   const int BH = p.B * p.H, N = p.N, Np = padded_rows(N), nblk = Np / 64;
   const bool ks = (p.smooth & SAGEBWD_SMOOTH_K) != 0;
   const bool qs = (p.smooth & SAGEBWD_SMOOTH_Q) != 0;
+  const RowView view = caller_view(p, 1);     // in bf16 elements
   float* muK = (float*)(ws + w.muK);
   if (ks) {
-    kmean_partial_kernel<D><<<dim3(w.nchunk, BH), 256, 0, st>>>((const unsigned short*)K,
+    kmean_partial_kernel<D><<<dim3(w.nchunk, BH), 256, 0, st>>>((const unsigned short*)K, view,
                                                                  (double*)(ws + w.kpart), N, w.nchunk);
     SAGE_LAUNCH_CHECK();
     kmean_final_kernel<<<BH, 128, 0, st>>>((const double*)(ws + w.kpart), muK, N, w.nchunk, D);
@@ -196,12 +220,12 @@ int run_prepass(const void* Q, const void* K, const void* V, const void* dO, con
     jobs.job[nj].nl2 = (float*)(ws + w.nl2);
     nj++;
   }
-  prepass_quant_kernel<D><<<dim3(nblk, BH, nj), 256, 0, st>>>(jobs, N, Np);
+  prepass_quant_kernel<D><<<dim3(nblk, BH, nj), 256, 0, st>>>(jobs, view, N, Np);
   SAGE_LAUNCH_CHECK();
   if (qs) {
     const float sl2 = logit_scale(p) * 1.4426950408889634f;
     qsmooth_bias_kernel<D><<<dim3(nblk, BH), 256, 0, st>>>(
-        (const unsigned short*)K, muK, (const float*)(ws + w.muQ), (float*)(ws + w.bias), N, Np,
+        (const unsigned short*)K, view, muK, (const float*)(ws + w.muQ), (float*)(ws + w.bias), N, Np,
         p.causal, sl2);
     SAGE_LAUNCH_CHECK();
   }
@@ -248,12 +272,13 @@ int launch_bwd(const BwdArgs& a, bool causal, bool qs, hipStream_t st) {
   return SAGEBWD_OK;
 }
 
-// [BH, n_in, row_bytes] -> [BH, n_out, row_bytes]: appends zero rows or drops the tail
-int resize_rows(const void* in, void* out, int BH, int n_in, int n_out, int row_bytes, hipStream_t st) {
+// rows of `row_bytes` bytes from one view of a [BH, n, row] tensor to another: appends zero rows or drops the tail
+int resize_rows(const void* in, const RowView& vin, void* out, const RowView& vout, int BH, int n_in, int n_out,
+                int row_bytes, hipStream_t st) {
   const size_t pieces = (size_t)BH * n_out * (row_bytes % 16 == 0 ? row_bytes / 16 : row_bytes / 4);
   size_t grid = (pieces + 255) / 256;
   if (grid > 65536) grid = 65536;
-  resize_rows_kernel<<<(unsigned)grid, 256, 0, st>>>((const char*)in, (char*)out, BH, n_in, n_out, row_bytes);
+  resize_rows_kernel<<<(unsigned)grid, 256, 0, st>>>((const char*)in, vin, (char*)out, vout, BH, n_in, n_out, row_bytes);
   SAGE_LAUNCH_CHECK();
   return SAGEBWD_OK;
 }
@@ -390,7 +415,7 @@ int sagebwd_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE
   const bool qs = (params->smooth & SAGEBWD_SMOOTH_Q) != 0;
   a.bias = qs ? (const float*)(ws + w.bias) : nullptr;
   const int Np = padded_rows(params->N);
-  const bool ragged = Np != params->N;
+  const bool ragged = staged(*params);
   a.O = ragged ? (unsigned short*)(ws + w.padO) : (unsigned short*)O;
   a.LSE = ragged ? (float*)(ws + w.padL) : LSE;
   a.BH = params->B * params->H;
@@ -403,8 +428,11 @@ int sagebwd_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE
     rc = params->d == 64 ? launch_fwd<64>(a, params->causal != 0, qs, st)
                          : launch_fwd<128>(a, params->causal != 0, qs, st);
     if (rc == SAGEBWD_OK && ragged) {
-      rc = resize_rows(a.O, O, a.BH, Np, params->N, params->d * 2, st);
-      if (rc == SAGEBWD_OK) rc = resize_rows(a.LSE, LSE, a.BH, Np, params->N, 4, st);
+      rc = resize_rows(a.O, dense_view(params->H, Np, params->d * 2), O, caller_view(*params, 2), a.BH, Np, params->N,
+                       params->d * 2, st);
+      if (rc == SAGEBWD_OK)
+        rc = resize_rows(a.LSE, dense_view(params->H, Np, 4), LSE, dense_view(params->H, params->N, 4), a.BH, Np,
+                         params->N, 4, st);
     }
   }
   return rc;
@@ -423,7 +451,8 @@ int sagebwd_bwd(const void* Q, const void* K, const void* V, const void* O, cons
   hipStream_t st = (hipStream_t)stream;
   char* ws = (char*)workspace;
   const int BH = params->B * params->H, N = padded_rows(params->N), d = params->d;
-  const bool ragged = N != params->N;
+  const bool ragged = staged(*params);
+  const RowView cview = caller_view(*params, 2), pview = dense_view(params->H, N, (size_t)d * 2);   // in bytes
   const bool qs = (params->smooth & SAGEBWD_SMOOTH_Q) != 0;
   {
     ScopedTimer tm(SAGEBWD_KERNEL_PREPASS_BWD, st);
@@ -432,8 +461,8 @@ int sagebwd_bwd(const void* Q, const void* K, const void* V, const void* O, cons
     if (rc != SAGEBWD_OK) return rc;
     if (ragged) {
       // the backward kernel reads bf16 V and dO itself: give it row-padded copies
-      rc = resize_rows(V, ws + w.padV, BH, params->N, N, d * 2, st);
-      if (rc == SAGEBWD_OK) rc = resize_rows(dO, ws + w.paddO, BH, params->N, N, d * 2, st);
+      rc = resize_rows(V, cview, ws + w.padV, pview, BH, params->N, N, d * 2, st);
+      if (rc == SAGEBWD_OK) rc = resize_rows(dO, cview, ws + w.paddO, pview, BH, params->N, N, d * 2, st);
       if (rc != SAGEBWD_OK) return rc;
     }
   }
@@ -484,9 +513,9 @@ int sagebwd_bwd(const void* Q, const void* K, const void* V, const void* O, cons
   }
   if (ragged) {
     ScopedTimer tm(SAGEBWD_KERNEL_BWD_DQ, st);
-    rc = resize_rows(q.dQ, dQ, BH, N, params->N, d * 2, st);
-    if (rc == SAGEBWD_OK) rc = resize_rows(a.dK, dK, BH, N, params->N, d * 2, st);
-    if (rc == SAGEBWD_OK) rc = resize_rows(a.dV, dV, BH, N, params->N, d * 2, st);
+    rc = resize_rows(q.dQ, pview, dQ, cview, BH, N, params->N, d * 2, st);
+    if (rc == SAGEBWD_OK) rc = resize_rows(a.dK, pview, dK, cview, BH, N, params->N, d * 2, st);
+    if (rc == SAGEBWD_OK) rc = resize_rows(a.dV, pview, dV, cview, BH, N, params->N, d * 2, st);
   }
   return rc;
 }

@@ -76,5 +76,8 @@ def test_entry_points_reject_bad_arguments_on_the_host(lib):
     bad = SageParams(1, 2, 128, 64).c()
     bad.smooth = 8
     assert lib.sagebwd_fwd(one, one, one, one, one, ctypes.byref(bad), one, 1 << 30, null) == -1
+    bad = SageParams(1, 2, 128, 64).c()
+    bad.layout = 2
+    assert lib.sagebwd_fwd(one, one, one, one, one, ctypes.byref(bad), one, 1 << 30, null) == -1
     tot, cnt = ctypes.c_double(0), ctypes.c_int(0)
     assert lib.sagebwd_read_timing(99, ctypes.byref(tot), ctypes.byref(cnt)) == -1

@@ -126,3 +126,24 @@ def test_bwd_two_steady_intervals_only():
     # N = 256 non-causal: 4 tile rows, the shortest loop that reaches the branch-free interval
     Q, K, V, dO = synth.gaussian_inputs(256, 128, seed=13, heads=2)
     _bwd_case(Q, K, V, dO, binding.SageParams(1, 2, 256, 128, causal=False))
+
+
+@pytest.mark.parametrize("N,d,causal,q_smooth", [(320, 64, True, False), (100, 128, False, False), (256, 128, True, True)])
+def test_token_major_layout_gives_the_same_bits(N, d, causal, q_smooth):
+    """[B, N, H, d] tensors (token-major): forward and backward must return exactly what the
+    [B, H, N, d] call returns on the same values (the same kernels run on dense workspace copies),
+    which the other tests hold to the oracle."""
+    Q, K, V, dO = synth.gaussian_inputs(N, d, sigma_qk=1.5, seed=7 * N + d, heads=6)      # [1, 6, N, d]
+    Q, K, V, dO = (t.reshape(2, 3, N, d).cuda() for t in (Q, K, V, dO))
+    p = binding.SageParams(2, 3, N, d, causal=causal, q_smooth=q_smooth)
+    pt = binding.SageParams(2, 3, N, d, causal=causal, q_smooth=q_smooth, token_major=True)
+    O, L = binding.sagebwd_fwd(Q, K, V, p)
+    dQ, dK, dV = binding.sagebwd_bwd(Q, K, V, O, dO, L, p)
+    tm = lambda t: t.permute(0, 2, 1, 3).contiguous()
+    Ot, Lt = binding.sagebwd_fwd(tm(Q), tm(K), tm(V), pt)
+    dQt, dKt, dVt = binding.sagebwd_bwd(tm(Q), tm(K), tm(V), Ot, tm(dO), Lt, pt)
+    torch.cuda.synchronize()
+    assert Ot.shape == (2, N, 3, d) and Lt.shape == (2, 3, N)
+    assert torch.equal(tm(O), Ot) and torch.equal(L, Lt)
+    for a, b, name in ((dQ, dQt, "dQ"), (dK, dKt, "dK"), (dV, dVt, "dV")):
+        assert torch.equal(tm(a), b), name
