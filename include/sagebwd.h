@@ -122,6 +122,19 @@ int sagebwd_export_stats(const sagebwd_params* params, const void* workspace,
                          void* stream);
 
 /*
+ * Copy the quantised score gradient psi(dS) (Algorithm 2, the dS line and its quantisation) that the
+ * last sagebwd_bwd on this workspace left in its scratch, for one head = b * H + h:
+ *   ds_out     int8    [Np, Np] row-major (query, key); tiles above the causal diagonal are zero
+ *   scale_out  float32 [Np/64, Np/64], one scale per 64x64 tile (dS ~ scale * code)
+ * Np = N rounded up to a multiple of 64.  Either output may be NULL.  Only defined when the backward
+ * ran all heads in one group (B*H*Np*Np bytes within the scratch budget), otherwise
+ * SAGEBWD_UNSUPPORTED_SHAPE.  A test / inspection hook: the in-loop quantisers depend on the
+ * hardware's exp2, so their codes are compared with a tolerance of one step, not bit for bit.
+ */
+int sagebwd_export_ds(const sagebwd_params* params, const void* workspace, size_t workspace_bytes,
+                      int head, int8_t* ds_out, float* scale_out, void* stream);
+
+/*
  * Forward (paper Algorithm 1 with K-smoothing applied before psi(K), Sec. 3):
  *   S_ij = (Q^_i K^_j^T) * s_Q * s_K * sm_scale  [+ mu_Qi K_sm_j^T * sm_scale with Q-smoothing],
  *   online softmax over the KV blocks, per-token quantisation of P~ relative to the

@@ -262,7 +262,9 @@ def backward_head(Q, K, V, O, dO, L, causal: bool = True, k_smooth: bool = True,
     (dQ, dK, dV); with return_raw the float64 values instead.
 
     If `intermediates` is a dict it receives the unquantised float64 P, dP, dS
-    of the whole head (tiny inputs only; used by the invariant tests).
+    of the whole head, the codes psi(dS) ("dSh", integers as float64) and their
+    tile scales ("sdS", [N/64, N/64] float32) (tiny inputs only; used by the
+    invariant tests and by the GPU check of the in-loop quantiser).
 
     Sampling for large N (tiles are independent given L and delta):
     `q_blocks` keeps only those Q blocks -- the rows of dQ that belong to them are
@@ -293,6 +295,8 @@ def backward_head(Q, K, V, O, dO, L, causal: bool = True, k_smooth: bool = True,
         intermediates["P"] = np.zeros((n, n))
         intermediates["dP"] = np.zeros((n, n))
         intermediates["dS"] = np.zeros((n, n))
+        intermediates["dSh"] = np.zeros((n, n))
+        intermediates["sdS"] = np.zeros((n // BLOCK, n // BLOCK), dtype=_F32)
     rows = np.arange(BLOCK)
     q_todo = range(n // BLOCK) if q_blocks is None else sorted(set(int(b) for b in q_blocks))
     kv_keep = None if kv_blocks is None else set(int(b) for b in kv_blocks)
@@ -326,6 +330,9 @@ def backward_head(Q, K, V, O, dO, L, causal: bool = True, k_smooth: bool = True,
             dV[j0:j0 + BLOCK] += (_F64(sP) * _F64(sdO[I])) * (Ph.T @ dOh_i)
             # psi(dS_ij); dQ_i += dS^ K^_j * s_dS * s_K ; dK_j += dS^^T Q^_i * s_dS * s_Q
             dSh, sdS = _quantize_tile_f32(dS[:, c0:c0 + BLOCK])
+            if intermediates is not None:
+                intermediates["dSh"][i0:i0 + BLOCK, j0:j0 + BLOCK] = dSh
+                intermediates["sdS"][I, J] = sdS
             dQ[i0:i0 + BLOCK] += (_F64(sm_scale) * _F64(sdS) * _F64(pp["sK"][J])) * (dSh @ Kh[j0:j0 + BLOCK])
             dK[j0:j0 + BLOCK] += (_F64(sm_scale) * _F64(sdS) * _F64(pp["sQ"][I])) * (dSh.T @ Qh_i)
             if q_smooth:

@@ -23,7 +23,7 @@ TENSOR_Q, TENSOR_K, TENSOR_V, TENSOR_DO = 0, 1, 2, 3
 KERNEL_PREPASS_FWD, KERNEL_FWD, KERNEL_PREPASS_BWD, KERNEL_BWD, KERNEL_BWD_DQ = range(5)
 
 EXPORTS = (
-    "sagebwd_workspace_bytes", "sagebwd_quantize", "sagebwd_export_quantized", "sagebwd_export_stats",
+    "sagebwd_workspace_bytes", "sagebwd_quantize", "sagebwd_export_quantized", "sagebwd_export_stats", "sagebwd_export_ds",
     "sagebwd_fwd", "sagebwd_bwd", "sagebwd_set_scratch_budget", "sagebwd_set_timing", "sagebwd_read_timing", "sagebwd_strerror",
 )
 
@@ -76,6 +76,7 @@ def load_library():
     lib.sagebwd_quantize.argtypes = [vp, vp, vp, vp, vp, pp, vp, sz, vp]
     lib.sagebwd_export_quantized.argtypes = [pp, vp, sz, i32, vp, vp, vp]
     lib.sagebwd_export_stats.argtypes = [pp, vp, sz, vp, vp, vp, vp]
+    lib.sagebwd_export_ds.argtypes = [pp, vp, sz, i32, vp, vp, vp]
     lib.sagebwd_fwd.argtypes = [vp, vp, vp, vp, vp, pp, vp, sz, vp]
     lib.sagebwd_bwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, pp, vp, sz, vp]
     lib.sagebwd_set_timing.argtypes = [i32]
@@ -168,6 +169,18 @@ def sagebwd_export_stats(p: SageParams, workspace, want_delta=False):
     _check(load_library().sagebwd_export_stats(ctypes.byref(cp), _ptr(workspace), workspace.numel(), _ptr(muK),
                                                _ptr(muQ), _ptr(delta), _stream()), "sagebwd_export_stats")
     return muK, muQ, delta
+
+
+def sagebwd_export_ds(p: SageParams, workspace, head: int):
+    """psi(dS) of one head after a backward on this workspace: int8 [Np, Np] codes and float32
+    [Np/64, Np/64] tile scales."""
+    Np = padded_rows(p.N)
+    ds = torch.empty((Np, Np), dtype=torch.int8, device=workspace.device)
+    sc = torch.empty((Np // 64, Np // 64), dtype=torch.float32, device=workspace.device)
+    cp = p.c()
+    _check(load_library().sagebwd_export_ds(ctypes.byref(cp), _ptr(workspace), workspace.numel(), int(head),
+                                            _ptr(ds), _ptr(sc), _stream()), "sagebwd_export_ds")
+    return ds, sc
 
 
 def sagebwd_fwd(Q, K, V, p: SageParams, workspace=None, O=None, LSE=None):

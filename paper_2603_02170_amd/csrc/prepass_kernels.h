@@ -385,6 +385,29 @@ __global__ void __launch_bounds__(256) qsmooth_bias_kernel(const unsigned short*
   }
 }
 
+// ---- inspection: the psi(dS) tiles the backward left in its scratch, as a row-major [Np, Np] matrix ----
+// Tile (i, j) holds four 1 KiB fragments (32-query block qb, 32-key step kb): lane (r, half), byte
+// 4 a + b = psi(dS)[64 i + 32 qb + r][64 j + 32 kb + 8 a + 4 half + b] (the keys of a step are in the
+// order in which the K^ operand of the dQ product holds its rows).  Tiles above the causal diagonal
+// were never written: they are returned as zeros.  One thread per 16 bytes.
+__global__ void export_ds_kernel(const int8_t* __restrict__ tiles, const float* __restrict__ scales,
+                                 int8_t* __restrict__ ds_out, float* __restrict__ scale_out, int Np, int causal) {
+  const int nblk = Np / kBlock;
+  const size_t c = blockIdx.x * (size_t)blockDim.x + threadIdx.x;
+  if (c >= (size_t)nblk * nblk * 256) return;
+  const int tile = (int)(c / 256), i = tile / nblk, j = tile % nblk;
+  const int frag = (int)(c % 256) / 64, lane = (int)(c % 64);
+  const bool there = !causal || j <= i;
+  v4i v = {0, 0, 0, 0};
+  if (there) v = *(const v4i*)(tiles + c * 16);
+  const int qrow = 64 * i + 32 * (frag >> 1) + (lane & 31), key = 64 * j + 32 * (frag & 1) + 4 * (lane >> 5);
+  if (ds_out != nullptr) {
+#pragma unroll
+    for (int a = 0; a < 4; a++) *(int*)(ds_out + (size_t)qrow * Np + key + 8 * a) = v[a];
+  }
+  if (scale_out != nullptr && c % 256 == 0) scale_out[tile] = there ? scales[tile] : 0.f;
+}
+
 // ---- row-padded / re-laid-out copies ---------------------------------------------------
 // Copies rows of `row_bytes` bytes (a multiple of 16, or 4 for the LSE) between two views of a
 // [BH, n, row] tensor: rows past n_in are written as zeros (inputs of the backward when N is not a

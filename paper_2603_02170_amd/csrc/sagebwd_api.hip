@@ -389,6 +389,26 @@ int sagebwd_export_stats(const sagebwd_params* params, const void* workspace, si
   return SAGEBWD_OK;
 }
 
+int sagebwd_export_ds(const sagebwd_params* params, const void* workspace, size_t workspace_bytes, int head,
+                      int8_t* ds_out, float* scale_out, void* stream) {
+  int rc = check_params(params);
+  if (rc != SAGEBWD_OK) return rc;
+  if (workspace == nullptr || head < 0 || head >= params->B * params->H) return SAGEBWD_INVALID_ARG;
+  const Workspace w = make_layout(*params);
+  if (workspace_bytes < w.total) return SAGEBWD_WORKSPACE_TOO_SMALL;
+  // the scratch holds the heads of the LAST group the backward processed: only a backward that ran
+  // in one group leaves every head behind
+  if (w.heads_per_group < params->B * params->H) return SAGEBWD_UNSUPPORTED_SHAPE;
+  const int Np = padded_rows(params->N), nblk = Np / 64;
+  const char* ws = (const char*)workspace;
+  const size_t n = (size_t)nblk * nblk * 256;
+  export_ds_kernel<<<(unsigned)((n + 255) / 256), 256, 0, (hipStream_t)stream>>>(
+      (const int8_t*)(ws + w.dSq) + (size_t)head * Np * Np, (const float*)(ws + w.sdS) + (size_t)head * nblk * nblk,
+      ds_out, scale_out, Np, params->causal);
+  SAGE_LAUNCH_CHECK();
+  return SAGEBWD_OK;
+}
+
 int sagebwd_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE,
                 const sagebwd_params* params, void* workspace, size_t workspace_bytes, void* stream) {
   int rc = check_params(params);
