@@ -63,6 +63,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="headline")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--token-major", action="store_true",
+                    help="hold Q, K, V, O, dO and the gradients as [B, N, H, d] (the default is [B, H, N, d])")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run only a plain 1 GiB device copy (known HBM bytes) to calibrate rocprofv3's "
                          "FETCH_SIZE / WRITE_SIZE counters, then exit")
@@ -88,11 +90,14 @@ def main():
     w = synth.WORKLOADS[a.workload]
     binding.load_library()      # fails loudly if the HIP library is missing
     torch.cuda.set_device(0)
-    p = binding.SageParams(w.B, w.H, w.N, w.d, causal=w.causal, k_smooth=w.k_smooth, q_smooth=w.q_smooth)
+    p = binding.SageParams(w.B, w.H, w.N, w.d, causal=w.causal, k_smooth=w.k_smooth, q_smooth=w.q_smooth,
+                           token_major=a.token_major)
     Q, K, V, dO = (t.cuda() for t in synth.make_inputs(w))
+    if a.token_major:
+        Q, K, V, dO = (t.permute(0, 2, 1, 3).contiguous() for t in (Q, K, V, dO))
     ws = binding.alloc_workspace(p)
     O = torch.empty_like(Q)
-    L = torch.empty(Q.shape[:3], dtype=torch.float32, device="cuda")
+    L = torch.empty((w.B, w.H, w.N), dtype=torch.float32, device="cuda")
     dQ, dK, dV = (torch.empty_like(Q) for _ in range(3))
 
     def step():
@@ -137,7 +142,8 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int8", "data": "synthetic",
         "config": {"workload": f"{w.name}: B={w.B} H={w.H} N={w.N} d={w.d} causal={w.causal} bf16 N(0,1) "
                                f"{'with' if w.qk_norm else 'without'} QK-norm, K-smoothing {'on' if w.k_smooth else 'off'}, "
-                               f"Q-smoothing {'on' if w.q_smooth else 'off'}, 64x64 blocks",
+                               f"Q-smoothing {'on' if w.q_smooth else 'off'}, 64x64 blocks"
+                               f"{', tensors [B,N,H,d]' if a.token_major else ''}",
                    "work_convention": "fwd 4*BH*N^2*d + bwd 10*BH*N^2*d ops, x0.5 causal"},
         "pct_of_int8_peak": 100.0 * tops / INT8_PEAK_TOPS,
         "fwd_only": {"ms": fwd_ms, "TOPS": fwd_ops / (fwd_ms * 1e-3) / 1e12,

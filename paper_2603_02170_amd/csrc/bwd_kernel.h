@@ -38,8 +38,9 @@ struct BwdArgs {
   const int8_t* QT;    // TF layout  (dK, A operand)
   const int8_t* KF;    // F layout   (S recompute, B operand)
   const int8_t* dOT;   // TF layout  (dV, A operand)
-  const unsigned short* V;    // bf16 [BH, N, D]
-  const unsigned short* dO;   // bf16 [BH, N, D]
+  const unsigned short* V;    // bf16, rows addressed through `cv` (dense [BH, N, D] or the caller's token-major tensors)
+  const unsigned short* dO;   // bf16, likewise
+  RowView cv;                 // also addresses dK, dV
   const float* sQ;
   const float* sK;
   const float* sdO;
@@ -172,7 +173,9 @@ __global__ void __launch_bounds__(512, 1) sage_bwd_kernel(BwdArgs args) {
   const int jc = gvalid ? j : nblk - 1;                    // clamped: an idle group still loads in bounds
   const int kvalid = min(64, args.nvalid - 64 * jc);       // key columns of this group's KV block that exist
 
-  const size_t head = (size_t)bh * N * D;
+  const size_t head = (size_t)bh * N * D;                  // in the dense workspace tensors
+  const size_t chead = args.cv.row(bh, 0);                 // in V, dO, dK, dV
+  const size_t rs = args.cv.row_stride;
   const float sKj = args.sK[(size_t)bh * nblk + jc];
 
   // ---- operands that stay in registers for the whole loop ----
@@ -191,7 +194,7 @@ __global__ void __launch_bounds__(512, 1) sage_bwd_kernel(BwdArgs args) {
     const int f = w4 + 4 * k;
     if (f < 2 * KB) {
       const int fkb = f / KB, fs = f % KB;
-      async_copy_16((const char*)(args.V + head + (size_t)(64 * jc + 32 * fkb) * D + 16 * fs) + ll * (2 * D) + h * 16,
+      async_copy_16((const char*)(args.V + chead + (size_t)(64 * jc + 32 * fkb) * rs + 16 * fs) + ll * (2 * rs) + h * 16,
                     vst[grp] + f * 1024);
     }
   }
@@ -241,8 +244,8 @@ __global__ void __launch_bounds__(512, 1) sage_bwd_kernel(BwdArgs args) {
         const int f = o - NF;
         const int rb = f / KB, sst = f % KB;
         const unsigned orig = lane ^ (sst & 7);
-        const unsigned loff = (orig & 31) * (2 * D) + (orig >> 5) * 16;          // bytes: row, channel half
-        const char* base = (const char*)(args.dO + head + (size_t)(64 * i + 32 * rb) * D + 16 * sst);
+        const size_t loff = (orig & 31) * (2 * rs) + (orig >> 5) * 16;           // bytes: row, channel half
+        const char* base = (const char*)(args.dO + chead + (size_t)(64 * i + 32 * rb) * rs + 16 * sst);
         async_copy_16(base + loff, st.dof + f * 1024);
       }
     }
@@ -470,8 +473,8 @@ __global__ void __launch_bounds__(512, 1) sage_bwd_kernel(BwdArgs args) {
 #pragma unroll
   for (int t = 0; t < NPB; t++) {
     const int key = 64 * j + 32 * (blk0 + t) + ll;
-    unsigned short* pv = args.dV + head + (size_t)key * D + 32 * cb + 4 * h;
-    unsigned short* pk = args.dK + head + (size_t)key * D + 32 * cb + 4 * h;
+    unsigned short* pv = args.dV + chead + (size_t)key * rs + 32 * cb + 4 * h;
+    unsigned short* pk = args.dK + chead + (size_t)key * rs + 32 * cb + 4 * h;
 #pragma unroll
     for (int aa = 0; aa < 4; aa++) {
       v4us ov, ok;
@@ -496,7 +499,8 @@ struct DqArgs {
   const float* sdS;
   const int8_t* KT;
   const float* sK;
-  unsigned short* dQ;   // bf16 [BH, N, D]
+  unsigned short* dQ;   // bf16, rows addressed through `cv` (dense [BH, N, D] or the caller's token-major tensor)
+  RowView cv;
   int BH, N, bh0;
   float sm_scale;
 };
@@ -641,7 +645,7 @@ __global__ void __launch_bounds__(512, 2) sage_bwd_dq_kernel(DqArgs args) {
   for (int c = tid; c < 2 * 64 * CPR; c += 512) {
     const int qb = c / (64 * CPR), row = (c / CPR) % 64, pc = c % CPR;
     if (i0 + qb < nblk)
-      *(v8us*)(args.dQ + head + (size_t)(64 * (i0 + qb) + row) * D + 8 * pc) = *(const v8us*)(stg + (qb * 64 + row) * LDQ + 8 * pc);
+      *(v8us*)(args.dQ + args.cv.row(bh, 64 * (i0 + qb) + row) + 8 * pc) = *(const v8us*)(stg + (qb * 64 + row) * LDQ + 8 * pc);
   }
 }
 

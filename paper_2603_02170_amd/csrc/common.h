@@ -108,4 +108,14 @@ __device__ __forceinline__ void barrier_all_memory() {
   asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
 }
 
+// Where row n of head bh = b * H + h of one of the caller's [.., N, d] tensors starts, in elements:
+// dense [B, H, N, d] has strides (H N d, N d, d), token-major [B, N, H, d] has (N H d, d, H d).
+struct RowView {
+  size_t batch_stride, head_stride, row_stride;
+  int H;
+  __host__ __device__ size_t row(int bh, size_t n) const {
+    return (size_t)(bh / H) * batch_stride + (size_t)(bh % H) * head_stride + n * row_stride;
+  }
+};
+
 }  // namespace sage

@@ -53,7 +53,8 @@ struct FwdArgs {
   const float* sK;
   const float* sV;
   const float* bias;    // Q-smoothing: [BH, N/64, N] = sm_scale*log2e * mu_Qi . K_sm[k], else nullptr
-  unsigned short* O;    // bf16 [BH, N, D]
+  unsigned short* O;    // bf16, rows addressed through `oview` (dense [BH, N, D] or the caller's token-major tensor)
+  RowView oview;
   float* LSE;           // [BH, N]
   int BH, N;            // N = rows of the workspace tensors (a multiple of 64)
   int nvalid;           // keys >= nvalid do not exist (nvalid = N unless the caller's N is not a multiple of 64)
@@ -441,7 +442,7 @@ __global__ void __launch_bounds__(64 * NW, (NW == 4 ? (D == 64 ? 3 : 2) : 1)) sa
     // ---- epilogue: O = O / l, L = m + log(l) (l carries a factor 127) ----
     const float l_tot = half_swap_sum_f32(l_part);
     const float inv_l = 1.0f / l_tot;
-    unsigned short* Oh = args.O + ((size_t)bh * N + q) * D;
+    unsigned short* Oh = args.O + args.oview.row(bh, q);
 #pragma unroll
     for (int cb = 0; cb < KS; cb++)
 #pragma unroll

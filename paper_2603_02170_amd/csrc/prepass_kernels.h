@@ -18,15 +18,6 @@ namespace sage {
 
 constexpr int kMeanChunkRows = 256;
 
-// Where row n of head bh = b * H + h of one of the caller's [.., N, d] tensors starts, in elements:
-// dense [B, H, N, d] has strides (H N d, N d, d), token-major [B, N, H, d] has (N H d, d, H d).
-struct RowView {
-  size_t batch_stride, head_stride, row_stride;
-  int H;
-  __host__ __device__ size_t row(int bh, size_t n) const {
-    return (size_t)(bh / H) * batch_stride + (size_t)(bh % H) * head_stride + n * row_stride;
-  }
-};
 
 // ---- K mean, stage 1: float64 column sums of a 256-row chunk ----------------------
 template <int D>

@@ -45,8 +45,9 @@ inline RowView dense_view(int H, size_t rows, size_t row_units) {
   v.batch_stride = (size_t)H * rows * row_units; v.head_stride = rows * row_units; v.row_stride = row_units;
   return v;
 }
-// the kernels work on dense [BH, Np, d] copies in the workspace unless the caller's tensors already are that
-inline bool staged(const sagebwd_params& p) { return padded_rows(p.N) != p.N || p.layout != SAGEBWD_LAYOUT_BHND; }
+// When N is not a multiple of 64 the kernels work on dense row-padded [BH, Np, d] copies in the
+// workspace; otherwise they address the caller's tensors (either layout) directly.
+inline bool staged(const sagebwd_params& p) { return padded_rows(p.N) != p.N; }
 
 // Byte offsets of every buffer inside the caller's workspace.
 struct Workspace {
@@ -58,8 +59,7 @@ struct Workspace {
   int heads_per_group;      // the backward runs in groups of heads that share the dS scratch
   size_t bias;              // Q-smoothing: logit bias table [BH, N/64, N]
   size_t colsum;            // Q-smoothing backward: colsum(dS) per (Q block, key) [BH, N/64, N]
-  // only when N is not a multiple of 64 or the caller's layout is token-major: dense row-padded copies
-  // [BH, Np, d] bf16 (and [BH, Np] float)
+  // only when N is not a multiple of 64: dense row-padded copies [BH, Np, d] bf16 (and [BH, Np] float)
   size_t padO, padL;        // forward outputs
   size_t padV, paddO;       // backward inputs
   size_t paddQ, paddK, paddV;   // backward outputs
@@ -437,6 +437,7 @@ int sagebwd_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE
   const int Np = padded_rows(params->N);
   const bool ragged = staged(*params);
   a.O = ragged ? (unsigned short*)(ws + w.padO) : (unsigned short*)O;
+  a.oview = ragged ? dense_view(params->H, Np, params->d) : caller_view(*params, 1);
   a.LSE = ragged ? (float*)(ws + w.padL) : LSE;
   a.BH = params->B * params->H;
   a.N = Np;
@@ -491,6 +492,7 @@ int sagebwd_bwd(const void* Q, const void* K, const void* V, const void* O, cons
   a.QT = (const int8_t*)(ws + w.QT);
   a.KF = (const int8_t*)(ws + w.KF);
   a.dOT = (const int8_t*)(ws + w.dOT);
+  a.cv = ragged ? dense_view(params->H, N, d) : caller_view(*params, 1);   // in bf16 elements
   a.V = ragged ? (const unsigned short*)(ws + w.padV) : (const unsigned short*)V;
   a.dO = ragged ? (const unsigned short*)(ws + w.paddO) : (const unsigned short*)dO;
   a.sQ = (const float*)(ws + w.sQ);
@@ -509,6 +511,7 @@ int sagebwd_bwd(const void* Q, const void* K, const void* V, const void* O, cons
   a.sm_scale = logit_scale(*params);
   a.scale_log2e = a.sm_scale * 1.4426950408889634f;
   DqArgs q;
+  q.cv = a.cv;
   q.dSq = a.dSq;
   q.sdS = a.sdS;
   q.KT = (const int8_t*)(ws + w.KT);
