@@ -50,9 +50,8 @@ typedef enum sagebwd_status {
 
 /* Layouts of the bf16 tensors (LSE is float32 [B, H, N] in both). */
 #define SAGEBWD_LAYOUT_BHND 0 /* [B, H, N, d]: what the kernels read and write directly */
-#define SAGEBWD_LAYOUT_BNHD 1 /* [B, N, H, d], token-major as most frameworks hold activations: the
-                                 pre-pass reads it in place; O, dQ, dK, dV and the backward's V, dO pass
-                                 through dense copies in the workspace (extra traffic, more workspace) */
+#define SAGEBWD_LAYOUT_BNHD 1 /* [B, N, H, d], token-major as most frameworks hold activations: read and
+                                 written in place through row strides (rows lie H*d elements apart) */
 
 typedef struct sagebwd_params {
   int32_t B, H, N, d;
