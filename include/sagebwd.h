@@ -22,9 +22,8 @@
  *     up to a multiple of 64.  The paper assumes N/B_q and N/B_kv integral (Algorithm 1
  *     line 2); for other N the last block is a partial block whose missing rows do not
  *     exist: they enter no mean, no block maximum, no softmax and receive no gradient.
- *     (The kernels then run on Np rows with the missing keys masked, and the library
- *     moves O, LSE, dQ, dK, dV and the backward's V, dO through row-padded copies in the
- *     workspace: extra traffic that a multiple of 64 does not pay.)
+ *     (The kernels run on Np rows of workspace operands with the missing keys masked; the
+ *     caller's tensors are read and written on their N rows only.)
  */
 #ifndef SAGEBWD_H
 #define SAGEBWD_H

@@ -194,8 +194,9 @@ __global__ void __launch_bounds__(512, 1) sage_bwd_kernel(BwdArgs args) {
     const int f = w4 + 4 * k;
     if (f < 2 * KB) {
       const int fkb = f / KB, fs = f % KB;
-      async_copy_16((const char*)(args.V + chead + (size_t)(64 * jc + 32 * fkb) * rs + 16 * fs) + ll * (2 * rs) + h * 16,
-                    vst[grp] + f * 1024);
+      // (a key row that does not exist re-reads the last one that does: its P is masked to zero)
+      const int vrow = min(64 * jc + 32 * fkb + ll, args.nvalid - 1);
+      async_copy_16(args.V + chead + (size_t)vrow * rs + 16 * fs + 8 * h, vst[grp] + f * 1024);
     }
   }
 
@@ -228,7 +229,10 @@ __global__ void __launch_bounds__(512, 1) sage_bwd_kernel(BwdArgs args) {
   // which array a wave copies from is a compile-time fact per copy, and the small vectors are
   // copied by every wave (duplicates of identical data), so that the steady-state interval stays
   // one basic block.  Every address is a wave-uniform base plus a 32-bit lane offset.
-  auto load_A = [&](int i, BwdStageA<D>& st) {
+  // (LAST: Q block i may be the partial last block; query rows that do not exist re-read the last one
+  // that does: their P is zero because the pre-pass gave them -L = -inf)
+  auto load_A = [&](int i, BwdStageA<D>& st, auto last_tag) {
+    constexpr bool LAST = decltype(last_tag)::value;
     const size_t toff = head + (size_t)i * TILE;
     const unsigned lane16 = lane * 16;
 #pragma unroll
@@ -244,9 +248,14 @@ __global__ void __launch_bounds__(512, 1) sage_bwd_kernel(BwdArgs args) {
         const int f = o - NF;
         const int rb = f / KB, sst = f % KB;
         const unsigned orig = lane ^ (sst & 7);
-        const size_t loff = (orig & 31) * (2 * rs) + (orig >> 5) * 16;           // bytes: row, channel half
-        const char* base = (const char*)(args.dO + chead + (size_t)(64 * i + 32 * rb) * rs + 16 * sst);
-        async_copy_16(base + loff, st.dof + f * 1024);
+        if constexpr (LAST) {
+          const int row = min(64 * i + 32 * rb + (int)(orig & 31), args.nvalid - 1);
+          async_copy_16(args.dO + chead + (size_t)row * rs + 16 * sst + 8 * (orig >> 5), st.dof + f * 1024);
+        } else {
+          const size_t loff = (orig & 31) * (2 * rs) + (orig >> 5) * 16;           // bytes: row, channel half
+          const char* base = (const char*)(args.dO + chead + (size_t)(64 * i + 32 * rb) * rs + 16 * sst);
+          async_copy_16(base + loff, st.dof + f * 1024);
+        }
       }
     }
     // -L*log2e (even waves) or delta (odd waves), and s_Q[i] broadcast to 64 entries
@@ -280,7 +289,7 @@ __global__ void __launch_bounds__(512, 1) sage_bwd_kernel(BwdArgs args) {
     }
   };
 
-  load_A(nblk - 1, stA[0]);
+  load_A(nblk - 1, stA[0], std::true_type{});
   barrier_all_memory();
 
   float p[16], ds[16];           // P and dS of the tile between its phases A and Q
@@ -300,7 +309,7 @@ __global__ void __launch_bounds__(512, 1) sage_bwd_kernel(BwdArgs args) {
 
     // operands of the coming intervals; the copies are issued in two batches so that the eight
     // waves do not queue up behind each other at the memory pipeline
-    if (STEADY || t + 1 < T) load_A(ia - 1, stA[(t + 1) & 1]);
+    if (STEADY || t + 1 < T) load_A(ia - 1, stA[(t + 1) & 1], std::false_type{});
 
     __builtin_amdgcn_sched_barrier(0);
     // ---------------- phase Q of tile t - 1 ----------------
@@ -485,8 +494,10 @@ __global__ void __launch_bounds__(512, 1) sage_bwd_kernel(BwdArgs args) {
         ov[b] = float_to_bf16_bits(dvacc[t][4 * aa + b]);
         ok[b] = float_to_bf16_bits(kv);
       }
-      *(v4us*)(pv + 8 * aa) = ov;
-      *(v4us*)(pk + 8 * aa) = ok;
+      if (key < args.nvalid) {
+        *(v4us*)(pv + 8 * aa) = ov;
+        *(v4us*)(pk + 8 * aa) = ok;
+      }
     }
   }
 }
@@ -502,6 +513,7 @@ struct DqArgs {
   unsigned short* dQ;   // bf16, rows addressed through `cv` (dense [BH, N, D] or the caller's token-major tensor)
   RowView cv;
   int BH, N, bh0;
+  int nvalid;           // query rows >= nvalid do not exist (N rounded down from a multiple of 64)
   float sm_scale;
 };
 
@@ -644,7 +656,7 @@ __global__ void __launch_bounds__(512, 2) sage_bwd_dq_kernel(DqArgs args) {
   constexpr int CPR = D / 8;                                   // 16-byte pieces per row
   for (int c = tid; c < 2 * 64 * CPR; c += 512) {
     const int qb = c / (64 * CPR), row = (c / CPR) % 64, pc = c % CPR;
-    if (i0 + qb < nblk)
+    if (i0 + qb < nblk && 64 * (i0 + qb) + row < args.nvalid)
       *(v8us*)(args.dQ + args.cv.row(bh, 64 * (i0 + qb) + row) + 8 * pc) = *(const v8us*)(stg + (qb * 64 + row) * LDQ + 8 * pc);
   }
 }

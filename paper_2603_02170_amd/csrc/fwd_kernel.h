@@ -55,7 +55,7 @@ struct FwdArgs {
   const float* bias;    // Q-smoothing: [BH, N/64, N] = sm_scale*log2e * mu_Qi . K_sm[k], else nullptr
   unsigned short* O;    // bf16, rows addressed through `oview` (dense [BH, N, D] or the caller's token-major tensor)
   RowView oview;
-  float* LSE;           // [BH, N]
+  float* LSE;           // [BH, nvalid]
   int BH, N;            // N = rows of the workspace tensors (a multiple of 64)
   int nvalid;           // keys >= nvalid do not exist (nvalid = N unless the caller's N is not a multiple of 64)
   int n_qtiles;         // workgroups per head
@@ -442,6 +442,7 @@ __global__ void __launch_bounds__(64 * NW, (NW == 4 ? (D == 64 ? 3 : 2) : 1)) sa
     // ---- epilogue: O = O / l, L = m + log(l) (l carries a factor 127) ----
     const float l_tot = half_swap_sum_f32(l_part);
     const float inv_l = 1.0f / l_tot;
+    if (q >= args.nvalid) return;                      // a query row that does not exist
     unsigned short* Oh = args.O + args.oview.row(bh, q);
 #pragma unroll
     for (int cb = 0; cb < KS; cb++)
@@ -452,7 +453,8 @@ __global__ void __launch_bounds__(64 * NW, (NW == 4 ? (D == 64 ? 3 : 2) : 1)) sa
         for (int b = 0; b < 4; b++) o[b] = float_to_bf16_bits(oacc[cb][4 * aa + b] * inv_l);
         *(v4us*)(Oh + 32 * cb + 8 * aa + 4 * h) = o;
       }
-    if (h == 0) args.LSE[(size_t)bh * N + q] = (m_ref + __builtin_amdgcn_logf(l_tot) - kLog2_127) * kLn2;
+    // (LSE is [BH, nvalid]: the caller's own row count)
+    if (h == 0) args.LSE[(size_t)bh * args.nvalid + q] = (m_ref + __builtin_amdgcn_logf(l_tot) - kLog2_127) * kLn2;
   };
   // (each path runs to the end of the kernel, so that no register state has to be merged)
   if (__builtin_amdgcn_readfirstlane((int)use_sbias)) run(std::true_type{});

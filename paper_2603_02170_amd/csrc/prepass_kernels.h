@@ -399,33 +399,4 @@ __global__ void export_ds_kernel(const int8_t* __restrict__ tiles, const float* 
   if (scale_out != nullptr && c % 256 == 0) scale_out[tile] = there ? scales[tile] : 0.f;
 }
 
-// ---- row-padded / re-laid-out copies ---------------------------------------------------
-// Copies rows of `row_bytes` bytes (a multiple of 16, or 4 for the LSE) between two views of a
-// [BH, n, row] tensor: rows past n_in are written as zeros (inputs of the backward when N is not a
-// multiple of 64), rows past n_out are dropped (outputs).  Strides of the views are in bytes.
-__global__ void __launch_bounds__(256) resize_rows_kernel(const char* __restrict__ in, RowView vin,
-                                                          char* __restrict__ out, RowView vout, int BH,
-                                                          int n_in, int n_out, int row_bytes) {
-  const int unit = row_bytes % 16 == 0 ? 16 : 4;
-  const size_t per_row = row_bytes / unit;
-  const size_t total = (size_t)BH * n_out * per_row;
-  const size_t stride = (size_t)gridDim.x * blockDim.x;
-  for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < total; i += stride) {
-    const size_t piece = i % per_row, row = (i / per_row) % n_out;
-    const int bh = (int)(i / (per_row * n_out));
-    const bool there = row < (size_t)n_in;
-    const char* src = in + vin.row(bh, row) + piece * unit;
-    char* dst = out + vout.row(bh, row) + piece * unit;
-    if (unit == 16) {
-      v4i v = {0, 0, 0, 0};
-      if (there) v = *(const v4i*)src;
-      *(v4i*)dst = v;
-    } else {
-      int v = 0;
-      if (there) v = *(const int*)src;
-      *(int*)dst = v;
-    }
-  }
-}
-
 }  // namespace sage

@@ -22,12 +22,11 @@ size_t g_ds_budget = (size_t)8 << 30;   // bytes of INT8 dS scratch the backward
 inline size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
 
 // Rows of every workspace tensor: the caller's N rounded up to the 64-row block.  When the two differ
-// the kernels run on the rounded shape (the rows that do not exist are zero rows behind a key mask)
-// and the library moves the caller's tensors in and out of row-padded copies in the workspace.
+// the kernels run on the rounded shape: the rows that do not exist are zero rows behind a key mask in
+// the workspace, are never read from the caller's tensors (loaders clamp) and never stored.
 inline int padded_rows(int N) { return (N + 63) / 64 * 64; }
 
-// The caller's [.., N, d] tensors in elements of `unit` bytes per channel (2 for bf16; pass unit = 2 * 1
-// and scale for byte views), and the dense [BH, rows, d] tensors of the workspace.
+// Where the rows of the caller's bf16 tensors start, in elements (times `scale`).
 inline RowView caller_view(const sagebwd_params& p, size_t scale) {
   const size_t N = p.N, H = p.H, d = p.d;
   RowView v;
@@ -39,15 +38,7 @@ inline RowView caller_view(const sagebwd_params& p, size_t scale) {
   }
   return v;
 }
-inline RowView dense_view(int H, size_t rows, size_t row_units) {
-  RowView v;
-  v.H = H;
-  v.batch_stride = (size_t)H * rows * row_units; v.head_stride = rows * row_units; v.row_stride = row_units;
-  return v;
-}
-// When N is not a multiple of 64 the kernels work on dense row-padded [BH, Np, d] copies in the
-// workspace; otherwise they address the caller's tensors (either layout) directly.
-inline bool staged(const sagebwd_params& p) { return padded_rows(p.N) != p.N; }
+
 
 // Byte offsets of every buffer inside the caller's workspace.
 struct Workspace {
@@ -59,10 +50,6 @@ struct Workspace {
   int heads_per_group;      // the backward runs in groups of heads that share the dS scratch
   size_t bias;              // Q-smoothing: logit bias table [BH, N/64, N]
   size_t colsum;            // Q-smoothing backward: colsum(dS) per (Q block, key) [BH, N/64, N]
-  // only when N is not a multiple of 64: dense row-padded copies [BH, Np, d] bf16 (and [BH, Np] float)
-  size_t padO, padL;        // forward outputs
-  size_t padV, paddO;       // backward inputs
-  size_t paddQ, paddK, paddV;   // backward outputs
   size_t total;
   int nchunk;
 };
@@ -71,7 +58,6 @@ Workspace make_layout(const sagebwd_params& p) {
   Workspace w;
   const size_t BH = (size_t)p.B * p.H, N = padded_rows(p.N), d = p.d, nblk = N / 64;
   const bool qs = (p.smooth & SAGEBWD_SMOOTH_Q) != 0;
-  const bool ragged = staged(p);
   w.nchunk = (int)(((size_t)p.N + kMeanChunkRows - 1) / kMeanChunkRows);
   size_t off = 0;
   auto take = [&](size_t bytes) { size_t o = off; off += align_up(bytes); return o; };
@@ -99,14 +85,6 @@ Workspace make_layout(const sagebwd_params& p) {
   w.sdS = take(hpg * nblk * nblk * 4);
   w.bias = take(qs ? BH * nblk * N * 4 : 0);
   w.colsum = take(qs ? BH * nblk * N * 4 : 0);
-  const size_t padded = ragged ? BH * N * d * 2 : 0;
-  w.padO = take(padded);
-  w.padL = take(ragged ? BH * N * 4 : 0);
-  w.padV = take(padded);
-  w.paddO = take(padded);
-  w.paddQ = take(padded);
-  w.paddK = take(padded);
-  w.paddV = take(padded);
   w.total = off;
   return w;
 }
@@ -272,17 +250,6 @@ int launch_bwd(const BwdArgs& a, bool causal, bool qs, hipStream_t st) {
   return SAGEBWD_OK;
 }
 
-// rows of `row_bytes` bytes from one view of a [BH, n, row] tensor to another: appends zero rows or drops the tail
-int resize_rows(const void* in, const RowView& vin, void* out, const RowView& vout, int BH, int n_in, int n_out,
-                int row_bytes, hipStream_t st) {
-  const size_t pieces = (size_t)BH * n_out * (row_bytes % 16 == 0 ? row_bytes / 16 : row_bytes / 4);
-  size_t grid = (pieces + 255) / 256;
-  if (grid > 65536) grid = 65536;
-  resize_rows_kernel<<<(unsigned)grid, 256, 0, st>>>((const char*)in, vin, (char*)out, vout, BH, n_in, n_out, row_bytes);
-  SAGE_LAUNCH_CHECK();
-  return SAGEBWD_OK;
-}
-
 template <int D>
 int launch_bwd_dq(const DqArgs& a, bool causal, hipStream_t st) {
   const int npair = (a.N / 64 + 1) / 2;     // one workgroup per pair of Q blocks
@@ -435,10 +402,9 @@ int sagebwd_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE
   const bool qs = (params->smooth & SAGEBWD_SMOOTH_Q) != 0;
   a.bias = qs ? (const float*)(ws + w.bias) : nullptr;
   const int Np = padded_rows(params->N);
-  const bool ragged = staged(*params);
-  a.O = ragged ? (unsigned short*)(ws + w.padO) : (unsigned short*)O;
-  a.oview = ragged ? dense_view(params->H, Np, params->d) : caller_view(*params, 1);
-  a.LSE = ragged ? (float*)(ws + w.padL) : LSE;
+  a.O = (unsigned short*)O;
+  a.oview = caller_view(*params, 1);
+  a.LSE = LSE;
   a.BH = params->B * params->H;
   a.N = Np;
   a.nvalid = params->N;
@@ -448,13 +414,6 @@ int sagebwd_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE
     ScopedTimer tm(SAGEBWD_KERNEL_FWD, st);
     rc = params->d == 64 ? launch_fwd<64>(a, params->causal != 0, qs, st)
                          : launch_fwd<128>(a, params->causal != 0, qs, st);
-    if (rc == SAGEBWD_OK && ragged) {
-      rc = resize_rows(a.O, dense_view(params->H, Np, params->d * 2), O, caller_view(*params, 2), a.BH, Np, params->N,
-                       params->d * 2, st);
-      if (rc == SAGEBWD_OK)
-        rc = resize_rows(a.LSE, dense_view(params->H, Np, 4), LSE, dense_view(params->H, params->N, 4), a.BH, Np,
-                         params->N, 4, st);
-    }
   }
   return rc;
 }
@@ -472,29 +431,21 @@ int sagebwd_bwd(const void* Q, const void* K, const void* V, const void* O, cons
   hipStream_t st = (hipStream_t)stream;
   char* ws = (char*)workspace;
   const int BH = params->B * params->H, N = padded_rows(params->N), d = params->d;
-  const bool ragged = staged(*params);
-  const RowView cview = caller_view(*params, 2), pview = dense_view(params->H, N, (size_t)d * 2);   // in bytes
   const bool qs = (params->smooth & SAGEBWD_SMOOTH_Q) != 0;
   {
     ScopedTimer tm(SAGEBWD_KERNEL_PREPASS_BWD, st);
     rc = d == 64 ? run_prepass<64>(Q, K, V, dO, O, LSE, *params, ws, w, true, st)
                  : run_prepass<128>(Q, K, V, dO, O, LSE, *params, ws, w, true, st);
     if (rc != SAGEBWD_OK) return rc;
-    if (ragged) {
-      // the backward kernel reads bf16 V and dO itself: give it row-padded copies
-      rc = resize_rows(V, cview, ws + w.padV, pview, BH, params->N, N, d * 2, st);
-      if (rc == SAGEBWD_OK) rc = resize_rows(dO, cview, ws + w.paddO, pview, BH, params->N, N, d * 2, st);
-      if (rc != SAGEBWD_OK) return rc;
-    }
   }
   BwdArgs a;
   a.QF = (const int8_t*)(ws + w.QF);
   a.QT = (const int8_t*)(ws + w.QT);
   a.KF = (const int8_t*)(ws + w.KF);
   a.dOT = (const int8_t*)(ws + w.dOT);
-  a.cv = ragged ? dense_view(params->H, N, d) : caller_view(*params, 1);   // in bf16 elements
-  a.V = ragged ? (const unsigned short*)(ws + w.padV) : (const unsigned short*)V;
-  a.dO = ragged ? (const unsigned short*)(ws + w.paddO) : (const unsigned short*)dO;
+  a.cv = caller_view(*params, 1);   // in bf16 elements
+  a.V = (const unsigned short*)V;
+  a.dO = (const unsigned short*)dO;
   a.sQ = (const float*)(ws + w.sQ);
   a.sK = (const float*)(ws + w.sK);
   a.sdO = (const float*)(ws + w.sdO);
@@ -504,8 +455,8 @@ int sagebwd_bwd(const void* Q, const void* K, const void* V, const void* O, cons
   a.muQ = qs ? (const float*)(ws + w.muQ) : nullptr;
   a.dSq = (int8_t*)(ws + w.dSq);
   a.sdS = (float*)(ws + w.sdS);
-  a.dK = ragged ? (unsigned short*)(ws + w.paddK) : (unsigned short*)dK;
-  a.dV = ragged ? (unsigned short*)(ws + w.paddV) : (unsigned short*)dV;
+  a.dK = (unsigned short*)dK;
+  a.dV = (unsigned short*)dV;
   a.N = N;
   a.nvalid = params->N;
   a.sm_scale = logit_scale(*params);
@@ -516,7 +467,8 @@ int sagebwd_bwd(const void* Q, const void* K, const void* V, const void* O, cons
   q.sdS = a.sdS;
   q.KT = (const int8_t*)(ws + w.KT);
   q.sK = a.sK;
-  q.dQ = ragged ? (unsigned short*)(ws + w.paddQ) : (unsigned short*)dQ;
+  q.dQ = (unsigned short*)dQ;
+  q.nvalid = params->N;
   q.N = N;
   q.sm_scale = a.sm_scale;
   for (int h0 = 0; h0 < BH; h0 += w.heads_per_group) {
@@ -533,12 +485,6 @@ int sagebwd_bwd(const void* Q, const void* K, const void* V, const void* O, cons
       rc = d == 64 ? launch_bwd_dq<64>(q, params->causal != 0, st) : launch_bwd_dq<128>(q, params->causal != 0, st);
       if (rc != SAGEBWD_OK) return rc;
     }
-  }
-  if (ragged) {
-    ScopedTimer tm(SAGEBWD_KERNEL_BWD_DQ, st);
-    rc = resize_rows(q.dQ, pview, dQ, cview, BH, N, params->N, d * 2, st);
-    if (rc == SAGEBWD_OK) rc = resize_rows(a.dK, pview, dK, cview, BH, N, params->N, d * 2, st);
-    if (rc == SAGEBWD_OK) rc = resize_rows(a.dV, pview, dV, cview, BH, N, params->N, d * 2, st);
   }
   return rc;
 }
