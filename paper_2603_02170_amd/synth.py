@@ -46,7 +46,7 @@ WORKLOADS = {
     # other benchmarked head dimension (Sec. 5.5).
     "headline_qsmooth": Workload("headline_qsmooth", 5, 2, 32, 8192, 128, True, q_smooth=True),
     "headline_d64": Workload("headline_d64", 6, 2, 32, 8192, 64, True),
-    # One token short of the headline length: the last block is partial (costs the row-padded copies).
+    # One token short of the headline length: the last block is partial.
     "headline_n8191": Workload("headline_n8191", 8, 2, 32, 8191, 128, True),
 }
 
