@@ -454,3 +454,27 @@ def test_partial_last_block_means_and_prefix_property():
     O, L = oracle.forward_head(Q, K, V, causal=True, k_smooth=False)
     O64, L64 = oracle.forward_head(Q[:64], K[:64], V[:64], causal=True, k_smooth=False)
     assert np.array_equal(O[:64], O64) and np.array_equal(L[:64], L64)
+
+
+def test_intermediate_error_ordering_follows_the_paper():
+    """The paper's trace of intermediate tensors (Sec. 5 "Tracing intermediate tensor error", its
+    Table 2) on a trained layer cannot be reproduced without the checkpoint, but its structure can:
+    dP is exact (both operands stay unquantised), dS is the least accurate intermediate, and the
+    gradients downstream of dS (dQ, dK) are less accurate than O and dV.  Gaussian Q, K of standard
+    deviation 5 put the errors in the range the table shows (rel-l2 of dS about 0.2)."""
+    N, d, sc = 512, 64, 1 / math.sqrt(64)
+    err = {k: [] for k in ("P", "dP", "dS", "O", "dQ", "dK", "dV")}
+    for seed in (50, 51):
+        Q, K, V, dO = _rand(N, d, sigma=5.0, seed=seed)
+        O, L = oracle.forward_head(Q, K, V, causal=False)
+        inter = {}
+        dQ, dK, dV = oracle.backward_head(Q, K, V, O, dO, L, causal=False, intermediates=inter)
+        ref = fpa_backward(Q, K, V, dO, False, sc)
+        got = dict(P=inter["P"], dP=inter["dP"], dS=inter["dS"], O=O, dQ=dQ, dK=dK, dV=dV)
+        for k in err:
+            err[k].append(rel_l2(got[k], ref[k]))
+    e = {k: float(np.mean(v)) for k, v in err.items()}
+    assert e["dP"] < 1e-12                                   # unquantised matmul of the caller's values
+    assert e["dS"] > e["P"] and e["dS"] > 0.05               # dS: the bottleneck
+    assert min(e["dQ"], e["dK"]) > max(e["O"], e["dV"])      # what follows dS suffers most
+    assert 0.05 < e["dS"] < 0.6 and e["O"] < 0.15
