@@ -151,14 +151,14 @@ __global__ void __launch_bounds__(512, 1) sage_bwd_kernel(BwdArgs args) {
   auto& csum = L.csum;
 
   const int gidx = blockIdx.x;
-  const int xcd = gidx & 7, slot = gidx >> 3;
   const int N = args.N;
   const int nblk = N / kBlock;
   const int npair = (nblk + 1) / 2;
-  const int hl = xcd + 8 * (slot / npair);   // head within this launch
+  const WorkItem wi = work_item(gidx, npair, head_set_for(npair));
+  const int hl = wi.head;             // head within this launch
   if (hl >= args.BH) return;
   const int bh = args.bh0 + hl;
-  const int jp = slot % npair;        // small jp = most Q blocks under the causal mask: scheduled first
+  const int jp = wi.item;             // small jp = most Q blocks under the causal mask: scheduled first
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -541,14 +541,14 @@ __global__ void __launch_bounds__(512, 2) sage_bwd_dq_kernel(DqArgs args) {
   int8_t* const ktr = lds + ND * DSLOT;
 
   const int g = blockIdx.x;
-  const int xcd = g & 7, slot = g >> 3;
   const int N = args.N;
   const int nblk = N / kBlock;
   const int npair = (nblk + 1) / 2;
-  const int hl = xcd + 8 * (slot / npair);
+  const WorkItem wi = work_item(g, npair, 4);       // the memory-bound dQ kernel gains from head sets at every length
+  const int hl = wi.head;
   if (hl >= args.BH) return;
   const int bh = args.bh0 + hl;
-  const int i0 = 2 * (npair - 1 - (slot % npair));     // longest rows first under the causal mask
+  const int i0 = 2 * (npair - 1 - wi.item);            // longest rows first under the causal mask
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);

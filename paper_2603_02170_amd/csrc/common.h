@@ -118,4 +118,24 @@ struct RowView {
   }
 };
 
+// Workgroup id -> (head, work item of the head).  Consecutive ids go round-robin over the 8 XCDs, so a
+// head's workgroups share one L2.  The heads of an XCD are taken `head_set` at a time, and inside such a
+// set the items go heaviest first over ALL its heads (item 0 of every head, then item 1, ...): with the
+// causal mask the last workgroups to start are then the lightest of several heads, not of one.  That
+// shortens the tail of short-sequence launches (13 % of the step at N = 2048); at N = 8192 the compute
+// kernels lose 2 % to it (several heads' operands compete for the L2), so they take one head at a time there.
+struct WorkItem {
+  int head, item;
+};
+__host__ __device__ inline int head_set_for(int items) { return items <= 32 ? 4 : 1; }
+__host__ __device__ inline int grid_for(int heads, int items, int head_set) {
+  const int per_xcd = ((heads + 7) / 8 + head_set - 1) / head_set * head_set;
+  return 8 * per_xcd * items;
+}
+__device__ inline WorkItem work_item(int block, int items, int head_set) {
+  const int xcd = block & 7, slot = block >> 3;
+  const int hset = slot / (items * head_set), rem = slot % (items * head_set);
+  return WorkItem{xcd + 8 * (hset * head_set + rem % head_set), rem / head_set};
+}
+
 }  // namespace sage

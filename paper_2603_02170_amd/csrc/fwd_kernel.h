@@ -282,14 +282,12 @@ __global__ void __launch_bounds__(64 * NW, (NW == 4 ? (D == 64 ? 3 : 2) : 1)) sa
   constexpr int SLOT = BIAS_OFF + (QSMOOTH ? NW * 256 : 0);
   __shared__ __attribute__((aligned(16))) int8_t lds[4][SLOT];   // K^ | V^ | per-wave (s_K, s_V) | per-wave bias row
 
-  // XCD-aware mapping: consecutive workgroup ids go round-robin over the 8 XCDs, so all
-  // query tiles of one head are given ids with the same residue and share one L2.
-  const int g = blockIdx.x;
-  const int xcd = g & 7, slot = g >> 3;
-  const int bh = xcd + 8 * (slot / args.n_qtiles);
+  // workgroup -> (head, query tile): a head's tiles share one XCD's L2; heaviest (last) query
+  // tiles first under the causal mask, over sets of heads (see work_item)
+  const WorkItem wi = work_item(blockIdx.x, args.n_qtiles, head_set_for(args.n_qtiles));
+  const int bh = wi.head;
   if (bh >= args.BH) return;
-  // heaviest (last) query tiles first under the causal mask
-  const int qt = args.n_qtiles - 1 - (slot % args.n_qtiles);
+  const int qt = args.n_qtiles - 1 - wi.item;
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
