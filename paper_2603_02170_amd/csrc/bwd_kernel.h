@@ -55,6 +55,7 @@ struct BwdArgs {
   unsigned short* dV;
   int BH, N;           // N = rows of the workspace tensors (a multiple of 64)
   int nvalid;          // keys >= nvalid do not exist (nvalid = N unless the caller's N is not a multiple of 64)
+  int head_set;        // heads per XCD whose work items are interleaved (see work_item)
   float sm_scale;
   float scale_log2e;
 };
@@ -154,7 +155,7 @@ __global__ void __launch_bounds__(512, 1) sage_bwd_kernel(BwdArgs args) {
   const int N = args.N;
   const int nblk = N / kBlock;
   const int npair = (nblk + 1) / 2;
-  const WorkItem wi = work_item(gidx, npair, head_set_for(npair));
+  const WorkItem wi = work_item(gidx, npair, args.head_set);
   const int hl = wi.head;             // head within this launch
   if (hl >= args.BH) return;
   const int bh = args.bh0 + hl;
@@ -514,6 +515,7 @@ struct DqArgs {
   RowView cv;
   int BH, N, bh0;
   int nvalid;           // query rows >= nvalid do not exist (N rounded down from a multiple of 64)
+  int head_set;         // heads per XCD whose work items are interleaved (see work_item)
   float sm_scale;
 };
 
@@ -544,7 +546,7 @@ __global__ void __launch_bounds__(512, 2) sage_bwd_dq_kernel(DqArgs args) {
   const int N = args.N;
   const int nblk = N / kBlock;
   const int npair = (nblk + 1) / 2;
-  const WorkItem wi = work_item(g, npair, 4);       // the memory-bound dQ kernel gains from head sets at every length
+  const WorkItem wi = work_item(g, npair, args.head_set);
   const int hl = wi.head;
   if (hl >= args.BH) return;
   const int bh = args.bh0 + hl;

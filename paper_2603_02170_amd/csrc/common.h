@@ -127,7 +127,14 @@ struct RowView {
 struct WorkItem {
   int head, item;
 };
-__host__ __device__ inline int head_set_for(int items) { return items <= 32 ? 4 : 1; }
+// (a set never exceeds or straddles the heads an XCD has: workgroups without work would still
+// queue for a whole workgroup's LDS and wave slots before they can exit)
+__host__ __device__ inline int head_set_for(int items, int heads, bool always = false) {
+  const int per_xcd = (heads + 7) / 8;
+  int hs = (always || items <= 32) ? 4 : 1;
+  while (hs > 1 && per_xcd % hs != 0) hs >>= 1;
+  return hs;
+}
 __host__ __device__ inline int grid_for(int heads, int items, int head_set) {
   const int per_xcd = ((heads + 7) / 8 + head_set - 1) / head_set * head_set;
   return 8 * per_xcd * items;

@@ -59,6 +59,7 @@ struct FwdArgs {
   int BH, N;            // N = rows of the workspace tensors (a multiple of 64)
   int nvalid;           // keys >= nvalid do not exist (nvalid = N unless the caller's N is not a multiple of 64)
   int n_qtiles;         // workgroups per head
+  int head_set;         // heads per XCD whose work items are interleaved (see work_item)
   float scale_log2e;    // sm_scale * log2(e)
 };
 
@@ -284,7 +285,7 @@ __global__ void __launch_bounds__(64 * NW, (NW == 4 ? (D == 64 ? 3 : 2) : 1)) sa
 
   // workgroup -> (head, query tile): a head's tiles share one XCD's L2; heaviest (last) query
   // tiles first under the causal mask, over sets of heads (see work_item)
-  const WorkItem wi = work_item(blockIdx.x, args.n_qtiles, head_set_for(args.n_qtiles));
+  const WorkItem wi = work_item(blockIdx.x, args.n_qtiles, args.head_set);
   const int bh = wi.head;
   if (bh >= args.BH) return;
   const int qt = args.n_qtiles - 1 - wi.item;
