@@ -118,31 +118,34 @@ struct RowView {
   }
 };
 
-// Workgroup id -> (head, work item of the head).  Consecutive ids go round-robin over the 8 XCDs, so a
-// head's workgroups share one L2.  The heads of an XCD are taken `head_set` at a time, and inside such a
-// set the items go heaviest first over ALL its heads (item 0 of every head, then item 1, ...): with the
-// causal mask the last workgroups to start are then the lightest of several heads, not of one.  That
-// shortens the tail of short-sequence launches (13 % of the step at N = 2048); at N = 8192 the compute
-// kernels lose 2 % to it (several heads' operands compete for the L2), so they take one head at a time there.
+// Workgroup id -> (head, work item of the head).  Consecutive ids go round-robin over the 8 XCDs, so
+// with a multiple of 8 heads every head's workgroups are given one XCD and share its L2.  The heads of
+// an XCD are taken `head_set` at a time, and inside such a set the items go heaviest first over ALL its
+// heads (item 0 of every head, then item 1, ...): with the causal mask the last workgroups to start
+// are then the lightest of several heads, not of one.  That shortens the tail of short-sequence
+// launches (13 % of the step at N = 2048); at N = 8192 the compute kernels lose 2 % to it (several
+// heads' operands compete for the L2), so they take one head at a time there.
+// Other head counts are laid out densely, head after head: no workgroup is without
+// work (it would still queue for a whole workgroup's LDS and wave slots before it could exit) and a
+// single head spreads over all XCDs instead of one.
 struct WorkItem {
   int head, item;
 };
-// (a set never exceeds or straddles the heads an XCD has: workgroups without work would still
-// queue for a whole workgroup's LDS and wave slots before they can exit)
+// head_set > 0: that many heads of an XCD per set; head_set < 0: the dense layout (written as a set of
+// one head on a machine of one XCD, so that the mapping below stays one formula)
 __host__ __device__ inline int head_set_for(int items, int heads, bool always = false) {
-  const int per_xcd = (heads + 7) / 8;
+  if (heads % 8 != 0) return -1;
+  const int per_xcd = heads / 8;
   int hs = (always || items <= 32) ? 4 : 1;
   while (hs > 1 && per_xcd % hs != 0) hs >>= 1;
   return hs;
 }
-__host__ __device__ inline int grid_for(int heads, int items, int head_set) {
-  const int per_xcd = ((heads + 7) / 8 + head_set - 1) / head_set * head_set;
-  return 8 * per_xcd * items;
-}
+__host__ __device__ inline int grid_for(int heads, int items) { return heads * items; }
 __device__ inline WorkItem work_item(int block, int items, int head_set) {
-  const int xcd = block & 7, slot = block >> 3;
-  const int hset = slot / (items * head_set), rem = slot % (items * head_set);
-  return WorkItem{xcd + 8 * (hset * head_set + rem % head_set), rem / head_set};
+  const int xcds = head_set < 0 ? 1 : 8, hs = head_set < 0 ? 1 : head_set;
+  const int xcd = block % xcds, slot = block / xcds;
+  const int hset = slot / (items * hs), rem = slot % (items * hs);
+  return WorkItem{xcd + xcds * (hset * hs + rem % hs), rem / hs};
 }
 
 }  // namespace sage

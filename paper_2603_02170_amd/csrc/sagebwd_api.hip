@@ -221,7 +221,7 @@ int launch_fwd_nw(const FwdArgs& a, int nw, hipStream_t st) {
   FwdArgs args = a;
   args.n_qtiles = a.N / (32 * nw);
   args.head_set = head_set_for(args.n_qtiles, a.BH);
-  const int grid = grid_for(a.BH, args.n_qtiles, args.head_set);
+  const int grid = grid_for(a.BH, args.n_qtiles);
   if (nw == 4) sage_fwd_kernel<D, CAUSAL, QS, 4><<<grid, 256, 0, st>>>(args);
   else sage_fwd_kernel<D, CAUSAL, QS, 2><<<grid, 128, 0, st>>>(args);
   SAGE_LAUNCH_CHECK();
@@ -240,7 +240,7 @@ int launch_bwd(const BwdArgs& a, bool causal, bool qs, hipStream_t st) {
   const int npair = (a.N / 64 + 1) / 2;     // one workgroup per pair of KV blocks
   BwdArgs args = a;
   args.head_set = head_set_for(npair, a.BH);
-  const int grid = grid_for(a.BH, npair, args.head_set);
+  const int grid = grid_for(a.BH, npair);
   if (causal) {
     if (qs) sage_bwd_kernel<D, true, true><<<grid, 512, 0, st>>>(args);
     else sage_bwd_kernel<D, true, false><<<grid, 512, 0, st>>>(args);
@@ -257,7 +257,7 @@ int launch_bwd_dq(const DqArgs& a, bool causal, hipStream_t st) {
   const int npair = (a.N / 64 + 1) / 2;     // one workgroup per pair of Q blocks
   DqArgs args = a;
   args.head_set = head_set_for(npair, a.BH, true);   // memory-bound: gains from head sets at every length
-  const int grid = grid_for(a.BH, npair, args.head_set);
+  const int grid = grid_for(a.BH, npair);
   if (causal) sage_bwd_dq_kernel<D, true><<<grid, 512, 0, st>>>(args);
   else sage_bwd_dq_kernel<D, false><<<grid, 512, 0, st>>>(args);
   SAGE_LAUNCH_CHECK();
