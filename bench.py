@@ -23,7 +23,7 @@ HBM_PEAK_GBS = 8000.0       # MI355X HBM3E peak (published)
 
 # HBM bytes per launch at the headline workload, from the rocprofv3 FETCH_SIZE / WRITE_SIZE runs
 # summarised in profiles/hbm_traffic_headline_fwd_bwd.txt (scaled by the copy-kernel calibration).
-MEASURED_TRAFFIC_BYTES = {"headline": {"bwd": 3.4681e9, "fwd": 3.382e8, "bwd_dq": 2.4393e9}}
+MEASURED_TRAFFIC_BYTES = {"headline": {"bwd": 3.4796e9, "fwd": 3.382e8, "bwd_dq": 2.6434e9}}
 
 
 def work_ops(w, fwd=True, bwd=True):
