@@ -70,7 +70,7 @@ def main():
                          "FETCH_SIZE / WRITE_SIZE counters, then exit")
     a = ap.parse_args()
     if a.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this build runs on ONE GPU only (heads shard with no communication; see DESIGN.md); "
+        print("bench.py: this build runs on ONE GPU only (every head is independent: shard heads over GPUs with no communication); "
               "use --gpus 1", file=sys.stderr)
         sys.exit(2)
 
