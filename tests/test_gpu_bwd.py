@@ -197,3 +197,24 @@ def test_side_stream_gives_the_same_bits():
     assert torch.equal(O, O2) and torch.equal(L, L2)
     for a, b in zip(ref, got):
         assert torch.equal(a, b)
+
+
+def test_backward_is_deterministic_and_needs_nothing_from_an_old_workspace():
+    """dQ comes from stored tiles and a second kernel, not from atomics: two calls return the same
+    bits, also when the workspace was overwritten in between (the backward re-runs its pre-pass and
+    relies on nothing a previous call left there) and when the scratch budget forces head groups."""
+    Q, K, V, dO = (t.cuda() for t in synth.gaussian_inputs(448, 128, sigma_qk=1.0, seed=78, heads=5))
+    p = binding.SageParams(1, 5, 448, 128, causal=True, q_smooth=True)
+    ws = binding.alloc_workspace(p)
+    O, L = binding.sagebwd_fwd(Q, K, V, p, ws)
+    a = [t.clone() for t in binding.sagebwd_bwd(Q, K, V, O, dO, L, p, ws)]
+    ws.fill_(0x5A)
+    b = [t.clone() for t in binding.sagebwd_bwd(Q, K, V, O, dO, L, p, ws)]
+    try:
+        binding.set_scratch_budget(2 * 448 * 448)          # two heads at a time
+        c = binding.sagebwd_bwd(Q, K, V, O, dO, L, p, binding.alloc_workspace(p))
+    finally:
+        binding.set_scratch_budget(8 << 30)
+    torch.cuda.synchronize()
+    for x, y, z in zip(a, b, c):
+        assert torch.equal(x, y) and torch.equal(x, z)
