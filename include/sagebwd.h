@@ -14,7 +14,9 @@
  *   - Tensors are dense and contiguous: Q, K, V, O, dO, dQ, dK, dV are bf16
  *     [B, H, N, d] (or [B, N, H, d], see sagebwd_params.layout); LSE is float32 [B, H, N].
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Work
- *     is enqueued on it and the call returns without synchronising.
+ *     is enqueued on it and the call returns without synchronising.  The entry points
+ *     only launch kernels (no allocation, no memset, no host synchronisation), so
+ *     sagebwd_fwd / sagebwd_bwd may be recorded under stream capture and replayed.
  *   - Return value: SAGEBWD_OK (0) or a negative sagebwd_status.  Arguments are
  *     validated on the host before anything is launched; on error nothing runs.
  *   - Numerics blocks are B_q = B_kv = 64 (one FP32 scale per 64 rows x d channels).
