@@ -25,8 +25,8 @@
 // result is unchanged because O/l and m + log l do not depend on the reference chosen.
 //
 // INT32 -> FP32 without a conversion instruction: the P^V^ accumulators start from the bit
-// pattern B0 of the float C0 = 1/(2 pi), which the MFMA takes as an inline constant (no
-// registers).  B0's mantissa leaves more than 2^20 codes to either end of its binade, so for
+// pattern B0 of the float C0 = 1/(2 pi) (an inline constant of the ISA; the compiler keeps the
+// splat in 16 registers because several MFMAs start from it).  B0's mantissa leaves more than 2^20 codes to either end of its binade, so for
 // every possible sum |a| <= 64 * 127 * 127 the bits B0 + a read as the float C0 + a * 2^-26
 // exactly.  The FP32 accumulators take w * 2^26 * (C0 + a * 2^-26) with ONE fused multiply-add
 // per value and so carry the bias C0 * 2^26 * sum(w), the same for every channel of a query;
