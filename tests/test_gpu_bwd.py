@@ -171,10 +171,10 @@ def test_in_loop_quantiser_of_ds_within_one_step_of_the_oracle(N, d, causal):
         torch.cuda.synchronize()
         ds, sc = ds.cpu().numpy().astype(np.int32), sc.cpu().numpy()
         ref, rsc = inter["dSh"].astype(np.int32), inter["sdS"]
-        assert np.allclose(sc, rsc, rtol=2e-5, atol=0), np.abs(sc / np.where(rsc > 0, rsc, 1) - 1).max()
+        assert np.allclose(sc, rsc, rtol=5e-6, atol=0), np.abs(sc / np.where(rsc > 0, rsc, 1) - 1).max()
         diff = np.abs(ds - ref)
         assert diff.max() <= 1, diff.max()
-        assert (diff == 0).mean() > 0.99, (diff == 0).mean()
+        assert (diff == 0).mean() > 0.999, (diff == 0).mean()    # (measured: every code equal, scales within 6e-7)
 
 
 def test_side_stream_gives_the_same_bits():
