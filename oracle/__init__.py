@@ -11,6 +11,7 @@ from .sage_oracle import (  # noqa: F401
     key_mean,
     block_mean,
     pad_rows,
+    padded_len,
     quantize_blocks,
     prepass_head,
     delta_rows,

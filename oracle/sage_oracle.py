@@ -28,6 +28,12 @@ as float32 arrays), L is float32.
 Readings taken where the paper's text is silent or garbled are listed next to
 the code that uses them (R1..R17).
 
+Block sizes: Algorithm 1 takes B_q and B_kv as inputs and fixes neither; every
+function takes them as `bq`, `bkv` (default 64 x 64, the configuration the GPU
+kernels implement; one must divide the other).  Q, dO and mu_Q are blocked by
+bq rows, K and V by bkv rows, psi(P_ij) and psi(dS_ij) act on bq x bkv tiles, and
+the forward's per-token psi(P~) on the bkv keys of a tile.
+
 Sequence lengths that are not a multiple of the block (the paper assumes N/B_q and
 N/B_kv integral, Algorithm 1 line 2): the last block is a partial block whose
 missing rows do not exist.  They enter no mean, no absmax, no sum, no softmax.
@@ -39,7 +45,9 @@ from __future__ import annotations
 
 import numpy as np
 
-BLOCK = 64  # B_q = B_kv = 64: the FlashAttention tile that psi's scale is shared over
+BLOCK = 64  # default B_q = B_kv: the FlashAttention tile that psi's scale is shared over.
+# Algorithm 1 (its input line) leaves B_q and B_kv free; every function below takes them as
+# `bq` (rows of a Q / dO block) and `bkv` (rows of a K / V block), both defaulting to 64.
 
 _F32 = np.float32
 _F64 = np.float64
@@ -72,16 +80,16 @@ def key_mean(K: np.ndarray) -> np.ndarray:
     return (K.astype(_F64).sum(axis=0) / _F64(K.shape[0])).astype(_F32)
 
 
-def block_mean(Q: np.ndarray) -> np.ndarray:
-    """mu_{Q_i} = mean_row(Q_i) for every 64-row block (R17: per block, the
+def block_mean(Q: np.ndarray, block: int = BLOCK) -> np.ndarray:
+    """mu_{Q_i} = mean_row(Q_i) for every block of `block` rows (R17: per block, the
     Sec. 3 definition); a partial last block is averaged over the rows it has.
-    Returns [ceil(N/64), d] float32 (float64 sum, one rounding)."""
+    Returns [ceil(N/block), d] float32 (float64 sum, one rounding)."""
     Q = np.asarray(Q, dtype=_F32)
     n, d = Q.shape
-    nb = -(-n // BLOCK)
+    nb = -(-n // block)
     out = np.zeros((nb, d), dtype=_F32)
     for b in range(nb):
-        rows = Q[b * BLOCK:(b + 1) * BLOCK].astype(_F64)
+        rows = Q[b * block:(b + 1) * block].astype(_F64)
         out[b] = (rows.sum(axis=0) / _F64(rows.shape[0])).astype(_F32)
     return out
 
@@ -96,20 +104,20 @@ def pad_rows(X: np.ndarray, n_pad: int) -> np.ndarray:
     return out
 
 
-def quantize_blocks(X: np.ndarray):
-    """psi applied to every 64-row block of X [N, d] (R8: one scale per block of
-    64 rows x all d channels).
+def quantize_blocks(X: np.ndarray, block: int = BLOCK):
+    """psi applied to every block of `block` rows of X [N, d] (R8: one scale per block of
+    `block` rows x all d channels; 64 unless said).
 
     Sec. 3: X^ = round(X / delta_X), delta_X = max|X| / 127, delta in FP32.
     R5: round = nearest-even; result clamped to [-127, 127].
     R6: all in float32: a = max|x|, s = a / 127, r = 127 / a, q = rne(x * r).
     R7: an all-zero block has s = 0 and q = 0.
-    Returns (q int8 [N, d], s float32 [N/64]).
+    Returns (q int8 [N, d], s float32 [N/block]).
     """
     X = np.ascontiguousarray(np.asarray(X, dtype=_F32))
     n, d = X.shape
-    assert n % BLOCK == 0
-    xb = X.reshape(n // BLOCK, BLOCK * d)
+    assert n % block == 0
+    xb = X.reshape(n // block, block * d)
     a = np.abs(xb).max(axis=1).astype(_F32)
     nz = a > 0
     safe = np.where(nz, a, _F32(1))
@@ -137,33 +145,45 @@ def _quantize_tile_f32(x64: np.ndarray):
 # --------------------------------------------------------------------------
 # pre-pass: smoothing + psi for Q, K, V (and dO in the backward)
 # --------------------------------------------------------------------------
-def prepass_head(Q, K, V, k_smooth: bool = True, q_smooth: bool = False):
+def _check_blocks(bq: int, bkv: int):
+    assert bq >= 1 and bkv >= 1 and max(bq, bkv) % min(bq, bkv) == 0, "one block size must divide the other"
+
+
+def padded_len(n: int, bq: int = BLOCK, bkv: int = BLOCK) -> int:
+    """Rows after appending: n rounded up to a multiple of both block sizes."""
+    big = max(bq, bkv)
+    return -(-n // big) * big
+
+
+def prepass_head(Q, K, V, k_smooth: bool = True, q_smooth: bool = False, bq: int = BLOCK, bkv: int = BLOCK):
     """Smoothing and per-block quantisation of one head (Algorithm 1, the
-    "Quantization" step, preceded by the smoothing of Sec. 3).
+    "Quantization" step, preceded by the smoothing of Sec. 3).  Q is quantised per
+    block of bq rows, K and V per block of bkv rows.
 
     Returns a dict with Qh, sQ, Kh, sK, Vh, sV (int8 / float32), muK [d],
-    muQ [ceil(N/64), d] (zeros when the smoothing is off) and Ksm (float32 K - mu_K).
-    When N is not a multiple of 64 the row-indexed entries have ceil(N/64)*64 rows,
-    the appended ones zero (module header); "n" is the true N.
+    muQ [rows/bq, d] (zeros when the smoothing is off) and Ksm (float32 K - mu_K).
+    When N is not a multiple of the blocks the row-indexed entries have N rounded up
+    to a multiple of both, the appended rows zero (module header); "n" is the true N.
     """
+    _check_blocks(bq, bkv)
     Q = np.asarray(Q, dtype=_F32)
     K = np.asarray(K, dtype=_F32)
     V = np.asarray(V, dtype=_F32)
     n, d = Q.shape
-    nb = -(-n // BLOCK)
+    n_pad = padded_len(n, bq, bkv)
     muK = key_mean(K) if k_smooth else np.zeros(d, dtype=_F32)   # over the N tokens that exist
     Ksm = (K - muK[None, :]).astype(_F32)       # f32 subtraction, R6
     if q_smooth:
-        muQ = block_mean(Q)
-        Qsm = (Q - np.repeat(muQ, BLOCK, axis=0)[:n]).astype(_F32)
+        muQ = pad_rows(block_mean(Q, bq), n_pad // bq)           # blocks with no row at all: mean 0
+        Qsm = (Q - np.repeat(muQ, bq, axis=0)[:n]).astype(_F32)
     else:
-        muQ = np.zeros((nb, d), dtype=_F32)
+        muQ = np.zeros((n_pad // bq, d), dtype=_F32)
         Qsm = Q
-    Qsm, Ksm, Vp = (pad_rows(x, nb * BLOCK) for x in (Qsm, Ksm, V))
-    Qh, sQ = quantize_blocks(Qsm)
-    Kh, sK = quantize_blocks(Ksm)
-    Vh, sV = quantize_blocks(Vp)
-    return dict(Qh=Qh, sQ=sQ, Kh=Kh, sK=sK, Vh=Vh, sV=sV, muK=muK, muQ=muQ, Ksm=Ksm, n=n)
+    Qsm, Ksm, Vp = (pad_rows(x, n_pad) for x in (Qsm, Ksm, V))
+    Qh, sQ = quantize_blocks(Qsm, bq)
+    Kh, sK = quantize_blocks(Ksm, bkv)
+    Vh, sV = quantize_blocks(Vp, bkv)
+    return dict(Qh=Qh, sQ=sQ, Kh=Kh, sK=sK, Vh=Vh, sV=sV, muK=muK, muQ=muQ, Ksm=Ksm, n=n, bq=bq, bkv=bkv)
 
 
 def delta_rows(dO, O) -> np.ndarray:
@@ -173,19 +193,20 @@ def delta_rows(dO, O) -> np.ndarray:
 
 
 def _logits_block(pp, i0: int, n_keys: int, sm_scale: float, q_smooth: bool, key_idx=None) -> np.ndarray:
-    """S for the 64 queries starting at i0 against keys [0, n_keys) (or against the
+    """S for the bq queries starting at i0 against keys [0, n_keys) (or against the
     keys listed in key_idx, a sampling aid that changes no value):
     S = (Q^ K^^T) * s_Q * s_K * sm_scale (Algorithm 1, the S_ij line; R1: the
     1/sqrt(d) of Sec. 4 is applied in the dequantisation factor) plus the
     Q-smoothing bias mu_Qi K^sm^T when that smoothing is on (Sec. 3 decomposition;
     the mu_K terms are row constants and are dropped, so S lives in the smoothed
     frame, R10)."""
-    I = i0 // BLOCK
+    bq, bkv = pp["bq"], pp["bkv"]
+    I = i0 // bq
     sel = slice(0, n_keys) if key_idx is None else key_idx
-    qi = pp["Qh"][i0:i0 + BLOCK].astype(_F64)
+    qi = pp["Qh"][i0:i0 + bq].astype(_F64)
     kj = pp["Kh"][sel].astype(_F64)
     acc = qi @ kj.T                                           # exact integers
-    sk_per_key = np.repeat(pp["sK"].astype(_F64), BLOCK)[sel]
+    sk_per_key = np.repeat(pp["sK"].astype(_F64), bkv)[sel]
     S = acc * (_F64(pp["sQ"][I]) * _F64(sm_scale)) * sk_per_key[None, :]
     if q_smooth:
         bias = pp["Ksm"][sel].astype(_F64) @ pp["muQ"][I].astype(_F64)
@@ -193,33 +214,43 @@ def _logits_block(pp, i0: int, n_keys: int, sm_scale: float, q_smooth: bool, key
     return S
 
 
+def _visible_keys(i0: int, n: int, causal: bool, bq: int, bkv: int) -> int:
+    """Keys [0, n_keys) that the Q block starting at i0 works on: all n without the mask; under the
+    causal mask (R13) the KV blocks that hold a key k <= i for some row i of the block (whole KV
+    blocks, since psi's scales are per block; fully masked blocks are skipped)."""
+    if not causal:
+        return n
+    return min(n, -(-(i0 + bq) // bkv) * bkv)
+
+
 # --------------------------------------------------------------------------
 # forward (Algorithm 1)
 # --------------------------------------------------------------------------
 def forward_head(Q, K, V, causal: bool = True, k_smooth: bool = True, q_smooth: bool = False,
-                 sm_scale: float | None = None, return_raw: bool = False, q_blocks=None):
+                 sm_scale: float | None = None, return_raw: bool = False, q_blocks=None,
+                 bq: int = BLOCK, bkv: int = BLOCK):
     """INT8 attention forward of one head.  Q, K, V: [N, d] float32 (bf16 values).
 
     Returns (O [N, d] bf16-rounded float32, L [N] float32); with return_raw the
-    unrounded float64 O and L come too.  `q_blocks` (iterable of 64-row block
+    unrounded float64 O and L come too.  `q_blocks` (iterable of bq-row block
     indices) restricts the work to those query blocks -- rows are independent --
     and leaves the other rows zero (sampling for large N).
     """
     Q = np.asarray(Q, dtype=_F32)
     n_true, d = Q.shape
-    n = -(-n_true // BLOCK) * BLOCK                   # rows after appending (module header)
+    n = padded_len(n_true, bq, bkv)                   # rows after appending (module header)
     if sm_scale is None:
         sm_scale = 1.0 / np.sqrt(d)
-    pp = prepass_head(Q, K, V, k_smooth, q_smooth)
-    Vh = pp["Vh"].astype(_F64).reshape(n // BLOCK, BLOCK, d)
+    pp = prepass_head(Q, K, V, k_smooth, q_smooth, bq, bkv)
+    Vh = pp["Vh"].astype(_F64).reshape(n // bkv, bkv, d)
     sV = pp["sV"].astype(_F64)
     O = np.zeros((n, d), dtype=_F64)
     L = np.zeros(n, dtype=_F64)
-    rows = np.arange(BLOCK)
-    todo = range(n // BLOCK) if q_blocks is None else sorted(set(int(b) for b in q_blocks))
-    for i0 in (BLOCK * b for b in todo):
-        n_keys = i0 + BLOCK if causal else n          # R13: keys k <= i only
-        tj = n_keys // BLOCK
+    rows = np.arange(bq)
+    todo = range(n // bq) if q_blocks is None else sorted(set(int(b) for b in q_blocks))
+    for i0 in (bq * b for b in todo):
+        n_keys = _visible_keys(i0, n, causal, bq, bkv)            # R13: keys k <= i only
+        tj = n_keys // bkv
         S = _logits_block(pp, i0, n_keys, sm_scale, q_smooth)
         kk = np.arange(n_keys)
         if causal:
@@ -228,18 +259,20 @@ def forward_head(Q, K, V, causal: bool = True, k_smooth: bool = True, q_smooth: 
         # softmax statistics over the whole row: what m_{i,Tn}, l_{i,Tn} evaluate to (R2, R3)
         m = S.max(axis=1)
         l = np.exp(S - m[:, None]).sum(axis=1)        # unquantised P~ feeds l
-        L[i0:i0 + BLOCK] = m + np.log(l)
+        L[i0:i0 + bq] = m + np.log(l)
         # per KV block j: per-token quantisation of P~ (the s_P line of Algorithm 1).
         # R12: P~/s_P = exp(S - m) * 127 / exp(rowmax(S_ij) - m) = 127 exp(S - rowmax(S_ij)),
-        # rounded to nearest; the value is decided in float32.
-        St = S.reshape(BLOCK, tj, BLOCK)
-        Mloc = St.max(axis=2)                         # rowmax(S_ij), [64, tj]
-        e = np.exp(St - Mloc[:, :, None]).astype(_F32)
+        # rounded to nearest; the value is decided in float32.  (A row whose keys in block j are
+        # all masked has rowmax = -inf: its codes and its weight are zero.)
+        St = S.reshape(bq, tj, bkv)
+        Mloc = St.max(axis=2)                         # rowmax(S_ij), [bq, tj]
+        Msafe = np.where(np.isfinite(Mloc), Mloc, 0.0)
+        e = np.exp(St - Msafe[:, :, None]).astype(_F32)
         Ph = np.rint((e * _F32(127.0)).astype(_F32)).astype(_F64)      # integers 0..127
-        w = np.exp(Mloc - m[:, None]) / 127.0         # s_P relative to the final max
+        w = np.where(np.isfinite(Mloc), np.exp(Msafe - m[:, None]), 0.0) / 127.0   # s_P relative to the final max
         PV = np.einsum("qjk,jkc->qjc", Ph, Vh[:tj])   # exact integers
         acc = np.einsum("qj,qjc->qc", w * sV[None, :tj], PV)
-        O[i0:i0 + BLOCK] = acc / l[:, None]           # R4: O_i = diag(l)^-1 O_i
+        O[i0:i0 + bq] = acc / l[:, None]              # R4: O_i = diag(l)^-1 O_i
     O, L = O[:n_true], L[:n_true]                     # query rows that do not exist are dropped
     Ob = round_to_bf16(O)
     Lf = L.astype(_F32)
@@ -254,7 +287,7 @@ def forward_head(Q, K, V, causal: bool = True, k_smooth: bool = True, q_smooth: 
 def backward_head(Q, K, V, O, dO, L, causal: bool = True, k_smooth: bool = True,
                   q_smooth: bool = False, sm_scale: float | None = None,
                   return_raw: bool = False, intermediates: dict | None = None,
-                  q_blocks=None, kv_blocks=None):
+                  q_blocks=None, kv_blocks=None, bq: int = BLOCK, bkv: int = BLOCK):
     """INT8 attention backward of one head.
 
     Inputs as the caller holds them: Q, K, V, O, dO [N, d] (bf16 values as
@@ -263,25 +296,25 @@ def backward_head(Q, K, V, O, dO, L, causal: bool = True, k_smooth: bool = True,
 
     If `intermediates` is a dict it receives the unquantised float64 P, dP, dS
     of the whole head, the codes psi(dS) ("dSh", integers as float64) and their
-    tile scales ("sdS", [N/64, N/64] float32) (tiny inputs only; used by the
+    tile scales ("sdS", [N/bq, N/bkv] float32) (tiny inputs only; used by the
     invariant tests and by the GPU check of the in-loop quantiser).
 
     Sampling for large N (tiles are independent given L and delta):
-    `q_blocks` keeps only those Q blocks -- the rows of dQ that belong to them are
-    then complete, dK and dV are partial; `kv_blocks` keeps only those KV blocks --
-    the rows of dK and dV that belong to them are complete, dQ is partial.
+    `q_blocks` keeps only those Q blocks (of bq rows) -- the rows of dQ that belong to them
+    are then complete, dK and dV are partial; `kv_blocks` keeps only those KV blocks (of bkv
+    rows) -- the rows of dK and dV that belong to them are complete, dQ is partial.
     """
     Q = np.asarray(Q, dtype=_F32)
     n_true, d = Q.shape
-    n = -(-n_true // BLOCK) * BLOCK                           # rows after appending (module header)
+    n = padded_len(n_true, bq, bkv)                           # rows after appending (module header)
     if sm_scale is None:
         sm_scale = 1.0 / np.sqrt(d)
-    pp = prepass_head(Q, K, V, k_smooth, q_smooth)            # same blocks and scales as forward
+    pp = prepass_head(Q, K, V, k_smooth, q_smooth, bq, bkv)   # same blocks and scales as forward
     dO = pad_rows(np.asarray(dO, dtype=_F32), n)
     O = pad_rows(np.asarray(O, dtype=_F32), n)
     V = pad_rows(np.asarray(V, dtype=_F32), n)
     L = pad_rows(np.asarray(L, dtype=_F32), n)
-    dOh, sdO = quantize_blocks(dO)                            # psi(dO_i), per 64-row block
+    dOh, sdO = quantize_blocks(dO, bq)                        # psi(dO_i), per block of bq rows
     delta = delta_rows(dO, O)
     V64 = np.asarray(V, dtype=_F64)
     dO64 = np.asarray(dO, dtype=_F64)
@@ -296,49 +329,49 @@ def backward_head(Q, K, V, O, dO, L, causal: bool = True, k_smooth: bool = True,
         intermediates["dP"] = np.zeros((n, n))
         intermediates["dS"] = np.zeros((n, n))
         intermediates["dSh"] = np.zeros((n, n))
-        intermediates["sdS"] = np.zeros((n // BLOCK, n // BLOCK), dtype=_F32)
-    rows = np.arange(BLOCK)
-    q_todo = range(n // BLOCK) if q_blocks is None else sorted(set(int(b) for b in q_blocks))
+        intermediates["sdS"] = np.zeros((n // bq, n // bkv), dtype=_F32)
+    rows = np.arange(bq)
+    q_todo = range(n // bq) if q_blocks is None else sorted(set(int(b) for b in q_blocks))
     kv_keep = None if kv_blocks is None else set(int(b) for b in kv_blocks)
-    for i0 in (BLOCK * b for b in q_todo):
-        I = i0 // BLOCK
-        n_keys = i0 + BLOCK if causal else n
-        blocks = [J for J in range(n_keys // BLOCK) if kv_keep is None or J in kv_keep]
+    for i0 in (bq * b for b in q_todo):
+        I = i0 // bq
+        n_keys = _visible_keys(i0, n, causal, bq, bkv)
+        blocks = [J for J in range(n_keys // bkv) if kv_keep is None or J in kv_keep]
         if not blocks:
             continue
         # the key columns this row block works on (all visible keys unless KV blocks are sampled)
-        kk = np.concatenate([np.arange(BLOCK * J, BLOCK * J + BLOCK) for J in blocks])
+        kk = np.concatenate([np.arange(bkv * J, bkv * J + bkv) for J in blocks])
         S = _logits_block(pp, i0, n_keys, sm_scale, q_smooth, None if kv_keep is None else kk)
-        P = np.exp(S - L64[i0:i0 + BLOCK, None])              # P_ij = exp(S_ij - L_i)
+        P = np.exp(S - L64[i0:i0 + bq, None])                 # P_ij = exp(S_ij - L_i)
         if causal:
             P = np.where(kk[None, :] > (i0 + rows)[:, None], 0.0, P)   # R13: masked entries are 0
         # keys and query rows that do not exist
         P = np.where((kk[None, :] >= n_true) | ((i0 + rows)[:, None] >= n_true), 0.0, P)
-        dP = dO64[i0:i0 + BLOCK] @ V64[kk].T                  # unquantised matmul (R15)
-        dS = P * (dP - delta[i0:i0 + BLOCK, None])
+        dP = dO64[i0:i0 + bq] @ V64[kk].T                     # unquantised matmul (R15)
+        dS = P * (dP - delta[i0:i0 + bq, None])
         if intermediates is not None:
-            intermediates["P"][i0:i0 + BLOCK, kk] = P
-            intermediates["dP"][i0:i0 + BLOCK, kk] = dP
-            intermediates["dS"][i0:i0 + BLOCK, kk] = dS
-        dOh_i = dOh[i0:i0 + BLOCK].astype(_F64)
-        Qh_i = Qh[i0:i0 + BLOCK]
+            intermediates["P"][i0:i0 + bq, kk] = P
+            intermediates["dP"][i0:i0 + bq, kk] = dP
+            intermediates["dS"][i0:i0 + bq, kk] = dS
+        dOh_i = dOh[i0:i0 + bq].astype(_F64)
+        Qh_i = Qh[i0:i0 + bq]
         for t, J in enumerate(blocks):
-            j0 = J * BLOCK
-            c0 = t * BLOCK                                    # column offset of block J inside S, P, dS
+            j0 = J * bkv
+            c0 = t * bkv                                      # column offset of block J inside S, P, dS
             # dV_j += psi(P_ij)^T psi(dO_i) * s_P * s_dO   (R14: dynamic per-tile scale)
-            Ph, sP = _quantize_tile_f32(P[:, c0:c0 + BLOCK])
-            dV[j0:j0 + BLOCK] += (_F64(sP) * _F64(sdO[I])) * (Ph.T @ dOh_i)
+            Ph, sP = _quantize_tile_f32(P[:, c0:c0 + bkv])
+            dV[j0:j0 + bkv] += (_F64(sP) * _F64(sdO[I])) * (Ph.T @ dOh_i)
             # psi(dS_ij); dQ_i += dS^ K^_j * s_dS * s_K ; dK_j += dS^^T Q^_i * s_dS * s_Q
-            dSh, sdS = _quantize_tile_f32(dS[:, c0:c0 + BLOCK])
+            dSh, sdS = _quantize_tile_f32(dS[:, c0:c0 + bkv])
             if intermediates is not None:
-                intermediates["dSh"][i0:i0 + BLOCK, j0:j0 + BLOCK] = dSh
+                intermediates["dSh"][i0:i0 + bq, j0:j0 + bkv] = dSh
                 intermediates["sdS"][I, J] = sdS
-            dQ[i0:i0 + BLOCK] += (_F64(sm_scale) * _F64(sdS) * _F64(pp["sK"][J])) * (dSh @ Kh[j0:j0 + BLOCK])
-            dK[j0:j0 + BLOCK] += (_F64(sm_scale) * _F64(sdS) * _F64(pp["sQ"][I])) * (dSh.T @ Qh_i)
+            dQ[i0:i0 + bq] += (_F64(sm_scale) * _F64(sdS) * _F64(pp["sK"][J])) * (dSh @ Kh[j0:j0 + bkv])
+            dK[j0:j0 + bkv] += (_F64(sm_scale) * _F64(sdS) * _F64(pp["sQ"][I])) * (dSh.T @ Qh_i)
             if q_smooth:
                 # dK_bias = (dS^T 1) mu_Q^T (ablation section); R17: from the unquantised dS
-                colsum = dS[:, c0:c0 + BLOCK].sum(axis=0)
-                dK[j0:j0 + BLOCK] += _F64(sm_scale) * colsum[:, None] * pp["muQ"][I].astype(_F64)[None, :]
+                colsum = dS[:, c0:c0 + bkv].sum(axis=0)
+                dK[j0:j0 + bkv] += _F64(sm_scale) * colsum[:, None] * pp["muQ"][I].astype(_F64)[None, :]
     dQ, dK, dV = dQ[:n_true], dK[:n_true], dV[:n_true]
     if return_raw:
         return dQ, dK, dV

@@ -10,7 +10,7 @@ import numpy as np
 import pytest
 
 import oracle
-from oracle import alg_literal
+from oracle import tiled_form
 from fpa_ref import cos_sim, fpa_backward, fpa_forward, rel_l2
 
 GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
@@ -316,19 +316,46 @@ def test_one_hot_limit():
 
 
 # ------------------------------------------ two formulations, brute force
-@pytest.mark.parametrize("causal", [True, False])
-def test_non_tiled_oracle_equals_literal_algorithms(causal):
+@pytest.mark.parametrize("bq,bkv", [(64, 64), (128, 64), (128, 128), (64, 128)])
+@pytest.mark.parametrize("causal,q_smooth", [(True, False), (False, False), (True, True), (False, True)])
+def test_non_tiled_oracle_equals_tiled_formulation(causal, q_smooth, bq, bkv):
+    """oracle/tiled_form.py shares no code with the oracle (own smoothing, own psi, own delta,
+    online softmax, KV-outer backward): the two must agree.  Covers the Q-smoothing bias of the
+    logits and the dK bias branch, and the block sizes Algorithm 1 leaves free."""
     N, d = 256, 32
-    Q, K, V, dO = _rand(N, d, seed=14, qk_norm=True)
-    Ob, L, Oraw, Lraw = oracle.forward_head(Q, K, V, causal=causal, return_raw=True)
-    O2, L2 = alg_literal.forward_tiled(Q, K, V, causal=causal)
+    Q, K, V, dO = _rand(N, d, seed=14 + bq + 2 * bkv, qk_norm=True)
+    if q_smooth:
+        Q = _bf(Q + np.linspace(-1.5, 1.5, d)[None, :])
+    kw = dict(causal=causal, q_smooth=q_smooth, bq=bq, bkv=bkv)
+    Ob, L, Oraw, Lraw = oracle.forward_head(Q, K, V, return_raw=True, **kw)
+    O2, L2 = tiled_form.forward_tiled(Q, K, V, **kw)
     assert np.abs(Lraw - L2).max() < 1e-12
     # P~/s_P against 127*exp(S - rowmax): identical up to a handful of rounding-boundary codes
     assert rel_l2(O2, Oraw) < 2e-4
-    dQ, dK, dV = oracle.backward_head(Q, K, V, Ob, dO, L, causal=causal, return_raw=True)
-    dQ2, dK2, dV2 = alg_literal.backward_tiled(Q, K, V, Ob, dO, L, causal=causal)
+    dQ, dK, dV = oracle.backward_head(Q, K, V, Ob, dO, L, return_raw=True, **kw)
+    dQ2, dK2, dV2 = tiled_form.backward_tiled(Q, K, V, Ob, dO, L, **kw)
     for a, b in ((dQ, dQ2), (dK, dK2), (dV, dV2)):
         assert np.allclose(a, b, rtol=1e-10, atol=1e-12)
+
+
+def test_tiled_formulation_has_its_own_prepass():
+    """The second formulation imports nothing from the oracle (so that agreement means two
+    implementations), and its smoothing and quantiser give the oracle's bits."""
+    import ast
+    import inspect
+    tree = ast.parse(inspect.getsource(tiled_form))
+    mods = [n.module or "" for n in ast.walk(tree) if isinstance(n, ast.ImportFrom)] + \
+           [a.name for n in ast.walk(tree) if isinstance(n, ast.Import) for a in n.names]
+    assert all("oracle" not in m and not m.startswith(".") and m != "" for m in mods), mods
+    Q, K, V, _ = _rand(256, 32, seed=21)
+    Q = _bf(Q + 0.7)
+    K = _bf(K - 2.0)
+    pre = tiled_form._Prepared(Q, K, V, True, True, 128, 64)
+    pp = oracle.prepass_head(Q, K, V, True, True, 128, 64)
+    assert np.array_equal(pre.mu_k, pp["muK"]) and np.array_equal(np.stack(pre.mu_q), pp["muQ"])
+    for mine, codes, scales in ((pre.q_codes, "Qh", "sQ"), (pre.k_codes, "Kh", "sK"), (pre.v_codes, "Vh", "sV")):
+        assert np.array_equal(np.concatenate(mine), pp[codes].astype(np.float64))
+    assert np.array_equal(np.array(pre.q_scale), pp["sQ"]) and np.array_equal(np.array(pre.k_scale), pp["sK"])
 
 
 def test_kv_block_permutation_invariance():
@@ -343,14 +370,25 @@ def test_kv_block_permutation_invariance():
     assert np.allclose(a[3], b[3], rtol=1e-12, atol=1e-14)
 
 
-def test_brute_force_scalar_transcription():
-    """Every step re-done with Python scalars on a 128 x 8 causal problem."""
+@pytest.mark.parametrize("causal,q_smooth", [(True, False), (False, False), (True, True), (False, True)])
+def test_brute_force_scalar_transcription(causal, q_smooth):
+    """Every step re-done with Python scalars on a 128 x 8 problem: K-smoothing, optional
+    Q-smoothing (block means, the mu_Qi K^sm bias of the logits, the (dS^T 1) mu_Q^T branch of dK:
+    Sec. 3 decomposition and the dK_bias equation of the ablation section), with and without the
+    causal mask."""
     N, d = 128, 8
-    Q, K, V, dO = _rand(N, d, seed=16)
+    Q, K, V, dO = _rand(N, d, seed=16 + 2 * causal + q_smooth)
+    if q_smooth:
+        Q = _bf(Q + np.linspace(-2, 2, d)[None, :])
     sc = 1 / math.sqrt(d)
     f32 = np.float32
+    nb = N // 64
     muK = [f32(sum(float(K[n, c]) for n in range(N)) / N) for c in range(d)]
     Ksm = [[f32(K[n, c] - muK[c]) for c in range(d)] for n in range(N)]
+    muQ = [[f32(sum(float(Q[n, c]) for n in range(64 * b, 64 * b + 64)) / 64) if q_smooth else f32(0) for c in range(d)]
+           for b in range(nb)]
+    Qsm = [[f32(Q[n, c] - muQ[n // 64][c]) if q_smooth else Q[n, c] for c in range(d)] for n in range(N)]
+    vis = (lambda i, k: k <= i) if causal else (lambda i, k: True)
 
     def psi(rows):
         a = max(abs(float(x)) for r in rows for x in r)
@@ -360,47 +398,186 @@ def test_brute_force_scalar_transcription():
         return q, f32(a / f32(127.0))
 
     Qh, sQ, Kh, sK, Vh, sV, dOh, sdO = [], [], [], [], [], [], [], []
-    for b in range(N // 64):
-        for lst, sl, src in ((Qh, sQ, Q), (Kh, sK, Ksm), (Vh, sV, V), (dOh, sdO, dO)):
+    for b in range(nb):
+        for lst, sl, src in ((Qh, sQ, Qsm), (Kh, sK, Ksm), (Vh, sV, V), (dOh, sdO, dO)):
             q, s = psi([list(src[n]) for n in range(64 * b, 64 * b + 64)])
             lst.extend(q)
             sl.append(s)
-    S = [[(sum(Qh[i][c] * Kh[k][c] for c in range(d)) * float(sQ[i // 64]) * float(sK[k // 64]) * sc) if k <= i else -math.inf
-          for k in range(N)] for i in range(N)]
+
+    def logit(i, k):
+        s = sum(Qh[i][c] * Kh[k][c] for c in range(d)) * float(sQ[i // 64]) * float(sK[k // 64]) * sc
+        if q_smooth:
+            s += sc * sum(float(muQ[i // 64][c]) * float(Ksm[k][c]) for c in range(d))
+        return s
+
+    S = [[logit(i, k) if vis(i, k) else -math.inf for k in range(N)] for i in range(N)]
     O = np.zeros((N, d))
     Lr = np.zeros(N)
     for i in range(N):
         m = max(S[i])
         l = sum(math.exp(s - m) for s in S[i])
         Lr[i] = m + math.log(l)
-        for j in range(i // 64 + 1):
+        for j in range(nb):
             ks = range(64 * j, 64 * j + 64)
+            if not any(vis(i, k) for k in ks):
+                continue
             M = max(S[i][k] for k in ks)
             ph = [int(np.rint(f32(f32(math.exp(S[i][k] - M)) * f32(127.0)))) for k in ks]
             w = math.exp(M - m) / 127.0 * float(sV[j]) / l
             for c in range(d):
                 O[i, c] += w * sum(ph[t] * Vh[64 * j + t][c] for t in range(64))
-    Ob, L, Oraw, Lraw = oracle.forward_head(Q, K, V, causal=True, return_raw=True)
+    kw = dict(causal=causal, q_smooth=q_smooth)
+    Ob, L, Oraw, Lraw = oracle.forward_head(Q, K, V, return_raw=True, **kw)
     assert np.allclose(Oraw, O, rtol=1e-11, atol=1e-13) and np.allclose(Lraw, Lr, atol=1e-12)
     # backward
     delta = [sum(float(dO[i, c]) * float(Ob[i, c]) for c in range(d)) for i in range(N)]
     dQ = np.zeros((N, d)); dK = np.zeros((N, d)); dV = np.zeros((N, d))
-    for I in range(N // 64):
-        for J in range(I + 1):
-            P = [[math.exp(S[i][k] - float(L[i])) if k <= i else 0.0 for k in range(64 * J, 64 * J + 64)] for i in range(64 * I, 64 * I + 64)]
+    for I in range(nb):
+        for J in range(nb):
+            if causal and J > I:
+                continue
+            P = [[math.exp(S[i][k] - float(L[i])) if vis(i, k) else 0.0 for k in range(64 * J, 64 * J + 64)]
+                 for i in range(64 * I, 64 * I + 64)]
             dS = [[P[a][b] * (sum(float(dO[64 * I + a, c]) * float(V[64 * J + b, c]) for c in range(d)) - delta[64 * I + a])
                    for b in range(64)] for a in range(64)]
             Ph, sP = psi(P)
             dSh, sdS = psi(dS)
+            for b in range(64):
+                col = sum(dS[a][b] for a in range(64))
+                for c in range(d):
+                    dV[64 * J + b, c] += float(sP) * float(sdO[I]) * sum(Ph[a][b] * dOh[64 * I + a][c] for a in range(64))
+                    dK[64 * J + b, c] += sc * float(sdS) * float(sQ[I]) * sum(dSh[a][b] * Qh[64 * I + a][c] for a in range(64))
+                    if q_smooth:
+                        dK[64 * J + b, c] += sc * col * float(muQ[I][c])
             for a in range(64):
-                for b in range(64):
-                    for c in range(d):
-                        dV[64 * J + b, c] += float(sP) * float(sdO[I]) * Ph[a][b] * dOh[64 * I + a][c]
-                        dQ[64 * I + a, c] += sc * float(sdS) * float(sK[J]) * dSh[a][b] * Kh[64 * J + b][c]
-                        dK[64 * J + b, c] += sc * float(sdS) * float(sQ[I]) * dSh[a][b] * Qh[64 * I + a][c]
-    g = oracle.backward_head(Q, K, V, Ob, dO, L, causal=True, return_raw=True)
+                for c in range(d):
+                    dQ[64 * I + a, c] += sc * float(sdS) * float(sK[J]) * sum(dSh[a][b] * Kh[64 * J + b][c] for b in range(64))
+    g = oracle.backward_head(Q, K, V, Ob, dO, L, return_raw=True, **kw)
     for a, b in zip(g, (dQ, dK, dV)):
         assert np.allclose(a, b, rtol=1e-9, atol=1e-12)
+    if q_smooth:
+        # the bias terms are not negligible here: without them the comparison above would fail
+        g0 = oracle.backward_head(Q, K, V, Ob, dO, L, return_raw=True, causal=causal, q_smooth=False)
+        assert rel_l2(g0[1], dK) > 1e-3
+
+
+# ------------------------------------------- block sampling (used by the full-size GPU tests)
+@pytest.mark.parametrize("bq,bkv", [(64, 64), (128, 64)])
+@pytest.mark.parametrize("causal,q_smooth", [(True, False), (False, False), (True, True), (False, True)])
+def test_sampled_blocks_equal_the_full_run(causal, q_smooth, bq, bkv):
+    """forward_head(q_blocks=) and backward_head(q_blocks= / kv_blocks=) restrict the work to some
+    blocks; the rows they claim to complete must be the rows of the full run (N = 512: several
+    blocks on either side of every sampled one, so a wrong column offset or key index shows)."""
+    N, d = 512, 32
+    Q, K, V, dO = _rand(N, d, seed=60 + causal + 2 * q_smooth, qk_norm=True)
+    if q_smooth:
+        Q = _bf(Q + np.linspace(-1, 1, d)[None, :])
+    kw = dict(causal=causal, q_smooth=q_smooth, bq=bq, bkv=bkv)
+    Ob, L, Oraw, Lraw = oracle.forward_head(Q, K, V, return_raw=True, **kw)
+    qb = [0, 2, N // bq - 1]
+    rows = np.concatenate([np.arange(bq * i, bq * i + bq) for i in qb])
+    other = np.setdiff1d(np.arange(N), rows)
+    Os, Ls, Osr, Lsr = oracle.forward_head(Q, K, V, return_raw=True, q_blocks=qb, **kw)
+    assert np.abs(Osr[rows] - Oraw[rows]).max() <= 1e-12 and np.abs(Lsr[rows] - Lraw[rows]).max() <= 1e-12
+    assert np.array_equal(Os[rows], Ob[rows]) and not Osr[other].any()
+    full = oracle.backward_head(Q, K, V, Ob, dO, L, return_raw=True, **kw)
+    part = oracle.backward_head(Q, K, V, Ob, dO, L, return_raw=True, q_blocks=qb, **kw)
+    assert np.abs(part[0][rows] - full[0][rows]).max() <= 1e-12 * max(1.0, np.abs(full[0]).max())
+    assert not part[0][other].any()
+    kb = [1, 3, N // bkv - 2]
+    krows = np.concatenate([np.arange(bkv * j, bkv * j + bkv) for j in kb])
+    kother = np.setdiff1d(np.arange(N), krows)
+    part = oracle.backward_head(Q, K, V, Ob, dO, L, return_raw=True, kv_blocks=kb, **kw)
+    for x, y in ((part[1], full[1]), (part[2], full[2])):
+        assert np.abs(x[krows] - y[krows]).max() <= 1e-12 * max(1.0, np.abs(y).max())
+        assert not x[kother].any()
+    # both at once: only the tiles in (q_blocks x kv_blocks) are visited; dV of a sampled KV block
+    # then holds exactly the share of the sampled Q blocks
+    both = oracle.backward_head(Q, K, V, Ob, dO, L, return_raw=True, q_blocks=qb, kv_blocks=kb, **kw)
+    inter = {}
+    oracle.backward_head(Q, K, V, Ob, dO, L, intermediates=inter, **kw)
+    share = np.zeros((N, d))
+    dOh, sdO = oracle.quantize_blocks(dO, bq)
+    for I in qb:
+        for J in kb:
+            P = inter["P"][bq * I:bq * I + bq, bkv * J:bkv * J + bkv]
+            a = np.float32(np.abs(P.astype(np.float32)).max())
+            if a > 0:
+                Ph = np.rint((P.astype(np.float32) * (np.float32(127) / a)).astype(np.float32)).astype(np.float64)
+                share[bkv * J:bkv * J + bkv] += float(np.float32(a / np.float32(127))) * float(sdO[I]) * (Ph.T @ dOh[bq * I:bq * I + bq].astype(np.float64))
+    assert np.allclose(both[2], share, rtol=1e-10, atol=1e-13)
+
+
+def test_sampling_pin_catches_a_wrong_column_offset(monkeypatch):
+    """The pin above is sharp: an oracle whose sampled-KV path reads the wrong keys (planted here on
+    the CPU: the key index list shifted by one block) disagrees with the full run."""
+    N, d = 512, 32
+    Q, K, V, dO = _rand(N, d, seed=61, qk_norm=True)
+    Ob, L = oracle.forward_head(Q, K, V, causal=False)
+    full = oracle.backward_head(Q, K, V, Ob, dO, L, causal=False, return_raw=True)
+    from oracle import sage_oracle
+    good = sage_oracle._logits_block
+
+    def shifted(pp, i0, n_keys, sm_scale, q_smooth, key_idx=None):
+        if key_idx is not None:
+            key_idx = (np.asarray(key_idx) + 64) % n_keys
+        return good(pp, i0, n_keys, sm_scale, q_smooth, key_idx)
+
+    monkeypatch.setattr(sage_oracle, "_logits_block", shifted)
+    bad = oracle.backward_head(Q, K, V, Ob, dO, L, causal=False, return_raw=True, kv_blocks=[1, 3])
+    krows = np.concatenate([np.arange(64 * j, 64 * j + 64) for j in (1, 3)])
+    assert np.abs(bad[1][krows] - full[1][krows]).max() > 1e-3 * np.abs(full[1]).max()
+
+
+# ------------------------------------------- other numerics block sizes (Algorithm 1 leaves B_q, B_kv free)
+@pytest.mark.parametrize("bq,bkv", [(128, 64), (128, 128)])
+def test_larger_blocks_quantiser_and_prepass(bq, bkv):
+    rng = np.random.default_rng(70)
+    X = _bf(rng.standard_normal((256, 16)) * 2)
+    q, s = oracle.quantize_blocks(X, bq)
+    assert s.shape == (256 // bq,)
+    for b in range(256 // bq):
+        xb = X[bq * b:bq * b + bq].astype(np.float64)
+        assert s[b] == np.float32(np.float32(np.abs(xb).max()) / np.float32(127))
+        assert np.abs(q[bq * b:bq * b + bq]).max() == 127
+        assert np.abs(xb - float(s[b]) * q[bq * b:bq * b + bq]).max() <= float(s[b]) * (0.5 + 1e-4)
+    Q, K, V, _ = _rand(256, 16, seed=71)
+    pp = oracle.prepass_head(Q, K, V, True, True, bq, bkv)
+    assert pp["sQ"].shape == (256 // bq,) and pp["sK"].shape == (256 // bkv,) and pp["muQ"].shape == (256 // bq, 16)
+    assert np.allclose(pp["muQ"][1], Q[bq:2 * bq].mean(0), atol=1e-6)
+    # a scale shared by more rows is the maximum of the 64-row scales
+    s64 = oracle.quantize_blocks(K - pp["muK"], 64)[1]
+    assert np.array_equal(pp["sK"], s64.reshape(-1, bkv // 64).max(axis=1))
+
+
+@pytest.mark.parametrize("bq,bkv", [(128, 64), (128, 128)])
+@pytest.mark.parametrize("causal", [True, False])
+def test_larger_blocks_close_to_exact_attention_and_closed_forms(bq, bkv, causal):
+    N, d = 256, 64
+    Q, K, V, dO = _rand(N, d, seed=72 + causal, qk_norm=True)
+    sc = 1 / math.sqrt(d)
+    O, L = oracle.forward_head(Q, K, V, causal=causal, bq=bq, bkv=bkv)
+    dQ, dK, dV = oracle.backward_head(Q, K, V, O, dO, L, causal=causal, bq=bq, bkv=bkv)
+    ref = fpa_backward(Q, K, V, dO, causal, sc)
+    for name, got in (("O", O), ("dQ", dQ), ("dK", dK), ("dV", dV)):
+        assert cos_sim(got, ref[name]) > 0.997, name
+        assert rel_l2(got, ref[name]) < 0.08, name
+    # Q = 0: every P^ = 127 and O_i is the mean of the dequantised visible V rows, whatever the blocks
+    Z = np.zeros_like(Q)
+    _, _, Oraw, Lraw = oracle.forward_head(Z, K, V, causal=causal, bq=bq, bkv=bkv, return_raw=True)
+    Vh, sV = oracle.quantize_blocks(V, bkv)
+    Vdq = Vh.astype(np.float64) * np.repeat(sV.astype(np.float64), bkv)[:, None]
+    for i in (0, 63, 64, 127, 128, 255):
+        nvis = i + 1 if causal else N
+        assert math.isclose(Lraw[i], math.log(nvis), abs_tol=1e-12)
+        assert np.allclose(Oraw[i], Vdq[:nvis].mean(0), atol=1e-12)
+    # a partial last block with the larger blocks: N = 200 rounds up to 256
+    Q2, K2, V2, dO2 = _rand(200, d, seed=74, qk_norm=True)
+    O2, L2 = oracle.forward_head(Q2, K2, V2, causal=causal, bq=bq, bkv=bkv)
+    g2 = oracle.backward_head(Q2, K2, V2, O2, dO2, L2, causal=causal, bq=bq, bkv=bkv)
+    ref2 = fpa_backward(Q2, K2, V2, dO2, causal, sc)
+    for name, got in zip(("O", "dQ", "dK", "dV"), (O2,) + g2):
+        assert got.shape == (200, d) and rel_l2(got, ref2[name]) < 0.08, name
 
 
 # ------------------------------------------- sequence lengths that are not a multiple of 64
