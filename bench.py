@@ -21,15 +21,24 @@ if ROOT not in sys.path:
 INT8_PEAK_TOPS = 5000.0     # MI355X dense INT8 MFMA peak (published)
 HBM_PEAK_GBS = 8000.0       # MI355X HBM3E peak (published)
 
-# HBM bytes per launch at the headline workload, from the rocprofv3 FETCH_SIZE / WRITE_SIZE runs
-# summarised in profiles/hbm_traffic_headline_fwd_bwd.txt (scaled by the copy-kernel calibration).
-MEASURED_TRAFFIC_BYTES = {"headline": {"bwd": 3.4796e9, "fwd": 3.382e8, "bwd_dq": 2.6434e9}}
+# HBM bytes per launch at the headline workload.  NOT measured in this run: taken from the committed
+# rocprofv3 FETCH_SIZE / WRITE_SIZE runs summarised in profiles/hbm_traffic_headline_fwd_bwd.txt
+# (scaled by the copy-kernel calibration stated there).
+PROFILED_TRAFFIC_BYTES = {"headline": {"bwd": 3.4796e9, "fwd": 3.382e8, "bwd_dq": 2.6434e9}}
 
 
-def work_ops(w, fwd=True, bwd=True):
-    per = (4 if fwd else 0) + (10 if bwd else 0)
+def work_ops(w, fwd=True, bwd=True, matmuls=None):
+    """Work convention: 2*N^2*d ops per matmul and head (forward two matmuls, backward five),
+    halved under the causal mask.  `matmuls` overrides the count (a kernel that runs some of them)."""
+    per = 2 * matmuls if matmuls is not None else (4 if fwd else 0) + (10 if bwd else 0)
     ops = per * w.B * w.H * float(w.N) ** 2 * w.d
     return ops * (0.5 if w.causal else 1.0)
+
+
+def executed_tiles(w):
+    """64 x 64 tiles per head that the kernels visit."""
+    t = -(-w.N // 64)
+    return t * (t + 1) // 2 if w.causal else t * t
 
 
 def cpu_baseline(w, seconds_hint=20.0):
@@ -63,6 +72,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="headline")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-share", action="store_true",
+                    help="the backward forms psi(Q), psi(K) again instead of taking them from the forward's "
+                         "workspace (SAGEBWD_FLAG_SHARE_QUANTIZED off)")
     ap.add_argument("--token-major", action="store_true",
                     help="hold Q, K, V, O, dO and the gradients as [B, N, H, d] (the default is [B, H, N, d])")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -91,7 +103,7 @@ def main():
     binding.load_library()      # fails loudly if the HIP library is missing
     torch.cuda.set_device(0)
     p = binding.SageParams(w.B, w.H, w.N, w.d, causal=w.causal, k_smooth=w.k_smooth, q_smooth=w.q_smooth,
-                           token_major=a.token_major)
+                           token_major=a.token_major, share_quantized=not a.no_share)
     Q, K, V, dO = (t.cuda() for t in synth.make_inputs(w))
     if a.token_major:
         Q, K, V, dO = (t.permute(0, 2, 1, 3).contiguous() for t in (Q, K, V, dO))
@@ -130,12 +142,19 @@ def main():
     binding.set_timing(False)
 
     tops = work_ops(w) / (ms * 1e-3) / 1e12
-    bwd_ops = work_ops(w, fwd=False)
+    # sage_bwd_kernel runs four of the five backward matmuls (S recompute, dV, dP, dK); the fifth (dQ)
+    # runs in sage_bwd_dq_kernel from the staged psi(dS) tiles
+    bwd_ops = work_ops(w, matmuls=4)
     fwd_ops = work_ops(w, bwd=False)
     bwd_tops = bwd_ops / (kern["bwd"] * 1e-3) / 1e12
     fwd_tops = fwd_ops / (kern["fwd"] * 1e-3) / 1e12
     elems = w.B * w.H * w.N * w.d
-    pre_fwd_bytes = elems * (4 * 2 + 3 * 1)          # read Q, K (twice), V bf16; write three INT8 tensors
+    # pre-pass (forward): read Q, K, V bf16 once each, write three INT8 tensors = 9 B per (token, channel)
+    # algorithmic (K's second read, for the mean, is what a cache can serve); sharing adds two more layouts
+    pre_fwd_bytes = elems * (3 * 2 + 3 * 1 + (0 if a.no_share else 2))
+    # dQ kernel: reads the staged psi(dS) tiles (4 KiB each) and K^ once per head, writes dQ bf16
+    dq_bytes = w.B * w.H * (executed_tiles(w) * 4096.0 + w.N * w.d * 3.0)
+    traffic = PROFILED_TRAFFIC_BYTES.get(w.name, {})
     out = {
         "metric": f"attention fwd+bwd TOPS and % of INT8 MFMA peak on one MI355X, N={w.N} d={w.d}",
         "value": tops, "unit": "TOPS", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": ms,
@@ -144,23 +163,36 @@ def main():
                                f"{'with' if w.qk_norm else 'without'} QK-norm, K-smoothing {'on' if w.k_smooth else 'off'}, "
                                f"Q-smoothing {'on' if w.q_smooth else 'off'}, 64x64 blocks"
                                f"{', tensors [B,N,H,d]' if a.token_major else ''}",
-                   "work_convention": "fwd 4*BH*N^2*d + bwd 10*BH*N^2*d ops, x0.5 causal"},
+                   "work_convention": "fwd 4*BH*N^2*d + bwd 10*BH*N^2*d ops, x0.5 causal",
+                   "step": "sagebwd_fwd then sagebwd_bwd on one workspace, pre-passes included; "
+                           + ("the backward re-quantises Q and K" if a.no_share else
+                              "the backward takes psi(Q), psi(K) from the forward (Algorithm 2's inputs; "
+                              "SAGEBWD_FLAG_SHARE_QUANTIZED), every step of the method runs once per step")},
         "pct_of_int8_peak": 100.0 * tops / INT8_PEAK_TOPS,
         "fwd_only": {"ms": fwd_ms, "TOPS": fwd_ops / (fwd_ms * 1e-3) / 1e12,
                      "pct_of_int8_peak": 100.0 * fwd_ops / (fwd_ms * 1e-3) / 1e12 / INT8_PEAK_TOPS},
         "kernel_ms": kern,
         "roofline": {"bound": "mfma", "kernel": "sage_bwd_kernel", "achieved": bwd_tops, "peak": INT8_PEAK_TOPS,
                      "unit": "TOP/s", "frac": bwd_tops / INT8_PEAK_TOPS,
-                     "traffic": MEASURED_TRAFFIC_BYTES.get(w.name, {}).get("bwd"),
-                     "note": "algorithmic ops of the five backward matmuls (10*N^2*d per head, x0.5 causal) over "
-                             "the kernel's mean HIP-event duration; one of the five runs on bf16 MFMA (half rate), "
-                             "so the mixed roof is 5/6 of the INT8 peak"},
+                     "traffic": traffic.get("bwd"),
+                     "frac_of_mixed_roof": bwd_tops / (INT8_PEAK_TOPS * 0.8),
+                     "note": "algorithmic ops of the four matmuls this kernel runs (8*N^2*d per head, x0.5 causal) "
+                             "over its mean HIP-event duration, against the INT8 MFMA peak; one of the four (dP) "
+                             "runs on bf16 MFMA at half rate, so the kernel's own mixed roof is 4/5 of that peak "
+                             "(frac_of_mixed_roof).  traffic: from profiles/, not measured in this run"},
         "roofline_fwd": {"bound": "mfma", "kernel": "sage_fwd_kernel", "achieved": fwd_tops, "peak": INT8_PEAK_TOPS,
-                         "unit": "TOP/s", "frac": fwd_tops / INT8_PEAK_TOPS,
-                         "traffic": MEASURED_TRAFFIC_BYTES.get(w.name, {}).get("fwd")},
+                         "unit": "TOP/s", "frac": fwd_tops / INT8_PEAK_TOPS, "traffic": traffic.get("fwd")},
+        "roofline_bwd_dq": {"bound": "hbm", "kernel": "sage_bwd_dq_kernel",
+                            "achieved": dq_bytes / (kern["bwd_dq"] * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                            "frac": dq_bytes / (kern["bwd_dq"] * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                            "traffic": traffic.get("bwd_dq"),
+                            "note": "bytes = staged psi(dS) tiles + K^ + dQ; the tiles are this design's staging "
+                                    "of dS between the two backward kernels, not traffic the method itself requires"},
         "roofline_prepass": {"bound": "hbm", "kernel": "prepass (forward)",
                              "achieved": pre_fwd_bytes / (kern["prepass_fwd"] * 1e-3) / 1e9, "peak": HBM_PEAK_GBS,
-                             "unit": "GB/s", "frac": pre_fwd_bytes / (kern["prepass_fwd"] * 1e-3) / 1e9 / HBM_PEAK_GBS},
+                             "unit": "GB/s", "frac": pre_fwd_bytes / (kern["prepass_fwd"] * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                             "bytes_per_element": pre_fwd_bytes / elems,
+                             "note": "K is read twice (mean, then psi); the second read is not counted"},
     }
     if not a.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w)

@@ -10,7 +10,9 @@
  * Conventions shared by every entry point
  *   - All tensor pointers are DEVICE pointers owned by the caller.  The library
  *     allocates and frees no device memory; scratch lives in a caller-owned
- *     workspace of sagebwd_workspace_bytes() bytes (256-byte aligned).
+ *     workspace of sagebwd_workspace_bytes() bytes (256-byte aligned).  Apart from the
+ *     benchmark hooks at the end of this file the library keeps no state between calls:
+ *     everything that shapes a call, the scratch budget included, is in sagebwd_params.
  *   - Tensors are dense and contiguous: Q, K, V, O, dO, dQ, dK, dV are bf16
  *     [B, H, N, d] (or [B, N, H, d], see sagebwd_params.layout); LSE is float32 [B, H, N].
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Work
@@ -19,7 +21,12 @@
  *     sagebwd_fwd / sagebwd_bwd may be recorded under stream capture and replayed.
  *   - Return value: SAGEBWD_OK (0) or a negative sagebwd_status.  Arguments are
  *     validated on the host before anything is launched; on error nothing runs.
- *   - Numerics blocks are B_q = B_kv = 64 (one FP32 scale per 64 rows x d channels).
+ *   - Numerics blocks are B_q = B_kv = 64 (one FP32 scale per 64 rows x d channels); Algorithm 1
+ *     takes both as inputs, sagebwd_params carries them, other values are SAGEBWD_UNSUPPORTED_SHAPE.
+ *   - Bit-exact contract: the stored INT8 tensors Q^, K^, V^, dO^, their scales and the smoothing
+ *     means equal the paper's definitions evaluated in FP32 bit for bit.  The quantisers inside
+ *     the attention loops (P^ of the forward, psi(P) and psi(dS) of the backward) depend on the
+ *     hardware exp2 and are held to a tolerance (codes within one step), as are O, LSE, dQ, dK, dV.
  *   - Supported shapes: d in {64, 128}; N >= 1; B*H*Np*d < 2^40, where Np is N rounded
  *     up to a multiple of 64.  The paper assumes N/B_q and N/B_kv integral (Algorithm 1
  *     line 2); for other N the last block is a partial block whose missing rows do not
@@ -40,7 +47,7 @@ extern "C" {
 typedef enum sagebwd_status {
   SAGEBWD_OK = 0,
   SAGEBWD_INVALID_ARG = -1,        /* null pointer, non-positive size, unknown selector */
-  SAGEBWD_UNSUPPORTED_SHAPE = -2,  /* d not in {64,128}, sizes beyond the stated limits */
+  SAGEBWD_UNSUPPORTED_SHAPE = -2,  /* d not in {64,128}, blocks other than 64 x 64, sizes beyond the stated limits */
   SAGEBWD_WORKSPACE_TOO_SMALL = -3,
   SAGEBWD_HIP_ERROR = -4           /* a HIP runtime call or launch failed */
 } sagebwd_status;
@@ -54,12 +61,30 @@ typedef enum sagebwd_status {
 #define SAGEBWD_LAYOUT_BNHD 1 /* [B, N, H, d], token-major as most frameworks hold activations: read and
                                  written in place through row strides (rows lie H*d elements apart) */
 
+/* Flags.
+ * SAGEBWD_FLAG_SHARE_QUANTIZED: the backward takes psi(Q), psi(K), their scales and the smoothing
+ * means from the forward instead of forming them again (Algorithm 2 lists them among its inputs
+ * "from the forward").  With the flag set, sagebwd_fwd also leaves Q^ and K^ in the operand layouts
+ * of the backward (its workspace need grows by 2*B*H*Np*d bytes, see sagebwd_workspace_bytes), and
+ * sagebwd_bwd re-runs only the dO part of the pre-pass.  The caller guarantees that the same
+ * workspace, params, Q and K are passed to both calls and that nothing wrote the workspace in
+ * between (another sagebwd_fwd on it included).  Results are bit-identical to the calls without
+ * the flag.  Without the flag sagebwd_bwd relies on nothing an earlier call left behind. */
+#define SAGEBWD_FLAG_SHARE_QUANTIZED 1
+
 typedef struct sagebwd_params {
   int32_t B, H, N, d;
   int32_t causal;  /* 0 / 1: key index <= query index (square self-attention) */
   int32_t smooth;  /* OR of SAGEBWD_SMOOTH_* ; the paper's default is SAGEBWD_SMOOTH_K */
   float sm_scale;  /* logit scale; 0 selects 1/sqrt(d) (paper Sec. 4: S = Q K^T / sqrt(d)) */
   int32_t layout;  /* SAGEBWD_LAYOUT_*: how the caller holds Q, K, V, O, dO, dQ, dK, dV */
+  int32_t bq, bkv; /* numerics block sizes B_q, B_kv (Algorithm 1, input line); 0 selects 64 */
+  int32_t flags;   /* OR of SAGEBWD_FLAG_* */
+  int32_t reserved;          /* must be 0 */
+  uint64_t scratch_budget;   /* upper bound, in bytes, on the INT8 dS scratch that sagebwd_bwd holds at
+                                once; 0 selects 8 GiB.  The backward needs Np*Np bytes per head and
+                                processes the heads in groups that fit the bound (at least one head per
+                                group); the workspace size follows from it. */
 } sagebwd_params;
 
 /* Which quantised tensor sagebwd_export_quantized() copies out. */
@@ -80,10 +105,11 @@ typedef enum sagebwd_kernel {
   SAGEBWD_KERNEL_COUNT = 5
 } sagebwd_kernel;
 
-/* Bytes of workspace that sagebwd_fwd / sagebwd_bwd / sagebwd_quantize need for
- * these params (host computation only).  *bytes is the larger of the forward's
- * and the backward's need, so one buffer serves both calls. */
-int sagebwd_workspace_bytes(const sagebwd_params* params, size_t* bytes);
+/* Bytes of workspace the calls need for these params (host computation only): *fwd_bytes for
+ * sagebwd_fwd, *bwd_bytes (never smaller) for sagebwd_bwd, sagebwd_quantize and the export hooks.
+ * The forward's part is a prefix of the backward's, so a buffer of *bwd_bytes serves every call.
+ * Either pointer may be NULL. */
+int sagebwd_workspace_bytes(const sagebwd_params* params, size_t* fwd_bytes, size_t* bwd_bytes);
 
 /*
  * Pre-pass (paper Sec. 3 smoothing equations; Algorithm 1 "Quantization" line;
@@ -93,8 +119,10 @@ int sagebwd_workspace_bytes(const sagebwd_params* params, size_t* bytes);
  *   q = rne(x * (127/a)) in FP32, clamped to [-127,127]; a == 0 gives s = 0, q = 0.
  *   If dO is non-NULL: psi(dO) per 64-row block; if O is also non-NULL,
  *   delta = rowsum(dO o O) in FP32.
- * Results are left in `workspace` in the library's internal operand layouts; use
- * sagebwd_export_quantized() to read them in row-major form.  dO and O may be NULL.
+ * Results are left in `workspace` in the library's internal operand layouts (1 KiB fragments in
+ * the order the matrix instructions consume them, Q^ and K^ twice), which is why there is no call
+ * that returns raw pointers into the workspace: use sagebwd_export_quantized() /
+ * sagebwd_export_stats() to read them in row-major form.  dO and O may be NULL.
  */
 int sagebwd_quantize(const void* Q, const void* K, const void* V, const void* dO, const void* O,
                      const sagebwd_params* params, void* workspace, size_t workspace_bytes,
@@ -127,7 +155,7 @@ int sagebwd_export_stats(const sagebwd_params* params, const void* workspace,
  *   ds_out     int8    [Np, Np] row-major (query, key); tiles above the causal diagonal are zero
  *   scale_out  float32 [Np/64, Np/64], one scale per 64x64 tile (dS ~ scale * code)
  * Np = N rounded up to a multiple of 64.  Either output may be NULL.  Only defined when the backward
- * ran all heads in one group (B*H*Np*Np bytes within the scratch budget), otherwise
+ * ran all heads in one group (B*H*Np*Np bytes within params->scratch_budget), otherwise
  * SAGEBWD_UNSUPPORTED_SHAPE.  A test / inspection hook: the in-loop quantisers depend on the
  * hardware's exp2, so their codes are compared with a tolerance of one step, not bit for bit.
  */
@@ -157,25 +185,22 @@ int sagebwd_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE
  *   dK_j += psi(dS_ij)^T Q^_i * s_dS * s_Q * sm_scale [+ bias branch with Q-smoothing] (INT8)
  * Inputs are the caller's bf16 Q, K, V, O, dO and the LSE of sagebwd_fwd run with the
  * same params; the pre-pass is re-run inside, so the workspace need not survive
- * between the two calls.  dQ, dK, dV (bf16 [B,H,N,d]) are overwritten.
- * The quantised dS tiles are staged in the workspace (N*N bytes per head, at most 8 GiB
- * at a time: larger problems are processed in groups of heads) and dQ is formed from
- * them by a second kernel, so all three gradients are deterministic (no atomics).
+ * between the two calls (unless SAGEBWD_FLAG_SHARE_QUANTIZED is set).  dQ, dK, dV
+ * (bf16 [B,H,N,d]) are overwritten.
+ * The quantised dS tiles are staged in the workspace (Np*Np bytes per head, at most
+ * params->scratch_budget at a time: larger problems are processed in groups of heads) and dQ is
+ * formed from them by a second kernel, so all three gradients are deterministic (no atomics).
  */
 int sagebwd_bwd(const void* Q, const void* K, const void* V, const void* O, const void* dO,
                 const float* LSE, void* dQ, void* dK, void* dV, const sagebwd_params* params,
                 void* workspace, size_t workspace_bytes, void* stream);
 
-/* Upper bound, in bytes, on the INT8 dS scratch that sagebwd_bwd holds at once (default
- * 8 GiB).  The backward needs N*N bytes per head and processes the heads in groups that fit
- * the bound (at least one head per group).  Process-wide setting: call it before
- * sagebwd_workspace_bytes, and use the same value for the calls that share a workspace. */
-int sagebwd_set_scratch_budget(size_t bytes);
-
-/* Per-kernel device timing.  When enabled, every entry point brackets each kernel
+/* ---- benchmark hooks (not calls of the method; the only process-wide state of the library) ----
+ * Per-kernel device timing.  When enabled, every entry point brackets each kernel
  * it launches with HIP events on the caller's stream.  sagebwd_read_timing waits for
  * the recorded events of `kernel`, returns their summed milliseconds and the launch
- * count since the last read, and resets both.  Not thread-safe; meant for benchmarks. */
+ * count since the last read, and resets both.  The switch and the recorded events are shared by
+ * all threads of the process (guarded by a mutex); do not enable it under stream capture. */
 int sagebwd_set_timing(int enable);
 int sagebwd_read_timing(int kernel /* sagebwd_kernel */, double* total_ms, int* launches);
 

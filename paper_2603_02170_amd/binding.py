@@ -17,6 +17,7 @@ _LIB = None
 
 SMOOTH_K = 1
 SMOOTH_Q = 2
+FLAG_SHARE_QUANTIZED = 1
 LAYOUT_BHND, LAYOUT_BNHD = 0, 1
 
 TENSOR_Q, TENSOR_K, TENSOR_V, TENSOR_DO = 0, 1, 2, 3
@@ -24,14 +25,15 @@ KERNEL_PREPASS_FWD, KERNEL_FWD, KERNEL_PREPASS_BWD, KERNEL_BWD, KERNEL_BWD_DQ = 
 
 EXPORTS = (
     "sagebwd_workspace_bytes", "sagebwd_quantize", "sagebwd_export_quantized", "sagebwd_export_stats", "sagebwd_export_ds",
-    "sagebwd_fwd", "sagebwd_bwd", "sagebwd_set_scratch_budget", "sagebwd_set_timing", "sagebwd_read_timing", "sagebwd_strerror",
+    "sagebwd_fwd", "sagebwd_bwd", "sagebwd_set_timing", "sagebwd_read_timing", "sagebwd_strerror",
 )
 
 
 class _CParams(ctypes.Structure):
     _fields_ = [("B", ctypes.c_int32), ("H", ctypes.c_int32), ("N", ctypes.c_int32), ("d", ctypes.c_int32),
                 ("causal", ctypes.c_int32), ("smooth", ctypes.c_int32), ("sm_scale", ctypes.c_float),
-                ("layout", ctypes.c_int32)]
+                ("layout", ctypes.c_int32), ("bq", ctypes.c_int32), ("bkv", ctypes.c_int32),
+                ("flags", ctypes.c_int32), ("reserved", ctypes.c_int32), ("scratch_budget", ctypes.c_uint64)]
 
 
 @dataclass
@@ -45,11 +47,17 @@ class SageParams:
     q_smooth: bool = False
     sm_scale: float = 0.0   # 0 selects 1/sqrt(d)
     token_major: bool = False   # the bf16 tensors are [B, N, H, d] instead of [B, H, N, d]
+    share_quantized: bool = False   # the backward takes psi(Q), psi(K) from the forward's workspace
+    scratch_budget: int = 0     # bytes of dS scratch the backward holds at once; 0 selects 8 GiB
+    bq: int = 0                 # numerics block sizes; 0 selects 64
+    bkv: int = 0
 
     def c(self) -> _CParams:
         return _CParams(self.B, self.H, self.N, self.d, int(self.causal),
                         (SMOOTH_K if self.k_smooth else 0) | (SMOOTH_Q if self.q_smooth else 0),
-                        float(self.sm_scale), LAYOUT_BNHD if self.token_major else LAYOUT_BHND)
+                        float(self.sm_scale), LAYOUT_BNHD if self.token_major else LAYOUT_BHND,
+                        int(self.bq), int(self.bkv), FLAG_SHARE_QUANTIZED if self.share_quantized else 0, 0,
+                        int(self.scratch_budget))
 
     def tensor_shape(self):
         """Shape of Q, K, V, O, dO, dQ, dK, dV as the caller holds them."""
@@ -72,7 +80,7 @@ def load_library():
     lib = ctypes.CDLL(path)
     vp, sz, i32 = ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int
     pp = ctypes.POINTER(_CParams)
-    lib.sagebwd_workspace_bytes.argtypes = [pp, ctypes.POINTER(sz)]
+    lib.sagebwd_workspace_bytes.argtypes = [pp, ctypes.POINTER(sz), ctypes.POINTER(sz)]
     lib.sagebwd_quantize.argtypes = [vp, vp, vp, vp, vp, pp, vp, sz, vp]
     lib.sagebwd_export_quantized.argtypes = [pp, vp, sz, i32, vp, vp, vp]
     lib.sagebwd_export_stats.argtypes = [pp, vp, sz, vp, vp, vp, vp]
@@ -80,7 +88,6 @@ def load_library():
     lib.sagebwd_fwd.argtypes = [vp, vp, vp, vp, vp, pp, vp, sz, vp]
     lib.sagebwd_bwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, pp, vp, sz, vp]
     lib.sagebwd_set_timing.argtypes = [i32]
-    lib.sagebwd_set_scratch_budget.argtypes = [sz]
     lib.sagebwd_read_timing.argtypes = [i32, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i32)]
     lib.sagebwd_strerror.argtypes = [i32]
     lib.sagebwd_strerror.restype = ctypes.c_char_p
@@ -119,15 +126,17 @@ def _expect(t, dtype, shape, name):
         raise ValueError(f"{name}: need contiguous cuda {dtype} {tuple(shape)}, got {t.dtype} {tuple(t.shape)}")
 
 
-def workspace_bytes(p: SageParams) -> int:
-    out = ctypes.c_size_t(0)
+def workspace_bytes(p: SageParams, forward_only: bool = False) -> int:
+    """Bytes that serve every call (or, with forward_only, sagebwd_fwd alone)."""
+    fwd, bwd = ctypes.c_size_t(0), ctypes.c_size_t(0)
     cp = p.c()
-    _check(load_library().sagebwd_workspace_bytes(ctypes.byref(cp), ctypes.byref(out)), "sagebwd_workspace_bytes")
-    return int(out.value)
+    _check(load_library().sagebwd_workspace_bytes(ctypes.byref(cp), ctypes.byref(fwd), ctypes.byref(bwd)),
+           "sagebwd_workspace_bytes")
+    return int(fwd.value if forward_only else bwd.value)
 
 
-def alloc_workspace(p: SageParams, device="cuda"):
-    return torch.empty(workspace_bytes(p), dtype=torch.uint8, device=device)
+def alloc_workspace(p: SageParams, device="cuda", forward_only: bool = False):
+    return torch.empty(workspace_bytes(p, forward_only), dtype=torch.uint8, device=device)
 
 
 def sagebwd_quantize(Q, K, V, p: SageParams, workspace, dO=None, O=None):
@@ -190,7 +199,7 @@ def sagebwd_fwd(Q, K, V, p: SageParams, workspace=None, O=None, LSE=None):
     for t, n in ((Q, "Q"), (K, "K"), (V, "V")):
         _expect(t, torch.bfloat16, shp, n)
     if workspace is None:
-        workspace = alloc_workspace(p, Q.device)
+        workspace = alloc_workspace(p, Q.device, forward_only=True)
     if O is None:
         O = torch.empty(shp, dtype=torch.bfloat16, device=Q.device)
     if LSE is None:
@@ -222,10 +231,6 @@ def sagebwd_bwd(Q, K, V, O, dO, LSE, p: SageParams, workspace=None, dQ=None, dK=
                                       _ptr(outs[1]), _ptr(outs[2]), ctypes.byref(cp), _ptr(workspace),
                                       workspace.numel(), _stream()), "sagebwd_bwd")
     return tuple(outs)
-
-
-def set_scratch_budget(nbytes: int):
-    _check(load_library().sagebwd_set_scratch_budget(int(nbytes)), "sagebwd_set_scratch_budget")
 
 
 def set_timing(enable: bool):

@@ -16,27 +16,46 @@ namespace sage {
 
 #pragma clang fp contract(off)
 
-constexpr int kMeanChunkRows = 256;
+// Rows of K per workgroup of the mean reduction: the host picks the largest of these that still gives
+// the launch a few workgroups per CU (the consumer sums one partial per chunk and channel).
+inline int mean_chunk_rows(int heads, int N) {
+  int rows = 1024;
+  while (rows > 128 && (long long)heads * ((N + rows - 1) / rows) < 1024) rows >>= 1;
+  return rows;
+}
 
-
-// ---- K mean, stage 1: float64 column sums of a 256-row chunk ----------------------
+// ---- K mean, stage 1: float64 column sums of a chunk of rows -----------------------
+// (bf16 data of ordinary range sum exactly in float64, so the result does not depend on the order
+// or on the chunk size.)  Stage 2, the sum over the chunks, the division by N and the one rounding to
+// FP32, runs at the start of every workgroup that quantises a block of K (prepass_quant_kernel).
 template <int D>
 __global__ void __launch_bounds__(256) kmean_partial_kernel(const unsigned short* __restrict__ K, RowView view,
                                                             double* __restrict__ kpart, int N,
-                                                            int nchunk) {
+                                                            int nchunk, int chunk_rows) {
   constexpr int TPR = D / 8;          // threads per row, 8 channels (16 bytes) each
   constexpr int RPP = 256 / TPR;      // rows per pass
   __shared__ double red[256][8];
   const int t = threadIdx.x;
   const int chunk = blockIdx.x, bh = blockIdx.y;
-  const int row0 = chunk * kMeanChunkRows;
-  const int rows = min(kMeanChunkRows, N - row0);
+  const int row0 = chunk * chunk_rows;
+  const int rows = min(chunk_rows, N - row0);
   const unsigned short* base = K + view.row(bh, row0);
   double acc[8];
 #pragma unroll
   for (int e = 0; e < 8; e++) acc[e] = 0.0;
   const int tr = t / TPR, tc = t % TPR;
-  for (int r = tr; r < rows; r += RPP) {
+  int r = tr;
+  // four independent 16-byte loads in flight per thread
+  for (; r + 3 * RPP < rows; r += 4 * RPP) {
+    v8us v[4];
+#pragma unroll
+    for (int u = 0; u < 4; u++) v[u] = *(const v8us*)(base + (size_t)(r + u * RPP) * view.row_stride + tc * 8);
+#pragma unroll
+    for (int u = 0; u < 4; u++)
+#pragma unroll
+      for (int e = 0; e < 8; e++) acc[e] += (double)bf16_bits_to_float(v[u][e]);
+  }
+  for (; r < rows; r += RPP) {
     v8us v = *(const v8us*)(base + (size_t)r * view.row_stride + tc * 8);
 #pragma unroll
     for (int e = 0; e < 8; e++) acc[e] += (double)bf16_bits_to_float(v[e]);
@@ -51,16 +70,6 @@ __global__ void __launch_bounds__(256) kmean_partial_kernel(const unsigned short
   }
 }
 
-// ---- K mean, stage 2: sum the chunks, divide by N, round once to FP32 -------------
-__global__ void kmean_final_kernel(const double* __restrict__ kpart, float* __restrict__ muK, int N,
-                                   int nchunk, int D) {
-  const int bh = blockIdx.x, c = threadIdx.x;
-  if (c >= D) return;
-  double s = 0.0;
-  for (int k = 0; k < nchunk; k++) s += kpart[((size_t)bh * nchunk + k) * D + c];
-  muK[(size_t)bh * D + c] = (float)(s / (double)N);
-}
-
 __global__ void fill_zero_f32_kernel(float* __restrict__ p, size_t n) {
   size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x;
   const size_t stride = (size_t)gridDim.x * blockDim.x;
@@ -73,7 +82,10 @@ struct QuantJob {
   int8_t* outF;                // F layout or nullptr
   int8_t* outTF;               // TF layout or nullptr
   float* scale;                // [BH, N/64]
-  const float* mu_head;        // [BH, D] subtracted from every row (K-smoothing) or nullptr
+  const double* mean_part;     // K-smoothing: float64 column sums [BH, nchunk, D] of the whole head; the
+                               // mean (sum / N, rounded once to FP32) is subtracted from every row.  Else nullptr
+  int nchunk;
+  float* mu_head_out;          // [BH, D]: where block 0 of each head stores that mean
   float* mu_block_out;         // [BH, N/64, D]: if set, the block mean is computed, stored and subtracted
   const unsigned short* O;     // bf16 [BH, N, D] or nullptr: delta = rowsum(src o O)
   float* delta;                // [BH, N]
@@ -151,14 +163,22 @@ __global__ void __launch_bounds__(256) prepass_quant_kernel(QuantJobs jobs, RowV
     jb.nl2[(size_t)bh * Np + row] = t < rows_here ? -jb.lse[(size_t)bh * N + row] * 1.4426950408889634f : -INFINITY;
   }
 
-  if (jb.mu_head != nullptr) {
+  if (jb.mean_part != nullptr) {
+    // mu_K: the chunk sums of the head, added in float64, divided by N, rounded once to FP32
+    if (t < D) {
+      double s = 0.0;
+      for (int k = 0; k < jb.nchunk; k++) s += jb.mean_part[((size_t)bh * jb.nchunk + k) * D + t];
+      const float m = (float)(s / (double)N);
+      mu_s[t] = m;
+      if (blk == 0) jb.mu_head_out[(size_t)bh * D + t] = m;
+    }
+    __syncthreads();
 #pragma unroll
     for (int it = 0; it < NCH; it++) {
       const int row = (t + 256 * it) / CPR, ch = (t + 256 * it) % CPR;
-      const float* mu = jb.mu_head + (size_t)bh * D + ch * 16;
       if (row < rows_here) {
 #pragma unroll
-        for (int e = 0; e < 16; e++) x[it][e] = x[it][e] - mu[e];
+        for (int e = 0; e < 16; e++) x[it][e] = x[it][e] - mu_s[ch * 16 + e];
       }
     }
   }

@@ -6,6 +6,7 @@
 #include <math.h>
 #include <string.h>
 
+#include <mutex>
 #include <vector>
 
 #include "common.h"
@@ -17,7 +18,7 @@ namespace {
 
 using namespace sage;
 
-size_t g_ds_budget = (size_t)8 << 30;   // bytes of INT8 dS scratch the backward may hold at once
+constexpr size_t kDefaultDsBudget = (size_t)8 << 30;   // bytes of INT8 dS scratch the backward holds at once unless told otherwise
 
 inline size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
 
@@ -40,25 +41,29 @@ inline RowView caller_view(const sagebwd_params& p, size_t scale) {
 }
 
 
-// Byte offsets of every buffer inside the caller's workspace.
+// Byte offsets of every buffer inside the caller's workspace.  What the forward needs comes first
+// (`fwd_total` bytes), so that a forward-only caller can pass a much smaller buffer.
 struct Workspace {
-  size_t kpart, muK, muQ, sQ, sK, sV, sdO, delta, nl2;
+  size_t kpart, muK, muQ, sQ, sK, sV;
   size_t QF, KF, VT;        // forward operands (QF, KF also feed the backward's S recompute)
-  size_t QT, KT, dOT;       // backward operands (TF layouts)
+  size_t bias;              // Q-smoothing: logit bias table [BH, N/64, N]
+  size_t QT, KT;            // backward operands (TF layouts) that depend on Q and K only
+  size_t fwd_total;         // the forward's need (with SAGEBWD_FLAG_SHARE_QUANTIZED it includes QT, KT)
+  size_t sdO, delta, nl2, dOT;
   size_t dSq;               // psi(dS) tiles of one head group [heads_per_group, N/64, N/64, 4096]
   size_t sdS;               // their scales [heads_per_group, N/64, N/64]
   int heads_per_group;      // the backward runs in groups of heads that share the dS scratch
-  size_t bias;              // Q-smoothing: logit bias table [BH, N/64, N]
-  size_t colsum;            // Q-smoothing backward: colsum(dS) per (Q block, key) [BH, N/64, N]
   size_t total;
-  int nchunk;
+  int nchunk, chunk_rows;   // K-mean reduction: chunks per head, rows per chunk
 };
 
 Workspace make_layout(const sagebwd_params& p) {
   Workspace w;
   const size_t BH = (size_t)p.B * p.H, N = padded_rows(p.N), d = p.d, nblk = N / 64;
   const bool qs = (p.smooth & SAGEBWD_SMOOTH_Q) != 0;
-  w.nchunk = (int)(((size_t)p.N + kMeanChunkRows - 1) / kMeanChunkRows);
+  const bool share = (p.flags & SAGEBWD_FLAG_SHARE_QUANTIZED) != 0;
+  w.chunk_rows = mean_chunk_rows((int)BH, p.N);
+  w.nchunk = (p.N + w.chunk_rows - 1) / w.chunk_rows;
   size_t off = 0;
   auto take = [&](size_t bytes) { size_t o = off; off += align_up(bytes); return o; };
   w.kpart = take(BH * w.nchunk * d * sizeof(double));
@@ -67,24 +72,26 @@ Workspace make_layout(const sagebwd_params& p) {
   w.sQ = take(BH * nblk * 4);
   w.sK = take(BH * nblk * 4);
   w.sV = take(BH * nblk * 4);
-  w.sdO = take(BH * nblk * 4);
-  w.delta = take(BH * N * 4);
-  w.nl2 = take(BH * N * 4);
   w.QF = take(BH * N * d);
   w.KF = take(BH * N * d);
   w.VT = take(BH * N * d);
+  w.bias = take(qs ? BH * nblk * N * 4 : 0);
+  if (!share) w.fwd_total = off;
   w.QT = take(BH * N * d);
   w.KT = take(BH * N * d);
+  if (share) w.fwd_total = off;
+  w.sdO = take(BH * nblk * 4);
+  w.delta = take(BH * N * 4);
+  w.nl2 = take(BH * N * 4);
   w.dOT = take(BH * N * d);
-  // dS scratch: N*N bytes per head, capped at kDsBudget by processing the heads in groups
-  size_t hpg = g_ds_budget / (N * N);
+  // dS scratch: N*N bytes per head, capped at the budget by processing the heads in groups
+  const size_t budget = p.scratch_budget != 0 ? (size_t)p.scratch_budget : kDefaultDsBudget;
+  size_t hpg = budget / (N * N);
   if (hpg < 1) hpg = 1;
   if (hpg > BH) hpg = BH;
   w.heads_per_group = (int)hpg;
   w.dSq = take(hpg * N * N);
   w.sdS = take(hpg * nblk * nblk * 4);
-  w.bias = take(qs ? BH * nblk * N * 4 : 0);
-  w.colsum = take(qs ? BH * nblk * N * 4 : 0);
   w.total = off;
   return w;
 }
@@ -93,10 +100,13 @@ int check_params(const sagebwd_params* p) {
   if (p == nullptr) return SAGEBWD_INVALID_ARG;
   if (p->B <= 0 || p->H <= 0 || p->N <= 0 || p->d <= 0) return SAGEBWD_INVALID_ARG;
   if (p->layout != SAGEBWD_LAYOUT_BHND && p->layout != SAGEBWD_LAYOUT_BNHD) return SAGEBWD_INVALID_ARG;
+  if ((p->flags & ~SAGEBWD_FLAG_SHARE_QUANTIZED) != 0 || p->reserved != 0) return SAGEBWD_INVALID_ARG;
+  if (p->bq < 0 || p->bkv < 0) return SAGEBWD_INVALID_ARG;
   if ((p->smooth & ~(SAGEBWD_SMOOTH_K | SAGEBWD_SMOOTH_Q)) != 0) return SAGEBWD_INVALID_ARG;
   if (p->causal != 0 && p->causal != 1) return SAGEBWD_INVALID_ARG;
   if (!(p->sm_scale >= 0.f) || isinf(p->sm_scale)) return SAGEBWD_INVALID_ARG;
   if (p->d != 64 && p->d != 128) return SAGEBWD_UNSUPPORTED_SHAPE;
+  if ((p->bq != 0 && p->bq != 64) || (p->bkv != 0 && p->bkv != 64)) return SAGEBWD_UNSUPPORTED_SHAPE;
   if (p->N > (1 << 30)) return SAGEBWD_UNSUPPORTED_SHAPE;
   const double elems = (double)p->B * p->H * (double)padded_rows(p->N) * p->d;
   if (elems >= 1099511627776.0) return SAGEBWD_UNSUPPORTED_SHAPE;
@@ -112,6 +122,8 @@ float logit_scale(const sagebwd_params& p) {
 struct TimedSpan {
   hipEvent_t a, b;
 };
+// Benchmark hook: the only process-wide state of the library, guarded by one mutex.
+std::mutex g_timing_mutex;
 bool g_timing = false;
 std::vector<TimedSpan> g_spans[SAGEBWD_KERNEL_COUNT];
 std::vector<TimedSpan> g_pool;
@@ -121,7 +133,9 @@ struct ScopedTimer {
   hipStream_t st;
   TimedSpan span;
   bool on;
-  ScopedTimer(int kernel, hipStream_t s) : k(kernel), st(s), on(g_timing) {
+  ScopedTimer(int kernel, hipStream_t s) : k(kernel), st(s), on(false) {
+    std::lock_guard<std::mutex> lock(g_timing_mutex);
+    on = g_timing;
     if (!on) return;
     if (!g_pool.empty()) {
       span = g_pool.back();
@@ -135,6 +149,7 @@ struct ScopedTimer {
   ~ScopedTimer() {
     if (!on) return;
     (void)hipEventRecord(span.b, st);
+    std::lock_guard<std::mutex> lock(g_timing_mutex);
     g_spans[k].push_back(span);
   }
 };
@@ -145,42 +160,50 @@ struct ScopedTimer {
   } while (0)
 
 // ---- pre-pass ---------------------------------------------------------------
+// want_qk: smooth and quantise Q and K (F layouts; with want_tf also the backward's TF layouts);
+// want_v: quantise V; dO != nullptr: quantise dO and form delta and -L*log2(e).
 template <int D>
 int run_prepass(const void* Q, const void* K, const void* V, const void* dO, const void* O, const float* LSE,
-                const sagebwd_params& p, char* ws, const Workspace& w, bool for_bwd, hipStream_t st) {
+                const sagebwd_params& p, char* ws, const Workspace& w, bool want_qk, bool want_tf, bool want_v,
+                hipStream_t st) {
   const int BH = p.B * p.H, N = p.N, Np = padded_rows(N), nblk = Np / 64;
   const bool ks = (p.smooth & SAGEBWD_SMOOTH_K) != 0;
   const bool qs = (p.smooth & SAGEBWD_SMOOTH_Q) != 0;
   const RowView view = caller_view(p, 1);     // in bf16 elements
   float* muK = (float*)(ws + w.muK);
-  if (ks) {
-    kmean_partial_kernel<D><<<dim3(w.nchunk, BH), 256, 0, st>>>((const unsigned short*)K, view,
-                                                                 (double*)(ws + w.kpart), N, w.nchunk);
-    SAGE_LAUNCH_CHECK();
-    kmean_final_kernel<<<BH, 128, 0, st>>>((const double*)(ws + w.kpart), muK, N, w.nchunk, D);
-    SAGE_LAUNCH_CHECK();
-  } else {
-    fill_zero_f32_kernel<<<(BH * D + 255) / 256, 256, 0, st>>>(muK, (size_t)BH * D);
-    SAGE_LAUNCH_CHECK();
+  if (want_qk) {
+    if (ks) {
+      kmean_partial_kernel<D><<<dim3(w.nchunk, BH), 256, 0, st>>>((const unsigned short*)K, view,
+                                                                   (double*)(ws + w.kpart), N, w.nchunk, w.chunk_rows);
+      SAGE_LAUNCH_CHECK();
+    } else {
+      fill_zero_f32_kernel<<<(BH * D + 255) / 256, 256, 0, st>>>(muK, (size_t)BH * D);
+      SAGE_LAUNCH_CHECK();
+    }
   }
   QuantJobs jobs;
   memset(&jobs, 0, sizeof(jobs));
   int nj = 0;
-  // Q: F layout (S = Q^ K^^T in both passes) and, for the backward, TF layout (dK = dS^^T Q^)
-  jobs.job[nj].src = (const unsigned short*)Q;
-  jobs.job[nj].outF = (int8_t*)(ws + w.QF);
-  jobs.job[nj].outTF = for_bwd ? (int8_t*)(ws + w.QT) : nullptr;
-  jobs.job[nj].scale = (float*)(ws + w.sQ);
-  jobs.job[nj].mu_block_out = qs ? (float*)(ws + w.muQ) : nullptr;
-  nj++;
-  // K: F layout, and TF layout for the backward (dQ = dS^ K^)
-  jobs.job[nj].src = (const unsigned short*)K;
-  jobs.job[nj].outF = (int8_t*)(ws + w.KF);
-  jobs.job[nj].outTF = for_bwd ? (int8_t*)(ws + w.KT) : nullptr;
-  jobs.job[nj].scale = (float*)(ws + w.sK);
-  jobs.job[nj].mu_head = ks ? muK : nullptr;
-  nj++;
-  if (V != nullptr && !for_bwd) {
+  if (want_qk) {
+    // K first: the mean reduction has just read it, so these blocks find it in the memory-side cache.
+    // F layout, and TF layout for the backward (dQ = dS^ K^)
+    jobs.job[nj].src = (const unsigned short*)K;
+    jobs.job[nj].outF = (int8_t*)(ws + w.KF);
+    jobs.job[nj].outTF = want_tf ? (int8_t*)(ws + w.KT) : nullptr;
+    jobs.job[nj].scale = (float*)(ws + w.sK);
+    jobs.job[nj].mean_part = ks ? (const double*)(ws + w.kpart) : nullptr;
+    jobs.job[nj].nchunk = w.nchunk;
+    jobs.job[nj].mu_head_out = muK;
+    nj++;
+    // Q: F layout (S = Q^ K^^T in both passes) and, for the backward, TF layout (dK = dS^^T Q^)
+    jobs.job[nj].src = (const unsigned short*)Q;
+    jobs.job[nj].outF = (int8_t*)(ws + w.QF);
+    jobs.job[nj].outTF = want_tf ? (int8_t*)(ws + w.QT) : nullptr;
+    jobs.job[nj].scale = (float*)(ws + w.sQ);
+    jobs.job[nj].mu_block_out = qs ? (float*)(ws + w.muQ) : nullptr;
+    nj++;
+  }
+  if (want_v) {
     // V: TF layout (O = P^ V^ contracts over keys); the backward uses the bf16 V only
     jobs.job[nj].src = (const unsigned short*)V;
     jobs.job[nj].outTF = (int8_t*)(ws + w.VT);
@@ -198,9 +221,11 @@ int run_prepass(const void* Q, const void* K, const void* V, const void* dO, con
     jobs.job[nj].nl2 = (float*)(ws + w.nl2);
     nj++;
   }
-  prepass_quant_kernel<D><<<dim3(nblk, BH, nj), 256, 0, st>>>(jobs, view, N, Np);
-  SAGE_LAUNCH_CHECK();
-  if (qs) {
+  if (nj > 0) {
+    prepass_quant_kernel<D><<<dim3(nblk, BH, nj), 256, 0, st>>>(jobs, view, N, Np);
+    SAGE_LAUNCH_CHECK();
+  }
+  if (qs && want_qk) {
     const float sl2 = logit_scale(p) * 1.4426950408889634f;
     qsmooth_bias_kernel<D><<<dim3(nblk, BH), 256, 0, st>>>(
         (const unsigned short*)K, view, muK, (const float*)(ws + w.muQ), (float*)(ws + w.bias), N, Np,
@@ -208,6 +233,18 @@ int run_prepass(const void* Q, const void* K, const void* V, const void* dO, con
     SAGE_LAUNCH_CHECK();
   }
   return SAGEBWD_OK;
+}
+
+template <int D>
+int prepass_for_forward(const void* Q, const void* K, const void* V, const sagebwd_params& p, char* ws,
+                        const Workspace& w, hipStream_t st) {
+  const bool share = (p.flags & SAGEBWD_FLAG_SHARE_QUANTIZED) != 0;
+  return run_prepass<D>(Q, K, V, nullptr, nullptr, nullptr, p, ws, w, true, share, true, st);
+}
+template <int D>
+int prepass_for_backward(const void* Q, const void* K, const void* V, const void* dO, const void* O, const float* LSE,
+                         const sagebwd_params& p, char* ws, const Workspace& w, bool reuse, hipStream_t st) {
+  return run_prepass<D>(Q, K, V, dO, O, LSE, p, ws, w, !reuse, true, false, st);
 }
 
 // Waves per forward workgroup (32 queries each).  Four, with two (d = 128) or three (d = 64)
@@ -264,15 +301,49 @@ int launch_bwd_dq(const DqArgs& a, bool causal, hipStream_t st) {
   return SAGEBWD_OK;
 }
 
+// The forward on a workspace that holds at least w.fwd_total bytes (arguments already validated).
+int forward_impl(const void* Q, const void* K, const void* V, void* O, float* LSE, const sagebwd_params& p,
+                 char* ws, const Workspace& w, hipStream_t st) {
+  int rc;
+  {
+    ScopedTimer tm(SAGEBWD_KERNEL_PREPASS_FWD, st);
+    rc = p.d == 64 ? prepass_for_forward<64>(Q, K, V, p, ws, w, st) : prepass_for_forward<128>(Q, K, V, p, ws, w, st);
+  }
+  if (rc != SAGEBWD_OK) return rc;
+  FwdArgs a;
+  a.QF = (const int8_t*)(ws + w.QF);
+  a.KF = (const int8_t*)(ws + w.KF);
+  a.VT = (const int8_t*)(ws + w.VT);
+  a.sQ = (const float*)(ws + w.sQ);
+  a.sK = (const float*)(ws + w.sK);
+  a.sV = (const float*)(ws + w.sV);
+  const bool qs = (p.smooth & SAGEBWD_SMOOTH_Q) != 0;
+  a.bias = qs ? (const float*)(ws + w.bias) : nullptr;
+  a.O = (unsigned short*)O;
+  a.oview = caller_view(p, 1);
+  a.LSE = LSE;
+  a.BH = p.B * p.H;
+  a.N = padded_rows(p.N);
+  a.nvalid = p.N;
+  a.n_qtiles = 0;
+  a.scale_log2e = logit_scale(p) * 1.4426950408889634f;
+  {
+    ScopedTimer tm(SAGEBWD_KERNEL_FWD, st);
+    rc = p.d == 64 ? launch_fwd<64>(a, p.causal != 0, qs, st) : launch_fwd<128>(a, p.causal != 0, qs, st);
+  }
+  return rc;
+}
+
 }  // namespace
 
 extern "C" {
 
-int sagebwd_workspace_bytes(const sagebwd_params* params, size_t* bytes) {
+int sagebwd_workspace_bytes(const sagebwd_params* params, size_t* fwd_bytes, size_t* bwd_bytes) {
   int rc = check_params(params);
   if (rc != SAGEBWD_OK) return rc;
-  if (bytes == nullptr) return SAGEBWD_INVALID_ARG;
-  *bytes = make_layout(*params).total;
+  const Workspace w = make_layout(*params);
+  if (fwd_bytes != nullptr) *fwd_bytes = w.fwd_total;
+  if (bwd_bytes != nullptr) *bwd_bytes = w.total;
   return SAGEBWD_OK;
 }
 
@@ -290,14 +361,14 @@ int sagebwd_quantize(const void* Q, const void* K, const void* V, const void* dO
   // the inspection pre-pass fills every layout: forward operands first, then the backward's
   {
     ScopedTimer tm(SAGEBWD_KERNEL_PREPASS_FWD, st);
-    rc = params->d == 64 ? run_prepass<64>(Q, K, V, nullptr, nullptr, nullptr, *params, ws, w, false, st)
-                         : run_prepass<128>(Q, K, V, nullptr, nullptr, nullptr, *params, ws, w, false, st);
+    rc = params->d == 64 ? prepass_for_forward<64>(Q, K, V, *params, ws, w, st)
+                         : prepass_for_forward<128>(Q, K, V, *params, ws, w, st);
   }
   if (rc != SAGEBWD_OK || dO == nullptr) return rc;
   {
     ScopedTimer tm(SAGEBWD_KERNEL_PREPASS_BWD, st);
-    rc = params->d == 64 ? run_prepass<64>(Q, K, V, dO, O, nullptr, *params, ws, w, true, st)
-                         : run_prepass<128>(Q, K, V, dO, O, nullptr, *params, ws, w, true, st);
+    rc = params->d == 64 ? prepass_for_backward<64>(Q, K, V, dO, O, nullptr, *params, ws, w, false, st)
+                         : prepass_for_backward<128>(Q, K, V, dO, O, nullptr, *params, ws, w, false, st);
   }
   return rc;
 }
@@ -387,39 +458,8 @@ int sagebwd_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE
   if (Q == nullptr || K == nullptr || V == nullptr || O == nullptr || LSE == nullptr || workspace == nullptr)
     return SAGEBWD_INVALID_ARG;
   const Workspace w = make_layout(*params);
-  if (workspace_bytes < w.total) return SAGEBWD_WORKSPACE_TOO_SMALL;
-  hipStream_t st = (hipStream_t)stream;
-  char* ws = (char*)workspace;
-  {
-    ScopedTimer tm(SAGEBWD_KERNEL_PREPASS_FWD, st);
-    rc = params->d == 64 ? run_prepass<64>(Q, K, V, nullptr, nullptr, nullptr, *params, ws, w, false, st)
-                         : run_prepass<128>(Q, K, V, nullptr, nullptr, nullptr, *params, ws, w, false, st);
-  }
-  if (rc != SAGEBWD_OK) return rc;
-  FwdArgs a;
-  a.QF = (const int8_t*)(ws + w.QF);
-  a.KF = (const int8_t*)(ws + w.KF);
-  a.VT = (const int8_t*)(ws + w.VT);
-  a.sQ = (const float*)(ws + w.sQ);
-  a.sK = (const float*)(ws + w.sK);
-  a.sV = (const float*)(ws + w.sV);
-  const bool qs = (params->smooth & SAGEBWD_SMOOTH_Q) != 0;
-  a.bias = qs ? (const float*)(ws + w.bias) : nullptr;
-  const int Np = padded_rows(params->N);
-  a.O = (unsigned short*)O;
-  a.oview = caller_view(*params, 1);
-  a.LSE = LSE;
-  a.BH = params->B * params->H;
-  a.N = Np;
-  a.nvalid = params->N;
-  a.n_qtiles = 0;
-  a.scale_log2e = logit_scale(*params) * 1.4426950408889634f;
-  {
-    ScopedTimer tm(SAGEBWD_KERNEL_FWD, st);
-    rc = params->d == 64 ? launch_fwd<64>(a, params->causal != 0, qs, st)
-                         : launch_fwd<128>(a, params->causal != 0, qs, st);
-  }
-  return rc;
+  if (workspace_bytes < w.fwd_total) return SAGEBWD_WORKSPACE_TOO_SMALL;
+  return forward_impl(Q, K, V, O, LSE, *params, (char*)workspace, w, (hipStream_t)stream);
 }
 
 int sagebwd_bwd(const void* Q, const void* K, const void* V, const void* O, const void* dO,
@@ -438,8 +478,9 @@ int sagebwd_bwd(const void* Q, const void* K, const void* V, const void* O, cons
   const bool qs = (params->smooth & SAGEBWD_SMOOTH_Q) != 0;
   {
     ScopedTimer tm(SAGEBWD_KERNEL_PREPASS_BWD, st);
-    rc = d == 64 ? run_prepass<64>(Q, K, V, dO, O, LSE, *params, ws, w, true, st)
-                 : run_prepass<128>(Q, K, V, dO, O, LSE, *params, ws, w, true, st);
+    const bool reuse = (params->flags & SAGEBWD_FLAG_SHARE_QUANTIZED) != 0;   // Q^, K^ as the forward left them
+    rc = d == 64 ? prepass_for_backward<64>(Q, K, V, dO, O, LSE, *params, ws, w, reuse, st)
+                 : prepass_for_backward<128>(Q, K, V, dO, O, LSE, *params, ws, w, reuse, st);
     if (rc != SAGEBWD_OK) return rc;
   }
   BwdArgs a;
@@ -493,13 +534,8 @@ int sagebwd_bwd(const void* Q, const void* K, const void* V, const void* O, cons
   return rc;
 }
 
-int sagebwd_set_scratch_budget(size_t bytes) {
-  if (bytes == 0) return SAGEBWD_INVALID_ARG;
-  g_ds_budget = bytes;
-  return SAGEBWD_OK;
-}
-
 int sagebwd_set_timing(int enable) {
+  std::lock_guard<std::mutex> lock(g_timing_mutex);
   g_timing = enable != 0;
   return SAGEBWD_OK;
 }
@@ -509,6 +545,7 @@ int sagebwd_read_timing(int kernel, double* total_ms, int* launches) {
     return SAGEBWD_INVALID_ARG;
   double tot = 0.0;
   int n = 0;
+  std::lock_guard<std::mutex> lock(g_timing_mutex);
   for (TimedSpan& s : g_spans[kernel]) {
     if (hipEventSynchronize(s.b) != hipSuccess) return SAGEBWD_HIP_ERROR;
     float ms = 0.f;
@@ -527,7 +564,7 @@ const char* sagebwd_strerror(int status) {
   switch (status) {
     case SAGEBWD_OK: return "ok";
     case SAGEBWD_INVALID_ARG: return "invalid argument (null pointer, bad flag or size)";
-    case SAGEBWD_UNSUPPORTED_SHAPE: return "unsupported shape (need d in {64,128}, N a multiple of 64)";
+    case SAGEBWD_UNSUPPORTED_SHAPE: return "unsupported shape (need d in {64,128}, 64 x 64 numerics blocks, sizes within the stated limits)";
     case SAGEBWD_WORKSPACE_TOO_SMALL: return "workspace too small (see sagebwd_workspace_bytes)";
     case SAGEBWD_HIP_ERROR: return "HIP runtime error";
     default: return "unknown status";

@@ -35,6 +35,7 @@ def test_exports_every_declared_symbol(lib):
 
 def test_strerror(lib):
     assert binding.sagebwd_strerror(0) == "ok"
+    assert "multiple of 64" not in binding.sagebwd_strerror(-2)     # any N >= 1 is accepted
     for code in (-1, -2, -3, -4):
         assert binding.sagebwd_strerror(code) not in ("ok", "unknown status")
     assert binding.sagebwd_strerror(-99) == "unknown status"
@@ -46,16 +47,29 @@ def test_workspace_bytes_and_shape_validation(lib):
     elems = 2 * 32 * 8192 * 128
     assert n >= 6 * elems + 64 * 8192 * 8192   # six INT8 operand tensors + the INT8 dS scratch
     assert n < 7 * elems + 64 * 8192 * 8192 + (64 << 20)
-    # the dS scratch is capped at 8 GiB: larger problems run in groups of heads
+    # the forward alone needs three INT8 operand tensors and no dS scratch; sharing the quantised
+    # Q, K with the backward adds their two transposed layouts to the forward's part
+    nf = binding.workspace_bytes(p, forward_only=True)
+    assert 3 * elems <= nf < 3 * elems + (16 << 20)
+    ps = SageParams(2, 32, 8192, 128, share_quantized=True)
+    assert binding.workspace_bytes(ps) == n
+    assert 5 * elems <= binding.workspace_bytes(ps, forward_only=True) < 5 * elems + (16 << 20)
+    # a smaller scratch budget shrinks the backward's need (heads run in groups), never below one head
+    assert binding.workspace_bytes(SageParams(2, 32, 8192, 128, scratch_budget=1 << 30)) < 6 * elems + (1 << 30) + (64 << 20)
+    assert binding.workspace_bytes(SageParams(2, 32, 8192, 128, scratch_budget=1)) >= 6 * elems + 8192 * 8192
+    # the dS scratch is capped at 8 GiB by default: larger problems run in groups of heads
     assert binding.workspace_bytes(SageParams(1, 32, 32768, 128, causal=False)) < (8 << 30) + 7 * 32 * 32768 * 128 + (64 << 20)
     assert binding.workspace_bytes(SageParams(2, 32, 8192, 128, q_smooth=True)) > n
     # N that is not a multiple of 64: the workspace is laid out for N rounded up to the block
     assert binding.workspace_bytes(SageParams(1, 1, 100, 64)) == binding.workspace_bytes(SageParams(1, 1, 128, 64))
-    for bad in (SageParams(1, 1, 128, 96), SageParams(1, 1, 64, 256), SageParams(1, 1, (1 << 30) + 64, 64)):
+    assert binding.workspace_bytes(SageParams(1, 1, 128, 64, bq=64, bkv=64)) == binding.workspace_bytes(SageParams(1, 1, 128, 64))
+    for bad in (SageParams(1, 1, 128, 96), SageParams(1, 1, 64, 256), SageParams(1, 1, (1 << 30) + 64, 64),
+                SageParams(1, 1, 128, 64, bq=128), SageParams(1, 1, 128, 64, bkv=32)):
         with pytest.raises(binding.SageError) as e:
             binding.workspace_bytes(bad)
         assert e.value.status == -2
-    for bad in (SageParams(0, 1, 128, 64), SageParams(1, -1, 128, 64), SageParams(1, 1, 128, 64, sm_scale=-1.0)):
+    for bad in (SageParams(0, 1, 128, 64), SageParams(1, -1, 128, 64), SageParams(1, 1, 128, 64, sm_scale=-1.0),
+                SageParams(1, 1, 128, 64, bq=-64)):
         with pytest.raises(binding.SageError) as e:
             binding.workspace_bytes(bad)
         assert e.value.status == -1
@@ -74,6 +88,17 @@ def test_entry_points_reject_bad_arguments_on_the_host(lib):
     bad = SageParams(1, 2, 128, 64).c()
     bad.smooth = 8
     assert lib.sagebwd_fwd(one, one, one, one, one, ctypes.byref(bad), one, 1 << 30, null) == -1
+    bad = SageParams(1, 2, 128, 64).c()
+    bad.flags = 2
+    assert lib.sagebwd_fwd(one, one, one, one, one, ctypes.byref(bad), one, 1 << 30, null) == -1
+    bad = SageParams(1, 2, 128, 64).c()
+    bad.reserved = 1
+    assert lib.sagebwd_fwd(one, one, one, one, one, ctypes.byref(bad), one, 1 << 30, null) == -1
+    # the forward accepts its own (smaller) workspace size, the backward does not
+    fwd_only = binding.workspace_bytes(SageParams(1, 2, 128, 64), forward_only=True)
+    assert fwd_only < binding.workspace_bytes(SageParams(1, 2, 128, 64))
+    assert lib.sagebwd_fwd(one, one, one, one, one, ctypes.byref(cp), one, fwd_only - 1, null) == -3
+    assert lib.sagebwd_bwd(one, one, one, one, one, one, one, one, one, ctypes.byref(cp), one, fwd_only, null) == -3
     bad = SageParams(1, 2, 128, 64).c()
     bad.layout = 2
     assert lib.sagebwd_fwd(one, one, one, one, one, ctypes.byref(bad), one, 1 << 30, null) == -1

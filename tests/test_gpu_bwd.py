@@ -96,11 +96,7 @@ def test_bwd_outlier_shape_with_and_without_k_smoothing():
 def test_bwd_head_groups_share_the_ds_scratch():
     # a scratch budget of two heads' worth of dS forces the 5 heads through 3 groups
     Q, K, V, dO = synth.gaussian_inputs(256, 64, seed=21, heads=5)
-    binding.set_scratch_budget(2 * 256 * 256)
-    try:
-        _bwd_case(Q, K, V, dO, binding.SageParams(1, 5, 256, 64, causal=True))
-    finally:
-        binding.set_scratch_budget(8 << 30)
+    _bwd_case(Q, K, V, dO, binding.SageParams(1, 5, 256, 64, causal=True, scratch_budget=2 * 256 * 256))
 
 
 def test_bwd_q_smoothing_head_dim_64_odd_block_count():
@@ -210,14 +206,35 @@ def test_backward_is_deterministic_and_needs_nothing_from_an_old_workspace():
     a = [t.clone() for t in binding.sagebwd_bwd(Q, K, V, O, dO, L, p, ws)]
     ws.fill_(0x5A)
     b = [t.clone() for t in binding.sagebwd_bwd(Q, K, V, O, dO, L, p, ws)]
-    try:
-        binding.set_scratch_budget(2 * 448 * 448)          # two heads at a time
-        c = binding.sagebwd_bwd(Q, K, V, O, dO, L, p, binding.alloc_workspace(p))
-    finally:
-        binding.set_scratch_budget(8 << 30)
+    pg = binding.SageParams(1, 5, 448, 128, causal=True, q_smooth=True, scratch_budget=2 * 448 * 448)   # two heads at a time
+    c = binding.sagebwd_bwd(Q, K, V, O, dO, L, pg, binding.alloc_workspace(pg))
     torch.cuda.synchronize()
     for x, y, z in zip(a, b, c):
         assert torch.equal(x, y) and torch.equal(x, z)
+
+
+@pytest.mark.parametrize("N,d,causal,q_smooth,k_smooth", [(448, 128, True, False, True), (300, 64, False, True, True),
+                                                         (1024, 128, True, True, False)])
+def test_backward_sharing_the_forwards_quantised_operands_gives_the_same_bits(N, d, causal, q_smooth, k_smooth):
+    """SAGEBWD_FLAG_SHARE_QUANTIZED: the forward leaves psi(Q), psi(K) in both operand layouts and the
+    backward forms only the dO part of its pre-pass (Algorithm 2 takes the quantised Q, K from the
+    forward).  O, LSE and all three gradients must equal the default calls bit for bit."""
+    Q, K, V, dO = (t.cuda() for t in synth.gaussian_inputs(N, d, sigma_qk=1.5, seed=300 + N, heads=5))
+    if q_smooth:
+        Q = (Q.float() + torch.linspace(-2, 2, d, device="cuda")).to(torch.bfloat16)
+    kw = dict(causal=causal, q_smooth=q_smooth, k_smooth=k_smooth)
+    p = binding.SageParams(1, 5, N, d, **kw)
+    ps = binding.SageParams(1, 5, N, d, share_quantized=True, **kw)
+    O, L = binding.sagebwd_fwd(Q, K, V, p)
+    ref = binding.sagebwd_bwd(Q, K, V, O, dO, L, p)
+    ws = binding.alloc_workspace(ps)
+    ws.fill_(0x5A)
+    Os, Ls = binding.sagebwd_fwd(Q, K, V, ps, ws)
+    got = binding.sagebwd_bwd(Q, K, V, Os, dO, Ls, ps, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(O, Os) and torch.equal(L, Ls)
+    for a, b, name in zip(ref, got, ("dQ", "dK", "dV")):
+        assert torch.equal(a, b), name
 
 
 def test_graph_capture_and_replay():
@@ -260,12 +277,13 @@ def test_graph_capture_and_replay():
             assert torch.equal(a, b), seed
 
 
-@pytest.mark.parametrize("heads", [8, 16, 24, 48, 11])
-def test_workgroup_to_head_mappings_give_the_same_bits(heads):
-    """The order in which workgroups take (head, work item) pairs depends on the head count (sets of
-    4, 2 or 1 heads per XCD, or the dense layout); whatever the order, every head must get exactly
-    the result it gets when it is run alone."""
-    N, d = 512, 64
+@pytest.mark.parametrize("heads,N,d", [(8, 512, 64), (16, 512, 64), (24, 512, 64), (48, 512, 64), (11, 512, 64),
+                                       (32, 1024, 128), (64, 2048, 128), (32, 4096, 128)])
+def test_workgroup_to_head_mappings_give_the_same_bits(heads, N, d):
+    """The order in which workgroups take (head, work item) pairs depends on the head count and the
+    sequence length (sets of 4, 2 or 1 heads per XCD, or the dense layout; 32 heads of N <= 4096 and 64
+    heads of N = 2048 at d = 128 are the sets of four that the pre-training and outlier shapes launch
+    with); whatever the order, every head must get exactly the result it gets when it is run alone."""
     Q, K, V, dO = (t.cuda() for t in synth.gaussian_inputs(N, d, sigma_qk=1.0, seed=100 + heads, heads=heads))
     p = binding.SageParams(1, heads, N, d, causal=True)
     O, L = binding.sagebwd_fwd(Q, K, V, p)
