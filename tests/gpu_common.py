@@ -20,12 +20,15 @@ COS_MIN = 0.999
 #   gradient is not held to a relative bound on nothing), and no single element is off by more than
 #   MAX_ABS_IN_RMS times the RMS of the reference.
 BLOCK_REL_L1_MAX = 1e-2
-MAX_ABS_IN_RMS = 0.25
-# Regression guards: about five times the agreement measured on the MI355X for each kind of output
-# (whole-tensor relative L1; measured O 5e-4 .. 9e-4, gradients 1e-5 .. 2e-4, LSE max-abs 4e-5).
-# Far inside the stated tolerance; a kernel change that costs accuracy trips them first.
-GUARD_REL_L1 = {"O": 5e-3, "dQ": 1.5e-3, "dK": 1.5e-3, "dV": 1.5e-3}
-LSE_MAX_ABS = 5e-4
+MAX_ABS_IN_RMS = 0.5
+# (Measured over every comparison of the suite: worst block 1.8e-3, worst element 0.21 RMS -- one
+# psi(dS) code off by a step in a tile of large scale; a wrong element is off by about one RMS.)
+# Regression guards: about five times the worst agreement measured on the MI355X over every
+# comparison of the suite, per kind of output (whole-tensor relative L1: O 6.8e-4, dQ 3.8e-5,
+# dK 2.4e-5, dV 1.3e-4; LSE max-abs 1.7e-4, on the unsmoothed outlier inputs whose logits are in
+# the hundreds).  Far inside the stated tolerance; a kernel change that costs accuracy trips them first.
+GUARD_REL_L1 = {"O": 3.5e-3, "dQ": 2e-4, "dK": 1.5e-4, "dV": 7e-4}
+LSE_MAX_ABS = 8e-4
 
 
 def params_for(w, B=None, H=None, **kw):
