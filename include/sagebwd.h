@@ -49,7 +49,8 @@ typedef enum sagebwd_status {
   SAGEBWD_INVALID_ARG = -1,        /* null pointer, non-positive size, unknown selector */
   SAGEBWD_UNSUPPORTED_SHAPE = -2,  /* d not in {64,128}, blocks other than 64 x 64, sizes beyond the stated limits */
   SAGEBWD_WORKSPACE_TOO_SMALL = -3,
-  SAGEBWD_HIP_ERROR = -4           /* a HIP runtime call or launch failed */
+  SAGEBWD_HIP_ERROR = -4,          /* a HIP runtime call or launch failed */
+  SAGEBWD_STATIC_SCRATCH_TOO_SMALL = -5 /* sagebwd_fwd_static: the forward's workspace exceeds the built-in scratch */
 } sagebwd_status;
 
 /* Smoothing flags (paper Sec. 3 "Q and K Smoothing"). */
@@ -174,6 +175,25 @@ int sagebwd_export_ds(const sagebwd_params* params, const void* workspace, size_
 int sagebwd_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE,
                 const sagebwd_params* params, void* workspace, size_t workspace_bytes,
                 void* stream);
+
+/*
+ * sagebwd_fwd for callers that cannot allocate device memory or pass a workspace: code under
+ * stream capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, kernels
+ * and results (bit for bit) as sagebwd_fwd, but the forward's workspace is a built-in device array of
+ * SAGEBWD_STATIC_SCRATCH_BYTES that every GPU the library runs on holds until the process ends.
+ * The call allocates and frees nothing (its first call on a device looks the array's address up).
+ *   - Problems whose forward workspace (*fwd_bytes of sagebwd_workspace_bytes) exceeds the array
+ *     are rejected with SAGEBWD_STATIC_SCRATCH_TOO_SMALL before anything is launched; roughly
+ *     3*B*H*Np*d bytes plus the small vectors, e.g. up to B*H = 8 heads of N = 8192, d = 128.
+ *   - SAGEBWD_FLAG_SHARE_QUANTIZED is rejected (SAGEBWD_INVALID_ARG): the backward reads a caller's
+ *     workspace, not this array.
+ *   - All calls on one GPU share the one array: two calls that overlap in time on the same GPU
+ *     (different streams or threads) race.  Calls in stream order on one stream are safe; nothing
+ *     has to be cleared between calls (every byte read is written earlier in the same call).
+ */
+#define SAGEBWD_STATIC_SCRATCH_BYTES (32u << 20)
+int sagebwd_fwd_static(const void* Q, const void* K, const void* V, void* O, float* LSE,
+                       const sagebwd_params* params, void* stream);
 
 /*
  * Backward (paper Algorithm 2; gradient equations of Sec. 3):

@@ -25,7 +25,7 @@ KERNEL_PREPASS_FWD, KERNEL_FWD, KERNEL_PREPASS_BWD, KERNEL_BWD, KERNEL_BWD_DQ = 
 
 EXPORTS = (
     "sagebwd_workspace_bytes", "sagebwd_quantize", "sagebwd_export_quantized", "sagebwd_export_stats", "sagebwd_export_ds",
-    "sagebwd_fwd", "sagebwd_bwd", "sagebwd_set_timing", "sagebwd_read_timing", "sagebwd_strerror",
+    "sagebwd_fwd", "sagebwd_fwd_static", "sagebwd_bwd", "sagebwd_set_timing", "sagebwd_read_timing", "sagebwd_strerror",
 )
 
 
@@ -86,6 +86,7 @@ def load_library():
     lib.sagebwd_export_stats.argtypes = [pp, vp, sz, vp, vp, vp, vp]
     lib.sagebwd_export_ds.argtypes = [pp, vp, sz, i32, vp, vp, vp]
     lib.sagebwd_fwd.argtypes = [vp, vp, vp, vp, vp, pp, vp, sz, vp]
+    lib.sagebwd_fwd_static.argtypes = [vp, vp, vp, vp, vp, pp, vp]
     lib.sagebwd_bwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, pp, vp, sz, vp]
     lib.sagebwd_set_timing.argtypes = [i32]
     lib.sagebwd_read_timing.argtypes = [i32, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i32)]
@@ -209,6 +210,22 @@ def sagebwd_fwd(Q, K, V, p: SageParams, workspace=None, O=None, LSE=None):
     cp = p.c()
     _check(load_library().sagebwd_fwd(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(LSE), ctypes.byref(cp),
                                       _ptr(workspace), workspace.numel(), _stream()), "sagebwd_fwd")
+    return O, LSE
+
+
+STATIC_SCRATCH_BYTES = 32 << 20
+
+
+def sagebwd_fwd_static(Q, K, V, p: SageParams, O, LSE):
+    """The forward on the library's built-in scratch: the call allocates nothing, so the caller
+    passes the outputs too."""
+    shp = p.tensor_shape()
+    for t, n in ((Q, "Q"), (K, "K"), (V, "V"), (O, "O")):
+        _expect(t, torch.bfloat16, shp, n)
+    _expect(LSE, torch.float32, (p.B, p.H, p.N), "LSE")
+    cp = p.c()
+    _check(load_library().sagebwd_fwd_static(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(LSE), ctypes.byref(cp),
+                                             _stream()), "sagebwd_fwd_static")
     return O, LSE
 
 

@@ -14,9 +14,31 @@
 #include "fwd_kernel.h"
 #include "bwd_kernel.h"
 
+// Workspace of sagebwd_fwd_static: one array per GPU, held until the process ends.  In host code the
+// name `scratch` is only a handle for hipGetSymbolAddress; the device address it returns (per device)
+// is what the kernels are given.
+static __device__ __align__(256) unsigned char scratch[SAGEBWD_STATIC_SCRATCH_BYTES];
+
 namespace {
 
 using namespace sage;
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};   // device address of `scratch` on each GPU, looked up once
+
+// Device address of this GPU's copy of `scratch` (the current device's), or nullptr on failure.
+void* static_scratch_for_current_device() {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (g_scratch_ptr[dev] == nullptr) {
+    void* ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess) return nullptr;
+    g_scratch_ptr[dev] = ptr;
+  }
+  return g_scratch_ptr[dev];
+}
 
 constexpr size_t kDefaultDsBudget = (size_t)8 << 30;   // bytes of INT8 dS scratch the backward holds at once unless told otherwise
 
@@ -462,6 +484,23 @@ int sagebwd_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE
   return forward_impl(Q, K, V, O, LSE, *params, (char*)workspace, w, (hipStream_t)stream);
 }
 
+int sagebwd_fwd_static(const void* Q, const void* K, const void* V, void* O, float* LSE,
+                       const sagebwd_params* params, void* stream) {
+  int rc = check_params(params);
+  if (rc != SAGEBWD_OK) return rc;
+  if (Q == nullptr || K == nullptr || V == nullptr || O == nullptr || LSE == nullptr) return SAGEBWD_INVALID_ARG;
+  // the backward of such a call would need the caller's workspace anyway: nothing is shared through `scratch`
+  if ((params->flags & SAGEBWD_FLAG_SHARE_QUANTIZED) != 0) return SAGEBWD_INVALID_ARG;
+  const Workspace w = make_layout(*params);
+  if (w.fwd_total > (size_t)SAGEBWD_STATIC_SCRATCH_BYTES) return SAGEBWD_STATIC_SCRATCH_TOO_SMALL;
+  char* ws = (char*)static_scratch_for_current_device();
+  if (ws == nullptr) return SAGEBWD_HIP_ERROR;
+  // every byte of the forward's workspace that a kernel reads is written earlier in the same call
+  // (the pre-pass fills all operand rows, the missing ones of a partial block as zero codes), so nothing
+  // the previous call left in the array has to be cleared
+  return forward_impl(Q, K, V, O, LSE, *params, ws, w, (hipStream_t)stream);
+}
+
 int sagebwd_bwd(const void* Q, const void* K, const void* V, const void* O, const void* dO,
                 const float* LSE, void* dQ, void* dK, void* dV, const sagebwd_params* params,
                 void* workspace, size_t workspace_bytes, void* stream) {
@@ -567,6 +606,8 @@ const char* sagebwd_strerror(int status) {
     case SAGEBWD_UNSUPPORTED_SHAPE: return "unsupported shape (need d in {64,128}, 64 x 64 numerics blocks, sizes within the stated limits)";
     case SAGEBWD_WORKSPACE_TOO_SMALL: return "workspace too small (see sagebwd_workspace_bytes)";
     case SAGEBWD_HIP_ERROR: return "HIP runtime error";
+    case SAGEBWD_STATIC_SCRATCH_TOO_SMALL:
+      return "problem too large for the built-in scratch of sagebwd_fwd_static (use sagebwd_fwd with a workspace)";
     default: return "unknown status";
   }
 }

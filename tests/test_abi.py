@@ -36,7 +36,7 @@ def test_exports_every_declared_symbol(lib):
 def test_strerror(lib):
     assert binding.sagebwd_strerror(0) == "ok"
     assert "multiple of 64" not in binding.sagebwd_strerror(-2)     # any N >= 1 is accepted
-    for code in (-1, -2, -3, -4):
+    for code in (-1, -2, -3, -4, -5):
         assert binding.sagebwd_strerror(code) not in ("ok", "unknown status")
     assert binding.sagebwd_strerror(-99) == "unknown status"
 
@@ -99,6 +99,12 @@ def test_entry_points_reject_bad_arguments_on_the_host(lib):
     assert fwd_only < binding.workspace_bytes(SageParams(1, 2, 128, 64))
     assert lib.sagebwd_fwd(one, one, one, one, one, ctypes.byref(cp), one, fwd_only - 1, null) == -3
     assert lib.sagebwd_bwd(one, one, one, one, one, one, one, one, one, ctypes.byref(cp), one, fwd_only, null) == -3
+    # the no-allocation forward: too large a problem and the sharing flag are refused on the host
+    big = SageParams(2, 32, 8192, 128).c()
+    assert lib.sagebwd_fwd_static(one, one, one, one, one, ctypes.byref(big), null) == -5
+    sh = SageParams(1, 2, 128, 64, share_quantized=True).c()
+    assert lib.sagebwd_fwd_static(one, one, one, one, one, ctypes.byref(sh), null) == -1
+    assert lib.sagebwd_fwd_static(null, one, one, one, one, ctypes.byref(cp), null) == -1
     bad = SageParams(1, 2, 128, 64).c()
     bad.layout = 2
     assert lib.sagebwd_fwd(one, one, one, one, one, ctypes.byref(bad), one, 1 << 30, null) == -1
