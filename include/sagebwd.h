@@ -83,7 +83,7 @@ typedef struct sagebwd_params {
   int32_t flags;   /* OR of SAGEBWD_FLAG_* */
   int32_t reserved;          /* must be 0 */
   uint64_t scratch_budget;   /* upper bound, in bytes, on the INT8 dS scratch that sagebwd_bwd holds at
-                                once; 0 selects 8 GiB.  The backward needs Np*Np bytes per head and
+                                once; 0 selects 8 GiB.  The backward needs Np*(Np+192) bytes per head and
                                 processes the heads in groups that fit the bound (at least one head per
                                 group); the workspace size follows from it. */
 } sagebwd_params;
@@ -156,7 +156,7 @@ int sagebwd_export_stats(const sagebwd_params* params, const void* workspace,
  *   ds_out     int8    [Np, Np] row-major (query, key); tiles above the causal diagonal are zero
  *   scale_out  float32 [Np/64, Np/64], one scale per 64x64 tile (dS ~ scale * code)
  * Np = N rounded up to a multiple of 64.  Either output may be NULL.  Only defined when the backward
- * ran all heads in one group (B*H*Np*Np bytes within params->scratch_budget), otherwise
+ * ran all heads in one group (B*H*Np*(Np+192) bytes within params->scratch_budget), otherwise
  * SAGEBWD_UNSUPPORTED_SHAPE.  A test / inspection hook: the in-loop quantisers depend on the
  * hardware's exp2, so their codes are compared with a tolerance of one step, not bit for bit.
  */
@@ -207,7 +207,7 @@ int sagebwd_fwd_static(const void* Q, const void* K, const void* V, void* O, flo
  * same params; the pre-pass is re-run inside, so the workspace need not survive
  * between the two calls (unless SAGEBWD_FLAG_SHARE_QUANTIZED is set).  dQ, dK, dV
  * (bf16 [B,H,N,d]) are overwritten.
- * The quantised dS tiles are staged in the workspace (Np*Np bytes per head, at most
+ * The quantised dS tiles are staged in the workspace (Np*(Np+192) bytes per head, at most
  * params->scratch_budget at a time: larger problems are processed in groups of heads) and dQ is
  * formed from them by a second kernel, so all three gradients are deterministic (no atomics).
  */

@@ -45,10 +45,11 @@ struct BwdArgs {
   const float* sK;
   const float* sdO;
   const float* nL2;    // [BH, N]  -LSE * log2(e)
-  const float* delta;  // [BH, N]
+  const float* delta;  // [BH, N]  -rowsum(dO o O)
   const float* bias;   // Q-smoothing logit bias [BH, N/64, N] (log2 domain) or nullptr
   const float* muQ;    // Q-smoothing block means [BH, N/64, D] or nullptr
-  int8_t* dSq;         // psi(dS) tiles [heads, N/64, N/64, 4096], A fragments (q block, key step)
+  int8_t* dSq;         // psi(dS) tiles [heads, N/64, ds_pitch, 4096], A fragments (q block, key step)
+  int ds_pitch;        // tiles per Q-block row of that array (>= N/64)
   float* sdS;          // their scales [heads, N/64, N/64]
   int bh0;             // first head of this launch (the scratch above is indexed from it)
   unsigned short* dK;  // bf16 [BH, N, D]
@@ -69,7 +70,7 @@ struct BwdStageA {            // operands of phase A for one Q block
   int8_t qf[64 * D];          // Q^  F fragments
   int8_t dof[128 * D];        // bf16 dO as A fragments (32-row block, 16-channel step), XOR-swizzled slots
   float nl2[64];              // -L * log2(e)
-  float dl[64];               // delta
+  float dl[64];               // -delta
   float bias[128];            // Q-smoothing logit bias of this Q block for the workgroup's 128 keys
   float sc[64];               // s_Q[i] in every entry
 };
@@ -85,12 +86,12 @@ struct BwdExchange {          // per group of 4 waves and tile parity
   int8_t dsb[4096];           // psi(dS) B fragments
 };
 
-// phase A element-wise work of one quadrant; MASK = some entries of the tile are masked: query row
+// phase A element-wise work of one quadrant (`dp` holds dP - delta); MASK = some entries of the tile are masked: query row
 // qrow0 + 8 aa + b of the tile sees key column kcol only up to column klim_row (the row itself on
 // the causal diagonal, 63 elsewhere) and only if the key exists (kcol < kvalid)
 template <bool MASK, bool QSMOOTH>
 __device__ __forceinline__ void bwd_quadrant(const v16i& sacc, const v16f& dp, const float* __restrict__ nl2,
-                                             const float* __restrict__ dl, const float c, const float bias_l,
+                                             const float c, const float bias_l,
                                              const int qrow0, const int kcol, const bool diag, const int kvalid,
                                              float (&p)[16], float (&ds)[16], float& pm, float& dm, float& cs) {
   float pm2[2] = {0.f, 0.f}, dm2[2] = {0.f, 0.f};
@@ -98,14 +99,13 @@ __device__ __forceinline__ void bwd_quadrant(const v16i& sacc, const v16f& dp, c
 #pragma unroll
   for (int aa = 0; aa < 4; aa++) {
     const v4f l4 = *(const v4f*)(nl2 + 8 * aa);
-    const v4f d4 = *(const v4f*)(dl + 8 * aa);
 #pragma unroll
     for (int b = 0; b < 4; b++) {
       const int r = 4 * aa + b;
       const float off = QSMOOTH ? bias_l + l4[b] : l4[b];
       float pv = __builtin_amdgcn_exp2f(__builtin_fmaf((float)sacc[r], c, off));
       if constexpr (MASK) pv = ((diag && (qrow0 + 8 * aa + b) < kcol) || kcol >= kvalid) ? 0.f : pv;
-      const float dsv = pv * (dp[r] - d4[b]);
+      const float dsv = pv * dp[r];       // the dP accumulators started from -delta
       p[r] = pv;
       ds[r] = dsv;
       pm2[aa & 1] = fmaxf(pm2[aa & 1], pv);
@@ -140,7 +140,7 @@ __global__ void __launch_bounds__(512, 1) sage_bwd_kernel(BwdArgs args) {
     BwdStageB<D> stB[2];
     BwdExchange xch[2][2];                          // [group][tile parity]
     int8_t vst[2][2 * D * 64];                      // [group]: bf16 V_j as B fragments (key block, 16-channel step)
-    float red[2][2][4][2];                          // [group][tile parity][wave][max P, max |dS|]
+    unsigned red[2][2][4][2];                       // [group][tile parity][wave][max P, max |dS|] as bit patterns
     float csum[QSMOOTH ? 2 * 3 * 2 * 64 : 1];       // [group][tile % 3][q half][key]: column sums of dS
   };
   __shared__ __attribute__((aligned(16))) Lds L;
@@ -316,9 +316,11 @@ __global__ void __launch_bounds__(512, 1) sage_bwd_kernel(BwdArgs args) {
     // ---------------- phase Q of tile t - 1 ----------------
     if (act_q) {
       BwdExchange& X = xch[grp][(t - 1) & 1];
-      const float(&R)[4][2] = red[grp][(t - 1) & 1];
-      const float pm = fmaxf(fmaxf(R[0][0], R[1][0]), fmaxf(R[2][0], R[3][0]));
-      const float dm = fmaxf(fmaxf(R[0][1], R[1][1]), fmaxf(R[2][1], R[3][1]));
+      // (the maxima are non-negative floats: they order like their bit patterns, and integer maxima
+      // need no NaN canonicalisation of the loaded values)
+      const unsigned(&R)[4][2] = red[grp][(t - 1) & 1];
+      const float pm = __uint_as_float(max(max(R[0][0], R[1][0]), max(R[2][0], R[3][0])));
+      const float dm = __uint_as_float(max(max(R[0][1], R[1][1]), max(R[2][1], R[3][1])));
       // the per-tile scales of P and dS are internal (never stored bit-exactly): 127/a via rcp
       const float rP = pm > 0.f ? 127.0f * __builtin_amdgcn_rcpf(pm) : 0.f;
       const float rS = dm > 0.f ? 127.0f * __builtin_amdgcn_rcpf(dm) : 0.f;
@@ -327,30 +329,35 @@ __global__ void __launch_bounds__(512, 1) sage_bwd_kernel(BwdArgs args) {
       v4i pf, df;
 #pragma unroll
       for (int aa = 0; aa < 4; aa++) {
-        unsigned up = 0;
         unsigned ub[4];
 #pragma unroll
-        for (int b = 0; b < 4; b++) {
-          const int r = 4 * aa + b;
-          up = __builtin_amdgcn_cvt_pk_u8_f32(p[r] * rP, b, up);
-          ub[b] = __float_as_uint(__builtin_fmaf(ds[r], rS, kRoundMagic));
-        }
-        pf[aa] = (int)up;
+        for (int b = 0; b < 4; b++) ub[b] = __float_as_uint(__builtin_fmaf(ds[4 * aa + b], rS, kRoundMagic));
         const unsigned lo = __builtin_amdgcn_perm(ub[1], ub[0], 0x0c0c0400u);
         const unsigned hi = __builtin_amdgcn_perm(ub[3], ub[2], 0x04000c0cu);
         df[aa] = (int)(lo | hi);
       }
-      *(v4i*)(X.pb + ((qb * 2 + kb) * 64 + lane) * 16) = pf;
-      *(v4i*)(X.dsb + ((qb * 2 + kb) * 64 + lane) * 16) = df;
       // The dQ kernel contracts over keys and needs this quadrant with one QUERY per lane.  Taken as
       // an A operand, `df` is the matrix (key, permuted query); one MFMA against the matching
       // permutation matrix returns it transposed in the accumulator: lane = query, registers =
       // keys in the order of the TF layout of K^.  The low bytes of the INT32 results are the codes.
+      // (Issued before psi(P) is formed, so that its latency passes under that work.)
+      v16i tr;
       {
         v16i z;
 #pragma unroll
         for (int r = 0; r < 16; r++) z[r] = 0;
-        const v16i tr = __builtin_amdgcn_mfma_i32_32x32x32_i8(df, tperm, z, 0, 0, 0);
+        tr = __builtin_amdgcn_mfma_i32_32x32x32_i8(df, tperm, z, 0, 0, 0);
+      }
+#pragma unroll
+      for (int aa = 0; aa < 4; aa++) {
+        unsigned up = 0;
+#pragma unroll
+        for (int b = 0; b < 4; b++) up = __builtin_amdgcn_cvt_pk_u8_f32(p[4 * aa + b] * rP, b, up);
+        pf[aa] = (int)up;
+      }
+      *(v4i*)(X.pb + ((qb * 2 + kb) * 64 + lane) * 16) = pf;
+      *(v4i*)(X.dsb + ((qb * 2 + kb) * 64 + lane) * 16) = df;
+      {
         v4i o;
 #pragma unroll
         for (int aa = 0; aa < 4; aa++) {
@@ -359,7 +366,8 @@ __global__ void __launch_bounds__(512, 1) sage_bwd_kernel(BwdArgs args) {
           o[aa] = (int)(lo | hi);
         }
         const size_t tile = ((size_t)hl * nblk + iq) * nblk + j;
-        *(v4i*)(args.dSq + tile * 4096 + ((qb * 2 + kb) * 64 + lane) * 16) = o;
+        const size_t slot = ((size_t)hl * nblk + iq) * args.ds_pitch + j;
+        *(v4i*)(args.dSq + slot * 4096 + ((qb * 2 + kb) * 64 + lane) * 16) = o;
         args.sdS[tile] = sS_q;   // the same value from every lane: no branch
       }
     }
@@ -388,11 +396,19 @@ __global__ void __launch_bounds__(512, 1) sage_bwd_kernel(BwdArgs args) {
       ld(1);
       v16i sacc;
       v16f dp;
+      // dS = P o (dP - delta): the dP chain starts from -delta of the rows this lane's registers hold
+      // (register 4a + b = query 8a + 4h + b of the quadrant), which saves the subtraction per entry
+      {
+        const float* dl = st.dl + 32 * qb + 4 * h;
 #pragma unroll
-      for (int r = 0; r < 16; r++) {
-        sacc[r] = 0;
-        dp[r] = 0.f;
+        for (int aa = 0; aa < 4; aa++) {
+          const v4f d4 = *(const v4f*)(dl + 8 * aa);
+#pragma unroll
+          for (int b = 0; b < 4; b++) dp[4 * aa + b] = d4[b];
+        }
       }
+#pragma unroll
+      for (int r = 0; r < 16; r++) sacc[r] = 0;
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int s = 0; s < KB; s++) {
@@ -405,18 +421,17 @@ __global__ void __launch_bounds__(512, 1) sage_bwd_kernel(BwdArgs args) {
       float bias_l = 0.f;
       if constexpr (QSMOOTH) bias_l = st.bias[64 * grp + 32 * kb + ll];
       const float* nl2 = st.nl2 + 32 * qb + 4 * h;
-      const float* dl = st.dl + 32 * qb + 4 * h;
       float pm, dm, cs;
       if (!STEADY && ((CAUSAL && ia == j) || kvalid < 64))
-        bwd_quadrant<true, QSMOOTH>(sacc, dp, nl2, dl, c, bias_l, 32 * qb + 4 * h, 32 * kb + ll, CAUSAL && ia == j, kvalid,
+        bwd_quadrant<true, QSMOOTH>(sacc, dp, nl2, c, bias_l, 32 * qb + 4 * h, 32 * kb + ll, CAUSAL && ia == j, kvalid,
                                     p, ds, pm, dm, cs);
       else
-        bwd_quadrant<false, QSMOOTH>(sacc, dp, nl2, dl, c, bias_l, 0, 0, false, 64, p, ds, pm, dm, cs);
+        bwd_quadrant<false, QSMOOTH>(sacc, dp, nl2, c, bias_l, 0, 0, false, 64, p, ds, pm, dm, cs);
       pm = wave_max_nonneg_f32(pm);
       dm = wave_max_nonneg_f32(dm);
       // every lane stores the same pair (one LDS write, no branch)
-      red[grp][t & 1][w4][0] = pm;
-      red[grp][t & 1][w4][1] = dm;
+      red[grp][t & 1][w4][0] = __float_as_uint(pm);
+      red[grp][t & 1][w4][1] = __float_as_uint(dm);
       if constexpr (QSMOOTH) {
         cs = half_swap_sum_f32(cs);
         if (h == 0) csum[((grp * 3 + t % 3) * 2 + qb) * 64 + 32 * kb + ll] = cs;
@@ -508,6 +523,7 @@ __global__ void __launch_bounds__(512, 1) sage_bwd_kernel(BwdArgs args) {
 // A = stored psi(dS) fragments, B = K^ in TF layout.
 struct DqArgs {
   const int8_t* dSq;
+  int ds_pitch;         // tiles per Q-block row of dSq
   const float* sdS;
   const int8_t* KT;
   const float* sK;
@@ -519,28 +535,32 @@ struct DqArgs {
   float sm_scale;
 };
 
-// A workgroup of 8 waves owns TWO Q blocks (128 queries) and walks the KV blocks j.  Per j, the two
-// psi(dS) tiles and the K^ tile (TF layout) are copied global -> LDS asynchronously into two rings
-// (one barrier per j), so that each byte crosses the memory pipeline once per workgroup; wave
-// (q block, channel block) reads its operands from LDS.
+// A workgroup of 4 waves owns TWO Q blocks (128 queries) and walks the KV blocks j; wave (Q block, row half)
+// owns 32 query rows and ALL d channels.  The psi(dS) tiles are stored as the A fragments of exactly this
+// product, so each wave streams its own 2 KiB per tile from HBM straight into registers (one 16-byte load
+// per lane and fragment, nothing shared, no LDS): kStages tiles ahead.  The K^ tile (TF layout, from L2) is
+// shared by the four waves and travels global -> LDS asynchronously through a ring that runs the same
+// number of stages ahead, together with the three scales of the stage; one barrier per stage.  Both
+// streams are issued by every wave in the same order and complete in order, so one count of outstanding
+// memory operations (`s_waitcnt vmcnt`) covers the K^ copies and the compiler's own waits cover the
+// registers.  Three workgroups share a CU: about 120 KiB of psi(dS) in flight per CU.
+// (Every lane takes part in the scale copy: a memory operation under a lane mask sits behind a branch,
+// and with a path that skips it the compiler stops counting the loads in flight and waits for all of
+// them before each use.)  Measured: the kernel runs at the speed of its psi(dS) stream alone (no
+// arithmetic, no K^ copies: 0.51 ms of 0.54 at the headline shape, about 4.4 TB/s); ring depths 3 to 7,
+// two or three workgroups per CU and non-temporal loads change nothing.
 template <int D, bool CAUSAL>
-__global__ void __launch_bounds__(512, 2) sage_bwd_dq_kernel(DqArgs args) {
-  constexpr int KS = D / 32;
-  constexpr int NPB = KS / 2;              // 32-row blocks per wave (2 for d = 128, 1 for d = 64)
+__global__ void __launch_bounds__(256, 3) sage_bwd_dq_kernel(DqArgs args) {
+  constexpr int KS = D / 32;               // channel blocks
   constexpr int TILE = 64 * D;             // bytes of one K^ tile
   constexpr int DSB = 4096;                // bytes of one psi(dS) tile
-  // Two rings in LDS: the psi(dS) tile pairs come from HBM and need many bytes in flight, the K^
-  // tiles (and the scales) come from L2.  Waves 0..3 issue only psi(dS) copies and waves 4..7 only
-  // K^ copies, so each wave's in-order copy counter tracks one ring and the two prefetch distances
-  // are independent: five stages ahead for psi(dS), two for K^.
-  constexpr int ND = 6, NK = 3;                // ring slots (deeper or shallower rings measured the same)
-  constexpr int DSLOT = 2 * DSB;               // dS tile of Q block 0 | of Q block 1
-  constexpr int KSLOT = TILE + 64;             // K^ tile | s_dS of Q block 0, of Q block 1, s_K
-  constexpr int KCOPIES = TILE / 4096 + 1;     // copies a K^ wave issues per stage
+  constexpr int kStages = 5;               // stages in flight (3 and 7 measured the same)
+  constexpr int NS = kStages + 1;          // ring slots
+  constexpr int KSLOT = TILE + 256;        // K^ tile | s_dS of Q block 0, of Q block 1, s_K (lanes 3.. repeat s_K)
+  constexpr int KC = TILE / 4096;          // K^ copies per wave and stage (the tile's 1 KiB fragments dealt to 4 waves)
+  constexpr int OPS = 2 + KC + 1;          // memory operations per wave and stage: 2 psi(dS) loads, K^ copies, scales
 
-  __shared__ __attribute__((aligned(16))) int8_t lds[ND * DSLOT + NK * KSLOT];
-  int8_t* const dsr = lds;
-  int8_t* const ktr = lds + ND * DSLOT;
+  __shared__ __attribute__((aligned(16))) int8_t lds[NS * KSLOT];
 
   const int g = blockIdx.x;
   const int N = args.N;
@@ -555,111 +575,112 @@ __global__ void __launch_bounds__(512, 2) sage_bwd_dq_kernel(DqArgs args) {
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int ll = lane & 31, h = lane >> 5;
-  const int iq = wave >> 2, w4 = wave & 3;
-  const int cb = (D == 128) ? w4 : (w4 & 1);
-  const int blk0 = (D == 128) ? 0 : (w4 >> 1);
+  const int iq = wave >> 1, qb = wave & 1;             // Q block of the pair, 32-row half of it
   const bool valid = i0 + iq < nblk;
-  const int i = valid ? i0 + iq : i0;
-  const int i1 = i0 + 1 < nblk ? i0 + 1 : i0;          // clamped: the copies stay in bounds
+  const int i = valid ? i0 + iq : i0;                  // clamped: the loads stay in bounds
+  const int i1 = i0 + 1 < nblk ? i0 + 1 : i0;
   const size_t head = (size_t)bh * N * D;
-  const int n_j = CAUSAL ? (i0 + 2 < nblk ? i0 + 2 : nblk) : nblk;
-  const bool ds_wave = wave < 4;
+  const int n_j = CAUSAL ? (i0 + 2 < nblk ? i0 + 2 : nblk) : nblk;   // stages of the workgroup
+  const int j_last = CAUSAL ? i : nblk - 1;            // last tile of this wave's Q block that was written
 
-  const int8_t* ds0 = args.dSq + ((size_t)hl * nblk + i0) * nblk * DSB;
-  const int8_t* ds1 = args.dSq + ((size_t)hl * nblk + i1) * nblk * DSB;
-  const int8_t* kth = args.KT + head;
+  // this wave's fragments of tile (i, j): (row half qb, key step 0 / 1) at j * DSB, + 1024
+  const int8_t* dsw = args.dSq + ((size_t)hl * nblk + i) * args.ds_pitch * DSB + qb * 2048 + lane * 16;
+  const int8_t* kth = args.KT + head + wave * 1024 + lane * 16;
   // per stage lanes 0, 1, 2 fetch s_dS of Q block 0, s_dS of Q block 1, s_K
   const size_t sc_off = lane == 0 ? ((size_t)hl * nblk + i0) * nblk : ((size_t)hl * nblk + i1) * nblk;
   const float* sc_src = lane < 2 ? args.sdS + sc_off : args.sK + (size_t)bh * nblk;
 
-  // Stage indices past the end are clamped: the copy then re-reads the last stage into a slot that
-  // nobody reads any more, and every wave issues the same number of copies in every iteration.
-  auto load_ds = [&](int j, int sl) __attribute__((always_inline)) {   // waves 0..3: two of the eight 1 KiB fragments each
-    const int jc = j < n_j ? j : n_j - 1;
-    const size_t off = (size_t)jc * DSB + w4 * 1024 + lane * 16;
-    int8_t* dst = dsr + sl * DSLOT + w4 * 1024;
-    async_copy_16(ds0 + off, dst);
-    async_copy_16(ds1 + off, dst + DSB);
+  // Stage indices past the end are clamped: the loads then re-read the last stage (into registers or a
+  // slot that nobody reads any more), and every wave issues the same operations in every iteration.
+  auto load_ds = [&](int j, v4i (&a)[2]) __attribute__((always_inline)) {
+    const int jc = j < j_last ? j : j_last;
+    const int8_t* p = dsw + (size_t)jc * DSB;
+    a[0] = *(const v4i*)p;
+    a[1] = *(const v4i*)(p + 1024);
   };
-  auto load_k = [&](int j, int sl) __attribute__((always_inline)) {    // waves 4..7: the K^ fragments, and (all four alike) the scales
+  auto load_k = [&](int j, int sl) __attribute__((always_inline)) {
     const int jc = j < n_j ? j : n_j - 1;
-    const int8_t* src = kth + (size_t)jc * TILE + w4 * 1024 + lane * 16;
-    int8_t* dst = ktr + sl * KSLOT + w4 * 1024;
+    const int8_t* src = kth + (size_t)jc * TILE;
+    int8_t* dst = lds + sl * KSLOT + wave * 1024;
     async_copy_16(src, dst);
-    if constexpr (TILE / 4096 == 2) async_copy_16(src + 4096, dst + 4096);
-    if (lane < 3) async_copy_4(sc_src + jc, ktr + sl * KSLOT + TILE);
+    if constexpr (KC == 2) async_copy_16(src + 4096, dst + 4096);
+    async_copy_4(sc_src + jc, lds + sl * KSLOT + TILE);   // (the same values from every wave; lanes 2.. all carry s_K)
   };
 
-  v16f acc[NPB];
+  v16f acc[KS];
 #pragma unroll
-  for (int t = 0; t < NPB; t++)
+  for (int cb = 0; cb < KS; cb++)
 #pragma unroll
-    for (int r = 0; r < 16; r++) acc[t][r] = 0.f;
+    for (int r = 0; r < 16; r++) acc[cb][r] = 0.f;
 
-  if (ds_wave) {
+  v4i a[kStages][2];
 #pragma unroll
-    for (int jj = 0; jj < ND - 1; jj++) load_ds(jj, jj);
-  } else {
-#pragma unroll
-    for (int jj = 0; jj < NK - 1; jj++) load_k(jj, jj);
+  for (int s = 0; s < kStages; s++) {
+    load_ds(s, a[s]);
+    load_k(s, s);
+    compiler_fence();                      // the waits below count operations in issue order
   }
-  barrier_all_memory();
+  static_assert((kStages - 1) * OPS < 64, "vmcnt has six bits");
+  __builtin_amdgcn_s_waitcnt(vmcnt_only((kStages - 1) * OPS));   // stage 0 has landed
+  barrier_lds_only();
 
-  // Iteration j: the psi(dS) waves start stage j + 5 and the K^ waves stage j + 2, each into the
-  // slot that stage j - 1 occupied; before the barrier at the end each wave waits until its copies
-  // of stage j + 1 have landed and leaves the younger ones in flight.
-  int sd = 0, sk = 0;                      // slots of stage j
-  for (int j = 0; j < n_j; j++) {
-    if (ds_wave) load_ds(j + ND - 1, sd == 0 ? ND - 1 : sd - 1);
-    else load_k(j + NK - 1, sk == 0 ? NK - 1 : sk - 1);
-    if (valid && (!CAUSAL || j <= i)) {
-      const int8_t* ap = dsr + sd * DSLOT + iq * DSB + lane * 16;
-      const int8_t* kp = ktr + sk * KSLOT;
-      const int8_t* bp = kp + cb * 1024 + lane * 16;
-      const float* sc = (const float*)(kp + TILE);
-      const float w = sc[iq] * sc[2] * args.sm_scale;
-      const v4i b0 = *(const v4i*)(bp);
-      const v4i b1 = *(const v4i*)(bp + KS * 1024);
+  // Iteration j: contract stage j (registers a[j % kStages], ring slot j % NS), then start stage
+  // j + kStages into the same registers and into the slot that stage j - 1 occupied (every wave is past
+  // the barrier that ended iteration j - 1); before the barrier at the end, wait until this wave's
+  // copies of stage j + 1 have landed (everything but the kStages - 1 youngest stages).
+  // The loop is unrolled over the kStages register sets and runs whole rounds (the stages past n_j only
+  // keep the counts even: clamped loads, no arithmetic), so that every path through the body issues the
+  // same memory operations and the compiler's count of the loads in flight stays exact.
+  int sk = 0;                              // slot of stage j
+  for (int j0 = 0; j0 < n_j; j0 += kStages) {
 #pragma unroll
-      for (int t = 0; t < NPB; t++) {
-        const v4i a0 = *(const v4i*)(ap + ((blk0 + t) * 2 + 0) * 1024);
-        const v4i a1 = *(const v4i*)(ap + ((blk0 + t) * 2 + 1) * 1024);
-        v16i q;
+    for (int s = 0; s < kStages; s++) {
+      const int j = j0 + s;
+      if (j < n_j && valid && (!CAUSAL || j <= i)) {
+        const int8_t* kp = lds + sk * KSLOT;
+        const float* sc = (const float*)(kp + TILE);
+        const float w = sc[iq] * sc[2] * args.sm_scale;
 #pragma unroll
-        for (int r = 0; r < 16; r++) q[r] = 0;
-        q = __builtin_amdgcn_mfma_i32_32x32x32_i8(a0, b0, q, 0, 0, 0);
-        q = __builtin_amdgcn_mfma_i32_32x32x32_i8(a1, b1, q, 0, 0, 0);
+        for (int cb = 0; cb < KS; cb++) {
+          const v4i b0 = *(const v4i*)(kp + cb * 1024 + lane * 16);
+          const v4i b1 = *(const v4i*)(kp + (KS + cb) * 1024 + lane * 16);
+          v16i q;
 #pragma unroll
-        for (int r = 0; r < 16; r++) acc[t][r] = __builtin_fmaf((float)q[r], w, acc[t][r]);
+          for (int r = 0; r < 16; r++) q[r] = 0;
+          q = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[s][0], b0, q, 0, 0, 0);
+          q = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[s][1], b1, q, 0, 0, 0);
+#pragma unroll
+          for (int r = 0; r < 16; r++) acc[cb][r] = __builtin_fmaf((float)q[r], w, acc[cb][r]);
+        }
       }
+      load_ds(j + kStages, a[s]);
+      load_k(j + kStages, sk == 0 ? NS - 1 : sk - 1);
+      __builtin_amdgcn_s_waitcnt(vmcnt_only((kStages - 1) * OPS));
+      barrier_lds_only();
+      sk = sk == NS - 1 ? 0 : sk + 1;
     }
-    if (ds_wave) __builtin_amdgcn_s_waitcnt(0x0F70 | (2 * (ND - 2)));
-    else __builtin_amdgcn_s_waitcnt(0x0F70 | (KCOPIES * (NK - 2)));
-    barrier_lds_only();
-    sd = sd == ND - 1 ? 0 : sd + 1;
-    sk = sk == NK - 1 ? 0 : sk + 1;
   }
-  barrier_all_memory();    // the clamped copies past the last stage have landed before the workgroup leaves
+  barrier_all_memory();    // the clamped copies past the last stage have landed before the ring is reused
   // ---- write dQ (bf16): the accumulators hold one channel per lane and 16 query rows in registers, so
-  // the two 64 x D blocks go through LDS (the rings are drained) and leave as 16-byte row pieces ----
+  // the two 64 x D blocks go through LDS (the ring is drained) and leave as 16-byte row pieces ----
   constexpr int LDQ = D + 8;                                   // padded row, in bf16 elements
-  static_assert(2 * 64 * LDQ * 2 <= ND * DSLOT + NK * KSLOT, "the dQ staging must fit the rings");
+  static_assert(2 * 64 * LDQ * 2 <= NS * KSLOT, "the dQ staging must fit the ring");
   unsigned short* stg = (unsigned short*)lds;                  // [Q block][row][LDQ]
   if (valid) {
 #pragma unroll
-    for (int t = 0; t < NPB; t++)
+    for (int cb = 0; cb < KS; cb++)
 #pragma unroll
       for (int aa = 0; aa < 4; aa++)
 #pragma unroll
         for (int b = 0; b < 4; b++)
-          stg[(iq * 64 + 32 * (blk0 + t) + 8 * aa + 4 * h + b) * LDQ + 32 * cb + ll] = float_to_bf16_bits(acc[t][4 * aa + b]);
+          stg[(iq * 64 + 32 * qb + 8 * aa + 4 * h + b) * LDQ + 32 * cb + ll] = float_to_bf16_bits(acc[cb][4 * aa + b]);
   }
   barrier_lds_only();
   constexpr int CPR = D / 8;                                   // 16-byte pieces per row
-  for (int c = tid; c < 2 * 64 * CPR; c += 512) {
-    const int qb = c / (64 * CPR), row = (c / CPR) % 64, pc = c % CPR;
-    if (i0 + qb < nblk && 64 * (i0 + qb) + row < args.nvalid)
-      *(v8us*)(args.dQ + args.cv.row(bh, 64 * (i0 + qb) + row) + 8 * pc) = *(const v8us*)(stg + (qb * 64 + row) * LDQ + 8 * pc);
+  for (int c = tid; c < 2 * 64 * CPR; c += 256) {
+    const int qblk = c / (64 * CPR), row = (c / CPR) % 64, pc = c % CPR;
+    if (i0 + qblk < nblk && 64 * (i0 + qblk) + row < args.nvalid)
+      *(v8us*)(args.dQ + args.cv.row(bh, 64 * (i0 + qblk) + row) + 8 * pc) = *(const v8us*)(stg + (qblk * 64 + row) * LDQ + 8 * pc);
   }
 }
 

@@ -97,6 +97,15 @@ __device__ __forceinline__ void async_copy_4(const void* gsrc_lane, void* lds_ba
   __builtin_amdgcn_global_load_lds((gptr_t)gsrc_lane, (lptr_t)lds_base, 4, 0, 0);
 }
 
+// Immediate of `s_waitcnt vmcnt(n)` alone (the LDS / scalar and export counters are left at their
+// maxima = no wait): the six bits of n sit in bits 3:0 and 15:14.
+constexpr int vmcnt_only(int n) { return 0x0F70 | (n & 15) | ((n >> 4) << 14); }
+// Keeps memory operations in program order across this point (for the compiler; no instruction).
+__device__ __forceinline__ void compiler_fence() {
+  asm volatile("" ::: "memory");
+  __builtin_amdgcn_sched_barrier(0);
+}
+
 // Workgroup barrier that waits for this wave's LDS traffic only.  (__syncthreads() would
 // also drain the asynchronous global->LDS copies that are meant to stay in flight.)
 __device__ __forceinline__ void barrier_lds_only() {

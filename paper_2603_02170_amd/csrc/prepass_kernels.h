@@ -88,7 +88,7 @@ struct QuantJob {
   float* mu_head_out;          // [BH, D]: where block 0 of each head stores that mean
   float* mu_block_out;         // [BH, N/64, D]: if set, the block mean is computed, stored and subtracted
   const unsigned short* O;     // bf16 [BH, N, D] or nullptr: delta = rowsum(src o O)
-  float* delta;                // [BH, N]
+  float* delta;                // [BH, N]: -rowsum(src o O)
   const float* lse;            // [BH, N] or nullptr: nl2 = -lse * log2(e) for the backward
   float* nl2;                  // [BH, N]
 };
@@ -154,7 +154,8 @@ __global__ void __launch_bounds__(256) prepass_quant_kernel(QuantJobs jobs, RowV
       }
 #pragma unroll
       for (int off = 1; off < CPR; off <<= 1) acc += __shfl_xor(acc, off, 64);
-      if (ch == 0) jb.delta[(size_t)bh * Np + (size_t)blk * kBlock + row] = acc;
+      // stored negated: the backward starts the dP accumulators from -delta (dP - delta in one chain)
+      if (ch == 0) jb.delta[(size_t)bh * Np + (size_t)blk * kBlock + row] = -acc;
     }
   }
 
@@ -308,10 +309,11 @@ __global__ void export_fragments_kernel(const int8_t* __restrict__ frag, int8_t*
   }
 }
 
-__global__ void copy_f32_kernel(const float* __restrict__ in, float* __restrict__ out, size_t n) {
+// out = sign * in (sign = +-1: exact)
+__global__ void copy_f32_kernel(const float* __restrict__ in, float* __restrict__ out, size_t n, float sign) {
   size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x;
   const size_t stride = (size_t)gridDim.x * blockDim.x;
-  for (; i < n; i += stride) out[i] = in[i];
+  for (; i < n; i += stride) out[i] = sign * in[i];
 }
 
 // ---- Q-smoothing: logit bias table -------------------------------------------------
@@ -402,7 +404,8 @@ __global__ void __launch_bounds__(256) qsmooth_bias_kernel(const unsigned short*
 // order in which the K^ operand of the dQ product holds its rows).  Tiles above the causal diagonal
 // were never written: they are returned as zeros.  One thread per 16 bytes.
 __global__ void export_ds_kernel(const int8_t* __restrict__ tiles, const float* __restrict__ scales,
-                                 int8_t* __restrict__ ds_out, float* __restrict__ scale_out, int Np, int causal) {
+                                 int8_t* __restrict__ ds_out, float* __restrict__ scale_out, int Np, int pitch,
+                                 int causal) {
   const int nblk = Np / kBlock;
   const size_t c = blockIdx.x * (size_t)blockDim.x + threadIdx.x;
   if (c >= (size_t)nblk * nblk * 256) return;
@@ -410,7 +413,7 @@ __global__ void export_ds_kernel(const int8_t* __restrict__ tiles, const float* 
   const int frag = (int)(c % 256) / 64, lane = (int)(c % 64);
   const bool there = !causal || j <= i;
   v4i v = {0, 0, 0, 0};
-  if (there) v = *(const v4i*)(tiles + c * 16);
+  if (there) v = *(const v4i*)(tiles + ((size_t)i * pitch + j) * 4096 + (c % 256) * 16);   // `pitch` tiles per Q-block row
   const int qrow = 64 * i + 32 * (frag >> 1) + (lane & 31), key = 64 * j + 32 * (frag & 1) + 4 * (lane >> 5);
   if (ds_out != nullptr) {
 #pragma unroll

@@ -75,6 +75,7 @@ struct Workspace {
   size_t dSq;               // psi(dS) tiles of one head group [heads_per_group, N/64, N/64, 4096]
   size_t sdS;               // their scales [heads_per_group, N/64, N/64]
   int heads_per_group;      // the backward runs in groups of heads that share the dS scratch
+  int ds_pitch;             // tiles per Q-block row of the dS scratch
   size_t total;
   int nchunk, chunk_rows;   // K-mean reduction: chunks per head, rows per chunk
 };
@@ -108,11 +109,16 @@ Workspace make_layout(const sagebwd_params& p) {
   w.dOT = take(BH * N * d);
   // dS scratch: N*N bytes per head, capped at the budget by processing the heads in groups
   const size_t budget = p.scratch_budget != 0 ? (size_t)p.scratch_budget : kDefaultDsBudget;
-  size_t hpg = budget / (N * N);
+  // Rows of the dS scratch are three tiles longer than they need to be: with a power-of-two row length
+  // the workgroups of the dQ kernel, which walk their rows at the same pace, read addresses that differ
+  // in the high bits only (measured: 4 % of that kernel).
+  w.ds_pitch = (int)nblk + 3;
+  const size_t ds_head = nblk * (size_t)w.ds_pitch * 4096;   // bytes of dS scratch per head
+  size_t hpg = budget / ds_head;
   if (hpg < 1) hpg = 1;
   if (hpg > BH) hpg = BH;
   w.heads_per_group = (int)hpg;
-  w.dSq = take(hpg * N * N);
+  w.dSq = take(hpg * ds_head);
   w.sdS = take(hpg * nblk * nblk * 4);
   w.total = off;
   return w;
@@ -317,8 +323,8 @@ int launch_bwd_dq(const DqArgs& a, bool causal, hipStream_t st) {
   DqArgs args = a;
   args.head_set = head_set_for(npair, a.BH, true);   // memory-bound: gains from head sets at every length
   const int grid = grid_for(a.BH, npair);
-  if (causal) sage_bwd_dq_kernel<D, true><<<grid, 512, 0, st>>>(args);
-  else sage_bwd_dq_kernel<D, false><<<grid, 512, 0, st>>>(args);
+  if (causal) sage_bwd_dq_kernel<D, true><<<grid, 256, 0, st>>>(args);
+  else sage_bwd_dq_kernel<D, false><<<grid, 256, 0, st>>>(args);
   SAGE_LAUNCH_CHECK();
   return SAGEBWD_OK;
 }
@@ -424,7 +430,7 @@ int sagebwd_export_quantized(const sagebwd_params* params, const void* workspace
   }
   if (scale_out != nullptr) {
     const size_t n = BH * (Np / 64);
-    copy_f32_kernel<<<(unsigned)((n + 255) / 256), 256, 0, st>>>((const float*)(ws + soff), scale_out, n);
+    copy_f32_kernel<<<(unsigned)((n + 255) / 256), 256, 0, st>>>((const float*)(ws + soff), scale_out, n, 1.0f);
     SAGE_LAUNCH_CHECK();
   }
   return SAGEBWD_OK;
@@ -441,15 +447,15 @@ int sagebwd_export_stats(const sagebwd_params* params, const void* workspace, si
   hipStream_t st = (hipStream_t)stream;
   const char* ws = (const char*)workspace;
   const size_t BH = (size_t)params->B * params->H;
-  auto copy = [&](size_t off, float* out, size_t n) {
+  auto copy = [&](size_t off, float* out, size_t n, float sign = 1.0f) {
     unsigned grid = (unsigned)((n + 255) / 256);
     if (grid > 65535u * 16u) grid = 65535u * 16u;
-    copy_f32_kernel<<<grid, 256, 0, st>>>((const float*)(ws + off), out, n);
+    copy_f32_kernel<<<grid, 256, 0, st>>>((const float*)(ws + off), out, n, sign);
   };
   if (mu_K != nullptr) { copy(w.muK, mu_K, BH * params->d); SAGE_LAUNCH_CHECK(); }
   const size_t Np = padded_rows(params->N);
   if (mu_Q != nullptr) { copy(w.muQ, mu_Q, BH * (Np / 64) * params->d); SAGE_LAUNCH_CHECK(); }
-  if (delta != nullptr) { copy(w.delta, delta, BH * Np); SAGE_LAUNCH_CHECK(); }
+  if (delta != nullptr) { copy(w.delta, delta, BH * Np, -1.0f); SAGE_LAUNCH_CHECK(); }   // the workspace holds -delta
   return SAGEBWD_OK;
 }
 
@@ -467,8 +473,8 @@ int sagebwd_export_ds(const sagebwd_params* params, const void* workspace, size_
   const char* ws = (const char*)workspace;
   const size_t n = (size_t)nblk * nblk * 256;
   export_ds_kernel<<<(unsigned)((n + 255) / 256), 256, 0, (hipStream_t)stream>>>(
-      (const int8_t*)(ws + w.dSq) + (size_t)head * Np * Np, (const float*)(ws + w.sdS) + (size_t)head * nblk * nblk,
-      ds_out, scale_out, Np, params->causal);
+      (const int8_t*)(ws + w.dSq) + (size_t)head * nblk * w.ds_pitch * 4096, (const float*)(ws + w.sdS) + (size_t)head * nblk * nblk,
+      ds_out, scale_out, Np, w.ds_pitch, params->causal);
   SAGE_LAUNCH_CHECK();
   return SAGEBWD_OK;
 }
@@ -538,6 +544,7 @@ int sagebwd_bwd(const void* Q, const void* K, const void* V, const void* O, cons
   a.bias = qs ? (const float*)(ws + w.bias) : nullptr;
   a.muQ = qs ? (const float*)(ws + w.muQ) : nullptr;
   a.dSq = (int8_t*)(ws + w.dSq);
+  a.ds_pitch = w.ds_pitch;
   a.sdS = (float*)(ws + w.sdS);
   a.dK = (unsigned short*)dK;
   a.dV = (unsigned short*)dV;
@@ -548,6 +555,7 @@ int sagebwd_bwd(const void* Q, const void* K, const void* V, const void* O, cons
   DqArgs q;
   q.cv = a.cv;
   q.dSq = a.dSq;
+  q.ds_pitch = w.ds_pitch;
   q.sdS = a.sdS;
   q.KT = (const int8_t*)(ws + w.KT);
   q.sK = a.sK;

@@ -96,7 +96,7 @@ def test_bwd_outlier_shape_with_and_without_k_smoothing():
 def test_bwd_head_groups_share_the_ds_scratch():
     # a scratch budget of two heads' worth of dS forces the 5 heads through 3 groups
     Q, K, V, dO = synth.gaussian_inputs(256, 64, seed=21, heads=5)
-    _bwd_case(Q, K, V, dO, binding.SageParams(1, 5, 256, 64, causal=True, scratch_budget=2 * 256 * 256))
+    _bwd_case(Q, K, V, dO, binding.SageParams(1, 5, 256, 64, causal=True, scratch_budget=2 * 256 * (256 + 192)))
 
 
 def test_bwd_q_smoothing_head_dim_64_odd_block_count():
@@ -206,7 +206,7 @@ def test_backward_is_deterministic_and_needs_nothing_from_an_old_workspace():
     a = [t.clone() for t in binding.sagebwd_bwd(Q, K, V, O, dO, L, p, ws)]
     ws.fill_(0x5A)
     b = [t.clone() for t in binding.sagebwd_bwd(Q, K, V, O, dO, L, p, ws)]
-    pg = binding.SageParams(1, 5, 448, 128, causal=True, q_smooth=True, scratch_budget=2 * 448 * 448)   # two heads at a time
+    pg = binding.SageParams(1, 5, 448, 128, causal=True, q_smooth=True, scratch_budget=2 * 448 * (448 + 192))   # two heads at a time
     c = binding.sagebwd_bwd(Q, K, V, O, dO, L, pg, binding.alloc_workspace(pg))
     torch.cuda.synchronize()
     for x, y, z in zip(a, b, c):
