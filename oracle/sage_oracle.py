@@ -34,6 +34,13 @@ kernels implement; one must divide the other).  Q, dO and mu_Q are blocked by
 bq rows, K and V by bkv rows, psi(P_ij) and psi(dS_ij) act on bq x bkv tiles, and
 the forward's per-token psi(P~) on the bkv keys of a tile.
 
+Non-square attention (the paper states the method for Q, K, V of one length N; cross
+attention, chunked prefill and decoding against a cache have N_q != N_kv): Q, O, dO, dQ
+have N_q rows, K, V, dK, dV have N_kv rows; nothing else changes, every step acts on its
+own blocks.  Under the causal mask the last query is aligned with the last key: query i
+sees keys k <= i + (N_kv - N_q) (N_kv >= N_q), which is the square mask when the
+lengths agree.
+
 Sequence lengths that are not a multiple of the block (the paper assumes N/B_q and
 N/B_kv integral, Algorithm 1 line 2): the last block is a partial block whose
 missing rows do not exist.  They enter no mean, no absmax, no sum, no softmax.
@@ -163,15 +170,18 @@ def prepass_head(Q, K, V, k_smooth: bool = True, q_smooth: bool = False, bq: int
     Returns a dict with Qh, sQ, Kh, sK, Vh, sV (int8 / float32), muK [d],
     muQ [rows/bq, d] (zeros when the smoothing is off) and Ksm (float32 K - mu_K).
     When N is not a multiple of the blocks the row-indexed entries have N rounded up
-    to a multiple of both, the appended rows zero (module header); "n" is the true N.
+    to a multiple of both, the appended rows zero (module header); "n", "nk" are the true
+    N_q and N_kv (K and V may have another length than Q).
     """
     _check_blocks(bq, bkv)
     Q = np.asarray(Q, dtype=_F32)
     K = np.asarray(K, dtype=_F32)
     V = np.asarray(V, dtype=_F32)
     n, d = Q.shape
-    n_pad = padded_len(n, bq, bkv)
-    muK = key_mean(K) if k_smooth else np.zeros(d, dtype=_F32)   # over the N tokens that exist
+    nk = K.shape[0]
+    assert V.shape[0] == nk
+    n_pad, nk_pad = padded_len(n, bq, bkv), padded_len(nk, bq, bkv)
+    muK = key_mean(K) if k_smooth else np.zeros(d, dtype=_F32)   # over the N_kv tokens that exist
     Ksm = (K - muK[None, :]).astype(_F32)       # f32 subtraction, R6
     if q_smooth:
         muQ = pad_rows(block_mean(Q, bq), n_pad // bq)           # blocks with no row at all: mean 0
@@ -179,11 +189,12 @@ def prepass_head(Q, K, V, k_smooth: bool = True, q_smooth: bool = False, bq: int
     else:
         muQ = np.zeros((n_pad // bq, d), dtype=_F32)
         Qsm = Q
-    Qsm, Ksm, Vp = (pad_rows(x, n_pad) for x in (Qsm, Ksm, V))
+    Qsm = pad_rows(Qsm, n_pad)
+    Ksm, Vp = (pad_rows(x, nk_pad) for x in (Ksm, V))
     Qh, sQ = quantize_blocks(Qsm, bq)
     Kh, sK = quantize_blocks(Ksm, bkv)
     Vh, sV = quantize_blocks(Vp, bkv)
-    return dict(Qh=Qh, sQ=sQ, Kh=Kh, sK=sK, Vh=Vh, sV=sV, muK=muK, muQ=muQ, Ksm=Ksm, n=n, bq=bq, bkv=bkv)
+    return dict(Qh=Qh, sQ=sQ, Kh=Kh, sK=sK, Vh=Vh, sV=sV, muK=muK, muQ=muQ, Ksm=Ksm, n=n, nk=nk, bq=bq, bkv=bkv)
 
 
 def delta_rows(dO, O) -> np.ndarray:
@@ -214,13 +225,14 @@ def _logits_block(pp, i0: int, n_keys: int, sm_scale: float, q_smooth: bool, key
     return S
 
 
-def _visible_keys(i0: int, n: int, causal: bool, bq: int, bkv: int) -> int:
-    """Keys [0, n_keys) that the Q block starting at i0 works on: all n without the mask; under the
-    causal mask (R13) the KV blocks that hold a key k <= i for some row i of the block (whole KV
-    blocks, since psi's scales are per block; fully masked blocks are skipped)."""
+def _visible_keys(i0: int, nk: int, causal: bool, bq: int, bkv: int, shift: int = 0) -> int:
+    """Keys [0, n_keys) that the Q block starting at i0 works on: all nk without the mask; under the
+    causal mask (R13; query i sees keys k <= i + shift, shift = N_kv - N_q) the KV blocks that hold a
+    visible key for some row of the block (whole KV blocks, since psi's scales are per block; fully
+    masked blocks are skipped)."""
     if not causal:
-        return n
-    return min(n, -(-(i0 + bq) // bkv) * bkv)
+        return nk
+    return min(nk, -(-(i0 + bq + shift) // bkv) * bkv)
 
 
 # --------------------------------------------------------------------------
@@ -229,7 +241,7 @@ def _visible_keys(i0: int, n: int, causal: bool, bq: int, bkv: int) -> int:
 def forward_head(Q, K, V, causal: bool = True, k_smooth: bool = True, q_smooth: bool = False,
                  sm_scale: float | None = None, return_raw: bool = False, q_blocks=None,
                  bq: int = BLOCK, bkv: int = BLOCK):
-    """INT8 attention forward of one head.  Q, K, V: [N, d] float32 (bf16 values).
+    """INT8 attention forward of one head.  Q: [N_q, d], K, V: [N_kv, d] float32 (bf16 values).
 
     Returns (O [N, d] bf16-rounded float32, L [N] float32); with return_raw the
     unrounded float64 O and L come too.  `q_blocks` (iterable of bq-row block
@@ -238,27 +250,32 @@ def forward_head(Q, K, V, causal: bool = True, k_smooth: bool = True, q_smooth: 
     """
     Q = np.asarray(Q, dtype=_F32)
     n_true, d = Q.shape
-    n = padded_len(n_true, bq, bkv)                   # rows after appending (module header)
+    nk_true = np.asarray(K).shape[0]
+    n, nk = padded_len(n_true, bq, bkv), padded_len(nk_true, bq, bkv)   # rows after appending (module header)
+    shift = nk_true - n_true                          # causal: query i sees keys k <= i + shift
+    assert not causal or shift >= 0, "causal attention needs N_kv >= N_q"
     if sm_scale is None:
         sm_scale = 1.0 / np.sqrt(d)
     pp = prepass_head(Q, K, V, k_smooth, q_smooth, bq, bkv)
-    Vh = pp["Vh"].astype(_F64).reshape(n // bkv, bkv, d)
+    Vh = pp["Vh"].astype(_F64).reshape(nk // bkv, bkv, d)
     sV = pp["sV"].astype(_F64)
     O = np.zeros((n, d), dtype=_F64)
     L = np.zeros(n, dtype=_F64)
     rows = np.arange(bq)
     todo = range(n // bq) if q_blocks is None else sorted(set(int(b) for b in q_blocks))
     for i0 in (bq * b for b in todo):
-        n_keys = _visible_keys(i0, n, causal, bq, bkv)            # R13: keys k <= i only
+        n_keys = _visible_keys(i0, nk, causal, bq, bkv, shift)    # R13: keys k <= i + shift only
         tj = n_keys // bkv
         S = _logits_block(pp, i0, n_keys, sm_scale, q_smooth)
         kk = np.arange(n_keys)
         if causal:
-            S = np.where(kk[None, :] > (i0 + rows)[:, None], -np.inf, S)
-        S = np.where(kk[None, :] >= n_true, -np.inf, S)           # keys that do not exist
+            S = np.where(kk[None, :] > (i0 + rows + shift)[:, None], -np.inf, S)
+        S = np.where(kk[None, :] >= nk_true, -np.inf, S)          # keys that do not exist
         # softmax statistics over the whole row: what m_{i,Tn}, l_{i,Tn} evaluate to (R2, R3)
         m = S.max(axis=1)
+        m = np.where(np.isfinite(m), m, 0.0)          # (appended query rows past a short K see no key: dropped below)
         l = np.exp(S - m[:, None]).sum(axis=1)        # unquantised P~ feeds l
+        l = np.where(l > 0, l, 1.0)
         L[i0:i0 + bq] = m + np.log(l)
         # per KV block j: per-token quantisation of P~ (the s_P line of Algorithm 1).
         # R12: P~/s_P = exp(S - m) * 127 / exp(rowmax(S_ij) - m) = 127 exp(S - rowmax(S_ij)),
@@ -290,9 +307,9 @@ def backward_head(Q, K, V, O, dO, L, causal: bool = True, k_smooth: bool = True,
                   q_blocks=None, kv_blocks=None, bq: int = BLOCK, bkv: int = BLOCK):
     """INT8 attention backward of one head.
 
-    Inputs as the caller holds them: Q, K, V, O, dO [N, d] (bf16 values as
-    float32) and L [N] float32 from the forward.  Returns bf16-rounded
-    (dQ, dK, dV); with return_raw the float64 values instead.
+    Inputs as the caller holds them: Q, O, dO [N_q, d], K, V [N_kv, d] (bf16 values as
+    float32) and L [N_q] float32 from the forward.  Returns bf16-rounded
+    (dQ [N_q, d], dK, dV [N_kv, d]); with return_raw the float64 values instead.
 
     If `intermediates` is a dict it receives the unquantised float64 P, dP, dS
     of the whole head, the codes psi(dS) ("dSh", integers as float64) and their
@@ -306,13 +323,16 @@ def backward_head(Q, K, V, O, dO, L, causal: bool = True, k_smooth: bool = True,
     """
     Q = np.asarray(Q, dtype=_F32)
     n_true, d = Q.shape
-    n = padded_len(n_true, bq, bkv)                           # rows after appending (module header)
+    nk_true = np.asarray(K).shape[0]
+    n, nk = padded_len(n_true, bq, bkv), padded_len(nk_true, bq, bkv)   # rows after appending (module header)
+    shift = nk_true - n_true                                  # causal: query i sees keys k <= i + shift
+    assert not causal or shift >= 0, "causal attention needs N_kv >= N_q"
     if sm_scale is None:
         sm_scale = 1.0 / np.sqrt(d)
     pp = prepass_head(Q, K, V, k_smooth, q_smooth, bq, bkv)   # same blocks and scales as forward
     dO = pad_rows(np.asarray(dO, dtype=_F32), n)
     O = pad_rows(np.asarray(O, dtype=_F32), n)
-    V = pad_rows(np.asarray(V, dtype=_F32), n)
+    V = pad_rows(np.asarray(V, dtype=_F32), nk)
     L = pad_rows(np.asarray(L, dtype=_F32), n)
     dOh, sdO = quantize_blocks(dO, bq)                        # psi(dO_i), per block of bq rows
     delta = delta_rows(dO, O)
@@ -322,20 +342,20 @@ def backward_head(Q, K, V, O, dO, L, causal: bool = True, k_smooth: bool = True,
     Kh = pp["Kh"].astype(_F64)
     Qh = pp["Qh"].astype(_F64)
     dQ = np.zeros((n, d), dtype=_F64)
-    dK = np.zeros((n, d), dtype=_F64)
-    dV = np.zeros((n, d), dtype=_F64)
+    dK = np.zeros((nk, d), dtype=_F64)
+    dV = np.zeros((nk, d), dtype=_F64)
     if intermediates is not None:
-        intermediates["P"] = np.zeros((n, n))
-        intermediates["dP"] = np.zeros((n, n))
-        intermediates["dS"] = np.zeros((n, n))
-        intermediates["dSh"] = np.zeros((n, n))
-        intermediates["sdS"] = np.zeros((n // bq, n // bkv), dtype=_F32)
+        intermediates["P"] = np.zeros((n, nk))
+        intermediates["dP"] = np.zeros((n, nk))
+        intermediates["dS"] = np.zeros((n, nk))
+        intermediates["dSh"] = np.zeros((n, nk))
+        intermediates["sdS"] = np.zeros((n // bq, nk // bkv), dtype=_F32)
     rows = np.arange(bq)
     q_todo = range(n // bq) if q_blocks is None else sorted(set(int(b) for b in q_blocks))
     kv_keep = None if kv_blocks is None else set(int(b) for b in kv_blocks)
     for i0 in (bq * b for b in q_todo):
         I = i0 // bq
-        n_keys = _visible_keys(i0, n, causal, bq, bkv)
+        n_keys = _visible_keys(i0, nk, causal, bq, bkv, shift)
         blocks = [J for J in range(n_keys // bkv) if kv_keep is None or J in kv_keep]
         if not blocks:
             continue
@@ -344,9 +364,9 @@ def backward_head(Q, K, V, O, dO, L, causal: bool = True, k_smooth: bool = True,
         S = _logits_block(pp, i0, n_keys, sm_scale, q_smooth, None if kv_keep is None else kk)
         P = np.exp(S - L64[i0:i0 + bq, None])                 # P_ij = exp(S_ij - L_i)
         if causal:
-            P = np.where(kk[None, :] > (i0 + rows)[:, None], 0.0, P)   # R13: masked entries are 0
+            P = np.where(kk[None, :] > (i0 + rows + shift)[:, None], 0.0, P)   # R13: masked entries are 0
         # keys and query rows that do not exist
-        P = np.where((kk[None, :] >= n_true) | ((i0 + rows)[:, None] >= n_true), 0.0, P)
+        P = np.where((kk[None, :] >= nk_true) | ((i0 + rows)[:, None] >= n_true), 0.0, P)
         dP = dO64[i0:i0 + bq] @ V64[kk].T                     # unquantised matmul (R15)
         dS = P * (dP - delta[i0:i0 + bq, None])
         if intermediates is not None:
@@ -372,7 +392,7 @@ def backward_head(Q, K, V, O, dO, L, causal: bool = True, k_smooth: bool = True,
                 # dK_bias = (dS^T 1) mu_Q^T (ablation section); R17: from the unquantised dS
                 colsum = dS[:, c0:c0 + bkv].sum(axis=0)
                 dK[j0:j0 + bkv] += _F64(sm_scale) * colsum[:, None] * pp["muQ"][I].astype(_F64)[None, :]
-    dQ, dK, dV = dQ[:n_true], dK[:n_true], dV[:n_true]
+    dQ, dK, dV = dQ[:n_true], dK[:nk_true], dV[:nk_true]
     if return_raw:
         return dQ, dK, dV
     return round_to_bf16(dQ), round_to_bf16(dK), round_to_bf16(dV)

@@ -12,7 +12,8 @@ the running max starts at -inf with one entry per query row and the running sum 
 running sum and the output accumulator are both rescaled by exp(m_old - m_new) when the
 max moves; the logits carry sm_scale in the dequantisation factor; the causal mask is
 applied to the dequantised logits; psi rounds to nearest-even in float32 with r = 127 / a.
-N must be a multiple of both block sizes here (small test inputs only).
+N_q must be a multiple of B_q and N_kv of B_kv here (small test inputs only); the two may differ
+(the causal mask then aligns the last query with the last key).
 """
 from __future__ import annotations
 
@@ -53,8 +54,9 @@ class _Prepared:
     def __init__(self, Q, K, V, k_smooth, q_smooth, bq, bkv):
         Q, K, V = (np.asarray(x, dtype=f32) for x in (Q, K, V))
         n, d = Q.shape
-        assert n % bq == 0 and n % bkv == 0
-        self.n, self.d, self.bq, self.bkv = n, d, bq, bkv
+        nk = K.shape[0]
+        assert n % bq == 0 and nk % bkv == 0 and V.shape[0] == nk
+        self.n, self.nk, self.d, self.bq, self.bkv = n, nk, d, bq, bkv
         self.mu_k = _token_mean(K) if k_smooth else np.zeros(d, dtype=f32)
         self.k_sm = K - self.mu_k                 # float32 - float32
         self.mu_q = []
@@ -77,10 +79,13 @@ class _Prepared:
         return s
 
     def masked(self, i, j):
-        """Boolean [bq, bkv]: key index > query index."""
-        qi = i * self.bq + np.arange(self.bq)
+        """Boolean [bq, bkv]: key index > query index + (N_kv - N_q) (last query on last key)."""
+        qi = i * self.bq + np.arange(self.bq) + (self.nk - self.n)
         kj = j * self.bkv + np.arange(self.bkv)
         return kj[None, :] > qi[:, None]
+
+    def all_masked(self, i, j):
+        return j * self.bkv > i * self.bq + self.bq - 1 + (self.nk - self.n)
 
 
 def forward_tiled(Q, K, V, causal=True, k_smooth=True, q_smooth=False, sm_scale=None, bq=64, bkv=64):
@@ -95,8 +100,8 @@ def forward_tiled(Q, K, V, causal=True, k_smooth=True, q_smooth=False, sm_scale=
         run_max = np.full(bq, -np.inf)
         run_sum = np.zeros(bq)
         out = np.zeros((bq, d))
-        for j in range(n // bkv):
-            if causal and j * bkv > i * bq + bq - 1:
+        for j in range(pre.nk // bkv):
+            if causal and pre.all_masked(i, j):
                 break                                           # every key of this block is masked
             s = pre.logits(i, j, sm_scale)
             if causal:
@@ -134,12 +139,12 @@ def backward_tiled(Q, K, V, O, dO, L, causal=True, k_smooth=True, q_smooth=False
     v64 = np.asarray(V, dtype=f32).astype(np.float64)
     do64 = dO.astype(np.float64)
     dQ = np.zeros((n, d))
-    dK = np.zeros((n, d))
-    dV = np.zeros((n, d))
-    for j in range(n // bkv):
+    dK = np.zeros((pre.nk, d))
+    dV = np.zeros((pre.nk, d))
+    for j in range(pre.nk // bkv):
         ks = slice(j * bkv, (j + 1) * bkv)
         for i in range(n // bq):
-            if causal and j * bkv > i * bq + bq - 1:
+            if causal and pre.all_masked(i, j):
                 continue
             qs = slice(i * bq, (i + 1) * bq)
             p = np.exp(pre.logits(i, j, sm_scale) - lse[qs, None])

@@ -12,9 +12,10 @@ def fpa_forward(Q, K, V, causal, sm_scale):
     K = np.asarray(K, dtype=np.float64)
     V = np.asarray(V, dtype=np.float64)
     S = (Q @ K.T) * sm_scale
-    n = S.shape[0]
+    n, nk = S.shape
     if causal:
-        S = np.where(np.arange(S.shape[1])[None, :] > np.arange(n)[:, None], -np.inf, S)
+        # the last query is aligned with the last key (the square mask when the lengths agree)
+        S = np.where(np.arange(nk)[None, :] > (np.arange(n) + (nk - n))[:, None], -np.inf, S)
     m = S.max(axis=1, keepdims=True)
     E = np.exp(S - m)
     l = E.sum(axis=1, keepdims=True)

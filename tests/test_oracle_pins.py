@@ -529,6 +529,74 @@ def test_sampling_pin_catches_a_wrong_column_offset(monkeypatch):
     assert np.abs(bad[1][krows] - full[1][krows]).max() > 1e-3 * np.abs(full[1]).max()
 
 
+# ------------------------------------------- non-square attention (N_q != N_kv)
+@pytest.mark.parametrize("Nq,Nk,causal", [(64, 256, True), (100, 228, True), (192, 64, False), (37, 300, False), (1, 200, False)])
+def test_non_square_close_to_exact_attention(Nq, Nk, causal):
+    """Q of N_q rows against K, V of N_kv rows (cross attention, chunked prefill, decoding): the oracle
+    still approximates exact attention; under the mask the last query sees every key."""
+    d = 64
+    rng = np.random.default_rng(80 + Nq + Nk)
+    Q, dO = (_bf(rng.standard_normal((Nq, d))) for _ in range(2))
+    K, V = (_bf(rng.standard_normal((Nk, d))) for _ in range(2))
+    sc = 1 / math.sqrt(d)
+    O, L = oracle.forward_head(Q, K, V, causal=causal)
+    dQ, dK, dV = oracle.backward_head(Q, K, V, O, dO, L, causal=causal)
+    assert O.shape == dQ.shape == (Nq, d) and L.shape == (Nq,) and dK.shape == dV.shape == (Nk, d)
+    ref = fpa_backward(Q, K, V, dO, causal, sc)
+    for name, got in (("O", O), ("dQ", dQ), ("dK", dK), ("dV", dV)):
+        assert cos_sim(got, ref[name]) > 0.997, name
+        assert rel_l2(got, ref[name]) < 0.08, name
+    shift = sc * (Q.astype(np.float64) @ oracle.key_mean(K).astype(np.float64))
+    assert np.abs(L + shift - ref["L"]).max() < 0.05
+
+
+@pytest.mark.parametrize("q_smooth", [False, True])
+def test_non_square_reduces_to_the_square_oracle(q_smooth):
+    """Rows of the attention matrix are independent given K and V, so a block-aligned subset of the
+    queries must give exactly the rows the square problem gives: the first rows without the mask, the
+    last rows with it (last query on last key).  The backward agrees as well when the upstream gradient
+    of the other rows is zero (their psi(dO) blocks are all-zero blocks, which contribute nothing)."""
+    N, d = 320, 32
+    Q, K, V, dO = _rand(N, d, seed=85, qk_norm=True)
+    if q_smooth:
+        Q = _bf(Q + np.linspace(-1, 1, d)[None, :])
+    for causal, rows in ((False, slice(0, 128)), (False, slice(0, 64)), (True, slice(192, 320)), (True, slice(256, 320))):
+        kw = dict(causal=causal, q_smooth=q_smooth)
+        Ob, L, Oraw, Lraw = oracle.forward_head(Q, K, V, return_raw=True, **kw)
+        Os, Ls, Osr, Lsr = oracle.forward_head(Q[rows], K, V, return_raw=True, **kw)
+        assert np.array_equal(Osr, Oraw[rows]) and np.array_equal(Lsr, Lraw[rows])
+        dOz = np.zeros_like(dO)
+        dOz[rows] = dO[rows]
+        full = oracle.backward_head(Q, K, V, Ob, dOz, L, return_raw=True, **kw)
+        part = oracle.backward_head(Q[rows], K, V, Ob[rows], dO[rows], L[rows], return_raw=True, **kw)
+        assert np.array_equal(part[0], full[0][rows])
+        assert np.allclose(part[1], full[1], rtol=1e-12, atol=1e-15) and np.allclose(part[2], full[2], rtol=1e-12, atol=1e-15)
+        assert not np.delete(full[0], np.arange(N)[rows], axis=0).any()
+
+
+@pytest.mark.parametrize("causal", [True, False])
+def test_non_square_zero_queries_closed_form_and_tiled_formulation(causal):
+    Nq, Nk, d = 128, 320, 16
+    rng = np.random.default_rng(86)
+    K, V = (_bf(rng.standard_normal((Nk, d))) for _ in range(2))
+    Z = np.zeros((Nq, d), dtype=np.float32)
+    _, _, Oraw, Lraw = oracle.forward_head(Z, K, V, causal=causal, return_raw=True)
+    Vh, sV = oracle.quantize_blocks(V)
+    Vdq = Vh.astype(np.float64) * np.repeat(sV.astype(np.float64), 64)[:, None]
+    for i in (0, 63, 64, 127):
+        nvis = i + 1 + (Nk - Nq) if causal else Nk
+        assert math.isclose(Lraw[i], math.log(nvis), abs_tol=1e-12)
+        assert np.allclose(Oraw[i], Vdq[:nvis].mean(0), atol=1e-12)
+    Q, dO = (_bf(rng.standard_normal((Nq, d))) for _ in range(2))
+    Ob, L, Oraw, Lraw = oracle.forward_head(Q, K, V, causal=causal, return_raw=True)
+    O2, L2 = tiled_form.forward_tiled(Q, K, V, causal=causal)
+    assert np.abs(Lraw - L2).max() < 1e-12 and rel_l2(O2, Oraw) < 2e-4
+    g = oracle.backward_head(Q, K, V, Ob, dO, L, causal=causal, return_raw=True)
+    g2 = tiled_form.backward_tiled(Q, K, V, Ob, dO, L, causal=causal)
+    for a, b in zip(g, g2):
+        assert np.allclose(a, b, rtol=1e-10, atol=1e-12)
+
+
 # ------------------------------------------- other numerics block sizes (Algorithm 1 leaves B_q, B_kv free)
 @pytest.mark.parametrize("bq,bkv", [(128, 64), (128, 128)])
 def test_larger_blocks_quantiser_and_prepass(bq, bkv):
