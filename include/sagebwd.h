@@ -13,8 +13,10 @@
  *     workspace of sagebwd_workspace_bytes() bytes (256-byte aligned).  Apart from the
  *     benchmark hooks at the end of this file the library keeps no state between calls:
  *     everything that shapes a call, the scratch budget included, is in sagebwd_params.
- *   - Tensors are dense and contiguous: Q, K, V, O, dO, dQ, dK, dV are bf16
- *     [B, H, N, d] (or [B, N, H, d], see sagebwd_params.layout); LSE is float32 [B, H, N].
+ *   - Tensors are dense and contiguous: Q, O, dO, dQ are bf16 [B, H, N, d], K, V, dK, dV are bf16
+ *     [B, H, Nkv, d] (or [B, N, H, d] / [B, Nkv, H, d], see sagebwd_params.layout); LSE is float32
+ *     [B, H, N].  Nkv = N unless sagebwd_params.Nkv says otherwise (cross attention, chunked prefill,
+ *     decoding against a cache: the paper states the method for one length, nothing in it couples the two).
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Work
  *     is enqueued on it and the call returns without synchronising.  The entry points
  *     only launch kernels (no allocation, no memset, no host synchronisation), so
@@ -74,14 +76,17 @@ typedef enum sagebwd_status {
 #define SAGEBWD_FLAG_SHARE_QUANTIZED 1
 
 typedef struct sagebwd_params {
-  int32_t B, H, N, d;
-  int32_t causal;  /* 0 / 1: key index <= query index (square self-attention) */
+  int32_t B, H, N, d; /* N = rows of Q, O, dO, dQ (and of K, V, dK, dV unless Nkv is set) */
+  int32_t causal;  /* 0 / 1: key index <= query index (+ Nkv - N when the lengths differ) */
   int32_t smooth;  /* OR of SAGEBWD_SMOOTH_* ; the paper's default is SAGEBWD_SMOOTH_K */
   float sm_scale;  /* logit scale; 0 selects 1/sqrt(d) (paper Sec. 4: S = Q K^T / sqrt(d)) */
   int32_t layout;  /* SAGEBWD_LAYOUT_*: how the caller holds Q, K, V, O, dO, dQ, dK, dV */
   int32_t bq, bkv; /* numerics block sizes B_q, B_kv (Algorithm 1, input line); 0 selects 64 */
   int32_t flags;   /* OR of SAGEBWD_FLAG_* */
-  int32_t reserved;          /* must be 0 */
+  int32_t Nkv;     /* rows of K, V, dK, dV; 0 selects N (square attention).  With causal = 1 the last
+                      query is aligned with the last key (query i sees keys k <= i + Nkv - N), which needs
+                      Nkv >= N and Nkv - N a multiple of 64 (else SAGEBWD_UNSUPPORTED_SHAPE); a decoding
+                      step whose queries see the whole cache is the call with causal = 0 */
   uint64_t scratch_budget;   /* upper bound, in bytes, on the INT8 dS scratch that sagebwd_bwd holds at
                                 once; 0 selects 8 GiB.  The backward needs Np*(Np+192) bytes per head and
                                 processes the heads in groups that fit the bound (at least one head per
@@ -132,7 +137,8 @@ int sagebwd_quantize(const void* Q, const void* K, const void* V, const void* dO
 /*
  * Copy one quantised tensor out of a workspace filled by sagebwd_quantize (or by
  * sagebwd_fwd / sagebwd_bwd, which run the same pre-pass) into row-major form:
- *   q_out      int8    [B, H, Np, d]     (Np = N rounded up to a multiple of 64; rows N..Np-1 are zero)
+ *   q_out      int8    [B, H, Np, d]     (Np = the tensor's row count, N or Nkv, rounded up to a multiple
+ *                                         of 64; the rows past it are zero)
  *   scale_out  float32 [B, H, Np/64]
  * Either output may be NULL.  SAGEBWD_TENSOR_DO requires that dO was given.
  * This is a test / inspection hook for the bit-exact part of the contract.
@@ -153,9 +159,9 @@ int sagebwd_export_stats(const sagebwd_params* params, const void* workspace,
 /*
  * Copy the quantised score gradient psi(dS) (Algorithm 2, the dS line and its quantisation) that the
  * last sagebwd_bwd on this workspace left in its scratch, for one head = b * H + h:
- *   ds_out     int8    [Np, Np] row-major (query, key); tiles above the causal diagonal are zero
- *   scale_out  float32 [Np/64, Np/64], one scale per 64x64 tile (dS ~ scale * code)
- * Np = N rounded up to a multiple of 64.  Either output may be NULL.  Only defined when the backward
+ *   ds_out     int8    [Np, Nkp] row-major (query, key); tiles above the causal diagonal are zero
+ *   scale_out  float32 [Np/64, Nkp/64], one scale per 64x64 tile (dS ~ scale * code)
+ * Np, Nkp = N, Nkv rounded up to a multiple of 64.  Either output may be NULL.  Only defined when the backward
  * ran all heads in one group (B*H*Np*(Np+192) bytes within params->scratch_budget), otherwise
  * SAGEBWD_UNSUPPORTED_SHAPE.  A test / inspection hook: the in-loop quantisers depend on the
  * hardware's exp2, so their codes are compared with a tolerance of one step, not bit for bit.

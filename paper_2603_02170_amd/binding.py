@@ -33,7 +33,7 @@ class _CParams(ctypes.Structure):
     _fields_ = [("B", ctypes.c_int32), ("H", ctypes.c_int32), ("N", ctypes.c_int32), ("d", ctypes.c_int32),
                 ("causal", ctypes.c_int32), ("smooth", ctypes.c_int32), ("sm_scale", ctypes.c_float),
                 ("layout", ctypes.c_int32), ("bq", ctypes.c_int32), ("bkv", ctypes.c_int32),
-                ("flags", ctypes.c_int32), ("reserved", ctypes.c_int32), ("scratch_budget", ctypes.c_uint64)]
+                ("flags", ctypes.c_int32), ("Nkv", ctypes.c_int32), ("scratch_budget", ctypes.c_uint64)]
 
 
 @dataclass
@@ -51,17 +51,23 @@ class SageParams:
     scratch_budget: int = 0     # bytes of dS scratch the backward holds at once; 0 selects 8 GiB
     bq: int = 0                 # numerics block sizes; 0 selects 64
     bkv: int = 0
+    Nkv: int = 0                # rows of K, V, dK, dV; 0 selects N
 
     def c(self) -> _CParams:
         return _CParams(self.B, self.H, self.N, self.d, int(self.causal),
                         (SMOOTH_K if self.k_smooth else 0) | (SMOOTH_Q if self.q_smooth else 0),
                         float(self.sm_scale), LAYOUT_BNHD if self.token_major else LAYOUT_BHND,
-                        int(self.bq), int(self.bkv), FLAG_SHARE_QUANTIZED if self.share_quantized else 0, 0,
-                        int(self.scratch_budget))
+                        int(self.bq), int(self.bkv), FLAG_SHARE_QUANTIZED if self.share_quantized else 0,
+                        int(self.Nkv), int(self.scratch_budget))
 
-    def tensor_shape(self):
-        """Shape of Q, K, V, O, dO, dQ, dK, dV as the caller holds them."""
-        return (self.B, self.N, self.H, self.d) if self.token_major else (self.B, self.H, self.N, self.d)
+    @property
+    def kv_len(self) -> int:
+        return self.Nkv or self.N
+
+    def tensor_shape(self, kv: bool = False):
+        """Shape of Q, O, dO, dQ (or, with kv, of K, V, dK, dV) as the caller holds them."""
+        n = self.kv_len if kv else self.N
+        return (self.B, n, self.H, self.d) if self.token_major else (self.B, self.H, n, self.d)
 
 
 def lib_path() -> str:
@@ -141,9 +147,10 @@ def alloc_workspace(p: SageParams, device="cuda", forward_only: bool = False):
 
 
 def sagebwd_quantize(Q, K, V, p: SageParams, workspace, dO=None, O=None):
-    shp = p.tensor_shape()
-    for t, n in ((Q, "Q"), (K, "K"), (V, "V")):
-        _expect(t, torch.bfloat16, shp, n)
+    shp, kshp = p.tensor_shape(), p.tensor_shape(kv=True)
+    _expect(Q, torch.bfloat16, shp, "Q")
+    for t, n in ((K, "K"), (V, "V")):
+        _expect(t, torch.bfloat16, kshp, n)
     for t, n in ((dO, "dO"), (O, "O")):
         if t is not None:
             _expect(t, torch.bfloat16, shp, n)
@@ -160,7 +167,7 @@ def padded_rows(N: int) -> int:
 def sagebwd_export_quantized(p: SageParams, workspace, which: int):
     """Row-major int8 [B,H,Np,d] codes and float32 [B,H,Np/64] scales of one quantised tensor
     (Np = N rounded up to a multiple of 64; rows N..Np-1 are zero)."""
-    Np = padded_rows(p.N)
+    Np = padded_rows(p.kv_len if which in (TENSOR_K, TENSOR_V) else p.N)
     q = torch.empty((p.B, p.H, Np, p.d), dtype=torch.int8, device=workspace.device)
     s = torch.empty((p.B, p.H, Np // 64), dtype=torch.float32, device=workspace.device)
     cp = p.c()
@@ -184,9 +191,9 @@ def sagebwd_export_stats(p: SageParams, workspace, want_delta=False):
 def sagebwd_export_ds(p: SageParams, workspace, head: int):
     """psi(dS) of one head after a backward on this workspace: int8 [Np, Np] codes and float32
     [Np/64, Np/64] tile scales."""
-    Np = padded_rows(p.N)
-    ds = torch.empty((Np, Np), dtype=torch.int8, device=workspace.device)
-    sc = torch.empty((Np // 64, Np // 64), dtype=torch.float32, device=workspace.device)
+    Np, Nkp = padded_rows(p.N), padded_rows(p.kv_len)
+    ds = torch.empty((Np, Nkp), dtype=torch.int8, device=workspace.device)
+    sc = torch.empty((Np // 64, Nkp // 64), dtype=torch.float32, device=workspace.device)
     cp = p.c()
     _check(load_library().sagebwd_export_ds(ctypes.byref(cp), _ptr(workspace), workspace.numel(), int(head),
                                             _ptr(ds), _ptr(sc), _stream()), "sagebwd_export_ds")
@@ -195,10 +202,11 @@ def sagebwd_export_ds(p: SageParams, workspace, head: int):
 
 def sagebwd_fwd(Q, K, V, p: SageParams, workspace=None, O=None, LSE=None):
     """O, LSE = INT8 attention forward.  Allocates outputs / workspace when not given."""
-    shp = p.tensor_shape()
+    shp, kshp = p.tensor_shape(), p.tensor_shape(kv=True)
     lshp = (p.B, p.H, p.N)
-    for t, n in ((Q, "Q"), (K, "K"), (V, "V")):
-        _expect(t, torch.bfloat16, shp, n)
+    _expect(Q, torch.bfloat16, shp, "Q")
+    for t, n in ((K, "K"), (V, "V")):
+        _expect(t, torch.bfloat16, kshp, n)
     if workspace is None:
         workspace = alloc_workspace(p, Q.device, forward_only=True)
     if O is None:
@@ -219,9 +227,11 @@ STATIC_SCRATCH_BYTES = 32 << 20
 def sagebwd_fwd_static(Q, K, V, p: SageParams, O, LSE):
     """The forward on the library's built-in scratch: the call allocates nothing, so the caller
     passes the outputs too."""
-    shp = p.tensor_shape()
-    for t, n in ((Q, "Q"), (K, "K"), (V, "V"), (O, "O")):
+    shp, kshp = p.tensor_shape(), p.tensor_shape(kv=True)
+    for t, n in ((Q, "Q"), (O, "O")):
         _expect(t, torch.bfloat16, shp, n)
+    for t, n in ((K, "K"), (V, "V")):
+        _expect(t, torch.bfloat16, kshp, n)
     _expect(LSE, torch.float32, (p.B, p.H, p.N), "LSE")
     cp = p.c()
     _check(load_library().sagebwd_fwd_static(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(LSE), ctypes.byref(cp),
@@ -231,17 +241,19 @@ def sagebwd_fwd_static(Q, K, V, p: SageParams, O, LSE):
 
 def sagebwd_bwd(Q, K, V, O, dO, LSE, p: SageParams, workspace=None, dQ=None, dK=None, dV=None):
     """dQ, dK, dV = INT8 attention backward."""
-    shp = p.tensor_shape()
-    for t, n in ((Q, "Q"), (K, "K"), (V, "V"), (O, "O"), (dO, "dO")):
+    shp, kshp = p.tensor_shape(), p.tensor_shape(kv=True)
+    for t, n in ((Q, "Q"), (O, "O"), (dO, "dO")):
         _expect(t, torch.bfloat16, shp, n)
+    for t, n in ((K, "K"), (V, "V")):
+        _expect(t, torch.bfloat16, kshp, n)
     _expect(LSE, torch.float32, (p.B, p.H, p.N), "LSE")
     if workspace is None:
         workspace = alloc_workspace(p, Q.device)
     outs = []
-    for t, n in ((dQ, "dQ"), (dK, "dK"), (dV, "dV")):
+    for t, n, sh in ((dQ, "dQ", shp), (dK, "dK", kshp), (dV, "dV", kshp)):
         if t is None:
-            t = torch.empty(shp, dtype=torch.bfloat16, device=Q.device)
-        _expect(t, torch.bfloat16, shp, n)
+            t = torch.empty(sh, dtype=torch.bfloat16, device=Q.device)
+        _expect(t, torch.bfloat16, sh, n)
         outs.append(t)
     cp = p.c()
     _check(load_library().sagebwd_bwd(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(dO), _ptr(LSE), _ptr(outs[0]),

@@ -40,7 +40,8 @@ struct BwdArgs {
   const int8_t* dOT;   // TF layout  (dV, A operand)
   const unsigned short* V;    // bf16, rows addressed through `cv` (dense [BH, N, D] or the caller's token-major tensors)
   const unsigned short* dO;   // bf16, likewise
-  RowView cv;                 // also addresses dK, dV
+  RowView cv;                 // rows of the K-like tensors V, dK, dV
+  RowView cvq;                // rows of the Q-like tensor dO
   const float* sQ;
   const float* sK;
   const float* sdO;
@@ -54,8 +55,11 @@ struct BwdArgs {
   int bh0;             // first head of this launch (the scratch above is indexed from it)
   unsigned short* dK;  // bf16 [BH, N, D]
   unsigned short* dV;
-  int BH, N;           // N = rows of the workspace tensors (a multiple of 64)
-  int nvalid;          // keys >= nvalid do not exist (nvalid = N unless the caller's N is not a multiple of 64)
+  int BH, N;           // N = rows of the K-like workspace tensors (N_kv rounded up to a multiple of 64)
+  int nvalid;          // keys >= nvalid do not exist (nvalid = N unless N_kv is not a multiple of 64)
+  int Nq;              // rows of the Q-like workspace tensors (N_q rounded up to a multiple of 64)
+  int nq_valid;        // query rows >= nq_valid do not exist
+  int shift_blocks;    // causal: Q block i sees KV blocks j <= i + shift_blocks ((N_kv - N_q) / 64), diagonal at equality
   int head_set;        // heads per XCD whose work items are interleaved (see work_item)
   float sm_scale;
   float scale_log2e;
@@ -153,7 +157,9 @@ __global__ void __launch_bounds__(512, 1) sage_bwd_kernel(BwdArgs args) {
 
   const int gidx = blockIdx.x;
   const int N = args.N;
-  const int nblk = N / kBlock;
+  const int nblk = N / kBlock;        // KV blocks
+  const int nqblk = args.Nq / kBlock; // Q blocks
+  const int sb = CAUSAL ? args.shift_blocks : 0;
   const int npair = (nblk + 1) / 2;
   const WorkItem wi = work_item(gidx, npair, args.head_set);
   const int hl = wi.head;             // head within this launch
@@ -174,9 +180,12 @@ __global__ void __launch_bounds__(512, 1) sage_bwd_kernel(BwdArgs args) {
   const int jc = gvalid ? j : nblk - 1;                    // clamped: an idle group still loads in bounds
   const int kvalid = min(64, args.nvalid - 64 * jc);       // key columns of this group's KV block that exist
 
-  const size_t head = (size_t)bh * N * D;                  // in the dense workspace tensors
-  const size_t chead = args.cv.row(bh, 0);                 // in V, dO, dK, dV
+  const size_t head = (size_t)bh * N * D;                  // in the dense K-like workspace tensors
+  const size_t qhead = (size_t)bh * args.Nq * D;           // in the Q-like ones
+  const size_t chead = args.cv.row(bh, 0);                 // in V, dK, dV
   const size_t rs = args.cv.row_stride;
+  const size_t cqhead = args.cvq.row(bh, 0);               // in dO
+  const size_t rsq = args.cvq.row_stride;
   const float sKj = args.sK[(size_t)bh * nblk + jc];
 
   // ---- operands that stay in registers for the whole loop ----
@@ -211,8 +220,8 @@ __global__ void __launch_bounds__(512, 1) sage_bwd_kernel(BwdArgs args) {
       if constexpr (QSMOOTH) dkbias[t][r] = 0.f;
     }
 
-  const int i_first = CAUSAL ? 2 * jp : 0;
-  const int T = nblk - i_first;                 // tile rows of this workgroup; tile t is Q block nblk-1-t
+  const int i_first = CAUSAL ? max(2 * jp - sb, 0) : 0;
+  const int T = nqblk - i_first;                // tile rows of this workgroup; tile t is Q block nqblk-1-t
   // B operand of the transposing MFMA of phase Q: a quantised quadrant, read as an A operand, has
   // contraction index k = 16h + 4a + b for the query 8a + 4h + b; column n of the permutation
   // matrix picks the k that stands for query n.  Lane (n, hh) holds k = 16hh + t in byte t.
@@ -234,7 +243,7 @@ __global__ void __launch_bounds__(512, 1) sage_bwd_kernel(BwdArgs args) {
   // that does: their P is zero because the pre-pass gave them -L = -inf)
   auto load_A = [&](int i, BwdStageA<D>& st, auto last_tag) {
     constexpr bool LAST = decltype(last_tag)::value;
-    const size_t toff = head + (size_t)i * TILE;
+    const size_t toff = qhead + (size_t)i * TILE;
     const unsigned lane16 = lane * 16;
 #pragma unroll
     for (int k = 0; k < (3 * NF + 7) / 8; k++) {
@@ -250,28 +259,28 @@ __global__ void __launch_bounds__(512, 1) sage_bwd_kernel(BwdArgs args) {
         const int rb = f / KB, sst = f % KB;
         const unsigned orig = lane ^ (sst & 7);
         if constexpr (LAST) {
-          const int row = min(64 * i + 32 * rb + (int)(orig & 31), args.nvalid - 1);
-          async_copy_16(args.dO + chead + (size_t)row * rs + 16 * sst + 8 * (orig >> 5), st.dof + f * 1024);
+          const int row = min(64 * i + 32 * rb + (int)(orig & 31), args.nq_valid - 1);
+          async_copy_16(args.dO + cqhead + (size_t)row * rsq + 16 * sst + 8 * (orig >> 5), st.dof + f * 1024);
         } else {
-          const size_t loff = (orig & 31) * (2 * rs) + (orig >> 5) * 16;           // bytes: row, channel half
-          const char* base = (const char*)(args.dO + chead + (size_t)(64 * i + 32 * rb) * rs + 16 * sst);
+          const size_t loff = (orig & 31) * (2 * rsq) + (orig >> 5) * 16;          // bytes: row, channel half
+          const char* base = (const char*)(args.dO + cqhead + (size_t)(64 * i + 32 * rb) * rsq + 16 * sst);
           async_copy_16(base + loff, st.dof + f * 1024);
         }
       }
     }
     // -L*log2e (even waves) or delta (odd waves), and s_Q[i] broadcast to 64 entries
-    const float* vsrc = ((wave & 1) ? args.delta : args.nL2) + (size_t)bh * N + 64 * i;
+    const float* vsrc = ((wave & 1) ? args.delta : args.nL2) + (size_t)bh * args.Nq + 64 * i;
     async_copy_4((const char*)vsrc + lane * 4, (wave & 1) ? st.dl : st.nl2);
-    async_copy_4(args.sQ + (size_t)bh * nblk + i, st.sc);
+    async_copy_4(args.sQ + (size_t)bh * nqblk + i, st.sc);
     if constexpr (QSMOOTH) {
-      const char* brow = (const char*)(args.bias + ((size_t)bh * nblk + i) * N + 128 * jp);
+      const char* brow = (const char*)(args.bias + ((size_t)bh * nqblk + i) * N + 128 * jp);
       if (wave == 5) async_copy_4(brow + lane * 4, st.bias);
       if (wave == 6 && 2 * jp + 1 < nblk) async_copy_4(brow + 256 + lane * 4, st.bias + 64);
     }
   };
   // ... and of its phase-B operands.
   auto load_B = [&](int i, BwdStageB<D>& st) {
-    const size_t toff = head + (size_t)i * TILE;
+    const size_t toff = qhead + (size_t)i * TILE;
     const unsigned lane16 = lane * 16;
 #pragma unroll
     for (int k = 0; k < (2 * NF + 7) / 8; k++) {
@@ -282,15 +291,15 @@ __global__ void __launch_bounds__(512, 1) sage_bwd_kernel(BwdArgs args) {
       else if (in_range) async_copy_16(args.dOT + toff + (o - NF) * 1024 + lane16, st.dot + (o - NF) * 1024);
     }
     // s_Q[i] (even lanes) and s_dO[i] (odd lanes)
-    async_copy_4(((lane & 1) ? args.sdO : args.sQ) + (size_t)bh * nblk + i, st.sc);
+    async_copy_4(((lane & 1) ? args.sdO : args.sQ) + (size_t)bh * nqblk + i, st.sc);
     if constexpr (QSMOOTH) {
-      const char* mq = (const char*)(args.muQ + ((size_t)bh * nblk + i) * D);
+      const char* mq = (const char*)(args.muQ + ((size_t)bh * nqblk + i) * D);
       if (wave == 3) async_copy_4(mq + lane * 4, st.muq);
       if (D == 128 && wave == 4) async_copy_4(mq + 256 + lane * 4, st.muq + 64);
     }
   };
 
-  load_A(nblk - 1, stA[0], std::true_type{});
+  load_A(nqblk - 1, stA[0], std::true_type{});
   barrier_all_memory();
 
   float p[16], ds[16];           // P and dS of the tile between its phases A and Q
@@ -301,12 +310,12 @@ __global__ void __launch_bounds__(512, 1) sage_bwd_kernel(BwdArgs args) {
   auto interval = [&](const int t, auto steady_tag) __attribute__((always_inline)) {
     constexpr bool STEADY = decltype(steady_tag)::value;
     const float sP_b = sP_q, sS_b = sS_q;      // scales of tile t - 2 (its phase Q ran in the last interval)
-    const int ib = nblk - 1 - (t - 2);         // Q blocks of the three tiles in flight
-    const int iq = nblk - 1 - (t - 1);
-    const int ia = nblk - 1 - t;
-    const bool act_b = STEADY || (t >= 2 && gvalid && (!CAUSAL || ib >= j));
-    const bool act_q = STEADY || (t >= 1 && t - 1 < T && gvalid && (!CAUSAL || iq >= j));
-    const bool act_a = STEADY || (t < T && gvalid && (!CAUSAL || ia >= j));
+    const int ib = nqblk - 1 - (t - 2);        // Q blocks of the three tiles in flight
+    const int iq = nqblk - 1 - (t - 1);
+    const int ia = nqblk - 1 - t;
+    const bool act_b = STEADY || (t >= 2 && gvalid && (!CAUSAL || ib + sb >= j));
+    const bool act_q = STEADY || (t >= 1 && t - 1 < T && gvalid && (!CAUSAL || iq + sb >= j));
+    const bool act_a = STEADY || (t < T && gvalid && (!CAUSAL || ia + sb >= j));
 
     // operands of the coming intervals; the copies are issued in two batches so that the eight
     // waves do not queue up behind each other at the memory pipeline
@@ -365,8 +374,8 @@ __global__ void __launch_bounds__(512, 1) sage_bwd_kernel(BwdArgs args) {
           const unsigned hi = __builtin_amdgcn_perm((unsigned)tr[4 * aa + 3], (unsigned)tr[4 * aa + 2], 0x04000c0cu);
           o[aa] = (int)(lo | hi);
         }
-        const size_t tile = ((size_t)hl * nblk + iq) * nblk + j;
-        const size_t slot = ((size_t)hl * nblk + iq) * args.ds_pitch + j;
+        const size_t tile = ((size_t)hl * nqblk + iq) * nblk + j;
+        const size_t slot = ((size_t)hl * nqblk + iq) * args.ds_pitch + j;
         *(v4i*)(args.dSq + slot * 4096 + ((qb * 2 + kb) * 64 + lane) * 16) = o;
         args.sdS[tile] = sS_q;   // the same value from every lane: no branch
       }
@@ -422,8 +431,8 @@ __global__ void __launch_bounds__(512, 1) sage_bwd_kernel(BwdArgs args) {
       if constexpr (QSMOOTH) bias_l = st.bias[64 * grp + 32 * kb + ll];
       const float* nl2 = st.nl2 + 32 * qb + 4 * h;
       float pm, dm, cs;
-      if (!STEADY && ((CAUSAL && ia == j) || kvalid < 64))
-        bwd_quadrant<true, QSMOOTH>(sacc, dp, nl2, c, bias_l, 32 * qb + 4 * h, 32 * kb + ll, CAUSAL && ia == j, kvalid,
+      if (!STEADY && ((CAUSAL && ia + sb == j) || kvalid < 64))
+        bwd_quadrant<true, QSMOOTH>(sacc, dp, nl2, c, bias_l, 32 * qb + 4 * h, 32 * kb + ll, CAUSAL && ia + sb == j, kvalid,
                                     p, ds, pm, dm, cs);
       else
         bwd_quadrant<false, QSMOOTH>(sacc, dp, nl2, c, bias_l, 0, 0, false, 64, p, ds, pm, dm, cs);
@@ -486,7 +495,7 @@ __global__ void __launch_bounds__(512, 1) sage_bwd_kernel(BwdArgs args) {
   };
   // steady intervals: t >= 2 (all three tiles exist), tile t above the diagonal and not the last row
   // (a KV block with keys that do not exist masks them in every tile: no branch-free intervals for its group)
-  const int t_steady_end = (!gvalid || kvalid < 64) ? 0 : (CAUSAL ? nblk - 1 - j : T - 1);
+  const int t_steady_end = (!gvalid || kvalid < 64) ? 0 : (CAUSAL ? min(nqblk - 1 + sb - j, T - 1) : T - 1);
   int t = 0;
   for (; t < 2 && t < T + 2; t++) interval(t, std::false_type{});
   for (; t < t_steady_end; t++) interval(t, std::true_type{});
@@ -527,10 +536,12 @@ struct DqArgs {
   const float* sdS;
   const int8_t* KT;
   const float* sK;
-  unsigned short* dQ;   // bf16, rows addressed through `cv` (dense [BH, N, D] or the caller's token-major tensor)
+  unsigned short* dQ;   // bf16, rows addressed through `cv` (dense [BH, N_q, D] or the caller's token-major tensor)
   RowView cv;
-  int BH, N, bh0;
-  int nvalid;           // query rows >= nvalid do not exist (N rounded down from a multiple of 64)
+  int BH, N, bh0;       // N = rows of the K-like workspace tensors (a multiple of 64)
+  int Nq;               // rows of the Q-like ones
+  int nvalid;           // query rows >= nvalid do not exist
+  int shift_blocks;     // causal: Q block i sees KV blocks j <= i + shift_blocks
   int head_set;         // heads per XCD whose work items are interleaved (see work_item)
   float sm_scale;
 };
@@ -564,8 +575,10 @@ __global__ void __launch_bounds__(256, 3) sage_bwd_dq_kernel(DqArgs args) {
 
   const int g = blockIdx.x;
   const int N = args.N;
-  const int nblk = N / kBlock;
-  const int npair = (nblk + 1) / 2;
+  const int nblk = N / kBlock;                         // KV blocks
+  const int nqblk = args.Nq / kBlock;                  // Q blocks
+  const int sb = CAUSAL ? args.shift_blocks : 0;
+  const int npair = (nqblk + 1) / 2;
   const WorkItem wi = work_item(g, npair, args.head_set);
   const int hl = wi.head;
   if (hl >= args.BH) return;
@@ -576,18 +589,18 @@ __global__ void __launch_bounds__(256, 3) sage_bwd_dq_kernel(DqArgs args) {
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int ll = lane & 31, h = lane >> 5;
   const int iq = wave >> 1, qb = wave & 1;             // Q block of the pair, 32-row half of it
-  const bool valid = i0 + iq < nblk;
+  const bool valid = i0 + iq < nqblk;
   const int i = valid ? i0 + iq : i0;                  // clamped: the loads stay in bounds
-  const int i1 = i0 + 1 < nblk ? i0 + 1 : i0;
+  const int i1 = i0 + 1 < nqblk ? i0 + 1 : i0;
   const size_t head = (size_t)bh * N * D;
-  const int n_j = CAUSAL ? (i0 + 2 < nblk ? i0 + 2 : nblk) : nblk;   // stages of the workgroup
-  const int j_last = CAUSAL ? i : nblk - 1;            // last tile of this wave's Q block that was written
+  const int n_j = CAUSAL ? min(i0 + 2 + sb, nblk) : nblk;            // stages of the workgroup
+  const int j_last = CAUSAL ? i + sb : nblk - 1;       // last tile of this wave's Q block that was written
 
   // this wave's fragments of tile (i, j): (row half qb, key step 0 / 1) at j * DSB, + 1024
-  const int8_t* dsw = args.dSq + ((size_t)hl * nblk + i) * args.ds_pitch * DSB + qb * 2048 + lane * 16;
+  const int8_t* dsw = args.dSq + ((size_t)hl * nqblk + i) * args.ds_pitch * DSB + qb * 2048 + lane * 16;
   const int8_t* kth = args.KT + head + wave * 1024 + lane * 16;
   // per stage lanes 0, 1, 2 fetch s_dS of Q block 0, s_dS of Q block 1, s_K
-  const size_t sc_off = lane == 0 ? ((size_t)hl * nblk + i0) * nblk : ((size_t)hl * nblk + i1) * nblk;
+  const size_t sc_off = lane == 0 ? ((size_t)hl * nqblk + i0) * nblk : ((size_t)hl * nqblk + i1) * nblk;
   const float* sc_src = lane < 2 ? args.sdS + sc_off : args.sK + (size_t)bh * nblk;
 
   // Stage indices past the end are clamped: the loads then re-read the last stage (into registers or a
@@ -636,7 +649,7 @@ __global__ void __launch_bounds__(256, 3) sage_bwd_dq_kernel(DqArgs args) {
 #pragma unroll
     for (int s = 0; s < kStages; s++) {
       const int j = j0 + s;
-      if (j < n_j && valid && (!CAUSAL || j <= i)) {
+      if (j < n_j && valid && (!CAUSAL || j <= i + sb)) {
         const int8_t* kp = lds + sk * KSLOT;
         const float* sc = (const float*)(kp + TILE);
         const float w = sc[iq] * sc[2] * args.sm_scale;
@@ -679,7 +692,7 @@ __global__ void __launch_bounds__(256, 3) sage_bwd_dq_kernel(DqArgs args) {
   constexpr int CPR = D / 8;                                   // 16-byte pieces per row
   for (int c = tid; c < 2 * 64 * CPR; c += 256) {
     const int qblk = c / (64 * CPR), row = (c / CPR) % 64, pc = c % CPR;
-    if (i0 + qblk < nblk && 64 * (i0 + qblk) + row < args.nvalid)
+    if (i0 + qblk < nqblk && 64 * (i0 + qblk) + row < args.nvalid)
       *(v8us*)(args.dQ + args.cv.row(bh, 64 * (i0 + qblk) + row) + 8 * pc) = *(const v8us*)(stg + (qblk * 64 + row) * LDQ + 8 * pc);
   }
 }

@@ -55,9 +55,12 @@ struct FwdArgs {
   const float* bias;    // Q-smoothing: [BH, N/64, N] = sm_scale*log2e * mu_Qi . K_sm[k], else nullptr
   unsigned short* O;    // bf16, rows addressed through `oview` (dense [BH, N, D] or the caller's token-major tensor)
   RowView oview;
-  float* LSE;           // [BH, nvalid]
-  int BH, N;            // N = rows of the workspace tensors (a multiple of 64)
-  int nvalid;           // keys >= nvalid do not exist (nvalid = N unless the caller's N is not a multiple of 64)
+  float* LSE;           // [BH, nq_valid]
+  int BH, N;            // N = rows of the K-like workspace tensors (N_kv rounded up to a multiple of 64)
+  int nvalid;           // keys >= nvalid do not exist (nvalid = N unless N_kv is not a multiple of 64)
+  int Nq;               // rows of the Q-like workspace tensors (N_q rounded up to a multiple of 64)
+  int nq_valid;         // query rows >= nq_valid do not exist
+  int shift;            // causal: query i sees keys k <= i + shift (N_kv - N_q, a multiple of 64)
   int n_qtiles;         // workgroups per head
   int head_set;         // heads per XCD whose work items are interleaved (see work_item)
   float scale_log2e;    // sm_scale * log2(e)
@@ -297,10 +300,12 @@ __global__ void __launch_bounds__(64 * NW, (NW == 4 ? (D == 64 ? 3 : 2) : 1)) sa
   const int N = args.N;
   const int q0 = qt * QT + 32 * wave;        // first query of this wave
   const int q = q0 + ql;
-  // last visible key of this lane's query: under the causal mask the query itself (a query row
-  // that does not exist may see keys that do not exist: it is dropped anyway), else the last key
-  const int qlim = CAUSAL ? q : args.nvalid - 1;
-  const int nblk = N / kBlock;
+  // last visible key of this lane's query: under the causal mask the query's own position among the
+  // keys (a query row that does not exist may see keys that do not exist: it is dropped anyway), else
+  // the last key
+  const int qlim = CAUSAL ? q + args.shift : args.nvalid - 1;
+  const int nblk = N / kBlock;               // KV blocks
+  const int nqblk = args.Nq / kBlock;        // Q blocks
 
   const int8_t* KFh = args.KF + (size_t)bh * N * D;
   const int8_t* VTh = args.VT + (size_t)bh * N * D;
@@ -310,15 +315,15 @@ __global__ void __launch_bounds__(64 * NW, (NW == 4 ? (D == 64 ? 3 : 2) : 1)) sa
   // Q^ fragments stay in registers for the whole loop
   v4i qf[KS];
   {
-    const int8_t* p = args.QF + (size_t)bh * N * D + (size_t)(q0 / 32) * KS * 1024 + lane * 16;
+    const int8_t* p = args.QF + (size_t)bh * args.Nq * D + (size_t)(q0 / 32) * KS * 1024 + lane * 16;
 #pragma unroll
     for (int s = 0; s < KS; s++) qf[s] = *(const v4i*)(p + s * 1024);
   }
-  const float cq = args.sQ[(size_t)bh * nblk + q0 / kBlock] * args.scale_log2e;
-  const float* bias_row = QSMOOTH ? args.bias + ((size_t)bh * nblk + q0 / kBlock) * N : nullptr;
+  const float cq = args.sQ[(size_t)bh * nqblk + q0 / kBlock] * args.scale_log2e;
+  const float* bias_row = QSMOOTH ? args.bias + ((size_t)bh * nqblk + q0 / kBlock) * N : nullptr;
 
-  const int n_tiles = CAUSAL ? (qt * QT + QT) / kBlock : nblk;   // barrier count, uniform in the workgroup
-  const int last = CAUSAL ? (q0 + 31) / kBlock : nblk - 1;       // this wave's last tile (masked if causal)
+  const int n_tiles = CAUSAL ? (qt * QT + QT + args.shift) / kBlock : nblk;   // barrier count, uniform in the workgroup
+  const int last = CAUSAL ? (q0 + 31 + args.shift) / kBlock : nblk - 1;       // this wave's last tile (masked if causal)
 
   float oacc[KS][16];
 #pragma unroll
@@ -441,7 +446,7 @@ __global__ void __launch_bounds__(64 * NW, (NW == 4 ? (D == 64 ? 3 : 2) : 1)) sa
     // ---- epilogue: O = O / l, L = m + log(l) (l carries a factor 127) ----
     const float l_tot = half_swap_sum_f32(l_part);
     const float inv_l = 1.0f / l_tot;
-    if (q >= args.nvalid) return;                      // a query row that does not exist
+    if (q >= args.nq_valid) return;                    // a query row that does not exist
     unsigned short* Oh = args.O + args.oview.row(bh, q);
 #pragma unroll
     for (int cb = 0; cb < KS; cb++)
@@ -452,8 +457,8 @@ __global__ void __launch_bounds__(64 * NW, (NW == 4 ? (D == 64 ? 3 : 2) : 1)) sa
         for (int b = 0; b < 4; b++) o[b] = float_to_bf16_bits(oacc[cb][4 * aa + b] * inv_l);
         *(v4us*)(Oh + 32 * cb + 8 * aa + 4 * h) = o;
       }
-    // (LSE is [BH, nvalid]: the caller's own row count)
-    if (h == 0) args.LSE[(size_t)bh * args.nvalid + q] = (m_ref + __builtin_amdgcn_logf(l_tot) - kLog2_127) * kLn2;
+    // (LSE is [BH, nq_valid]: the caller's own row count)
+    if (h == 0) args.LSE[(size_t)bh * args.nq_valid + q] = (m_ref + __builtin_amdgcn_logf(l_tot) - kLog2_127) * kLn2;
   };
   // (each path runs to the end of the kernel, so that no register state has to be merged)
   if (__builtin_amdgcn_readfirstlane((int)use_sbias)) run(std::true_type{});

@@ -78,7 +78,9 @@ __global__ void fill_zero_f32_kernel(float* __restrict__ p, size_t n) {
 
 // ---- psi on one 64-row block ---------------------------------------------------
 struct QuantJob {
-  const unsigned short* src;   // bf16 [BH, N, D]
+  const unsigned short* src;   // bf16, rows addressed through `view`
+  RowView view;                // where the rows of src (and of O) lie in the caller's tensor
+  int N, Np;                   // rows of src that exist; rows of the workspace tensors (N rounded up to 64)
   int8_t* outF;                // F layout or nullptr
   int8_t* outTF;               // TF layout or nullptr
   float* scale;                // [BH, N/64]
@@ -96,11 +98,12 @@ struct QuantJobs {
   QuantJob job[4];
 };
 
-// N = rows of the caller's tensors, Np = N rounded up to a multiple of 64 = rows of every workspace
-// tensor.  Rows N .. Np-1 do not exist: they are read as zeros AFTER the smoothing (so they change
-// no absmax), enter no mean, get delta = 0 and -L*log2(e) = -inf (P = 0 in the backward).
+// Per job: N = rows of the caller's tensor, Np = N rounded up to a multiple of 64 = rows of its workspace
+// tensors (Q-like and K-like tensors may have different lengths).  Rows N .. Np-1 do not exist: they are
+// read as zeros AFTER the smoothing (so they change no absmax), enter no mean, get delta = 0 and
+// -L*log2(e) = -inf (P = 0 in the backward).  The grid's x extent covers the longest job.
 template <int D>
-__global__ void __launch_bounds__(256) prepass_quant_kernel(QuantJobs jobs, RowView view, int N, int Np) {
+__global__ void __launch_bounds__(256) prepass_quant_kernel(QuantJobs jobs) {
   constexpr int CPR = D / 16;            // 16-channel chunks per row
   constexpr int NCH = 64 * CPR / 256;    // chunks per thread (1 for D=64, 2 for D=128)
   constexpr int NTF = 4 * D / 256;       // TF chunks per thread
@@ -112,7 +115,10 @@ __global__ void __launch_bounds__(256) prepass_quant_kernel(QuantJobs jobs, RowV
   const QuantJob jb = jobs.job[blockIdx.z];
   const int t = threadIdx.x;
   const int blk = blockIdx.x, bh = blockIdx.y;
+  const int N = jb.N, Np = jb.Np;
+  const RowView view = jb.view;
   const int nblk = Np / kBlock;
+  if (blk >= nblk) return;
   const size_t tile_off = view.row(bh, (size_t)blk * kBlock);               // in the caller's tensors
   const int rows_here = min(kBlock, N - blk * kBlock);                      // rows of this block that exist
 
@@ -324,9 +330,10 @@ template <int D>
 __global__ void __launch_bounds__(256) qsmooth_bias_kernel(const unsigned short* __restrict__ K, RowView view,
                                                            const float* __restrict__ muK,
                                                            const float* __restrict__ muQ,
-                                                           float* __restrict__ bias, int N, int Np, int causal,
-                                                           float scale_log2e) {
-  // (N = rows of K as the caller holds it, Np = N rounded up to the block: keys that do not exist count as zero rows.)
+                                                           float* __restrict__ bias, int N, int Np, int nqblk,
+                                                           int causal_shift, float scale_log2e) {
+  // (N = rows of K as the caller holds it, Np = N rounded up to the block: keys that do not exist count as
+  // zero rows; nqblk = Q blocks; causal_shift < 0: no mask, else Q block I sees key blocks <= I + causal_shift.)
   // One workgroup per (key block, head): a [Q blocks] x [64 keys] x [D channels] FP32 product on
   // the FP32 matrix instruction (32x32x2).  The smoothed keys go through LDS once (coalesced
   // reads); every wave keeps half of them as B operands in registers and takes 32 Q blocks at a
@@ -372,10 +379,10 @@ __global__ void __launch_bounds__(256) qsmooth_bias_kernel(const unsigned short*
   v4f kb[D / 8];                                 // B operands: key 32 kt + r
 #pragma unroll
   for (int v = 0; v < D / 8; v++) kb[v] = *(const v4f*)(ks + (32 * kt + r) * LD + 8 * v + 4 * half);
-  const int first = causal ? kblk : 0;           // Q blocks below the key block are never read
-  for (int it = first / 32 + (wave >> 1); 32 * it < nblk; it += 2) {
-    const int I = min(32 * it + r, nblk - 1);    // rows past the end repeat the last one (not stored)
-    const float* mq = muQ + ((size_t)bh * nblk + I) * D + 4 * half;
+  const int first = causal_shift >= 0 ? max(kblk - causal_shift, 0) : 0;   // Q blocks that cannot see the key block are never read
+  for (int it = first / 32 + (wave >> 1); 32 * it < nqblk; it += 2) {
+    const int I = min(32 * it + r, nqblk - 1);   // rows past the end repeat the last one (not stored)
+    const float* mq = muQ + ((size_t)bh * nqblk + I) * D + 4 * half;
     v16f acc[2];                                 // two chains over alternate steps, summed at the end
 #pragma unroll
     for (int c = 0; c < 2; c++)
@@ -392,8 +399,8 @@ __global__ void __launch_bounds__(256) qsmooth_bias_kernel(const unsigned short*
 #pragma unroll
     for (int e = 0; e < 16; e++) {
       const int Io = 32 * it + 8 * (e >> 2) + 4 * half + (e & 3);
-      if (Io >= first && Io < nblk)
-        bias[((size_t)bh * nblk + Io) * Np + (size_t)kblk * kBlock + 32 * kt + r] = (acc[0][e] + acc[1][e]) * scale_log2e;
+      if (Io >= first && Io < nqblk)
+        bias[((size_t)bh * nqblk + Io) * Np + (size_t)kblk * kBlock + 32 * kt + r] = (acc[0][e] + acc[1][e]) * scale_log2e;
     }
   }
 }
@@ -404,14 +411,15 @@ __global__ void __launch_bounds__(256) qsmooth_bias_kernel(const unsigned short*
 // order in which the K^ operand of the dQ product holds its rows).  Tiles above the causal diagonal
 // were never written: they are returned as zeros.  One thread per 16 bytes.
 __global__ void export_ds_kernel(const int8_t* __restrict__ tiles, const float* __restrict__ scales,
-                                 int8_t* __restrict__ ds_out, float* __restrict__ scale_out, int Np, int pitch,
-                                 int causal) {
+                                 int8_t* __restrict__ ds_out, float* __restrict__ scale_out, int nqblk, int Np,
+                                 int pitch, int causal_shift) {
+  // [nqblk * 64, Np] out; causal_shift < 0: no mask, else tile (i, j) exists iff j <= i + causal_shift
   const int nblk = Np / kBlock;
   const size_t c = blockIdx.x * (size_t)blockDim.x + threadIdx.x;
-  if (c >= (size_t)nblk * nblk * 256) return;
+  if (c >= (size_t)nqblk * nblk * 256) return;
   const int tile = (int)(c / 256), i = tile / nblk, j = tile % nblk;
   const int frag = (int)(c % 256) / 64, lane = (int)(c % 64);
-  const bool there = !causal || j <= i;
+  const bool there = causal_shift < 0 || j <= i + causal_shift;
   v4i v = {0, 0, 0, 0};
   if (there) v = *(const v4i*)(tiles + ((size_t)i * pitch + j) * 4096 + (c % 256) * 16);   // `pitch` tiles per Q-block row
   const int qrow = 64 * i + 32 * (frag >> 1) + (lane & 31), key = 64 * j + 32 * (frag & 1) + 4 * (lane >> 5);

@@ -49,9 +49,13 @@ inline size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
 // the workspace, are never read from the caller's tensors (loaders clamp) and never stored.
 inline int padded_rows(int N) { return (N + 63) / 64 * 64; }
 
-// Where the rows of the caller's bf16 tensors start, in elements (times `scale`).
-inline RowView caller_view(const sagebwd_params& p, size_t scale) {
-  const size_t N = p.N, H = p.H, d = p.d;
+// Keys per head: N_kv, or N when the caller leaves it 0 (square attention).
+inline int kv_len(const sagebwd_params& p) { return p.Nkv > 0 ? p.Nkv : p.N; }
+
+// Where the rows of one of the caller's bf16 tensors start, in elements (times `scale`); `rows` = its
+// sequence length (N for Q, O, dO, dQ; N_kv for K, V, dK, dV).
+inline RowView caller_view(const sagebwd_params& p, size_t scale, int rows) {
+  const size_t N = rows, H = p.H, d = p.d;
   RowView v;
   v.H = p.H;
   if (p.layout == SAGEBWD_LAYOUT_BNHD) {
@@ -82,44 +86,47 @@ struct Workspace {
 
 Workspace make_layout(const sagebwd_params& p) {
   Workspace w;
-  const size_t BH = (size_t)p.B * p.H, N = padded_rows(p.N), d = p.d, nblk = N / 64;
+  // Nq, Nk: rows of the Q-like and K-like workspace tensors
+  const size_t BH = (size_t)p.B * p.H, Nq = padded_rows(p.N), Nk = padded_rows(kv_len(p)), d = p.d;
+  const size_t nqblk = Nq / 64, nkblk = Nk / 64;
   const bool qs = (p.smooth & SAGEBWD_SMOOTH_Q) != 0;
   const bool share = (p.flags & SAGEBWD_FLAG_SHARE_QUANTIZED) != 0;
-  w.chunk_rows = mean_chunk_rows((int)BH, p.N);
-  w.nchunk = (p.N + w.chunk_rows - 1) / w.chunk_rows;
+  w.chunk_rows = mean_chunk_rows((int)BH, kv_len(p));
+  w.nchunk = (kv_len(p) + w.chunk_rows - 1) / w.chunk_rows;
   size_t off = 0;
   auto take = [&](size_t bytes) { size_t o = off; off += align_up(bytes); return o; };
   w.kpart = take(BH * w.nchunk * d * sizeof(double));
   w.muK = take(BH * d * 4);
-  w.muQ = take(qs ? BH * nblk * d * 4 : 0);
-  w.sQ = take(BH * nblk * 4);
-  w.sK = take(BH * nblk * 4);
-  w.sV = take(BH * nblk * 4);
-  w.QF = take(BH * N * d);
-  w.KF = take(BH * N * d);
-  w.VT = take(BH * N * d);
-  w.bias = take(qs ? BH * nblk * N * 4 : 0);
+  w.muQ = take(qs ? BH * nqblk * d * 4 : 0);
+  w.sQ = take(BH * nqblk * 4);
+  w.sK = take(BH * nkblk * 4);
+  w.sV = take(BH * nkblk * 4);
+  w.QF = take(BH * Nq * d);
+  w.KF = take(BH * Nk * d);
+  w.VT = take(BH * Nk * d);
+  w.bias = take(qs ? BH * nqblk * Nk * 4 : 0);
   if (!share) w.fwd_total = off;
-  w.QT = take(BH * N * d);
-  w.KT = take(BH * N * d);
+  w.QT = take(BH * Nq * d);
+  w.KT = take(BH * Nk * d);
   if (share) w.fwd_total = off;
-  w.sdO = take(BH * nblk * 4);
-  w.delta = take(BH * N * 4);
-  w.nl2 = take(BH * N * 4);
-  w.dOT = take(BH * N * d);
-  // dS scratch: N*N bytes per head, capped at the budget by processing the heads in groups
-  const size_t budget = p.scratch_budget != 0 ? (size_t)p.scratch_budget : kDefaultDsBudget;
+  w.sdO = take(BH * nqblk * 4);
+  w.delta = take(BH * Nq * 4);
+  w.nl2 = take(BH * Nq * 4);
+  w.dOT = take(BH * Nq * d);
+  // dS scratch: one 4 KiB tile per (Q block, KV block) and head, capped at the budget by processing the
+  // heads in groups.
   // Rows of the dS scratch are three tiles longer than they need to be: with a power-of-two row length
   // the workgroups of the dQ kernel, which walk their rows at the same pace, read addresses that differ
   // in the high bits only (measured: 4 % of that kernel).
-  w.ds_pitch = (int)nblk + 3;
-  const size_t ds_head = nblk * (size_t)w.ds_pitch * 4096;   // bytes of dS scratch per head
+  w.ds_pitch = (int)nkblk + 3;
+  const size_t ds_head = nqblk * (size_t)w.ds_pitch * 4096;   // bytes of dS scratch per head
+  const size_t budget = p.scratch_budget != 0 ? (size_t)p.scratch_budget : kDefaultDsBudget;
   size_t hpg = budget / ds_head;
   if (hpg < 1) hpg = 1;
   if (hpg > BH) hpg = BH;
   w.heads_per_group = (int)hpg;
   w.dSq = take(hpg * ds_head);
-  w.sdS = take(hpg * nblk * nblk * 4);
+  w.sdS = take(hpg * nqblk * nkblk * 4);
   w.total = off;
   return w;
 }
@@ -128,15 +135,19 @@ int check_params(const sagebwd_params* p) {
   if (p == nullptr) return SAGEBWD_INVALID_ARG;
   if (p->B <= 0 || p->H <= 0 || p->N <= 0 || p->d <= 0) return SAGEBWD_INVALID_ARG;
   if (p->layout != SAGEBWD_LAYOUT_BHND && p->layout != SAGEBWD_LAYOUT_BNHD) return SAGEBWD_INVALID_ARG;
-  if ((p->flags & ~SAGEBWD_FLAG_SHARE_QUANTIZED) != 0 || p->reserved != 0) return SAGEBWD_INVALID_ARG;
+  if ((p->flags & ~SAGEBWD_FLAG_SHARE_QUANTIZED) != 0 || p->Nkv < 0) return SAGEBWD_INVALID_ARG;
   if (p->bq < 0 || p->bkv < 0) return SAGEBWD_INVALID_ARG;
   if ((p->smooth & ~(SAGEBWD_SMOOTH_K | SAGEBWD_SMOOTH_Q)) != 0) return SAGEBWD_INVALID_ARG;
   if (p->causal != 0 && p->causal != 1) return SAGEBWD_INVALID_ARG;
   if (!(p->sm_scale >= 0.f) || isinf(p->sm_scale)) return SAGEBWD_INVALID_ARG;
   if (p->d != 64 && p->d != 128) return SAGEBWD_UNSUPPORTED_SHAPE;
   if ((p->bq != 0 && p->bq != 64) || (p->bkv != 0 && p->bkv != 64)) return SAGEBWD_UNSUPPORTED_SHAPE;
-  if (p->N > (1 << 30)) return SAGEBWD_UNSUPPORTED_SHAPE;
-  const double elems = (double)p->B * p->H * (double)padded_rows(p->N) * p->d;
+  const int Nk = kv_len(*p);
+  if (p->N > (1 << 30) || Nk > (1 << 30)) return SAGEBWD_UNSUPPORTED_SHAPE;
+  // under the mask the last query sits on the last key; the kernels keep one diagonal tile per Q block,
+  // which needs the two lengths to differ by whole blocks
+  if (p->causal && (Nk < p->N || (Nk - p->N) % 64 != 0)) return SAGEBWD_UNSUPPORTED_SHAPE;
+  const double elems = (double)p->B * p->H * (double)padded_rows(p->N > Nk ? p->N : Nk) * p->d;
   if (elems >= 1099511627776.0) return SAGEBWD_UNSUPPORTED_SHAPE;
   if ((double)p->B * p->H > 65535.0) return SAGEBWD_UNSUPPORTED_SHAPE;   // grid.y limit
   return SAGEBWD_OK;
@@ -194,15 +205,15 @@ template <int D>
 int run_prepass(const void* Q, const void* K, const void* V, const void* dO, const void* O, const float* LSE,
                 const sagebwd_params& p, char* ws, const Workspace& w, bool want_qk, bool want_tf, bool want_v,
                 hipStream_t st) {
-  const int BH = p.B * p.H, N = p.N, Np = padded_rows(N), nblk = Np / 64;
+  const int BH = p.B * p.H, Nq = p.N, Nk = kv_len(p), Nqp = padded_rows(Nq), Nkp = padded_rows(Nk);
   const bool ks = (p.smooth & SAGEBWD_SMOOTH_K) != 0;
   const bool qs = (p.smooth & SAGEBWD_SMOOTH_Q) != 0;
-  const RowView view = caller_view(p, 1);     // in bf16 elements
+  const RowView qview = caller_view(p, 1, Nq), kview = caller_view(p, 1, Nk);     // in bf16 elements
   float* muK = (float*)(ws + w.muK);
   if (want_qk) {
     if (ks) {
-      kmean_partial_kernel<D><<<dim3(w.nchunk, BH), 256, 0, st>>>((const unsigned short*)K, view,
-                                                                   (double*)(ws + w.kpart), N, w.nchunk, w.chunk_rows);
+      kmean_partial_kernel<D><<<dim3(w.nchunk, BH), 256, 0, st>>>((const unsigned short*)K, kview,
+                                                                   (double*)(ws + w.kpart), Nk, w.nchunk, w.chunk_rows);
       SAGE_LAUNCH_CHECK();
     } else {
       fill_zero_f32_kernel<<<(BH * D + 255) / 256, 256, 0, st>>>(muK, (size_t)BH * D);
@@ -212,9 +223,12 @@ int run_prepass(const void* Q, const void* K, const void* V, const void* dO, con
   QuantJobs jobs;
   memset(&jobs, 0, sizeof(jobs));
   int nj = 0;
+  auto q_like = [&](QuantJob& j) { j.view = qview; j.N = Nq; j.Np = Nqp; };
+  auto k_like = [&](QuantJob& j) { j.view = kview; j.N = Nk; j.Np = Nkp; };
   if (want_qk) {
     // K first: the mean reduction has just read it, so these blocks find it in the memory-side cache.
     // F layout, and TF layout for the backward (dQ = dS^ K^)
+    k_like(jobs.job[nj]);
     jobs.job[nj].src = (const unsigned short*)K;
     jobs.job[nj].outF = (int8_t*)(ws + w.KF);
     jobs.job[nj].outTF = want_tf ? (int8_t*)(ws + w.KT) : nullptr;
@@ -224,6 +238,7 @@ int run_prepass(const void* Q, const void* K, const void* V, const void* dO, con
     jobs.job[nj].mu_head_out = muK;
     nj++;
     // Q: F layout (S = Q^ K^^T in both passes) and, for the backward, TF layout (dK = dS^^T Q^)
+    q_like(jobs.job[nj]);
     jobs.job[nj].src = (const unsigned short*)Q;
     jobs.job[nj].outF = (int8_t*)(ws + w.QF);
     jobs.job[nj].outTF = want_tf ? (int8_t*)(ws + w.QT) : nullptr;
@@ -233,6 +248,7 @@ int run_prepass(const void* Q, const void* K, const void* V, const void* dO, con
   }
   if (want_v) {
     // V: TF layout (O = P^ V^ contracts over keys); the backward uses the bf16 V only
+    k_like(jobs.job[nj]);
     jobs.job[nj].src = (const unsigned short*)V;
     jobs.job[nj].outTF = (int8_t*)(ws + w.VT);
     jobs.job[nj].scale = (float*)(ws + w.sV);
@@ -240,6 +256,7 @@ int run_prepass(const void* Q, const void* K, const void* V, const void* dO, con
   }
   if (dO != nullptr) {
     // dO: TF layout (dV = P^^T dO^ contracts over queries), plus delta when O is given
+    q_like(jobs.job[nj]);
     jobs.job[nj].src = (const unsigned short*)dO;
     jobs.job[nj].outTF = (int8_t*)(ws + w.dOT);
     jobs.job[nj].scale = (float*)(ws + w.sdO);
@@ -250,14 +267,15 @@ int run_prepass(const void* Q, const void* K, const void* V, const void* dO, con
     nj++;
   }
   if (nj > 0) {
-    prepass_quant_kernel<D><<<dim3(nblk, BH, nj), 256, 0, st>>>(jobs, view, N, Np);
+    const int nblk_max = (Nqp > Nkp ? Nqp : Nkp) / 64;
+    prepass_quant_kernel<D><<<dim3(nblk_max, BH, nj), 256, 0, st>>>(jobs);
     SAGE_LAUNCH_CHECK();
   }
   if (qs && want_qk) {
     const float sl2 = logit_scale(p) * 1.4426950408889634f;
-    qsmooth_bias_kernel<D><<<dim3(nblk, BH), 256, 0, st>>>(
-        (const unsigned short*)K, view, muK, (const float*)(ws + w.muQ), (float*)(ws + w.bias), N, Np,
-        p.causal, sl2);
+    qsmooth_bias_kernel<D><<<dim3(Nkp / 64, BH), 256, 0, st>>>(
+        (const unsigned short*)K, kview, muK, (const float*)(ws + w.muQ), (float*)(ws + w.bias), Nk, Nkp, Nqp / 64,
+        p.causal ? (Nk - Nq) / 64 : -1, sl2);
     SAGE_LAUNCH_CHECK();
   }
   return SAGEBWD_OK;
@@ -284,7 +302,7 @@ int pick_fwd_waves(int N) { return N % 128 == 0 ? 4 : 2; }
 template <int D, bool CAUSAL, bool QS>
 int launch_fwd_nw(const FwdArgs& a, int nw, hipStream_t st) {
   FwdArgs args = a;
-  args.n_qtiles = a.N / (32 * nw);
+  args.n_qtiles = a.Nq / (32 * nw);
   args.head_set = head_set_for(args.n_qtiles, a.BH);
   const int grid = grid_for(a.BH, args.n_qtiles);
   if (nw == 4) sage_fwd_kernel<D, CAUSAL, QS, 4><<<grid, 256, 0, st>>>(args);
@@ -295,7 +313,7 @@ int launch_fwd_nw(const FwdArgs& a, int nw, hipStream_t st) {
 
 template <int D>
 int launch_fwd(const FwdArgs& a, bool causal, bool qs, hipStream_t st) {
-  const int nw = pick_fwd_waves(a.N);
+  const int nw = pick_fwd_waves(a.Nq);
   if (causal) return qs ? launch_fwd_nw<D, true, true>(a, nw, st) : launch_fwd_nw<D, true, false>(a, nw, st);
   return qs ? launch_fwd_nw<D, false, true>(a, nw, st) : launch_fwd_nw<D, false, false>(a, nw, st);
 }
@@ -319,7 +337,7 @@ int launch_bwd(const BwdArgs& a, bool causal, bool qs, hipStream_t st) {
 
 template <int D>
 int launch_bwd_dq(const DqArgs& a, bool causal, hipStream_t st) {
-  const int npair = (a.N / 64 + 1) / 2;     // one workgroup per pair of Q blocks
+  const int npair = (a.Nq / 64 + 1) / 2;    // one workgroup per pair of Q blocks
   DqArgs args = a;
   args.head_set = head_set_for(npair, a.BH, true);   // memory-bound: gains from head sets at every length
   const int grid = grid_for(a.BH, npair);
@@ -348,11 +366,14 @@ int forward_impl(const void* Q, const void* K, const void* V, void* O, float* LS
   const bool qs = (p.smooth & SAGEBWD_SMOOTH_Q) != 0;
   a.bias = qs ? (const float*)(ws + w.bias) : nullptr;
   a.O = (unsigned short*)O;
-  a.oview = caller_view(p, 1);
+  a.oview = caller_view(p, 1, p.N);
   a.LSE = LSE;
   a.BH = p.B * p.H;
-  a.N = padded_rows(p.N);
-  a.nvalid = p.N;
+  a.N = padded_rows(kv_len(p));
+  a.nvalid = kv_len(p);
+  a.Nq = padded_rows(p.N);
+  a.nq_valid = p.N;
+  a.shift = p.causal ? kv_len(p) - p.N : 0;
   a.n_qtiles = 0;
   a.scale_log2e = logit_scale(p) * 1.4426950408889634f;
   {
@@ -421,7 +442,8 @@ int sagebwd_export_quantized(const sagebwd_params* params, const void* workspace
   hipStream_t st = (hipStream_t)stream;
   const char* ws = (const char*)workspace;
   const size_t BH = (size_t)params->B * params->H;
-  const int Np = padded_rows(params->N);
+  const bool k_like = which == SAGEBWD_TENSOR_K || which == SAGEBWD_TENSOR_V;
+  const int Np = padded_rows(k_like ? kv_len(*params) : params->N);
   if (q_out != nullptr) {
     const size_t n_chunks = BH * Np * params->d / 16;
     export_fragments_kernel<<<(unsigned)((n_chunks + 255) / 256), 256, 0, st>>>(
@@ -469,12 +491,13 @@ int sagebwd_export_ds(const sagebwd_params* params, const void* workspace, size_
   // the scratch holds the heads of the LAST group the backward processed: only a backward that ran
   // in one group leaves every head behind
   if (w.heads_per_group < params->B * params->H) return SAGEBWD_UNSUPPORTED_SHAPE;
-  const int Np = padded_rows(params->N), nblk = Np / 64;
+  const int Nkp = padded_rows(kv_len(*params)), nkblk = Nkp / 64, nqblk = padded_rows(params->N) / 64;
   const char* ws = (const char*)workspace;
-  const size_t n = (size_t)nblk * nblk * 256;
+  const size_t n = (size_t)nqblk * nkblk * 256;
   export_ds_kernel<<<(unsigned)((n + 255) / 256), 256, 0, (hipStream_t)stream>>>(
-      (const int8_t*)(ws + w.dSq) + (size_t)head * nblk * w.ds_pitch * 4096, (const float*)(ws + w.sdS) + (size_t)head * nblk * nblk,
-      ds_out, scale_out, Np, w.ds_pitch, params->causal);
+      (const int8_t*)(ws + w.dSq) + (size_t)head * nqblk * w.ds_pitch * 4096,
+      (const float*)(ws + w.sdS) + (size_t)head * nqblk * nkblk, ds_out, scale_out, nqblk, Nkp, w.ds_pitch,
+      params->causal ? (kv_len(*params) - params->N) / 64 : -1);
   SAGE_LAUNCH_CHECK();
   return SAGEBWD_OK;
 }
@@ -519,7 +542,9 @@ int sagebwd_bwd(const void* Q, const void* K, const void* V, const void* O, cons
   if (workspace_bytes < w.total) return SAGEBWD_WORKSPACE_TOO_SMALL;
   hipStream_t st = (hipStream_t)stream;
   char* ws = (char*)workspace;
-  const int BH = params->B * params->H, N = padded_rows(params->N), d = params->d;
+  const int BH = params->B * params->H, d = params->d;
+  const int Nk = kv_len(*params), Nkp = padded_rows(Nk), Nqp = padded_rows(params->N);
+  const int shift_blocks = params->causal ? (Nk - params->N) / 64 : 0;
   const bool qs = (params->smooth & SAGEBWD_SMOOTH_Q) != 0;
   {
     ScopedTimer tm(SAGEBWD_KERNEL_PREPASS_BWD, st);
@@ -533,7 +558,8 @@ int sagebwd_bwd(const void* Q, const void* K, const void* V, const void* O, cons
   a.QT = (const int8_t*)(ws + w.QT);
   a.KF = (const int8_t*)(ws + w.KF);
   a.dOT = (const int8_t*)(ws + w.dOT);
-  a.cv = caller_view(*params, 1);   // in bf16 elements
+  a.cv = caller_view(*params, 1, Nk);           // in bf16 elements
+  a.cvq = caller_view(*params, 1, params->N);
   a.V = (const unsigned short*)V;
   a.dO = (const unsigned short*)dO;
   a.sQ = (const float*)(ws + w.sQ);
@@ -548,12 +574,15 @@ int sagebwd_bwd(const void* Q, const void* K, const void* V, const void* O, cons
   a.sdS = (float*)(ws + w.sdS);
   a.dK = (unsigned short*)dK;
   a.dV = (unsigned short*)dV;
-  a.N = N;
-  a.nvalid = params->N;
+  a.N = Nkp;
+  a.nvalid = Nk;
+  a.Nq = Nqp;
+  a.nq_valid = params->N;
+  a.shift_blocks = shift_blocks;
   a.sm_scale = logit_scale(*params);
   a.scale_log2e = a.sm_scale * 1.4426950408889634f;
   DqArgs q;
-  q.cv = a.cv;
+  q.cv = a.cvq;
   q.dSq = a.dSq;
   q.ds_pitch = w.ds_pitch;
   q.sdS = a.sdS;
@@ -561,7 +590,9 @@ int sagebwd_bwd(const void* Q, const void* K, const void* V, const void* O, cons
   q.sK = a.sK;
   q.dQ = (unsigned short*)dQ;
   q.nvalid = params->N;
-  q.N = N;
+  q.N = Nkp;
+  q.Nq = Nqp;
+  q.shift_blocks = shift_blocks;
   q.sm_scale = a.sm_scale;
   for (int h0 = 0; h0 < BH; h0 += w.heads_per_group) {
     const int nh = BH - h0 < w.heads_per_group ? BH - h0 : w.heads_per_group;

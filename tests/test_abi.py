@@ -60,6 +60,11 @@ def test_workspace_bytes_and_shape_validation(lib):
     # the dS scratch is capped at 8 GiB by default: larger problems run in groups of heads
     assert binding.workspace_bytes(SageParams(1, 32, 32768, 128, causal=False)) < (8 << 30) + 7 * 32 * 32768 * 128 + (64 << 20)
     assert binding.workspace_bytes(SageParams(2, 32, 8192, 128, q_smooth=True)) > n
+    # more keys than queries: the K-like tensors and the dS scratch grow, the Q-like ones do not
+    sq, rect = SageParams(1, 4, 1024, 128), SageParams(1, 4, 1024, 128, Nkv=4096)
+    grow = binding.workspace_bytes(rect) - binding.workspace_bytes(sq)
+    assert 3 * 4 * 3072 * 128 + 4 * 1024 * 3072 <= grow < 3 * 4 * 3072 * 128 + 4 * 1024 * 3072 + (1 << 20)
+    assert binding.workspace_bytes(SageParams(1, 4, 1024, 128, Nkv=1024)) == binding.workspace_bytes(sq)
     # N that is not a multiple of 64: the workspace is laid out for N rounded up to the block
     assert binding.workspace_bytes(SageParams(1, 1, 100, 64)) == binding.workspace_bytes(SageParams(1, 1, 128, 64))
     assert binding.workspace_bytes(SageParams(1, 1, 128, 64, bq=64, bkv=64)) == binding.workspace_bytes(SageParams(1, 1, 128, 64))
@@ -92,8 +97,12 @@ def test_entry_points_reject_bad_arguments_on_the_host(lib):
     bad.flags = 2
     assert lib.sagebwd_fwd(one, one, one, one, one, ctypes.byref(bad), one, 1 << 30, null) == -1
     bad = SageParams(1, 2, 128, 64).c()
-    bad.reserved = 1
+    bad.Nkv = -64
     assert lib.sagebwd_fwd(one, one, one, one, one, ctypes.byref(bad), one, 1 << 30, null) == -1
+    # N_q != N_kv: under the mask the keys must be at least as many and differ by whole blocks
+    for nkv, causal, want in ((64, True, -2), (200, True, -2), (192, True, -3), (64, False, -3), (1000, False, -3)):
+        c = SageParams(1, 2, 128, 64, causal=causal, Nkv=nkv).c()
+        assert lib.sagebwd_fwd(one, one, one, one, one, ctypes.byref(c), one, 16, null) == want, (nkv, causal)
     # the forward accepts its own (smaller) workspace size, the backward does not
     fwd_only = binding.workspace_bytes(SageParams(1, 2, 128, 64), forward_only=True)
     assert fwd_only < binding.workspace_bytes(SageParams(1, 2, 128, 64))

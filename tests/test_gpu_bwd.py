@@ -13,9 +13,14 @@ from gpu_common import check_close, params_for, to_np
 pytestmark = pytest.mark.gpu
 
 
+def dQ_shape_ok(Q, K, p):
+    return Q.shape[2] == p.N and K.shape[2] == p.kv_len
+
+
 def _bwd_case(Q, K, V, dO, p, heads=None):
     Qn, Kn, Vn, dOn = (to_np(t) for t in (Q, K, V, dO))
     B, H = Q.shape[:2]
+    assert dQ_shape_ok(Q, K, p)
     On = np.zeros_like(Qn)
     Ln = np.zeros(Qn.shape[:3], np.float32)
     todo = [(b, h) for b in range(B) for h in range(H)] if heads is None else heads
@@ -298,3 +303,34 @@ def test_workgroup_to_head_mappings_give_the_same_bits(heads, N, d):
         assert torch.equal(O1, O[:, sl]) and torch.equal(L1, L[:, sl]), h
         for a, b in zip(g1, (dQ, dK, dV)):
             assert torch.equal(a, b[:, sl]), h
+
+
+@pytest.mark.parametrize("Nq,Nk,d,causal", [(64, 256, 64, True), (100, 228, 128, True), (192, 64, 64, False), (37, 300, 128, False),
+                                            (1, 200, 64, False), (256, 1024, 128, True), (448, 64, 128, False), (320, 384, 128, True)])
+def test_bwd_non_square(Nq, Nk, d, causal):
+    """Q, dO of N_q rows against K, V of N_kv rows: dQ has N_q rows, dK and dV have N_kv; under the mask
+    the last query sits on the last key (the diagonal tile of Q block i is KV block i + (N_kv - N_q) / 64)."""
+    from test_gpu_fwd import non_square_inputs
+    Q, K, V, dO = non_square_inputs(Nq, Nk, d, seed=5 * Nq + Nk)
+    _bwd_case(Q, K, V, dO, binding.SageParams(1, 3, Nq, d, causal=causal, Nkv=Nk))
+
+
+def test_bwd_non_square_q_smoothing_sharing_and_head_groups():
+    from test_gpu_fwd import non_square_inputs
+    Q, K, V, dO = non_square_inputs(128, 320, 128, seed=43, heads=4, q_offset=True)
+    _bwd_case(Q, K, V, dO, binding.SageParams(1, 4, 128, 128, causal=True, q_smooth=True, Nkv=320))
+    _bwd_case(Q, K, V, dO, binding.SageParams(1, 4, 128, 128, causal=False, q_smooth=True, Nkv=320))
+    # two heads of dS scratch at a time; and the backward taking psi(Q), psi(K) from the forward
+    _bwd_case(Q, K, V, dO, binding.SageParams(1, 4, 128, 128, causal=True, Nkv=320, scratch_budget=2 * 128 * (320 + 192)))
+    Qd, Kd, Vd, dOd = (t.cuda() for t in (Q, K, V, dO))
+    p = binding.SageParams(1, 4, 128, 128, causal=True, Nkv=320)
+    ps = binding.SageParams(1, 4, 128, 128, causal=True, Nkv=320, share_quantized=True)
+    O, L = binding.sagebwd_fwd(Qd, Kd, Vd, p)
+    ref = binding.sagebwd_bwd(Qd, Kd, Vd, O, dOd, L, p)
+    ws = binding.alloc_workspace(ps)
+    Os, Ls = binding.sagebwd_fwd(Qd, Kd, Vd, ps, ws)
+    got = binding.sagebwd_bwd(Qd, Kd, Vd, Os, dOd, Ls, ps, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(O, Os) and torch.equal(L, Ls)
+    for a, b in zip(ref, got):
+        assert torch.equal(a, b)

@@ -84,3 +84,39 @@ def test_fwd_outlier_shape_with_and_without_k_smoothing():
     Q, K, V, _ = synth.make_inputs(w, heads=[3, 20])
     for ks in (True, False):
         _fwd_case(Q, K, V, params_for(w, B=2, H=1, k_smooth=ks))
+
+
+NON_SQUARE = [(64, 256, 64, True), (100, 228, 128, True), (192, 64, 64, False), (37, 300, 128, False), (1, 200, 64, False),
+              (256, 1024, 128, True), (448, 64, 128, False)]
+
+
+def non_square_inputs(Nq, Nk, d, seed, heads=3, q_offset=False):
+    """Q, dO of Nq rows and K, V of Nk rows from the Gaussian recipe (two draws, so the values of one do
+    not depend on the length of the other)."""
+    Q, _, _, dO = synth.gaussian_inputs(Nq, d, sigma_qk=1.5, seed=seed, heads=heads)
+    _, K, V, _ = synth.gaussian_inputs(Nk, d, sigma_qk=1.5, seed=seed + 1, heads=heads)
+    if q_offset:
+        Q = (Q.float() + torch.linspace(-3, 3, d)).to(torch.bfloat16)
+    return Q, K, V, dO
+
+
+@pytest.mark.parametrize("Nq,Nk,d,causal", NON_SQUARE)
+def test_fwd_non_square(Nq, Nk, d, causal):
+    """Q of N_q rows against K, V of N_kv rows; under the mask the last query sits on the last key."""
+    Q, K, V, _ = non_square_inputs(Nq, Nk, d, seed=3 * Nq + Nk)
+    _fwd_case(Q, K, V, binding.SageParams(1, 3, Nq, d, causal=causal, Nkv=Nk))
+
+
+def test_fwd_non_square_q_smoothing_and_token_major():
+    Q, K, V, _ = non_square_inputs(128, 320, 128, seed=41, heads=4, q_offset=True)
+    _fwd_case(Q, K, V, binding.SageParams(1, 4, 128, 128, causal=True, q_smooth=True, Nkv=320))
+    _fwd_case(Q, K, V, binding.SageParams(1, 4, 128, 128, causal=False, q_smooth=True, Nkv=320))
+    # [B, N, H, d] tensors of the two lengths give the bits of the [B, H, N, d] call
+    p = binding.SageParams(2, 2, 128, 128, causal=True, Nkv=320)
+    pt = binding.SageParams(2, 2, 128, 128, causal=True, Nkv=320, token_major=True)
+    Qd, Kd, Vd = (t.reshape(2, 2, t.shape[2], 128).cuda() for t in (Q, K, V))
+    O, L = binding.sagebwd_fwd(Qd, Kd, Vd, p)
+    tm = lambda t: t.permute(0, 2, 1, 3).contiguous()
+    Ot, Lt = binding.sagebwd_fwd(tm(Qd), tm(Kd), tm(Vd), pt)
+    torch.cuda.synchronize()
+    assert torch.equal(tm(O), Ot) and torch.equal(L, Lt)

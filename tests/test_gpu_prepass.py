@@ -14,8 +14,11 @@ pytestmark = pytest.mark.gpu
 def _oracle_prepass(Q, K, V, dO, p):
     B, H, N, d = Q.shape
     Np = -(-N // 64) * 64      # the exported tensors have N rounded up to the block; the extra rows are zero
-    out = {k: np.zeros((B, H, Np, d), np.int8) for k in ("Qh", "Kh", "Vh", "dOh")}
-    out.update({k: np.zeros((B, H, Np // 64), np.float32) for k in ("sQ", "sK", "sV", "sdO")})
+    Nkp = -(-K.shape[2] // 64) * 64
+    out = {k: np.zeros((B, H, Np, d), np.int8) for k in ("Qh", "dOh")}
+    out.update({k: np.zeros((B, H, Nkp, d), np.int8) for k in ("Kh", "Vh")})
+    out.update({k: np.zeros((B, H, Np // 64), np.float32) for k in ("sQ", "sdO")})
+    out.update({k: np.zeros((B, H, Nkp // 64), np.float32) for k in ("sK", "sV")})
     out["muK"] = np.zeros((B, H, d), np.float32)
     out["muQ"] = np.zeros((B, H, Np // 64, d), np.float32)
     for b in range(B):
@@ -94,3 +97,13 @@ def test_prepass_bit_exact_sampled_heads_of_pretrain_shape():
     w = synth.WORKLOADS["pretrain"]
     Q, K, V, dO = synth.make_inputs(w, heads=[0, 17, 63])
     _run_case(Q, K, V, dO, params_for(w, B=3, H=1))
+
+
+@pytest.mark.parametrize("Nq,Nk,d,q_smooth", [(100, 300, 64, False), (320, 64, 128, True), (1, 200, 128, False)])
+def test_prepass_bit_exact_non_square(Nq, Nk, d, q_smooth):
+    """Q, dO of N_q rows and K, V of N_kv rows: every tensor is smoothed and quantised over its own blocks."""
+    g = torch.Generator().manual_seed(7 * Nq + Nk)
+    Q, dO = (torch.randn(1, 2, Nq, d, generator=g).to(torch.bfloat16) for _ in range(2))
+    K, V = (torch.randn(1, 2, Nk, d, generator=g).to(torch.bfloat16) for _ in range(2))
+    K = (K.float() + torch.randn(1, 2, 1, d, generator=g) * 4).to(torch.bfloat16)
+    _run_case(Q, K, V, dO, binding.SageParams(1, 2, Nq, d, causal=False, q_smooth=q_smooth, Nkv=Nk))
