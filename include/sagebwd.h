@@ -74,6 +74,17 @@ typedef enum sagebwd_status {
  * between (another sagebwd_fwd on it included).  Results are bit-identical to the calls without
  * the flag.  Without the flag sagebwd_bwd relies on nothing an earlier call left behind. */
 #define SAGEBWD_FLAG_SHARE_QUANTIZED 1
+/* SAGEBWD_FLAG_QK_NORM: Q and K are the projections BEFORE the model's QK-norm (paper Sec. 4,
+ * "Stabilizing Outliers with QK-Norm": RMS normalisation of every token of Q and K); the pre-pass applies
+ *     y = x / sqrt(mean_c(x^2) + qk_norm_eps) * gamma      per token and head, gamma = qk_gamma_q / qk_gamma_k,
+ * rounds y to bf16 (the tensor a bf16 model would hand to the attention) and goes on with the smoothing
+ * and the quantiser, so one pass over Q and K replaces the model's normalisation kernel plus this
+ * library's pre-pass, with the bits of running the two one after the other.  Arithmetic (part of the
+ * bit-exact contract): sum of squares in float64, r = 1 / sqrt(sum / d + eps) in float64 rounded once to
+ * FP32, y = bf16((x *_f32 r) *_f32 gamma).  O, LSE, dV are unchanged in meaning; dQ and dK are the
+ * gradients with respect to the NORMALISED Q and K (the chain rule through the normalisation is the
+ * caller's).  qk_gamma_q and qk_gamma_k are device pointers to d floats each, shared by all heads. */
+#define SAGEBWD_FLAG_QK_NORM 2
 
 typedef struct sagebwd_params {
   int32_t B, H, N, d; /* N = rows of Q, O, dO, dQ (and of K, V, dK, dV unless Nkv is set) */
@@ -88,9 +99,13 @@ typedef struct sagebwd_params {
                       Nkv >= N and Nkv - N a multiple of 64 (else SAGEBWD_UNSUPPORTED_SHAPE); a decoding
                       step whose queries see the whole cache is the call with causal = 0 */
   uint64_t scratch_budget;   /* upper bound, in bytes, on the INT8 dS scratch that sagebwd_bwd holds at
-                                once; 0 selects 8 GiB.  The backward needs Np*(Np+192) bytes per head and
+                                once; 0 selects 8 GiB.  The backward needs Np*(Nkp+192) bytes per head and
                                 processes the heads in groups that fit the bound (at least one head per
                                 group); the workspace size follows from it. */
+  const float* qk_gamma_q;   /* SAGEBWD_FLAG_QK_NORM: DEVICE pointers to the d gains of Q and of K; */
+  const float* qk_gamma_k;   /*   must be NULL without the flag                                      */
+  float qk_norm_eps;         /* SAGEBWD_FLAG_QK_NORM: >= 0, added to the mean square */
+  int32_t reserved;          /* must be 0 */
 } sagebwd_params;
 
 /* Which quantised tensor sagebwd_export_quantized() copies out. */

@@ -8,6 +8,7 @@ benchmark's cpu_baseline leg may use it.
 from .sage_oracle import (  # noqa: F401
     BLOCK,
     round_to_bf16,
+    qk_norm,
     key_mean,
     block_mean,
     pad_rows,

@@ -77,6 +77,22 @@ def round_to_bf16(x) -> np.ndarray:
     return out.reshape(a.shape)
 
 
+def qk_norm(X, gamma, eps: float = 1e-6) -> np.ndarray:
+    """QK-norm of one head (Sec. 4, "Stabilizing Outliers with QK-Norm": RMS normalisation of every
+    token of Q and K, with the learned per-channel gain gamma the paper mentions):
+        y[n, :] = x[n, :] / sqrt(mean_c x[n, c]^2 + eps) * gamma.
+    The model side of the method, here for the pre-pass that fuses it with the quantiser.  Arithmetic:
+    the mean of squares in float64 (exact for bf16 inputs), r = 1 / sqrt(mean + eps) in float64 rounded
+    once to float32, y = (x *_f32 r) *_f32 gamma, rounded to bf16 -- the tensor a bf16 model would hand
+    to the attention.  Returns float32 holding bf16 values."""
+    X = np.asarray(X, dtype=_F32)
+    g = np.asarray(gamma, dtype=_F32)
+    ms = (X.astype(_F64) ** 2).sum(axis=1) / _F64(X.shape[1])
+    r = (_F64(1.0) / np.sqrt(ms + _F64(_F32(eps)))).astype(_F32)      # eps is a float32 parameter
+    y = ((X * r[:, None]).astype(_F32) * g[None, :]).astype(_F32)
+    return round_to_bf16(y)
+
+
 def key_mean(K: np.ndarray) -> np.ndarray:
     """mu_K = mean_row(K) over ALL N tokens of the head (Sec. 3, smoothing eq.).
 

@@ -18,6 +18,7 @@ _LIB = None
 SMOOTH_K = 1
 SMOOTH_Q = 2
 FLAG_SHARE_QUANTIZED = 1
+FLAG_QK_NORM = 2
 LAYOUT_BHND, LAYOUT_BNHD = 0, 1
 
 TENSOR_Q, TENSOR_K, TENSOR_V, TENSOR_DO = 0, 1, 2, 3
@@ -33,7 +34,9 @@ class _CParams(ctypes.Structure):
     _fields_ = [("B", ctypes.c_int32), ("H", ctypes.c_int32), ("N", ctypes.c_int32), ("d", ctypes.c_int32),
                 ("causal", ctypes.c_int32), ("smooth", ctypes.c_int32), ("sm_scale", ctypes.c_float),
                 ("layout", ctypes.c_int32), ("bq", ctypes.c_int32), ("bkv", ctypes.c_int32),
-                ("flags", ctypes.c_int32), ("Nkv", ctypes.c_int32), ("scratch_budget", ctypes.c_uint64)]
+                ("flags", ctypes.c_int32), ("Nkv", ctypes.c_int32), ("scratch_budget", ctypes.c_uint64),
+                ("qk_gamma_q", ctypes.c_void_p), ("qk_gamma_k", ctypes.c_void_p), ("qk_norm_eps", ctypes.c_float),
+                ("reserved", ctypes.c_int32)]
 
 
 @dataclass
@@ -52,13 +55,25 @@ class SageParams:
     bq: int = 0                 # numerics block sizes; 0 selects 64
     bkv: int = 0
     Nkv: int = 0                # rows of K, V, dK, dV; 0 selects N
+    qk_gamma_q: object = None   # QK-norm fused into the pre-pass: float32 cuda tensors [d] (both or neither);
+    qk_gamma_k: object = None   # the caller keeps them alive while calls are in flight
+    qk_norm_eps: float = 1e-6
 
     def c(self) -> _CParams:
         return _CParams(self.B, self.H, self.N, self.d, int(self.causal),
                         (SMOOTH_K if self.k_smooth else 0) | (SMOOTH_Q if self.q_smooth else 0),
                         float(self.sm_scale), LAYOUT_BNHD if self.token_major else LAYOUT_BHND,
-                        int(self.bq), int(self.bkv), FLAG_SHARE_QUANTIZED if self.share_quantized else 0,
-                        int(self.Nkv), int(self.scratch_budget))
+                        int(self.bq), int(self.bkv),
+                        (FLAG_SHARE_QUANTIZED if self.share_quantized else 0) | (FLAG_QK_NORM if self.qk_gamma_q is not None else 0),
+                        int(self.Nkv), int(self.scratch_budget),
+                        None if self.qk_gamma_q is None else self._gain(self.qk_gamma_q),
+                        None if self.qk_gamma_k is None else self._gain(self.qk_gamma_k),
+                        float(self.qk_norm_eps) if self.qk_gamma_q is not None else 0.0, 0)
+
+    def _gain(self, g):
+        if g.dtype != torch.float32 or tuple(g.shape) != (self.d,) or not g.is_contiguous() or not g.is_cuda:
+            raise ValueError(f"QK-norm gain: need contiguous cuda float32 ({self.d},)")
+        return g.data_ptr()
 
     @property
     def kv_len(self) -> int:

@@ -24,6 +24,22 @@ inline int mean_chunk_rows(int heads, int N) {
   return rows;
 }
 
+// ---- QK-norm fused into the pre-pass (paper Sec. 4, "Stabilizing Outliers with QK-Norm") ----------
+// y = x / sqrt(mean_c x^2 + eps) * gamma per token, rounded to bf16: the tensor a bf16 model hands to the
+// attention, so the fused pre-pass gives the bits of "normalise, then quantise".  Arithmetic (part of the
+// bit-exact contract): sum of squares in float64 (exact for bf16 inputs), r = 1 / sqrt(sum / D + eps) in
+// float64 rounded once to FP32, y = bf16((x *_f32 r) *_f32 gamma).
+struct QkNorm {
+  const float* gamma;   // [D] per-channel gain, or nullptr: no normalisation
+  float eps;
+};
+__device__ __forceinline__ float qknorm_rscale(double sumsq, int D, float eps) {
+  return (float)(1.0 / sqrt(sumsq / (double)D + (double)eps));
+}
+__device__ __forceinline__ float qknorm_apply(float x, float r, float g) {
+  return bf16_bits_to_float(float_to_bf16_bits((x * r) * g));
+}
+
 // ---- K mean, stage 1: float64 column sums of a chunk of rows -----------------------
 // (bf16 data of ordinary range sum exactly in float64, so the result does not depend on the order
 // or on the chunk size.)  Stage 2, the sum over the chunks, the division by N and the one rounding to
@@ -31,7 +47,7 @@ inline int mean_chunk_rows(int heads, int N) {
 template <int D>
 __global__ void __launch_bounds__(256) kmean_partial_kernel(const unsigned short* __restrict__ K, RowView view,
                                                             double* __restrict__ kpart, int N,
-                                                            int nchunk, int chunk_rows) {
+                                                            int nchunk, int chunk_rows, QkNorm norm) {
   constexpr int TPR = D / 8;          // threads per row, 8 channels (16 bytes) each
   constexpr int RPP = 256 / TPR;      // rows per pass
   __shared__ double red[256][8];
@@ -45,6 +61,31 @@ __global__ void __launch_bounds__(256) kmean_partial_kernel(const unsigned short
   for (int e = 0; e < 8; e++) acc[e] = 0.0;
   const int tr = t / TPR, tc = t % TPR;
   int r = tr;
+  if (norm.gamma != nullptr) {
+    // the mean is taken over the normalised keys: the TPR threads of a row share its sum of squares
+    float g[8];
+#pragma unroll
+    for (int e = 0; e < 8; e++) g[e] = norm.gamma[tc * 8 + e];
+    for (int r0 = 0; r0 < rows; r0 += RPP) {      // whole passes: the shuffles need every lane
+      r = r0 + tr;
+      v8us v = {0, 0, 0, 0, 0, 0, 0, 0};
+      if (r < rows) v = *(const v8us*)(base + (size_t)r * view.row_stride + tc * 8);
+      double ss = 0.0;
+#pragma unroll
+      for (int e = 0; e < 8; e++) {
+        const float x = bf16_bits_to_float(v[e]);
+        ss += (double)(x * x);
+      }
+#pragma unroll
+      for (int off = 1; off < TPR; off <<= 1) ss += __shfl_xor(ss, off, 64);
+      if (r < rows) {
+        const float rs = qknorm_rscale(ss, D, norm.eps);
+#pragma unroll
+        for (int e = 0; e < 8; e++) acc[e] += (double)qknorm_apply(bf16_bits_to_float(v[e]), rs, g[e]);
+      }
+    }
+    r = rows;   // nothing left for the plain loops below
+  }
   // four independent 16-byte loads in flight per thread
   for (; r + 3 * RPP < rows; r += 4 * RPP) {
     v8us v[4];
@@ -93,6 +134,8 @@ struct QuantJob {
   float* delta;                // [BH, N]: -rowsum(src o O)
   const float* lse;            // [BH, N] or nullptr: nl2 = -lse * log2(e) for the backward
   float* nl2;                  // [BH, N]
+  QkNorm norm;                 // QK-norm applied to src before anything else (Q and K jobs), or gamma == nullptr
+  unsigned short* norm_out;    // if set: the normalised rows as dense bf16 [BH, Np, D] (for the Q-smoothing bias)
 };
 struct QuantJobs {
   QuantJob job[4];
@@ -137,6 +180,37 @@ __global__ void __launch_bounds__(256) prepass_quant_kernel(QuantJobs jobs) {
     for (int e = 0; e < 8; e++) {
       x[it][e] = bf16_bits_to_float(lo[e]);
       x[it][8 + e] = bf16_bits_to_float(hi[e]);
+    }
+  }
+
+  if (jb.norm.gamma != nullptr) {
+    // QK-norm: the CPR threads of a row (consecutive lanes) share its sum of squares
+#pragma unroll
+    for (int it = 0; it < NCH; it++) {
+      const int c = t + 256 * it;
+      const int row = c / CPR, ch = c % CPR;
+      double ss = 0.0;
+#pragma unroll
+      for (int e = 0; e < 16; e++) ss += (double)(x[it][e] * x[it][e]);
+#pragma unroll
+      for (int off = 1; off < CPR; off <<= 1) ss += __shfl_xor(ss, off, 64);
+      if (row < rows_here) {
+        const float rs = qknorm_rscale(ss, D, jb.norm.eps);
+        const float* g = jb.norm.gamma + ch * 16;
+#pragma unroll
+        for (int e = 0; e < 16; e++) x[it][e] = qknorm_apply(x[it][e], rs, g[e]);
+      }
+      if (jb.norm_out != nullptr) {
+        v8us lo, hi;
+#pragma unroll
+        for (int e = 0; e < 8; e++) {
+          lo[e] = float_to_bf16_bits(x[it][e]);        // exact: the values are bf16 already (zero in missing rows)
+          hi[e] = float_to_bf16_bits(x[it][8 + e]);
+        }
+        unsigned short* o = jb.norm_out + ((size_t)bh * Np + (size_t)blk * kBlock + row) * D + ch * 16;
+        *(v8us*)o = lo;
+        *(v8us*)(o + 8) = hi;
+      }
     }
   }
 

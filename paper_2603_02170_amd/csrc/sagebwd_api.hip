@@ -73,6 +73,7 @@ struct Workspace {
   size_t kpart, muK, muQ, sQ, sK, sV;
   size_t QF, KF, VT;        // forward operands (QF, KF also feed the backward's S recompute)
   size_t bias;              // Q-smoothing: logit bias table [BH, N/64, N]
+  size_t Knorm;             // QK-norm with Q-smoothing: the normalised K as dense bf16 [BH, Nk, d] (the bias kernel reads it)
   size_t QT, KT;            // backward operands (TF layouts) that depend on Q and K only
   size_t fwd_total;         // the forward's need (with SAGEBWD_FLAG_SHARE_QUANTIZED it includes QT, KT)
   size_t sdO, delta, nl2, dOT;
@@ -105,6 +106,7 @@ Workspace make_layout(const sagebwd_params& p) {
   w.KF = take(BH * Nk * d);
   w.VT = take(BH * Nk * d);
   w.bias = take(qs ? BH * nqblk * Nk * 4 : 0);
+  w.Knorm = take(qs && (p.flags & SAGEBWD_FLAG_QK_NORM) ? BH * Nk * d * 2 : 0);
   if (!share) w.fwd_total = off;
   w.QT = take(BH * Nq * d);
   w.KT = take(BH * Nk * d);
@@ -135,7 +137,14 @@ int check_params(const sagebwd_params* p) {
   if (p == nullptr) return SAGEBWD_INVALID_ARG;
   if (p->B <= 0 || p->H <= 0 || p->N <= 0 || p->d <= 0) return SAGEBWD_INVALID_ARG;
   if (p->layout != SAGEBWD_LAYOUT_BHND && p->layout != SAGEBWD_LAYOUT_BNHD) return SAGEBWD_INVALID_ARG;
-  if ((p->flags & ~SAGEBWD_FLAG_SHARE_QUANTIZED) != 0 || p->Nkv < 0) return SAGEBWD_INVALID_ARG;
+  if ((p->flags & ~(SAGEBWD_FLAG_SHARE_QUANTIZED | SAGEBWD_FLAG_QK_NORM)) != 0 || p->Nkv < 0 || p->reserved != 0)
+    return SAGEBWD_INVALID_ARG;
+  if (p->flags & SAGEBWD_FLAG_QK_NORM) {
+    if (p->qk_gamma_q == nullptr || p->qk_gamma_k == nullptr || !(p->qk_norm_eps >= 0.f) || isinf(p->qk_norm_eps))
+      return SAGEBWD_INVALID_ARG;
+  } else if (p->qk_gamma_q != nullptr || p->qk_gamma_k != nullptr) {
+    return SAGEBWD_INVALID_ARG;
+  }
   if (p->bq < 0 || p->bkv < 0) return SAGEBWD_INVALID_ARG;
   if ((p->smooth & ~(SAGEBWD_SMOOTH_K | SAGEBWD_SMOOTH_Q)) != 0) return SAGEBWD_INVALID_ARG;
   if (p->causal != 0 && p->causal != 1) return SAGEBWD_INVALID_ARG;
@@ -210,10 +219,13 @@ int run_prepass(const void* Q, const void* K, const void* V, const void* dO, con
   const bool qs = (p.smooth & SAGEBWD_SMOOTH_Q) != 0;
   const RowView qview = caller_view(p, 1, Nq), kview = caller_view(p, 1, Nk);     // in bf16 elements
   float* muK = (float*)(ws + w.muK);
+  const bool qkn = (p.flags & SAGEBWD_FLAG_QK_NORM) != 0;
+  const QkNorm norm_q{qkn ? p.qk_gamma_q : nullptr, p.qk_norm_eps}, norm_k{qkn ? p.qk_gamma_k : nullptr, p.qk_norm_eps};
   if (want_qk) {
     if (ks) {
       kmean_partial_kernel<D><<<dim3(w.nchunk, BH), 256, 0, st>>>((const unsigned short*)K, kview,
-                                                                   (double*)(ws + w.kpart), Nk, w.nchunk, w.chunk_rows);
+                                                                   (double*)(ws + w.kpart), Nk, w.nchunk, w.chunk_rows,
+                                                                   norm_k);
       SAGE_LAUNCH_CHECK();
     } else {
       fill_zero_f32_kernel<<<(BH * D + 255) / 256, 256, 0, st>>>(muK, (size_t)BH * D);
@@ -236,6 +248,8 @@ int run_prepass(const void* Q, const void* K, const void* V, const void* dO, con
     jobs.job[nj].mean_part = ks ? (const double*)(ws + w.kpart) : nullptr;
     jobs.job[nj].nchunk = w.nchunk;
     jobs.job[nj].mu_head_out = muK;
+    jobs.job[nj].norm = norm_k;
+    jobs.job[nj].norm_out = (qkn && qs) ? (unsigned short*)(ws + w.Knorm) : nullptr;
     nj++;
     // Q: F layout (S = Q^ K^^T in both passes) and, for the backward, TF layout (dK = dS^^T Q^)
     q_like(jobs.job[nj]);
@@ -244,6 +258,7 @@ int run_prepass(const void* Q, const void* K, const void* V, const void* dO, con
     jobs.job[nj].outTF = want_tf ? (int8_t*)(ws + w.QT) : nullptr;
     jobs.job[nj].scale = (float*)(ws + w.sQ);
     jobs.job[nj].mu_block_out = qs ? (float*)(ws + w.muQ) : nullptr;
+    jobs.job[nj].norm = norm_q;
     nj++;
   }
   if (want_v) {
@@ -273,9 +288,13 @@ int run_prepass(const void* Q, const void* K, const void* V, const void* dO, con
   }
   if (qs && want_qk) {
     const float sl2 = logit_scale(p) * 1.4426950408889634f;
+    // with QK-norm the bias is formed from the normalised keys, which the quantiser's K blocks left in the workspace
+    RowView dense;
+    dense.H = p.H;
+    dense.batch_stride = (size_t)p.H * Nkp * D; dense.head_stride = (size_t)Nkp * D; dense.row_stride = D;
     qsmooth_bias_kernel<D><<<dim3(Nkp / 64, BH), 256, 0, st>>>(
-        (const unsigned short*)K, kview, muK, (const float*)(ws + w.muQ), (float*)(ws + w.bias), Nk, Nkp, Nqp / 64,
-        p.causal ? (Nk - Nq) / 64 : -1, sl2);
+        qkn ? (const unsigned short*)(ws + w.Knorm) : (const unsigned short*)K, qkn ? dense : kview, muK,
+        (const float*)(ws + w.muQ), (float*)(ws + w.bias), Nk, Nkp, Nqp / 64, p.causal ? (Nk - Nq) / 64 : -1, sl2);
     SAGE_LAUNCH_CHECK();
   }
   return SAGEBWD_OK;

@@ -99,6 +99,17 @@ def test_entry_points_reject_bad_arguments_on_the_host(lib):
     bad = SageParams(1, 2, 128, 64).c()
     bad.Nkv = -64
     assert lib.sagebwd_fwd(one, one, one, one, one, ctypes.byref(bad), one, 1 << 30, null) == -1
+    # QK-norm fused into the pre-pass: both gains with the flag, none without it, eps >= 0
+    c = SageParams(1, 2, 128, 64).c()
+    c.flags = binding.FLAG_QK_NORM
+    assert lib.sagebwd_fwd(one, one, one, one, one, ctypes.byref(c), one, 16, null) == -1
+    c.qk_gamma_q, c.qk_gamma_k = 256, 256
+    assert lib.sagebwd_fwd(one, one, one, one, one, ctypes.byref(c), one, 16, null) == -3
+    c.qk_norm_eps = -1.0
+    assert lib.sagebwd_fwd(one, one, one, one, one, ctypes.byref(c), one, 16, null) == -1
+    c = SageParams(1, 2, 128, 64).c()
+    c.qk_gamma_k = 256
+    assert lib.sagebwd_fwd(one, one, one, one, one, ctypes.byref(c), one, 16, null) == -1
     # N_q != N_kv: under the mask the keys must be at least as many and differ by whole blocks
     for nkv, causal, want in ((64, True, -2), (200, True, -2), (192, True, -3), (64, False, -3), (1000, False, -3)):
         c = SageParams(1, 2, 128, 64, causal=causal, Nkv=nkv).c()

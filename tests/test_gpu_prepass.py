@@ -107,3 +107,73 @@ def test_prepass_bit_exact_non_square(Nq, Nk, d, q_smooth):
     K, V = (torch.randn(1, 2, Nk, d, generator=g).to(torch.bfloat16) for _ in range(2))
     K = (K.float() + torch.randn(1, 2, 1, d, generator=g) * 4).to(torch.bfloat16)
     _run_case(Q, K, V, dO, binding.SageParams(1, 2, Nq, d, causal=False, q_smooth=q_smooth, Nkv=Nk))
+
+
+def _qk_norm_case(N, d, H, q_smooth, k_smooth, Nk=0, eps=1e-6, seed=0):
+    g = torch.Generator().manual_seed(900 + seed)
+    Nk_ = Nk or N
+    Q, dO = (torch.randn(1, H, N, d, generator=g) * 3 for _ in range(2))
+    K, V = (torch.randn(1, H, Nk_, d, generator=g) * 3 for _ in range(2))
+    K = K + torch.randn(1, H, 1, d, generator=g) * 4                       # channel offsets survive the normalisation
+    Q = Q * torch.exp(torch.randn(1, H, N, 1, generator=g))                # token norms spread over a decade
+    Q, K, V, dO = (t.to(torch.bfloat16) for t in (Q, K, V, dO))
+    gq = (torch.rand(d, generator=g) + 0.5).float()
+    gk = (torch.rand(d, generator=g) * 2 + 0.25).float()
+    return Q, K, V, dO, gq, gk
+
+
+@pytest.mark.parametrize("N,d,q_smooth,k_smooth,Nk", [(128, 64, False, True, 0), (300, 128, True, True, 0), (100, 128, False, False, 0),
+                                                      (64, 64, True, True, 256), (1000, 128, False, True, 0)])
+def test_prepass_qk_norm_fused_is_bit_exact(N, d, q_smooth, k_smooth, Nk):
+    """SAGEBWD_FLAG_QK_NORM: the pre-pass normalises Q and K (RMS norm with a gain per channel, Sec. 4) before
+    smoothing and quantising them.  Codes, scales and means must equal the oracle's pre-pass run on the
+    oracle's normalised tensors bit for bit."""
+    Q, K, V, dO, gq, gk = _qk_norm_case(N, d, 2, q_smooth, k_smooth, Nk, seed=N + d)
+    Qn = np.stack([oracle.qk_norm(to_np(Q)[0, h], gq.numpy(), 1e-6) for h in range(2)])[None]
+    Kn = np.stack([oracle.qk_norm(to_np(K)[0, h], gk.numpy(), 1e-6) for h in range(2)])[None]
+    p = binding.SageParams(1, 2, N, d, causal=False, q_smooth=q_smooth, k_smooth=k_smooth, Nkv=Nk,
+                           qk_gamma_q=gq.cuda(), qk_gamma_k=gk.cuda(), qk_norm_eps=1e-6)
+    ws = binding.alloc_workspace(p)
+    ws.fill_(0x5A)
+    binding.sagebwd_quantize(Q.cuda(), K.cuda(), V.cuda(), p, ws, dO=dO.cuda(), O=dO.cuda())
+    ref = _oracle_prepass(Qn, Kn, to_np(V), to_np(dO), p)
+    for which, qn, sn in ((binding.TENSOR_Q, "Qh", "sQ"), (binding.TENSOR_K, "Kh", "sK"),
+                          (binding.TENSOR_V, "Vh", "sV"), (binding.TENSOR_DO, "dOh", "sdO")):
+        q, s = binding.sagebwd_export_quantized(p, ws, which)
+        assert np.array_equal(q.cpu().numpy(), ref[qn]), qn
+        assert np.array_equal(s.cpu().numpy().view(np.uint32), ref[sn].view(np.uint32)), sn
+    muK, muQ, _ = binding.sagebwd_export_stats(p, ws)
+    assert np.array_equal(muK.cpu().numpy().view(np.uint32), ref["muK"].view(np.uint32))
+    if q_smooth:
+        assert np.array_equal(muQ.cpu().numpy().view(np.uint32), ref["muQ"].view(np.uint32))
+
+
+@pytest.mark.parametrize("N,d,causal,q_smooth", [(320, 128, True, False), (200, 64, False, True), (448, 128, True, True)])
+def test_qk_norm_fused_gives_the_bits_of_normalise_then_attend(N, d, causal, q_smooth):
+    """Forward and backward with the fused normalisation equal, bit for bit, the calls without it on
+    the normalised bf16 tensors (which the oracle's normalisation supplies)."""
+    H = 3
+    Q, K, V, dO, gq, gk = _qk_norm_case(N, d, H, q_smooth, True, seed=3 * N + d)
+    Qn = torch.from_numpy(np.stack([oracle.qk_norm(to_np(Q)[0, h], gq.numpy(), 1e-6) for h in range(H)])[None]).to(torch.bfloat16)
+    Kn = torch.from_numpy(np.stack([oracle.qk_norm(to_np(K)[0, h], gk.numpy(), 1e-6) for h in range(H)])[None]).to(torch.bfloat16)
+    kw = dict(causal=causal, q_smooth=q_smooth)
+    pf = binding.SageParams(1, H, N, d, qk_gamma_q=gq.cuda(), qk_gamma_k=gk.cuda(), qk_norm_eps=1e-6, **kw)
+    pu = binding.SageParams(1, H, N, d, **kw)
+    Vd, dOd = V.cuda(), dO.cuda()
+    Of, Lf = binding.sagebwd_fwd(Q.cuda(), K.cuda(), Vd, pf)
+    gf = binding.sagebwd_bwd(Q.cuda(), K.cuda(), Vd, Of, dOd, Lf, pf)
+    Ou, Lu = binding.sagebwd_fwd(Qn.cuda(), Kn.cuda(), Vd, pu)
+    gu = binding.sagebwd_bwd(Qn.cuda(), Kn.cuda(), Vd, Ou, dOd, Lu, pu)
+    torch.cuda.synchronize()
+    assert torch.equal(Of, Ou) and torch.equal(Lf, Lu)
+    for a, b, name in zip(gf, gu, ("dQ", "dK", "dV")):
+        assert torch.equal(a, b), name
+    # and with the backward taking the quantised (normalised) Q, K from the forward
+    ps = binding.SageParams(1, H, N, d, qk_gamma_q=gq.cuda(), qk_gamma_k=gk.cuda(), qk_norm_eps=1e-6, share_quantized=True, **kw)
+    ws = binding.alloc_workspace(ps)
+    Os, Ls = binding.sagebwd_fwd(Q.cuda(), K.cuda(), Vd, ps, ws)
+    gs = binding.sagebwd_bwd(Q.cuda(), K.cuda(), Vd, Os, dOd, Ls, ps, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(Os, Ou)
+    for a, b in zip(gs, gu):
+        assert torch.equal(a, b)

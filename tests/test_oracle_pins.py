@@ -44,6 +44,31 @@ def test_round_to_bf16_matches_definition():
     assert np.array_equal(oracle.round_to_bf16(x), ref)
 
 
+def test_qk_norm_closed_forms():
+    """RMS normalisation (Sec. 4, QK-norm): a row of equal values maps to +-gamma / sqrt(1 + eps / v^2),
+    a scaled row gives the same result (eps = 0), the mean square of the output is 1 (unit gain) up to
+    the bf16 rounding, and torch's own rms_norm agrees to one bf16 step."""
+    d = 64
+    g = np.linspace(0.5, 2.0, d).astype(np.float32)
+    X = np.full((3, d), 4.0, dtype=np.float32)
+    X[1] = -0.5
+    X[2, ::2] = -4.0
+    y = oracle.qk_norm(X, g, eps=0.0)
+    assert np.array_equal(y[0], _bf(g)) and np.array_equal(y[1], _bf(-g)) and np.array_equal(np.abs(y[2]), _bf(g))
+    y = oracle.qk_norm(X, g, eps=1e-6)
+    assert np.array_equal(y[1], _bf((-np.float32(1 / np.sqrt(0.25 + 1e-6)) * np.float32(0.5)) * g))
+    rng = np.random.default_rng(90)
+    Z = _bf(rng.standard_normal((200, d)) * 3)
+    a, b = oracle.qk_norm(Z, g, eps=0.0), oracle.qk_norm(_bf(Z * 4), g, eps=0.0)     # x4 is exact in bf16
+    assert np.array_equal(a, b)
+    u = oracle.qk_norm(Z, np.ones(d), eps=0.0).astype(np.float64)
+    assert np.abs((u ** 2).mean(axis=1) - 1).max() < 2 ** -7
+    torch = pytest.importorskip("torch")
+    ref = torch.nn.functional.rms_norm(torch.from_numpy(Z), (d,), torch.from_numpy(g), eps=1e-6).to(torch.bfloat16).float().numpy()
+    got = oracle.qk_norm(Z, g, eps=1e-6)
+    assert np.abs(got - ref).max() <= np.abs(ref).max() * 2 ** -7 and (got == ref).mean() > 0.99
+
+
 # ------------------------------------------------------------- the quantiser
 def test_quantiser_bound_and_extremes():
     # Sec. 3 "Quantization": |x - delta*q| <= delta/2 and the absmax element maps to +-127
