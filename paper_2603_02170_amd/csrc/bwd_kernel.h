@@ -51,7 +51,7 @@ struct BwdArgs {
   const float* muQ;    // Q-smoothing block means [BH, N/64, D] or nullptr
   int8_t* dSq;         // psi(dS) tiles [heads, N/64, ds_pitch, 4096], A fragments (q block, key step)
   int ds_pitch;        // tiles per Q-block row of that array (>= N/64)
-  float* sdS;          // their scales [heads, N/64, N/64]
+  float* sdS;          // their scales [heads, N/64, ds_pitch]
   int bh0;             // first head of this launch (the scratch above is indexed from it)
   unsigned short* dK;  // bf16 [BH, N, D]
   unsigned short* dV;
@@ -90,12 +90,12 @@ struct BwdExchange {          // per group of 4 waves and tile parity
   int8_t dsb[4096];           // psi(dS) B fragments
 };
 
-// phase A element-wise work of one quadrant (`dp` holds dP - delta); MASK = some entries of the tile are masked: query row
+// phase A element-wise work of one quadrant (`dp` holds dP - delta, or dP with -delta passed in `dl`); MASK = some entries of the tile are masked: query row
 // qrow0 + 8 aa + b of the tile sees key column kcol only up to column klim_row (the row itself on
 // the causal diagonal, 63 elsewhere) and only if the key exists (kcol < kvalid)
 template <bool MASK, bool QSMOOTH>
 __device__ __forceinline__ void bwd_quadrant(const v16i& sacc, const v16f& dp, const float* __restrict__ nl2,
-                                             const float c, const float bias_l,
+                                             const float* __restrict__ dl, const float c, const float bias_l,
                                              const int qrow0, const int kcol, const bool diag, const int kvalid,
                                              float (&p)[16], float (&ds)[16], float& pm, float& dm, float& cs) {
   float pm2[2] = {0.f, 0.f}, dm2[2] = {0.f, 0.f};
@@ -103,13 +103,16 @@ __device__ __forceinline__ void bwd_quadrant(const v16i& sacc, const v16f& dp, c
 #pragma unroll
   for (int aa = 0; aa < 4; aa++) {
     const v4f l4 = *(const v4f*)(nl2 + 8 * aa);
+    v4f d4 = {0.f, 0.f, 0.f, 0.f};
+    if constexpr (QSMOOTH) d4 = *(const v4f*)(dl + 8 * aa);     // -delta
 #pragma unroll
     for (int b = 0; b < 4; b++) {
       const int r = 4 * aa + b;
       const float off = QSMOOTH ? bias_l + l4[b] : l4[b];
       float pv = __builtin_amdgcn_exp2f(__builtin_fmaf((float)sacc[r], c, off));
       if constexpr (MASK) pv = ((diag && (qrow0 + 8 * aa + b) < kcol) || kcol >= kvalid) ? 0.f : pv;
-      const float dsv = pv * dp[r];       // the dP accumulators started from -delta
+      // (without Q-smoothing the dP accumulators started from -delta)
+      const float dsv = QSMOOTH ? pv * (dp[r] + d4[b]) : pv * dp[r];
       p[r] = pv;
       ds[r] = dsv;
       pm2[aa & 1] = fmaxf(pm2[aa & 1], pv);
@@ -349,14 +352,16 @@ __global__ void __launch_bounds__(512, 1) sage_bwd_kernel(BwdArgs args) {
       // an A operand, `df` is the matrix (key, permuted query); one MFMA against the matching
       // permutation matrix returns it transposed in the accumulator: lane = query, registers =
       // keys in the order of the TF layout of K^.  The low bytes of the INT32 results are the codes.
-      // (Issued before psi(P) is formed, so that its latency passes under that work.)
+      // (Issued before psi(P) is formed, so that its latency passes under that work; with Q-smoothing
+      // psi(P) comes first: no 16 registers to spare there.)
       v16i tr;
-      {
+      auto transpose = [&]() __attribute__((always_inline)) {
         v16i z;
 #pragma unroll
         for (int r = 0; r < 16; r++) z[r] = 0;
         tr = __builtin_amdgcn_mfma_i32_32x32x32_i8(df, tperm, z, 0, 0, 0);
-      }
+      };
+      if constexpr (!QSMOOTH) transpose();
 #pragma unroll
       for (int aa = 0; aa < 4; aa++) {
         unsigned up = 0;
@@ -364,6 +369,7 @@ __global__ void __launch_bounds__(512, 1) sage_bwd_kernel(BwdArgs args) {
         for (int b = 0; b < 4; b++) up = __builtin_amdgcn_cvt_pk_u8_f32(p[4 * aa + b] * rP, b, up);
         pf[aa] = (int)up;
       }
+      if constexpr (QSMOOTH) transpose();
       *(v4i*)(X.pb + ((qb * 2 + kb) * 64 + lane) * 16) = pf;
       *(v4i*)(X.dsb + ((qb * 2 + kb) * 64 + lane) * 16) = df;
       {
@@ -374,9 +380,9 @@ __global__ void __launch_bounds__(512, 1) sage_bwd_kernel(BwdArgs args) {
           const unsigned hi = __builtin_amdgcn_perm((unsigned)tr[4 * aa + 3], (unsigned)tr[4 * aa + 2], 0x04000c0cu);
           o[aa] = (int)(lo | hi);
         }
-        const size_t tile = ((size_t)hl * nqblk + iq) * nblk + j;
-        const size_t slot = ((size_t)hl * nqblk + iq) * args.ds_pitch + j;
-        *(v4i*)(args.dSq + slot * 4096 + ((qb * 2 + kb) * 64 + lane) * 16) = o;
+        // (tiles and scales share one index: a second index product costs the Q-smoothing instantiation a spill)
+        const size_t tile = ((size_t)hl * nqblk + iq) * args.ds_pitch + j;
+        *(v4i*)(args.dSq + tile * 4096 + ((qb * 2 + kb) * 64 + lane) * 16) = o;
         args.sdS[tile] = sS_q;   // the same value from every lane: no branch
       }
     }
@@ -406,8 +412,13 @@ __global__ void __launch_bounds__(512, 1) sage_bwd_kernel(BwdArgs args) {
       v16i sacc;
       v16f dp;
       // dS = P o (dP - delta): the dP chain starts from -delta of the rows this lane's registers hold
-      // (register 4a + b = query 8a + 4h + b of the quadrant), which saves the subtraction per entry
-      {
+      // (register 4a + b = query 8a + 4h + b of the quadrant), which saves the subtraction per entry.
+      // (Not with Q-smoothing: that instantiation has no register to spare, and anything that lengthens
+      // a live range there ends in a scratch access inside the loop, whose wait drains the staging copies.)
+      if constexpr (QSMOOTH) {
+#pragma unroll
+        for (int r = 0; r < 16; r++) dp[r] = 0.f;
+      } else {
         const float* dl = st.dl + 32 * qb + 4 * h;
 #pragma unroll
         for (int aa = 0; aa < 4; aa++) {
@@ -432,10 +443,10 @@ __global__ void __launch_bounds__(512, 1) sage_bwd_kernel(BwdArgs args) {
       const float* nl2 = st.nl2 + 32 * qb + 4 * h;
       float pm, dm, cs;
       if (!STEADY && ((CAUSAL && ia + sb == j) || kvalid < 64))
-        bwd_quadrant<true, QSMOOTH>(sacc, dp, nl2, c, bias_l, 32 * qb + 4 * h, 32 * kb + ll, CAUSAL && ia + sb == j, kvalid,
+        bwd_quadrant<true, QSMOOTH>(sacc, dp, nl2, st.dl + 32 * qb + 4 * h, c, bias_l, 32 * qb + 4 * h, 32 * kb + ll, CAUSAL && ia + sb == j, kvalid,
                                     p, ds, pm, dm, cs);
       else
-        bwd_quadrant<false, QSMOOTH>(sacc, dp, nl2, c, bias_l, 0, 0, false, 64, p, ds, pm, dm, cs);
+        bwd_quadrant<false, QSMOOTH>(sacc, dp, nl2, st.dl + 32 * qb + 4 * h, c, bias_l, 0, 0, false, 64, p, ds, pm, dm, cs);
       pm = wave_max_nonneg_f32(pm);
       dm = wave_max_nonneg_f32(dm);
       // every lane stores the same pair (one LDS write, no branch)
@@ -600,7 +611,7 @@ __global__ void __launch_bounds__(256, 3) sage_bwd_dq_kernel(DqArgs args) {
   const int8_t* dsw = args.dSq + ((size_t)hl * nqblk + i) * args.ds_pitch * DSB + qb * 2048 + lane * 16;
   const int8_t* kth = args.KT + head + wave * 1024 + lane * 16;
   // per stage lanes 0, 1, 2 fetch s_dS of Q block 0, s_dS of Q block 1, s_K
-  const size_t sc_off = lane == 0 ? ((size_t)hl * nqblk + i0) * nblk : ((size_t)hl * nqblk + i1) * nblk;
+  const size_t sc_off = lane == 0 ? ((size_t)hl * nqblk + i0) * args.ds_pitch : ((size_t)hl * nqblk + i1) * args.ds_pitch;
   const float* sc_src = lane < 2 ? args.sdS + sc_off : args.sK + (size_t)bh * nblk;
 
   // Stage indices past the end are clamped: the loads then re-read the last stage (into registers or a

@@ -501,7 +501,7 @@ __global__ void export_ds_kernel(const int8_t* __restrict__ tiles, const float* 
 #pragma unroll
     for (int a = 0; a < 4; a++) *(int*)(ds_out + (size_t)qrow * Np + key + 8 * a) = v[a];
   }
-  if (scale_out != nullptr && c % 256 == 0) scale_out[tile] = there ? scales[tile] : 0.f;
+  if (scale_out != nullptr && c % 256 == 0) scale_out[tile] = there ? scales[(size_t)i * pitch + j] : 0.f;
 }
 
 }  // namespace sage

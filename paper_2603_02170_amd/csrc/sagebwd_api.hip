@@ -78,7 +78,7 @@ struct Workspace {
   size_t fwd_total;         // the forward's need (with SAGEBWD_FLAG_SHARE_QUANTIZED it includes QT, KT)
   size_t sdO, delta, nl2, dOT;
   size_t dSq;               // psi(dS) tiles of one head group [heads_per_group, N/64, N/64, 4096]
-  size_t sdS;               // their scales [heads_per_group, N/64, N/64]
+  size_t sdS;               // their scales [heads_per_group, N/64, ds_pitch]
   int heads_per_group;      // the backward runs in groups of heads that share the dS scratch
   int ds_pitch;             // tiles per Q-block row of the dS scratch
   size_t total;
@@ -128,7 +128,7 @@ Workspace make_layout(const sagebwd_params& p) {
   if (hpg > BH) hpg = BH;
   w.heads_per_group = (int)hpg;
   w.dSq = take(hpg * ds_head);
-  w.sdS = take(hpg * nqblk * nkblk * 4);
+  w.sdS = take(hpg * nqblk * (size_t)w.ds_pitch * 4);
   w.total = off;
   return w;
 }
@@ -515,7 +515,7 @@ int sagebwd_export_ds(const sagebwd_params* params, const void* workspace, size_
   const size_t n = (size_t)nqblk * nkblk * 256;
   export_ds_kernel<<<(unsigned)((n + 255) / 256), 256, 0, (hipStream_t)stream>>>(
       (const int8_t*)(ws + w.dSq) + (size_t)head * nqblk * w.ds_pitch * 4096,
-      (const float*)(ws + w.sdS) + (size_t)head * nqblk * nkblk, ds_out, scale_out, nqblk, Nkp, w.ds_pitch,
+      (const float*)(ws + w.sdS) + (size_t)head * nqblk * w.ds_pitch, ds_out, scale_out, nqblk, Nkp, w.ds_pitch,
       params->causal ? (kv_len(*params) - params->N) / 64 : -1);
   SAGE_LAUNCH_CHECK();
   return SAGEBWD_OK;
