@@ -9,7 +9,7 @@
 //            P = exp(S - L), dS = P o (dP - delta), kept in registers; the wave maxima of P and
 //            |dS| go to LDS.
 //   phase Q  with the tile-wide maxima: psi(P), psi(dS) to LDS as MFMA operand fragments, and
-//            psi(dS) transposed (one MFMA against a permutation matrix) to the scratch buffer.
+//            the psi(dS) fragments also to the scratch buffer (the dQ kernel transposes them).
 //   phase B  each wave takes one 32-channel slice of the outputs and contracts over the whole
 //            tile: dV^T += dO^^T P^, dK^T += Q^^T dS^ (accumulated in FP32 registers with the
 //            per-tile scales).
@@ -24,7 +24,9 @@
 // S is formed untransposed (queries x keys): an accumulator lane then holds one key and 16
 // queries, which is the B-operand form of the two contractions over queries (dV, dK).  The
 // contraction over keys (dQ) needs dS^ with one query per lane; scattering it bytewise through
-// LDS cost more LDS time than all operand reads together, hence the transposing MFMA.
+// LDS cost more LDS time than all operand reads together, hence a transposing MFMA (one matrix
+// instruction against a permutation matrix), which runs in the dQ kernel: that kernel waits for
+// memory and has the issue slots to spare, this one does not.
 #pragma once
 
 #include <type_traits>
@@ -49,7 +51,7 @@ struct BwdArgs {
   const float* delta;  // [BH, N]  -rowsum(dO o O)
   const float* bias;   // Q-smoothing logit bias [BH, N/64, N] (log2 domain) or nullptr
   const float* muQ;    // Q-smoothing block means [BH, N/64, D] or nullptr
-  int8_t* dSq;         // psi(dS) tiles [heads, N/64, ds_pitch, 4096], A fragments (q block, key step)
+  int8_t* dSq;         // psi(dS) tiles [heads, N/64, ds_pitch, 4096]: the four quadrant fragments as phase Q forms them
   int ds_pitch;        // tiles per Q-block row of that array (>= N/64)
   float* sdS;          // their scales [heads, N/64, ds_pitch]
   int bh0;             // first head of this launch (the scratch above is indexed from it)
@@ -225,18 +227,6 @@ __global__ void __launch_bounds__(512, 1) sage_bwd_kernel(BwdArgs args) {
 
   const int i_first = CAUSAL ? max(2 * jp - sb, 0) : 0;
   const int T = nqblk - i_first;                // tile rows of this workgroup; tile t is Q block nqblk-1-t
-  // B operand of the transposing MFMA of phase Q: a quantised quadrant, read as an A operand, has
-  // contraction index k = 16h + 4a + b for the query 8a + 4h + b; column n of the permutation
-  // matrix picks the k that stands for query n.  Lane (n, hh) holds k = 16hh + t in byte t.
-  v4i tperm;
-#pragma unroll
-  for (int aa = 0; aa < 4; aa++) {
-    unsigned u = 0;
-#pragma unroll
-    for (int b = 0; b < 4; b++) u |= (unsigned)((8 * aa + 4 * h + b) == ll) << (8 * b);
-    tperm[aa] = (int)u;
-  }
-
   // Asynchronous staging (global -> LDS, no registers) of the phase-A operands of Q block i.
   // Written without branches where the fragment counts divide evenly among the 8 waves (d = 128):
   // which array a wave copies from is a compile-time fact per copy, and the small vectors are
@@ -348,20 +338,6 @@ __global__ void __launch_bounds__(512, 1) sage_bwd_kernel(BwdArgs args) {
         const unsigned hi = __builtin_amdgcn_perm(ub[3], ub[2], 0x04000c0cu);
         df[aa] = (int)(lo | hi);
       }
-      // The dQ kernel contracts over keys and needs this quadrant with one QUERY per lane.  Taken as
-      // an A operand, `df` is the matrix (key, permuted query); one MFMA against the matching
-      // permutation matrix returns it transposed in the accumulator: lane = query, registers =
-      // keys in the order of the TF layout of K^.  The low bytes of the INT32 results are the codes.
-      // (Issued before psi(P) is formed, so that its latency passes under that work; with Q-smoothing
-      // psi(P) comes first: no 16 registers to spare there.)
-      v16i tr;
-      auto transpose = [&]() __attribute__((always_inline)) {
-        v16i z;
-#pragma unroll
-        for (int r = 0; r < 16; r++) z[r] = 0;
-        tr = __builtin_amdgcn_mfma_i32_32x32x32_i8(df, tperm, z, 0, 0, 0);
-      };
-      if constexpr (!QSMOOTH) transpose();
 #pragma unroll
       for (int aa = 0; aa < 4; aa++) {
         unsigned up = 0;
@@ -369,20 +345,14 @@ __global__ void __launch_bounds__(512, 1) sage_bwd_kernel(BwdArgs args) {
         for (int b = 0; b < 4; b++) up = __builtin_amdgcn_cvt_pk_u8_f32(p[4 * aa + b] * rP, b, up);
         pf[aa] = (int)up;
       }
-      if constexpr (QSMOOTH) transpose();
       *(v4i*)(X.pb + ((qb * 2 + kb) * 64 + lane) * 16) = pf;
       *(v4i*)(X.dsb + ((qb * 2 + kb) * 64 + lane) * 16) = df;
       {
-        v4i o;
-#pragma unroll
-        for (int aa = 0; aa < 4; aa++) {
-          const unsigned lo = __builtin_amdgcn_perm((unsigned)tr[4 * aa + 1], (unsigned)tr[4 * aa], 0x0c0c0400u);
-          const unsigned hi = __builtin_amdgcn_perm((unsigned)tr[4 * aa + 3], (unsigned)tr[4 * aa + 2], 0x04000c0cu);
-          o[aa] = (int)(lo | hi);
-        }
+        // the same fragment goes to the scratch buffer for the dQ kernel: fragment (qb, kb), lane (key, h),
+        // byte 4 a + b = psi(dS)[32 qb + 8 a + 4 h + b][32 kb + key]
         // (tiles and scales share one index: a second index product costs the Q-smoothing instantiation a spill)
         const size_t tile = ((size_t)hl * nqblk + iq) * args.ds_pitch + j;
-        *(v4i*)(args.dSq + tile * 4096 + ((qb * 2 + kb) * 64 + lane) * 16) = o;
+        *(v4i*)(args.dSq + tile * 4096 + ((qb * 2 + kb) * 64 + lane) * 16) = df;
         args.sdS[tile] = sS_q;   // the same value from every lane: no branch
       }
     }
@@ -540,7 +510,7 @@ __global__ void __launch_bounds__(512, 1) sage_bwd_kernel(BwdArgs args) {
 
 // ---------------------------------------------------------------------------------
 // dQ_i = sum_j (dS^_ij K^_j) * s_dS(i,j) * s_K(j) * sm_scale        (Algorithm 2, the dQ line)
-// A = stored psi(dS) fragments, B = K^ in TF layout.
+// A = the stored psi(dS) fragments, transposed here, B = K^ in TF layout.
 struct DqArgs {
   const int8_t* dSq;
   int ds_pitch;         // tiles per Q-block row of dSq
@@ -558,9 +528,13 @@ struct DqArgs {
 };
 
 // A workgroup of 4 waves owns TWO Q blocks (128 queries) and walks the KV blocks j; wave (Q block, row half)
-// owns 32 query rows and ALL d channels.  The psi(dS) tiles are stored as the A fragments of exactly this
-// product, so each wave streams its own 2 KiB per tile from HBM straight into registers (one 16-byte load
-// per lane and fragment, nothing shared, no LDS): kStages tiles ahead.  The K^ tile (TF layout, from L2) is
+// owns 32 query rows and ALL d channels.  A stored psi(dS) fragment holds one KEY per lane and 16 queries in
+// its bytes (the form the backward kernel's own products need); the product over keys needs one QUERY per
+// lane, so each fragment is transposed on arrival by one MFMA against a permutation matrix: read as an A
+// operand it is the matrix (key, permuted query), and the accumulator comes back with lane = query and
+// registers = keys in the order of the TF layout of K^; the low bytes of the INT32 results are the codes.
+// Each wave streams its own 2 KiB per tile from HBM straight into registers (one 16-byte load per lane
+// and fragment, nothing shared, no LDS): kStages tiles ahead.  The K^ tile (TF layout, from L2) is
 // shared by the four waves and travels global -> LDS asynchronously through a ring that runs the same
 // number of stages ahead, together with the three scales of the stage; one barrier per stage.  Both
 // streams are issued by every wave in the same order and complete in order, so one count of outstanding
@@ -576,7 +550,7 @@ __global__ void __launch_bounds__(256, 3) sage_bwd_dq_kernel(DqArgs args) {
   constexpr int KS = D / 32;               // channel blocks
   constexpr int TILE = 64 * D;             // bytes of one K^ tile
   constexpr int DSB = 4096;                // bytes of one psi(dS) tile
-  constexpr int kStages = 5;               // stages in flight (3 and 7 measured the same)
+  constexpr int kStages = 4;               // stages in flight (3 to 7 measured the same)
   constexpr int NS = kStages + 1;          // ring slots
   constexpr int KSLOT = TILE + 256;        // K^ tile | s_dS of Q block 0, of Q block 1, s_K (lanes 3.. repeat s_K)
   constexpr int KC = TILE / 4096;          // K^ copies per wave and stage (the tile's 1 KiB fragments dealt to 4 waves)
@@ -637,6 +611,32 @@ __global__ void __launch_bounds__(256, 3) sage_bwd_dq_kernel(DqArgs args) {
 #pragma unroll
     for (int r = 0; r < 16; r++) acc[cb][r] = 0.f;
 
+  // B operand of the transposing MFMA: a stored fragment, read as an A operand, has contraction index
+  // k = 16 h + 4 a + b for the query 8 a + 4 h + b; column n of the permutation matrix picks the k that
+  // stands for query n.  Lane (n, hh) holds k = 16 hh + t in byte t.
+  v4i tperm;
+#pragma unroll
+  for (int aa = 0; aa < 4; aa++) {
+    unsigned u = 0;
+#pragma unroll
+    for (int b = 0; b < 4; b++) u |= (unsigned)((8 * aa + 4 * h + b) == ll) << (8 * b);
+    tperm[aa] = (int)u;
+  }
+  auto transposed = [&](const v4i& f) __attribute__((always_inline)) {
+    v16i z;
+#pragma unroll
+    for (int r = 0; r < 16; r++) z[r] = 0;
+    const v16i tr = __builtin_amdgcn_mfma_i32_32x32x32_i8(f, tperm, z, 0, 0, 0);
+    v4i o;
+#pragma unroll
+    for (int aa = 0; aa < 4; aa++) {
+      const unsigned lo = __builtin_amdgcn_perm((unsigned)tr[4 * aa + 1], (unsigned)tr[4 * aa], 0x0c0c0400u);
+      const unsigned hi = __builtin_amdgcn_perm((unsigned)tr[4 * aa + 3], (unsigned)tr[4 * aa + 2], 0x04000c0cu);
+      o[aa] = (int)(lo | hi);
+    }
+    return o;
+  };
+
   v4i a[kStages][2];
 #pragma unroll
   for (int s = 0; s < kStages; s++) {
@@ -664,6 +664,7 @@ __global__ void __launch_bounds__(256, 3) sage_bwd_dq_kernel(DqArgs args) {
         const int8_t* kp = lds + sk * KSLOT;
         const float* sc = (const float*)(kp + TILE);
         const float w = sc[iq] * sc[2] * args.sm_scale;
+        const v4i a0 = transposed(a[s][0]), a1 = transposed(a[s][1]);
 #pragma unroll
         for (int cb = 0; cb < KS; cb++) {
           const v4i b0 = *(const v4i*)(kp + cb * 1024 + lane * 16);
@@ -671,8 +672,8 @@ __global__ void __launch_bounds__(256, 3) sage_bwd_dq_kernel(DqArgs args) {
           v16i q;
 #pragma unroll
           for (int r = 0; r < 16; r++) q[r] = 0;
-          q = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[s][0], b0, q, 0, 0, 0);
-          q = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[s][1], b1, q, 0, 0, 0);
+          q = __builtin_amdgcn_mfma_i32_32x32x32_i8(a0, b0, q, 0, 0, 0);
+          q = __builtin_amdgcn_mfma_i32_32x32x32_i8(a1, b1, q, 0, 0, 0);
 #pragma unroll
           for (int r = 0; r < 16; r++) acc[cb][r] = __builtin_fmaf((float)q[r], w, acc[cb][r]);
         }

@@ -480,9 +480,9 @@ __global__ void __launch_bounds__(256) qsmooth_bias_kernel(const unsigned short*
 }
 
 // ---- inspection: the psi(dS) tiles the backward left in its scratch, as a row-major [Np, Np] matrix ----
-// Tile (i, j) holds four 1 KiB fragments (32-query block qb, 32-key step kb): lane (r, half), byte
-// 4 a + b = psi(dS)[64 i + 32 qb + r][64 j + 32 kb + 8 a + 4 half + b] (the keys of a step are in the
-// order in which the K^ operand of the dQ product holds its rows).  Tiles above the causal diagonal
+// Tile (i, j) holds four 1 KiB fragments (32-query block qb, 32-key block kb): lane (key, half), byte
+// 4 a + b = psi(dS)[64 i + 32 qb + 8 a + 4 half + b][64 j + 32 kb + key] (a quantised accumulator quadrant
+// as the backward kernel holds it).  Tiles above the causal diagonal
 // were never written: they are returned as zeros.  One thread per 16 bytes.
 __global__ void export_ds_kernel(const int8_t* __restrict__ tiles, const float* __restrict__ scales,
                                  int8_t* __restrict__ ds_out, float* __restrict__ scale_out, int nqblk, int Np,
@@ -496,10 +496,13 @@ __global__ void export_ds_kernel(const int8_t* __restrict__ tiles, const float* 
   const bool there = causal_shift < 0 || j <= i + causal_shift;
   v4i v = {0, 0, 0, 0};
   if (there) v = *(const v4i*)(tiles + ((size_t)i * pitch + j) * 4096 + (c % 256) * 16);   // `pitch` tiles per Q-block row
-  const int qrow = 64 * i + 32 * (frag >> 1) + (lane & 31), key = 64 * j + 32 * (frag & 1) + 4 * (lane >> 5);
+  // fragment (qb, kb), lane (key, h), byte 4 a + b = psi(dS)[32 qb + 8 a + 4 h + b][32 kb + key]
+  const int qrow0 = 64 * i + 32 * (frag >> 1) + 4 * (lane >> 5), key = 64 * j + 32 * (frag & 1) + (lane & 31);
   if (ds_out != nullptr) {
 #pragma unroll
-    for (int a = 0; a < 4; a++) *(int*)(ds_out + (size_t)qrow * Np + key + 8 * a) = v[a];
+    for (int a = 0; a < 4; a++)
+#pragma unroll
+      for (int b = 0; b < 4; b++) ds_out[(size_t)(qrow0 + 8 * a + b) * Np + key] = (int8_t)((v[a] >> (8 * b)) & 0xff);
   }
   if (scale_out != nullptr && c % 256 == 0) scale_out[tile] = there ? scales[(size_t)i * pitch + j] : 0.f;
 }
