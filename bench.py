@@ -65,6 +65,30 @@ def cpu_baseline(w, seconds_hint=20.0):
                       f"(NumPy float64; whole-workload estimate {t_total / heads * w.B * w.H:.0f} s)"}
 
 
+def measured_peaks(torch, binding):
+    """What this GPU sustains on the resources the rooflines name, from the library's probe kernels: a
+    dense loop of the MFMA instruction the kernels use (INT8 32x32x32, bf16 32x32x16), and 16-byte-per-lane
+    streams over 1 GiB (copy, and read only).  Context beside the published peaks, measured under the same
+    clocks and power limit as the attention kernels; run after the timed region."""
+    sink = torch.zeros(1, dtype=torch.int32, device="cuda")
+    out = {}
+    zero = binding.PROBE_MFMA_ZERO_OPERANDS
+    for name, kind in (("int8_mfma", binding.PROBE_MFMA_INT8), ("bf16_mfma", binding.PROBE_MFMA_BF16),
+                       ("int8_mfma_zero_operands", binding.PROBE_MFMA_INT8 | zero),
+                       ("bf16_mfma_zero_operands", binding.PROBE_MFMA_BF16 | zero)):
+        ms, ops = binding.sagebwd_probe_mfma(kind, iters=4096, reps=3, sink=sink)
+        out[name] = {"value": ops / (ms * 1e-3) / 1e12, "unit": "TFLOP/s" if kind & binding.PROBE_MFMA_BF16 else "TOP/s",
+                     "ms": ms}
+    src = torch.full((1 << 30,), 7, dtype=torch.uint8, device="cuda")
+    dst = torch.empty_like(src)
+    ms = binding.sagebwd_probe_stream(binding.PROBE_STREAM_COPY, src, dst, reps=5, sink=sink)
+    out["hbm_copy"] = {"value": 2 * (1 << 30) / (ms * 1e-3) / 1e9, "unit": "GB/s", "ms": ms, "note": "1 GiB read + 1 GiB written"}
+    ms = binding.sagebwd_probe_stream(binding.PROBE_STREAM_READ, src, None, reps=5, sink=sink)
+    out["hbm_read"] = {"value": (1 << 30) / (ms * 1e-3) / 1e9, "unit": "GB/s", "ms": ms, "note": "1 GiB read"}
+    del src, dst
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -147,6 +171,7 @@ def main():
         kern[name] = tot / max(n, 1)
     binding.set_timing(False)
 
+    peaks = measured_peaks(torch, binding)
     tops = work_ops(w) / (ms * 1e-3) / 1e12
     # sage_bwd_kernel runs four of the five backward matmuls (S recompute, dV, dP, dK); the fifth (dQ)
     # runs in sage_bwd_dq_kernel from the staged psi(dS) tiles
@@ -178,26 +203,32 @@ def main():
         "fwd_only": {"ms": fwd_ms, "TOPS": fwd_ops / (fwd_ms * 1e-3) / 1e12,
                      "pct_of_int8_peak": 100.0 * fwd_ops / (fwd_ms * 1e-3) / 1e12 / INT8_PEAK_TOPS},
         "kernel_ms": kern,
+        "measured_peaks": peaks,
+        "pct_of_measured_int8_peak": 100.0 * tops / peaks["int8_mfma"]["value"],
         "roofline": {"bound": "mfma", "kernel": "sage_bwd_kernel", "achieved": bwd_tops, "peak": INT8_PEAK_TOPS,
                      "unit": "TOP/s", "frac": bwd_tops / INT8_PEAK_TOPS,
                      "traffic": traffic.get("bwd"),
                      "frac_of_mixed_roof": bwd_tops / (INT8_PEAK_TOPS * 0.8),
+                     "frac_of_measured_peak": bwd_tops / peaks["int8_mfma"]["value"],
                      "note": "algorithmic ops of the four matmuls this kernel runs (8*N^2*d per head, x0.5 causal) "
                              "over its mean HIP-event duration, against the INT8 MFMA peak; one of the four (dP) "
                              "runs on bf16 MFMA at half rate, so the kernel's own mixed roof is 4/5 of that peak "
                              "(frac_of_mixed_roof).  traffic: from profiles/, not measured in this run"},
         "roofline_fwd": {"bound": "mfma", "kernel": "sage_fwd_kernel", "achieved": fwd_tops, "peak": INT8_PEAK_TOPS,
-                         "unit": "TOP/s", "frac": fwd_tops / INT8_PEAK_TOPS, "traffic": traffic.get("fwd")},
+                         "unit": "TOP/s", "frac": fwd_tops / INT8_PEAK_TOPS, "traffic": traffic.get("fwd"),
+                         "frac_of_measured_peak": fwd_tops / peaks["int8_mfma"]["value"]},
         "roofline_bwd_dq": {"bound": "hbm", "kernel": "sage_bwd_dq_kernel",
                             "achieved": dq_bytes / (kern["bwd_dq"] * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                             "frac": dq_bytes / (kern["bwd_dq"] * 1e-3) / 1e9 / HBM_PEAK_GBS,
                             "traffic": traffic.get("bwd_dq"),
+                            "frac_of_measured_read": dq_bytes / (kern["bwd_dq"] * 1e-3) / 1e9 / peaks["hbm_read"]["value"],
                             "note": "bytes = staged psi(dS) tiles + K^ + dQ; the tiles are this design's staging "
                                     "of dS between the two backward kernels, not traffic the method itself requires"},
         "roofline_prepass": {"bound": "hbm", "kernel": "prepass (forward)",
                              "achieved": pre_fwd_bytes / (kern["prepass_fwd"] * 1e-3) / 1e9, "peak": HBM_PEAK_GBS,
                              "unit": "GB/s", "frac": pre_fwd_bytes / (kern["prepass_fwd"] * 1e-3) / 1e9 / HBM_PEAK_GBS,
                              "bytes_per_element": pre_fwd_bytes / elems,
+                             "frac_of_measured_copy": pre_fwd_bytes / (kern["prepass_fwd"] * 1e-3) / 1e9 / peaks["hbm_copy"]["value"],
                              "note": "K is read twice (mean, then psi); the second read is not counted"},
     }
     if not a.no_cpu_baseline:

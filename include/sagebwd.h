@@ -245,6 +245,30 @@ int sagebwd_bwd(const void* Q, const void* K, const void* V, const void* O, cons
 int sagebwd_set_timing(int enable);
 int sagebwd_read_timing(int kernel /* sagebwd_kernel */, double* total_ms, int* launches);
 
+/* Machine probes (not calls of the method): what this GPU sustains, under the clocks and the power
+ * limit the attention kernels run under, on the two resources they are priced against.  Each call
+ * launches its kernel once untimed and `reps` (1..1000) times between two events on `stream`, waits
+ * for them and returns the mean milliseconds per launch through *ms.  `sink` is a device address of
+ * at least 4 bytes that the kernels may or may not write one word to.  Nothing is allocated.
+ *
+ * sagebwd_probe_mfma: every wave of a grid that fills the GPU (two waves per SIMD) issues
+ * `iters` (1..2^20) rounds of four independent accumulator chains of the matrix instruction the
+ * attention kernels use, operands in registers; *ops = operations of one launch (2 per multiply-add). */
+#define SAGEBWD_PROBE_MFMA_INT8 0 /* 32x32x32 INT8 -> INT32 */
+#define SAGEBWD_PROBE_MFMA_BF16 1 /* 32x32x16 bf16 -> FP32  */
+#define SAGEBWD_PROBE_MFMA_ZERO_OPERANDS 2 /* OR into kind: all-zero operands instead of random codes (the same
+                                             instructions at lower power: what the clock then allows) */
+int sagebwd_probe_mfma(int kind, int iters, int reps, void* sink /* device */, void* stream, double* ms /* host */,
+                       double* ops /* host */);
+/* sagebwd_probe_stream: 16-byte pieces per lane over `bytes` (a multiple of 16) of device memory at
+ * `src` (16-byte aligned): copied to `dst` (COPY: `bytes` read and `bytes` written per launch), or
+ * read and folded into a word (READ: `dst` is ignored).  Buffers well beyond the 256 MB memory-side
+ * cache measure HBM. */
+#define SAGEBWD_PROBE_STREAM_COPY 0
+#define SAGEBWD_PROBE_STREAM_READ 1
+int sagebwd_probe_stream(int kind, const void* src /* device */, void* dst /* device */, size_t bytes, int reps,
+                         void* sink /* device */, void* stream, double* ms /* host */);
+
 /* Static description of a status code. */
 const char* sagebwd_strerror(int status);
 

@@ -26,7 +26,8 @@ KERNEL_PREPASS_FWD, KERNEL_FWD, KERNEL_PREPASS_BWD, KERNEL_BWD, KERNEL_BWD_DQ = 
 
 EXPORTS = (
     "sagebwd_workspace_bytes", "sagebwd_quantize", "sagebwd_export_quantized", "sagebwd_export_stats", "sagebwd_export_ds",
-    "sagebwd_fwd", "sagebwd_fwd_static", "sagebwd_bwd", "sagebwd_set_timing", "sagebwd_read_timing", "sagebwd_strerror",
+    "sagebwd_fwd", "sagebwd_fwd_static", "sagebwd_bwd", "sagebwd_set_timing", "sagebwd_read_timing",
+    "sagebwd_probe_mfma", "sagebwd_probe_stream", "sagebwd_strerror",
 )
 
 
@@ -111,6 +112,9 @@ def load_library():
     lib.sagebwd_bwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, pp, vp, sz, vp]
     lib.sagebwd_set_timing.argtypes = [i32]
     lib.sagebwd_read_timing.argtypes = [i32, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i32)]
+    dp = ctypes.POINTER(ctypes.c_double)
+    lib.sagebwd_probe_mfma.argtypes = [i32, i32, i32, vp, vp, dp, dp]
+    lib.sagebwd_probe_stream.argtypes = [i32, vp, vp, sz, i32, vp, vp, dp]
     lib.sagebwd_strerror.argtypes = [i32]
     lib.sagebwd_strerror.restype = ctypes.c_char_p
     for name in EXPORTS:
@@ -286,3 +290,26 @@ def read_timing(kernel: int):
     n = ctypes.c_int(0)
     _check(load_library().sagebwd_read_timing(kernel, ctypes.byref(ms), ctypes.byref(n)), "sagebwd_read_timing")
     return float(ms.value), int(n.value)
+
+
+PROBE_MFMA_INT8, PROBE_MFMA_BF16, PROBE_MFMA_ZERO_OPERANDS = 0, 1, 2
+PROBE_STREAM_COPY, PROBE_STREAM_READ = 0, 1
+
+
+def sagebwd_probe_mfma(kind: int, iters: int = 4096, reps: int = 3, sink=None):
+    """(ms per launch, operations per launch) of the dense matrix-instruction probe."""
+    sink = torch.zeros(1, dtype=torch.int32, device="cuda") if sink is None else sink
+    ms, ops = ctypes.c_double(0), ctypes.c_double(0)
+    _check(load_library().sagebwd_probe_mfma(kind, iters, reps, _ptr(sink), _stream(), ctypes.byref(ms), ctypes.byref(ops)),
+           "sagebwd_probe_mfma")
+    return float(ms.value), float(ops.value)
+
+
+def sagebwd_probe_stream(kind: int, src, dst=None, reps: int = 3, sink=None):
+    """ms per launch of the streaming probe over the bytes of `src` (copied to `dst`, or only read)."""
+    sink = torch.zeros(1, dtype=torch.int32, device="cuda") if sink is None else sink
+    nbytes = src.numel() * src.element_size()
+    ms = ctypes.c_double(0)
+    _check(load_library().sagebwd_probe_stream(kind, _ptr(src), _ptr(dst) if dst is not None else None, nbytes, reps,
+                                               _ptr(sink), _stream(), ctypes.byref(ms)), "sagebwd_probe_stream")
+    return float(ms.value)

@@ -13,6 +13,7 @@
 #include "prepass_kernels.h"
 #include "fwd_kernel.h"
 #include "bwd_kernel.h"
+#include "probe_kernels.h"
 
 // Workspace of sagebwd_fwd_static: one array per GPU, held until the process ends.  In host code the
 // name `scratch` is only a handle for hipGetSymbolAddress; the device address it returns (per device)
@@ -402,6 +403,32 @@ int forward_impl(const void* Q, const void* K, const void* V, void* O, float* LS
   return rc;
 }
 
+// Times `reps` launches of `launch` on `st` with one pair of events around them, after one untimed launch;
+// waits for them.  Returns the mean milliseconds per launch through *ms.
+template <class F>
+int time_probe(F launch, int reps, hipStream_t st, double* ms) {
+  hipEvent_t a = nullptr, b = nullptr;
+  if (hipEventCreate(&a) != hipSuccess) return SAGEBWD_HIP_ERROR;
+  if (hipEventCreate(&b) != hipSuccess) {
+    (void)hipEventDestroy(a);
+    return SAGEBWD_HIP_ERROR;
+  }
+  int rc = SAGEBWD_OK;
+  launch();
+  if (hipEventRecord(a, st) != hipSuccess) rc = SAGEBWD_HIP_ERROR;
+  for (int r = 0; r < reps && rc == SAGEBWD_OK; r++) launch();
+  if (rc == SAGEBWD_OK && hipEventRecord(b, st) != hipSuccess) rc = SAGEBWD_HIP_ERROR;
+  if (rc == SAGEBWD_OK && hipEventSynchronize(b) != hipSuccess) rc = SAGEBWD_HIP_ERROR;
+  float t = 0.f;
+  if (rc == SAGEBWD_OK && hipEventElapsedTime(&t, a, b) != hipSuccess) rc = SAGEBWD_HIP_ERROR;
+  if (rc == SAGEBWD_OK && hipGetLastError() != hipSuccess) rc = SAGEBWD_HIP_ERROR;
+  (void)hipEventDestroy(a);
+  (void)hipEventDestroy(b);
+  *ms = (double)t / reps;
+  return rc;
+}
+
+
 }  // namespace
 
 extern "C" {
@@ -655,6 +682,46 @@ int sagebwd_read_timing(int kernel, double* total_ms, int* launches) {
   *total_ms = tot;
   *launches = n;
   return SAGEBWD_OK;
+}
+
+int sagebwd_probe_mfma(int kind, int iters, int reps, void* sink, void* stream, double* ms, double* ops) {
+  if (kind < 0 || kind > (SAGEBWD_PROBE_MFMA_BF16 | SAGEBWD_PROBE_MFMA_ZERO_OPERANDS) || iters < 1 || iters > (1 << 20) || reps < 1 ||
+      reps > 1000 || sink == nullptr || ms == nullptr || ops == nullptr)
+    return SAGEBWD_INVALID_ARG;
+  hipStream_t st = (hipStream_t)stream;
+  int cus = 0, dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
+    return SAGEBWD_HIP_ERROR;
+  // two workgroups of four waves per CU = two waves per SIMD, eight rounds of them
+  const int grid = cus * 2 * 8;
+  const bool bf16 = (kind & SAGEBWD_PROBE_MFMA_BF16) != 0;
+  const int mask = (kind & SAGEBWD_PROBE_MFMA_ZERO_OPERANDS) ? 0 : -1;
+  auto launch = [&]() {
+    if (bf16) probe_mfma_kernel<true><<<grid, 256, 0, st>>>(iters, 0x5A6E, mask, (int*)sink);
+    else probe_mfma_kernel<false><<<grid, 256, 0, st>>>(iters, 0x5A6E, mask, (int*)sink);
+  };
+  *ops = (double)grid * 4.0 * iters * 4.0 * 2.0 * 32 * 32 * (bf16 ? 16 : 32);
+  return time_probe(launch, reps, st, ms);
+}
+
+int sagebwd_probe_stream(int kind, const void* src, void* dst, size_t bytes, int reps, void* sink, void* stream, double* ms) {
+  if ((kind != SAGEBWD_PROBE_STREAM_COPY && kind != SAGEBWD_PROBE_STREAM_READ) || src == nullptr || bytes < 16 || bytes % 16 != 0 ||
+      reps < 1 || reps > 1000 || sink == nullptr || ms == nullptr || (kind == SAGEBWD_PROBE_STREAM_COPY && dst == nullptr))
+    return SAGEBWD_INVALID_ARG;
+  if (((uintptr_t)src | (uintptr_t)dst) % 16 != 0) return SAGEBWD_INVALID_ARG;
+  hipStream_t st = (hipStream_t)stream;
+  int cus = 0, dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
+    return SAGEBWD_HIP_ERROR;
+  const size_t pieces = bytes / 16;
+  size_t want = (pieces + 255) / 256;
+  const int grid = (int)(want < (size_t)cus * 8 ? want : (size_t)cus * 8);
+  const bool copy = kind == SAGEBWD_PROBE_STREAM_COPY;
+  auto launch = [&]() {
+    if (copy) probe_stream_kernel<true><<<grid, 256, 0, st>>>((const v4i*)src, (v4i*)dst, pieces, 0x5A6E, (int*)sink);
+    else probe_stream_kernel<false><<<grid, 256, 0, st>>>((const v4i*)src, nullptr, pieces, 0x5A6E, (int*)sink);
+  };
+  return time_probe(launch, reps, st, ms);
 }
 
 const char* sagebwd_strerror(int status) {

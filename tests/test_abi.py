@@ -130,3 +130,18 @@ def test_entry_points_reject_bad_arguments_on_the_host(lib):
     assert lib.sagebwd_fwd(one, one, one, one, one, ctypes.byref(bad), one, 1 << 30, null) == -1
     tot, cnt = ctypes.c_double(0), ctypes.c_int(0)
     assert lib.sagebwd_read_timing(99, ctypes.byref(tot), ctypes.byref(cnt)) == -1
+
+
+def test_probes_reject_bad_arguments_on_the_host(lib):
+    ms, ops = ctypes.c_double(0), ctypes.c_double(0)
+    fake = ctypes.c_void_p(4096)       # never dereferenced: every call below fails its argument check first
+    INVALID = -1
+    assert lib.sagebwd_probe_mfma(4, 16, 1, fake, None, ctypes.byref(ms), ctypes.byref(ops)) == INVALID     # unknown kind
+    assert lib.sagebwd_probe_mfma(0, 0, 1, fake, None, ctypes.byref(ms), ctypes.byref(ops)) == INVALID      # no iterations
+    assert lib.sagebwd_probe_mfma(0, 16, 0, fake, None, ctypes.byref(ms), ctypes.byref(ops)) == INVALID     # no launches
+    assert lib.sagebwd_probe_mfma(0, 16, 1, None, None, ctypes.byref(ms), ctypes.byref(ops)) == INVALID     # no sink
+    assert lib.sagebwd_probe_mfma(0, 16, 1, fake, None, None, ctypes.byref(ops)) == INVALID
+    assert lib.sagebwd_probe_stream(0, fake, None, 4096, 1, fake, None, ctypes.byref(ms)) == INVALID         # copy without dst
+    assert lib.sagebwd_probe_stream(1, fake, None, 100, 1, fake, None, ctypes.byref(ms)) == INVALID          # not 16-byte pieces
+    assert lib.sagebwd_probe_stream(1, ctypes.c_void_p(4100), None, 4096, 1, fake, None, ctypes.byref(ms)) == INVALID   # misaligned
+    assert lib.sagebwd_probe_stream(3, fake, fake, 4096, 1, fake, None, ctypes.byref(ms)) == INVALID
