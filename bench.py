@@ -24,7 +24,7 @@ HBM_PEAK_GBS = 8000.0       # MI355X HBM3E peak (published)
 # HBM bytes per launch at the headline workload.  NOT measured in this run: taken from the committed
 # rocprofv3 FETCH_SIZE / WRITE_SIZE runs summarised in profiles/hbm_traffic_headline_fwd_bwd.txt
 # (scaled by the copy-kernel calibration stated there).
-PROFILED_TRAFFIC_BYTES = {"headline": {"bwd": 3.5053e9, "fwd": 3.381e8, "bwd_dq": 2.682e9}}
+PROFILED_TRAFFIC_BYTES = {"headline": {"bwd": 3.5082e9, "fwd": 3.382e8, "bwd_dq": 2.656e9}}
 
 
 def work_ops(w, fwd=True, bwd=True, matmuls=None):
