@@ -18,8 +18,9 @@
 //   dQ_i = sum_j s_dS(i,j) s_K(j) sm_scale * (dS^_ij K^_j)
 // from the stored INT8 tiles: a plain scaled INT8 GEMM with no atomics, so dQ is
 // deterministic.  It is bound by the memory pipeline (the tiles are read once, from HBM), so
-// its work goes into how the copies are issued and how dQ leaves, not into its arithmetic.  (A first version added dQ with FP32 atomics from the first kernel; at
-// N=8192 the 4.3e9 atomic adds alone took 13 ms.)
+// its work goes into how the copies are issued and how dQ leaves, not into its arithmetic.
+// (A first version added dQ with FP32 atomics from the first kernel; at N=8192 the 4.3e9
+// atomic adds alone took 13 ms.)
 //
 // S is formed untransposed (queries x keys): an accumulator lane then holds one key and 16
 // queries, which is the B-operand form of the two contractions over queries (dV, dK).  The
@@ -539,12 +540,13 @@ struct DqArgs {
 // number of stages ahead, together with the three scales of the stage; one barrier per stage.  Both
 // streams are issued by every wave in the same order and complete in order, so one count of outstanding
 // memory operations (`s_waitcnt vmcnt`) covers the K^ copies and the compiler's own waits cover the
-// registers.  Three workgroups share a CU: about 120 KiB of psi(dS) in flight per CU.
+// registers.  Three workgroups share a CU: about 96 KiB of psi(dS) in flight per CU.
 // (Every lane takes part in the scale copy: a memory operation under a lane mask sits behind a branch,
 // and with a path that skips it the compiler stops counting the loads in flight and waits for all of
 // them before each use.)  Measured: the kernel runs at the speed of its psi(dS) stream alone (no
-// arithmetic, no K^ copies: 0.51 ms of 0.54 at the headline shape, about 4.4 TB/s); ring depths 3 to 7,
-// two or three workgroups per CU and non-temporal loads change nothing.
+// arithmetic, no K^ copies: 0.51 ms of 0.54 at the headline shape, about 4.4 TB/s, where a plain read
+// stream over the same bytes reaches 5.6 TB/s on this GPU); ring depths 3 to 7, two or three workgroups
+// per CU and non-temporal loads change nothing.
 template <int D, bool CAUSAL>
 __global__ void __launch_bounds__(256, 3) sage_bwd_dq_kernel(DqArgs args) {
   constexpr int KS = D / 32;               // channel blocks
