@@ -106,12 +106,21 @@ __device__ __forceinline__ void fwd_s_mfma(const int8_t* __restrict__ Kt, const 
 // chunk pairs one MFMA (and the LDS read of an operand two MFMAs ahead) with the vector work of
 // four logits or of sixteen output values, so that the matrix pipe and the LDS latency hide
 // under the vector instructions of the same wave.
-template <int D, bool QSMOOTH, bool MASK, bool NEXT, bool SBIAS>
+//
+// KV128 = numerics blocks of 128 keys: the per-token quantiser of P~ (Algorithm 1 line 9) then takes its row
+// max over both 64-key tiles of the block.  `pair` carries the other tile's row max in (INT_MIN / -inf if
+// the other tile has no visible key) and this tile's own row max out.
+struct PairMax {
+  int i;      // integer domain (no Q-smoothing: both tiles of a block share the scale c)
+  float f;    // log2 domain (Q-smoothing)
+};
+template <int D, bool QSMOOTH, bool MASK, bool NEXT, bool SBIAS, bool KV128 = false>
 __device__ __forceinline__ void fwd_tile(const int8_t* __restrict__ Knext, const int8_t* __restrict__ Vt,
                                          const v4i (&qf)[D / 32], v16i (&sacc)[2], v16i (&snext)[2],
                                          float (&oacc)[D / 32][16], float& w_bias, float& m_ref, float& l_part,
                                          const float c, const float sv, const float* __restrict__ bias_row,
-                                         const int k0, const int q, const int lane, const int h) {
+                                         const int k0, const int q, const int lane, const int h,
+                                         PairMax* pair = nullptr) {
   constexpr int KS = D / 32;
   constexpr int NSM = 2 * KS;    // MFMAs of the next tile's logits; MFMA m = (k-step m / 2, key block m % 2)
   const int8_t* kl = Knext + lane * 16;
@@ -144,7 +153,12 @@ __device__ __forceinline__ void fwd_tile(const int8_t* __restrict__ Knext, const
         mi[kb] = max(mi[kb], v);
       }
     // (with SBIAS the accumulators hold B0 + s: the same order, and B0 + s never is INT_MIN)
-    const int mrow = half_swap_max_i32(max(mi[0], mi[1]));
+    int mrow = half_swap_max_i32(max(mi[0], mi[1]));
+    if constexpr (KV128) {
+      const int own = mrow;
+      mrow = max(mrow, pair->i);
+      pair->i = own;
+    }
     mloc = (float)(mrow - (SBIAS ? kBiasBits : 0)) * c;
     if constexpr (SBIAS) bmax_f = __int_as_float(mrow);
   } else {
@@ -164,6 +178,11 @@ __device__ __forceinline__ void fwd_tile(const int8_t* __restrict__ Knext, const
         }
       }
     mloc = half_swap_max_f32(mf);
+    if constexpr (KV128) {
+      const float own = mloc;
+      mloc = fmaxf(mloc, pair->f);
+      pair->f = own;
+    }
   }
   // ---- online softmax reference (rarely raised) ----
   if (__builtin_amdgcn_ballot_w64(mloc > m_ref + kTau) != 0) {
@@ -273,7 +292,36 @@ __device__ __forceinline__ void fwd_tile(const int8_t* __restrict__ Knext, const
   }
 }
 
-template <int D, bool CAUSAL, bool QSMOOTH, int NW>
+// Row max of one tile's logits `s` over the keys a lane's query sees (key <= qlim), as fwd_tile forms it:
+// the integer max (no Q-smoothing) or the max of s * c + bias in the log2 domain.
+template <bool QSMOOTH, bool MASK>
+__device__ __forceinline__ PairMax tile_row_max(const v16i (&s)[2], const float c, const float* __restrict__ bias_row,
+                                                const int k0, const int qlim, const int h) {
+  PairMax m{INT_MIN, -INFINITY};
+#pragma unroll
+  for (int kb = 0; kb < 2; kb++)
+#pragma unroll
+    for (int aa = 0; aa < 4; aa++) {
+      const int key = k0 + 32 * kb + 8 * aa + 4 * h;
+      v4f b4 = {0.f, 0.f, 0.f, 0.f};
+      if constexpr (QSMOOTH) b4 = *(const v4f*)(bias_row + (key - k0));
+#pragma unroll
+      for (int b = 0; b < 4; b++) {
+        const bool hidden = MASK && (key + b) > qlim;
+        if constexpr (QSMOOTH) {
+          const float v = __builtin_fmaf((float)s[kb][4 * aa + b], c, b4[b]);
+          m.f = fmaxf(m.f, hidden ? -INFINITY : v);
+        } else {
+          m.i = max(m.i, hidden ? INT_MIN : s[kb][4 * aa + b]);
+        }
+      }
+    }
+  if constexpr (QSMOOTH) m.f = half_swap_max_f32(m.f);
+  else m.i = half_swap_max_i32(m.i);
+  return m;
+}
+
+template <int D, bool CAUSAL, bool QSMOOTH, int NW, bool KV128 = false>
 __global__ void __launch_bounds__(64 * NW, (NW == 4 ? (D == 64 ? 3 : 2) : 1)) sage_fwd_kernel(FwdArgs args) {
   constexpr int KS = D / 32;                 // k-steps of Q K^T; also channel blocks of O
   constexpr int TILE_BYTES = 64 * D;         // one K^ or V^ tile of 64 keys
@@ -407,21 +455,40 @@ __global__ void __launch_bounds__(64 * NW, (NW == 4 ? (D == 64 ? 3 : 2) : 1)) sa
     constexpr bool SBIAS = decltype(sbias_tag)::value;
     v16i sA[2], sB[2];
     fwd_s_mfma<D, SBIAS>(cur, qf, sA, lane);
+    // KV128: numerics blocks of 128 keys = pairs of tiles (j even, j + 1).  The row max of the pair must be
+    // known before either tile is quantised, so before the even tile the logits of the odd one are formed
+    // once just for their row max (8 or 4 MFMAs that nothing overlaps) and dropped; fwd_tile then forms them
+    // again under the even tile's softmax as it always does (the matrix pipe has the time, and holding them
+    // instead would cost 32 registers this kernel does not have).  The odd tile takes the even tile's own
+    // row max, which fwd_tile leaves in `pm`.
+    PairMax pm{INT_MIN, -INFINITY};
+    auto partner_max = [&](const int jn, auto mask_tag) __attribute__((always_inline)) {
+      constexpr bool MASKED = decltype(mask_tag)::value;
+      v16i sT[2];
+      fwd_s_mfma<D, SBIAS>(nxt, qf, sT, lane);      // tile jn = j + 1 sits in the next ring slot
+      const v2f scn = *(const v2f*)(nxt + PAIR + wave * 8);
+      // (with SBIAS the accumulators hold B0 + s: the same order)
+      pm = tile_row_max<QSMOOTH, MASKED>(sT, cq * scn[0], (const float*)(nxt + BIAS_OFF + wave * 256), jn * kBlock, qlim, h);
+    };
     auto full_iter = [&](const int j, v16i (&sc)[2], v16i (&sn)[2]) __attribute__((always_inline)) {
       const bool issue = j + 3 < n_tiles;
       if (issue) stage_load(j + 3, nx3);
       const v2f sc2 = *(const v2f*)(cur + PAIR + wave * 8);
-      fwd_tile<D, QSMOOTH, false, true, SBIAS>(nxt, cur + TILE_BYTES, qf, sc, sn, oacc, w_bias, m_ref, l_part,
-                                        cq * sc2[0], sc2[1], (const float*)(cur + BIAS_OFF + wave * 256), j * kBlock, q, lane, h);
+      fwd_tile<D, QSMOOTH, false, true, SBIAS, KV128>(nxt, cur + TILE_BYTES, qf, sc, sn, oacc, w_bias, m_ref, l_part,
+                                        cq * sc2[0], sc2[1], (const float*)(cur + BIAS_OFF + wave * 256), j * kBlock, q, lane, h, &pm);
       if ((j & (kBiasPeriod - 1)) == kBiasPeriod - 1) unbias();
       end_iter(issue);
     };
     int j = 0;
     for (; j + 1 < last; j += 2) {
+      if constexpr (KV128) partner_max(j + 1, std::false_type{});
       full_iter(j, sA, sB);
       full_iter(j + 1, sB, sA);
     }
+    // (j is even here: either the last tile itself, which then has no partner, or the tile before it)
+    if constexpr (KV128) pm = PairMax{INT_MIN, -INFINITY};
     if (j < last) {
+      if constexpr (KV128) partner_max(j + 1, std::true_type{});
       full_iter(j, sA, sB);
 #pragma unroll
       for (int kb = 0; kb < 2; kb++) sA[kb] = sB[kb];
@@ -432,8 +499,8 @@ __global__ void __launch_bounds__(64 * NW, (NW == 4 ? (D == 64 ? 3 : 2) : 1)) sa
       if (issue) stage_load(j + 3, nx3);
       const v2f sc2 = *(const v2f*)(cur + PAIR + wave * 8);
       // (the last tile always takes the masked path: without the causal mask it hides the keys past nvalid)
-      fwd_tile<D, QSMOOTH, true, false, SBIAS>(nxt, cur + TILE_BYTES, qf, sA, sB, oacc, w_bias, m_ref, l_part,
-                                        cq * sc2[0], sc2[1], (const float*)(cur + BIAS_OFF + wave * 256), j * kBlock, qlim, lane, h);
+      fwd_tile<D, QSMOOTH, true, false, SBIAS, KV128>(nxt, cur + TILE_BYTES, qf, sA, sB, oacc, w_bias, m_ref, l_part,
+                                        cq * sc2[0], sc2[1], (const float*)(cur + BIAS_OFF + wave * 256), j * kBlock, qlim, lane, h, &pm);
       end_iter(issue);
       j++;
     }

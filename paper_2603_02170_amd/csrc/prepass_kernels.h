@@ -117,11 +117,12 @@ __global__ void fill_zero_f32_kernel(float* __restrict__ p, size_t n) {
   for (; i < n; i += stride) p[i] = 0.f;
 }
 
-// ---- psi on one 64-row block ---------------------------------------------------
+// ---- psi on one 64-row block (of a numerics block of 64 or 128 rows) -------------
 struct QuantJob {
   const unsigned short* src;   // bf16, rows addressed through `view`
   RowView view;                // where the rows of src (and of O) lie in the caller's tensor
   int N, Np;                   // rows of src that exist; rows of the workspace tensors (N rounded up to 64)
+  int q_like;                  // host side only: a Q-like tensor (numerics blocks of B_q rows) or a K-like one (B_kv)
   int8_t* outF;                // F layout or nullptr
   int8_t* outTF;               // TF layout or nullptr
   float* scale;                // [BH, N/64]
@@ -145,11 +146,19 @@ struct QuantJobs {
 // tensors (Q-like and K-like tensors may have different lengths).  Rows N .. Np-1 do not exist: they are
 // read as zeros AFTER the smoothing (so they change no absmax), enter no mean, get delta = 0 and
 // -L*log2(e) = -inf (P = 0 in the backward).  The grid's x extent covers the longest job.
-template <int D>
+//
+// SUB = 64-row blocks per numerics block (Algorithm 1 leaves B_q, B_kv free): 1, or 2 for blocks of 128 rows.
+// A workgroup always writes ONE 64-row block; with SUB = 2 it also reads the other half of its numerics
+// block (its "partner") and takes the block mean and the absmax over both, so that the two workgroups of a
+// numerics block arrive at the same scale (and mean) without exchanging anything, and store it once per
+// 64-row block: the attention kernels index scales, means and bias rows by 64-row block whatever the
+// numerics block is.
+template <int D, int SUB>
 __global__ void __launch_bounds__(256) prepass_quant_kernel(QuantJobs jobs) {
   constexpr int CPR = D / 16;            // 16-channel chunks per row
   constexpr int NCH = 64 * CPR / 256;    // chunks per thread (1 for D=64, 2 for D=128)
   constexpr int NTF = 4 * D / 256;       // TF chunks per thread
+  static_assert(SUB == 1 || SUB == 2, "numerics blocks of 64 or 128 rows");
   __shared__ __attribute__((aligned(16))) int8_t tile[64 * D];
   __shared__ float colbuf[64 * D / 4];   // used by the block mean only (16 rows at a time)
   __shared__ float mu_s[D];
@@ -164,54 +173,101 @@ __global__ void __launch_bounds__(256) prepass_quant_kernel(QuantJobs jobs) {
   if (blk >= nblk) return;
   const size_t tile_off = view.row(bh, (size_t)blk * kBlock);               // in the caller's tensors
   const int rows_here = min(kBlock, N - blk * kBlock);                      // rows of this block that exist
+  // the partner block (SUB = 2): the other 64 rows of this numerics block, possibly past the end
+  const int pblk = blk ^ 1;
+  const int rows_partner = SUB == 2 ? max(0, min(kBlock, N - pblk * kBlock)) : 0;
 
-  float x[NCH][16];
+  // rows of 64-row block `b` (the first `rows` of them exist) as FP32, 16 channels per chunk
+  auto load_rows = [&](float (&v)[NCH][16], const int b, const int rows) {
+    const size_t off = view.row(bh, (size_t)b * kBlock);
 #pragma unroll
-  for (int it = 0; it < NCH; it++) {
-    const int c = t + 256 * it;
-    const int row = c / CPR, ch = c % CPR;
-    v8us lo = {0, 0, 0, 0, 0, 0, 0, 0}, hi = {0, 0, 0, 0, 0, 0, 0, 0};
-    if (row < rows_here) {
-      const unsigned short* p = jb.src + tile_off + (size_t)row * view.row_stride + ch * 16;
-      lo = *(const v8us*)p;
-      hi = *(const v8us*)(p + 8);
-    }
+    for (int it = 0; it < NCH; it++) {
+      const int c = t + 256 * it;
+      const int row = c / CPR, ch = c % CPR;
+      v8us lo = {0, 0, 0, 0, 0, 0, 0, 0}, hi = {0, 0, 0, 0, 0, 0, 0, 0};
+      if (row < rows) {
+        const unsigned short* p = jb.src + off + (size_t)row * view.row_stride + ch * 16;
+        lo = *(const v8us*)p;
+        hi = *(const v8us*)(p + 8);
+      }
 #pragma unroll
-    for (int e = 0; e < 8; e++) {
-      x[it][e] = bf16_bits_to_float(lo[e]);
-      x[it][8 + e] = bf16_bits_to_float(hi[e]);
+      for (int e = 0; e < 8; e++) {
+        v[it][e] = bf16_bits_to_float(lo[e]);
+        v[it][8 + e] = bf16_bits_to_float(hi[e]);
+      }
     }
-  }
-
-  if (jb.norm.gamma != nullptr) {
-    // QK-norm: the CPR threads of a row (consecutive lanes) share its sum of squares
+  };
+  // QK-norm of the rows held in `v`: the CPR threads of a row (consecutive lanes) share its sum of squares
+  auto qk_normalise = [&](float (&v)[NCH][16], const int rows, unsigned short* out_rows) {
 #pragma unroll
     for (int it = 0; it < NCH; it++) {
       const int c = t + 256 * it;
       const int row = c / CPR, ch = c % CPR;
       double ss = 0.0;
 #pragma unroll
-      for (int e = 0; e < 16; e++) ss += (double)(x[it][e] * x[it][e]);
+      for (int e = 0; e < 16; e++) ss += (double)(v[it][e] * v[it][e]);
 #pragma unroll
       for (int off = 1; off < CPR; off <<= 1) ss += __shfl_xor(ss, off, 64);
-      if (row < rows_here) {
+      if (row < rows) {
         const float rs = qknorm_rscale(ss, D, jb.norm.eps);
         const float* g = jb.norm.gamma + ch * 16;
 #pragma unroll
-        for (int e = 0; e < 16; e++) x[it][e] = qknorm_apply(x[it][e], rs, g[e]);
+        for (int e = 0; e < 16; e++) v[it][e] = qknorm_apply(v[it][e], rs, g[e]);
       }
-      if (jb.norm_out != nullptr) {
+      if (out_rows != nullptr) {
         v8us lo, hi;
 #pragma unroll
         for (int e = 0; e < 8; e++) {
-          lo[e] = float_to_bf16_bits(x[it][e]);        // exact: the values are bf16 already (zero in missing rows)
-          hi[e] = float_to_bf16_bits(x[it][8 + e]);
+          lo[e] = float_to_bf16_bits(v[it][e]);        // exact: the values are bf16 already (zero in missing rows)
+          hi[e] = float_to_bf16_bits(v[it][8 + e]);
         }
-        unsigned short* o = jb.norm_out + ((size_t)bh * Np + (size_t)blk * kBlock + row) * D + ch * 16;
+        unsigned short* o = out_rows + (size_t)row * D + ch * 16;
         *(v8us*)o = lo;
         *(v8us*)(o + 8) = hi;
       }
     }
+  };
+  // v -= mu_s on the rows that exist
+  auto subtract_mu = [&](float (&v)[NCH][16], const int rows) {
+#pragma unroll
+    for (int it = 0; it < NCH; it++) {
+      const int row = (t + 256 * it) / CPR, ch = (t + 256 * it) % CPR;
+      if (row < rows) {
+#pragma unroll
+        for (int e = 0; e < 16; e++) v[it][e] = v[it][e] - mu_s[ch * 16 + e];
+      }
+    }
+  };
+  // float64 column sums of the rows held in `v` (zeros where a row does not exist), thread t < D taking
+  // channel t; in 4 passes of 16 rows through `colbuf` to bound LDS
+  auto add_column_sums = [&](const float (&v)[NCH][16], double& part) {
+    for (int pass = 0; pass < 4; pass++) {
+      __syncthreads();
+#pragma unroll
+      for (int it = 0; it < NCH; it++) {
+        const int c = t + 256 * it;
+        const int row = c / CPR, ch = c % CPR;
+        if (row / 16 == pass) {
+#pragma unroll
+          for (int e = 0; e < 16; e++) colbuf[(row % 16) * D + ch * 16 + e] = v[it][e];
+        }
+      }
+      __syncthreads();
+      if (t < D) {
+        for (int r = 0; r < 16; r++) part += (double)colbuf[r * D + t];
+      }
+    }
+  };
+
+  float x[NCH][16];
+  float xp[SUB == 2 ? NCH : 1][16];      // the partner's rows (SUB = 2)
+  load_rows(x, blk, rows_here);
+  if constexpr (SUB == 2) load_rows(xp, pblk, rows_partner);
+
+  if (jb.norm.gamma != nullptr) {
+    qk_normalise(x, rows_here,
+                 jb.norm_out != nullptr ? jb.norm_out + ((size_t)bh * Np + (size_t)blk * kBlock) * D : nullptr);
+    if constexpr (SUB == 2) qk_normalise(xp, rows_partner, nullptr);
   }
 
   // delta = rowsum(dO o O), FP32 (not part of the bit-exact contract)
@@ -254,50 +310,23 @@ __global__ void __launch_bounds__(256) prepass_quant_kernel(QuantJobs jobs) {
       if (blk == 0) jb.mu_head_out[(size_t)bh * D + t] = m;
     }
     __syncthreads();
-#pragma unroll
-    for (int it = 0; it < NCH; it++) {
-      const int row = (t + 256 * it) / CPR, ch = (t + 256 * it) % CPR;
-      if (row < rows_here) {
-#pragma unroll
-        for (int e = 0; e < 16; e++) x[it][e] = x[it][e] - mu_s[ch * 16 + e];
-      }
-    }
+    subtract_mu(x, rows_here);
+    if constexpr (SUB == 2) subtract_mu(xp, rows_partner);
   }
 
   if (jb.mu_block_out != nullptr) {
-    // block mean over the rows of the block that exist: float64 sum (exact for bf16 data), one rounding.
-    // Done in 4 passes of 16 rows through `colbuf` to bound LDS.
+    // block mean over the rows of the numerics block that exist: float64 sum (exact for bf16 data), one rounding
     double part = 0.0;   // thread t < D accumulates channel t
-    for (int pass = 0; pass < 4; pass++) {
-      __syncthreads();
-#pragma unroll
-      for (int it = 0; it < NCH; it++) {
-        const int c = t + 256 * it;
-        const int row = c / CPR, ch = c % CPR;
-        if (row / 16 == pass) {
-#pragma unroll
-          for (int e = 0; e < 16; e++) colbuf[(row % 16) * D + ch * 16 + e] = x[it][e];
-        }
-      }
-      __syncthreads();
-      if (t < D) {
-        for (int r = 0; r < 16; r++) part += (double)colbuf[r * D + t];
-      }
-    }
+    add_column_sums(x, part);
+    if constexpr (SUB == 2) add_column_sums(xp, part);
     if (t < D) {
-      const float m = (float)(part / (double)rows_here);
+      const float m = (float)(part / (double)(rows_here + rows_partner));
       mu_s[t] = m;
       jb.mu_block_out[((size_t)bh * nblk + blk) * D + t] = m;
     }
     __syncthreads();
-#pragma unroll
-    for (int it = 0; it < NCH; it++) {
-      const int row = (t + 256 * it) / CPR, ch = (t + 256 * it) % CPR;
-      if (row < rows_here) {
-#pragma unroll
-        for (int e = 0; e < 16; e++) x[it][e] = x[it][e] - mu_s[ch * 16 + e];
-      }
-    }
+    subtract_mu(x, rows_here);
+    if constexpr (SUB == 2) subtract_mu(xp, rows_partner);
   }
 
   // block absmax
@@ -306,6 +335,12 @@ __global__ void __launch_bounds__(256) prepass_quant_kernel(QuantJobs jobs) {
   for (int it = 0; it < NCH; it++)
 #pragma unroll
     for (int e = 0; e < 16; e++) a = fmaxf(a, fabsf(x[it][e]));
+  if constexpr (SUB == 2) {
+#pragma unroll
+    for (int it = 0; it < NCH; it++)
+#pragma unroll
+      for (int e = 0; e < 16; e++) a = fmaxf(a, fabsf(xp[it][e]));
+  }
   a = wave_max_nonneg_f32(a);
   if ((t & 63) == 0) wmax[t >> 6] = a;
   __syncthreads();

@@ -50,6 +50,11 @@ inline size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
 // the workspace, are never read from the caller's tensors (loaders clamp) and never stored.
 inline int padded_rows(int N) { return (N + 63) / 64 * 64; }
 
+// Numerics block sizes (rows that share one quantisation scale): 64 unless the caller says 128.
+inline int block_q(const sagebwd_params& p) { return p.bq > 0 ? p.bq : 64; }
+inline int block_kv(const sagebwd_params& p) { return p.bkv > 0 ? p.bkv : 64; }
+inline bool big_blocks(const sagebwd_params& p) { return block_q(p) != 64 || block_kv(p) != 64; }
+
 // Keys per head: N_kv, or N when the caller leaves it 0 (square attention).
 inline int kv_len(const sagebwd_params& p) { return p.Nkv > 0 ? p.Nkv : p.N; }
 
@@ -151,7 +156,8 @@ int check_params(const sagebwd_params* p) {
   if (p->causal != 0 && p->causal != 1) return SAGEBWD_INVALID_ARG;
   if (!(p->sm_scale >= 0.f) || isinf(p->sm_scale)) return SAGEBWD_INVALID_ARG;
   if (p->d != 64 && p->d != 128) return SAGEBWD_UNSUPPORTED_SHAPE;
-  if ((p->bq != 0 && p->bq != 64) || (p->bkv != 0 && p->bkv != 64)) return SAGEBWD_UNSUPPORTED_SHAPE;
+  if ((p->bq != 0 && p->bq != 64 && p->bq != 128) || (p->bkv != 0 && p->bkv != 64 && p->bkv != 128))
+    return SAGEBWD_UNSUPPORTED_SHAPE;
   const int Nk = kv_len(*p);
   if (p->N > (1 << 30) || Nk > (1 << 30)) return SAGEBWD_UNSUPPORTED_SHAPE;
   // under the mask the last query sits on the last key; the kernels keep one diagonal tile per Q block,
@@ -236,8 +242,8 @@ int run_prepass(const void* Q, const void* K, const void* V, const void* dO, con
   QuantJobs jobs;
   memset(&jobs, 0, sizeof(jobs));
   int nj = 0;
-  auto q_like = [&](QuantJob& j) { j.view = qview; j.N = Nq; j.Np = Nqp; };
-  auto k_like = [&](QuantJob& j) { j.view = kview; j.N = Nk; j.Np = Nkp; };
+  auto q_like = [&](QuantJob& j) { j.view = qview; j.N = Nq; j.Np = Nqp; j.q_like = 1; };
+  auto k_like = [&](QuantJob& j) { j.view = kview; j.N = Nk; j.Np = Nkp; j.q_like = 0; };
   if (want_qk) {
     // K first: the mean reduction has just read it, so these blocks find it in the memory-side cache.
     // F layout, and TF layout for the backward (dQ = dS^ K^)
@@ -283,9 +289,21 @@ int run_prepass(const void* Q, const void* K, const void* V, const void* dO, con
     nj++;
   }
   if (nj > 0) {
+    // one launch per numerics block size in use (64-row blocks per numerics block: 1 or 2); Q-like jobs
+    // quantise per B_q rows, K-like jobs per B_kv rows
     const int nblk_max = (Nqp > Nkp ? Nqp : Nkp) / 64;
-    prepass_quant_kernel<D><<<dim3(nblk_max, BH, nj), 256, 0, st>>>(jobs);
-    SAGE_LAUNCH_CHECK();
+    for (int sub = 1; sub <= 2; sub++) {
+      QuantJobs part;
+      memset(&part, 0, sizeof(part));
+      int np = 0;
+      for (int k = 0; k < nj; k++) {
+        if ((jobs.job[k].q_like ? block_q(p) : block_kv(p)) / 64 == sub) part.job[np++] = jobs.job[k];
+      }
+      if (np == 0) continue;
+      if (sub == 1) prepass_quant_kernel<D, 1><<<dim3(nblk_max, BH, np), 256, 0, st>>>(part);
+      else prepass_quant_kernel<D, 2><<<dim3(nblk_max, BH, np), 256, 0, st>>>(part);
+      SAGE_LAUNCH_CHECK();
+    }
   }
   if (qs && want_qk) {
     const float sl2 = logit_scale(p) * 1.4426950408889634f;
@@ -319,23 +337,29 @@ int prepass_for_backward(const void* Q, const void* K, const void* V, const void
 // that stages every K^/V^ tile once for twice as many queries).
 int pick_fwd_waves(int N) { return N % 128 == 0 ? 4 : 2; }
 
+// kv128: numerics blocks of 128 keys (the per-token quantiser of P~ takes its row max over two tiles)
 template <int D, bool CAUSAL, bool QS>
-int launch_fwd_nw(const FwdArgs& a, int nw, hipStream_t st) {
+int launch_fwd_nw(const FwdArgs& a, int nw, bool kv128, hipStream_t st) {
   FwdArgs args = a;
   args.n_qtiles = a.Nq / (32 * nw);
   args.head_set = head_set_for(args.n_qtiles, a.BH);
   const int grid = grid_for(a.BH, args.n_qtiles);
-  if (nw == 4) sage_fwd_kernel<D, CAUSAL, QS, 4><<<grid, 256, 0, st>>>(args);
-  else sage_fwd_kernel<D, CAUSAL, QS, 2><<<grid, 128, 0, st>>>(args);
+  if (kv128) {
+    if (nw == 4) sage_fwd_kernel<D, CAUSAL, QS, 4, true><<<grid, 256, 0, st>>>(args);
+    else sage_fwd_kernel<D, CAUSAL, QS, 2, true><<<grid, 128, 0, st>>>(args);
+  } else {
+    if (nw == 4) sage_fwd_kernel<D, CAUSAL, QS, 4><<<grid, 256, 0, st>>>(args);
+    else sage_fwd_kernel<D, CAUSAL, QS, 2><<<grid, 128, 0, st>>>(args);
+  }
   SAGE_LAUNCH_CHECK();
   return SAGEBWD_OK;
 }
 
 template <int D>
-int launch_fwd(const FwdArgs& a, bool causal, bool qs, hipStream_t st) {
+int launch_fwd(const FwdArgs& a, bool causal, bool qs, bool kv128, hipStream_t st) {
   const int nw = pick_fwd_waves(a.Nq);
-  if (causal) return qs ? launch_fwd_nw<D, true, true>(a, nw, st) : launch_fwd_nw<D, true, false>(a, nw, st);
-  return qs ? launch_fwd_nw<D, false, true>(a, nw, st) : launch_fwd_nw<D, false, false>(a, nw, st);
+  if (causal) return qs ? launch_fwd_nw<D, true, true>(a, nw, kv128, st) : launch_fwd_nw<D, true, false>(a, nw, kv128, st);
+  return qs ? launch_fwd_nw<D, false, true>(a, nw, kv128, st) : launch_fwd_nw<D, false, false>(a, nw, kv128, st);
 }
 
 template <int D>
@@ -398,7 +422,8 @@ int forward_impl(const void* Q, const void* K, const void* V, void* O, float* LS
   a.scale_log2e = logit_scale(p) * 1.4426950408889634f;
   {
     ScopedTimer tm(SAGEBWD_KERNEL_FWD, st);
-    rc = p.d == 64 ? launch_fwd<64>(a, p.causal != 0, qs, st) : launch_fwd<128>(a, p.causal != 0, qs, st);
+    const bool kv128 = block_kv(p) == 128;
+    rc = p.d == 64 ? launch_fwd<64>(a, p.causal != 0, qs, kv128, st) : launch_fwd<128>(a, p.causal != 0, qs, kv128, st);
   }
   return rc;
 }
@@ -584,6 +609,7 @@ int sagebwd_bwd(const void* Q, const void* K, const void* V, const void* O, cons
   if (Q == nullptr || K == nullptr || V == nullptr || O == nullptr || dO == nullptr || LSE == nullptr ||
       dQ == nullptr || dK == nullptr || dV == nullptr || workspace == nullptr)
     return SAGEBWD_INVALID_ARG;
+  if (big_blocks(*params)) return SAGEBWD_UNSUPPORTED_SHAPE;   // the backward implements 64 x 64 numerics blocks only
   const Workspace w = make_layout(*params);
   if (workspace_bytes < w.total) return SAGEBWD_WORKSPACE_TOO_SMALL;
   hipStream_t st = (hipStream_t)stream;

@@ -68,8 +68,11 @@ def test_workspace_bytes_and_shape_validation(lib):
     # N that is not a multiple of 64: the workspace is laid out for N rounded up to the block
     assert binding.workspace_bytes(SageParams(1, 1, 100, 64)) == binding.workspace_bytes(SageParams(1, 1, 128, 64))
     assert binding.workspace_bytes(SageParams(1, 1, 128, 64, bq=64, bkv=64)) == binding.workspace_bytes(SageParams(1, 1, 128, 64))
+    # numerics blocks of 128 rows are served from the same buffers (scales are stored once per 64-row block)
+    assert binding.workspace_bytes(SageParams(1, 1, 128, 64, bq=128, bkv=128), forward_only=True) == \
+        binding.workspace_bytes(SageParams(1, 1, 128, 64), forward_only=True)
     for bad in (SageParams(1, 1, 128, 96), SageParams(1, 1, 64, 256), SageParams(1, 1, (1 << 30) + 64, 64),
-                SageParams(1, 1, 128, 64, bq=128), SageParams(1, 1, 128, 64, bkv=32)):
+                SageParams(1, 1, 128, 64, bq=256), SageParams(1, 1, 128, 64, bq=96), SageParams(1, 1, 128, 64, bkv=32)):
         with pytest.raises(binding.SageError) as e:
             binding.workspace_bytes(bad)
         assert e.value.status == -2

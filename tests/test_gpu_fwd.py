@@ -20,7 +20,7 @@ def _fwd_case(Q, K, V, p, heads=None):
     todo = [(b, h) for b in range(B) for h in range(H)] if heads is None else heads
     for b, h in todo:
         Or, Lr = oracle.forward_head(Qn[b, h], Kn[b, h], Vn[b, h], p.causal, p.k_smooth, p.q_smooth,
-                                     p.sm_scale or None)
+                                     p.sm_scale or None, bq=p.bq or 64, bkv=p.bkv or 64)
         check_close(f"O[{b},{h}]", O[b, h], Or)
         check_lse(f"LSE[{b},{h}]", L[b, h], Lr)
     return O, L
@@ -120,3 +120,31 @@ def test_fwd_non_square_q_smoothing_and_token_major():
     Ot, Lt = binding.sagebwd_fwd(tm(Qd), tm(Kd), tm(Vd), pt)
     torch.cuda.synchronize()
     assert torch.equal(tm(O), Ot) and torch.equal(L, Lt)
+
+
+BIG_BLOCKS = [(128, 64), (64, 128), (128, 128)]
+
+
+@pytest.mark.parametrize("bq,bkv", BIG_BLOCKS)
+@pytest.mark.parametrize("N,d,causal", [(128, 64, True), (256, 128, True), (320, 64, False), (448, 128, True), (576, 64, True),
+                                        (1024, 128, False), (100, 128, True), (333, 64, False), (200, 64, True)])
+def test_fwd_numerics_blocks_of_128(bq, bkv, N, d, causal):
+    """B_q, B_kv of 128 (Algorithm 1 leaves them free): Q shares a scale per 128 rows, K and V per 128 keys, and
+    the per-token quantiser of P~ takes its row max over the 128 keys of a block (the visible ones); odd and
+    even tile counts, a partial last block, the diagonal in the first or the second tile of a block."""
+    Q, K, V, _ = synth.gaussian_inputs(N, d, sigma_qk=1.5, seed=N + d + bq, heads=3)
+    _fwd_case(Q, K, V, binding.SageParams(1, 3, N, d, causal=causal, bq=bq, bkv=bkv))
+
+
+@pytest.mark.parametrize("bq,bkv", BIG_BLOCKS)
+def test_fwd_numerics_blocks_of_128_q_smoothing_non_square_unsmoothed(bq, bkv):
+    Q, K, V, _ = non_square_inputs(192, 448, 128, seed=77, heads=2, q_offset=True)
+    _fwd_case(Q, K, V, binding.SageParams(1, 2, 192, 128, causal=True, q_smooth=True, Nkv=448, bq=bq, bkv=bkv))
+    _fwd_case(Q, K, V, binding.SageParams(1, 2, 192, 128, causal=False, q_smooth=True, Nkv=448, bq=bq, bkv=bkv))
+    Q, K, V, _ = non_square_inputs(100, 300, 64, seed=78, heads=2)
+    _fwd_case(Q, K, V, binding.SageParams(1, 2, 100, 64, causal=False, k_smooth=False, Nkv=300, bq=bq, bkv=bkv))
+    # the differences from 64 x 64 are real: the same inputs give other bits
+    Qd, Kd, Vd = (t.cuda() for t in (Q, K, V))
+    O64, _ = binding.sagebwd_fwd(Qd, Kd, Vd, binding.SageParams(1, 2, 100, 64, causal=False, Nkv=300))
+    Ob, _ = binding.sagebwd_fwd(Qd, Kd, Vd, binding.SageParams(1, 2, 100, 64, causal=False, Nkv=300, bq=bq, bkv=bkv))
+    assert not torch.equal(O64, Ob)

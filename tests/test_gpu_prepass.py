@@ -21,12 +21,22 @@ def _oracle_prepass(Q, K, V, dO, p):
     out.update({k: np.zeros((B, H, Nkp // 64), np.float32) for k in ("sK", "sV")})
     out["muK"] = np.zeros((B, H, d), np.float32)
     out["muQ"] = np.zeros((B, H, Np // 64, d), np.float32)
+    # numerics blocks of 128 rows: the library stores scales and block means once per 64-row block
+    # (the value of the numerics block it lies in), and its tensors end at the 64-row block
+    bq, bkv = p.bq or 64, p.bkv or 64
+    big = max(bq, bkv)
     for b in range(B):
         for h in range(H):
-            pp = oracle.prepass_head(Q[b, h], K[b, h], V[b, h], p.k_smooth, p.q_smooth)
-            for k in ("Qh", "Kh", "Vh", "sQ", "sK", "sV", "muK", "muQ"):
-                out[k][b, h] = pp[k]
-            out["dOh"][b, h], out["sdO"][b, h] = oracle.quantize_blocks(oracle.pad_rows(dO[b, h], Np))
+            pp = oracle.prepass_head(Q[b, h], K[b, h], V[b, h], p.k_smooth, p.q_smooth, bq=bq, bkv=bkv)
+            dq, dsc = oracle.quantize_blocks(oracle.pad_rows(dO[b, h], oracle.padded_len(N, bq, bkv)), bq)
+            out["Qh"][b, h], out["dOh"][b, h] = pp["Qh"][:Np], dq[:Np]
+            out["Kh"][b, h], out["Vh"][b, h] = pp["Kh"][:Nkp], pp["Vh"][:Nkp]
+            out["sQ"][b, h] = np.repeat(pp["sQ"], bq // 64)[:Np // 64]
+            out["sdO"][b, h] = np.repeat(dsc, bq // 64)[:Np // 64]
+            out["sK"][b, h] = np.repeat(pp["sK"], bkv // 64)[:Nkp // 64]
+            out["sV"][b, h] = np.repeat(pp["sV"], bkv // 64)[:Nkp // 64]
+            out["muK"][b, h] = pp["muK"]
+            out["muQ"][b, h] = np.repeat(pp["muQ"], bq // 64, axis=0)[:Np // 64]
     return out
 
 
@@ -177,3 +187,20 @@ def test_qk_norm_fused_gives_the_bits_of_normalise_then_attend(N, d, causal, q_s
     assert torch.equal(Os, Ou)
     for a, b in zip(gs, gu):
         assert torch.equal(a, b)
+
+
+
+@pytest.mark.parametrize("bq,bkv", [(128, 64), (64, 128), (128, 128)])
+@pytest.mark.parametrize("Nq,Nk,d,q_smooth,k_smooth", [(256, 256, 64, False, True), (320, 320, 128, True, True), (100, 300, 128, True, False),
+                                                       (37, 37, 64, True, True), (448, 192, 64, False, True)])
+def test_prepass_bit_exact_numerics_blocks_of_128_rows(bq, bkv, Nq, Nk, d, q_smooth, k_smooth):
+    """B_q, B_kv of 128 rows (Algorithm 1 leaves them free): Q and dO share a scale (and Q its smoothing mean)
+    per B_q rows, K and V per B_kv rows, a partial last block over the rows it has; codes, scales and means
+    equal the oracle's bit for bit."""
+    g = torch.Generator().manual_seed(11 * Nq + Nk + bq)
+    Q, dO = (torch.randn(1, 2, Nq, d, generator=g).to(torch.bfloat16) for _ in range(2))
+    K, V = (torch.randn(1, 2, Nk, d, generator=g).to(torch.bfloat16) for _ in range(2))
+    K = (K.float() + torch.randn(1, 2, 1, d, generator=g) * 4).to(torch.bfloat16)
+    Q = (Q.float() * torch.linspace(0.5, 3, Nq)[:, None] + torch.linspace(-2, 2, d)).to(torch.bfloat16)   # blocks of different range
+    _run_case(Q, K, V, dO, binding.SageParams(1, 2, Nq, d, causal=False, q_smooth=q_smooth, k_smooth=k_smooth,
+                                              Nkv=0 if Nk == Nq else Nk, bq=bq, bkv=bkv))
