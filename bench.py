@@ -99,6 +99,8 @@ def main():
     ap.add_argument("--no-share", action="store_true",
                     help="the backward forms psi(Q), psi(K) again instead of taking them from the forward's "
                          "workspace (SAGEBWD_FLAG_SHARE_QUANTIZED off)")
+    ap.add_argument("--blocks", default="64x64",
+                    help="numerics block sizes B_q x B_kv (64 or 128 each; the headline metric is quoted on 64x64)")
     ap.add_argument("--token-major", action="store_true",
                     help="hold Q, K, V, O, dO and the gradients as [B, N, H, d] (the default is [B, H, N, d])")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -126,8 +128,9 @@ def main():
     w = synth.WORKLOADS[a.workload]
     binding.load_library()      # fails loudly if the HIP library is missing
     torch.cuda.set_device(0)
+    bq, bkv = (int(x) for x in a.blocks.split("x"))
     p = binding.SageParams(w.B, w.H, w.N, w.d, causal=w.causal, k_smooth=w.k_smooth, q_smooth=w.q_smooth,
-                           token_major=a.token_major, share_quantized=not a.no_share)
+                           token_major=a.token_major, share_quantized=not a.no_share, bq=bq, bkv=bkv)
     Q, K, V, dO = (t.cuda() for t in synth.make_inputs(w))
     if a.token_major:
         Q, K, V, dO = (t.permute(0, 2, 1, 3).contiguous() for t in (Q, K, V, dO))
@@ -146,7 +149,7 @@ def main():
     # forward alone (same inputs), for the fwd-only figure: a forward that no backward follows leaves
     # nothing behind for one (no sharing flag)
     pf = binding.SageParams(w.B, w.H, w.N, w.d, causal=w.causal, k_smooth=w.k_smooth, q_smooth=w.q_smooth,
-                            token_major=a.token_major)
+                            token_major=a.token_major, bq=bq, bkv=bkv)
     for _ in range(2):
         binding.sagebwd_fwd(Q, K, V, pf, ws, O, L)
     torch.cuda.synchronize()
@@ -192,7 +195,7 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int8", "data": "synthetic",
         "config": {"workload": f"{w.name}: B={w.B} H={w.H} N={w.N} d={w.d} causal={w.causal} bf16 N(0,1) "
                                f"{'with' if w.qk_norm else 'without'} QK-norm, K-smoothing {'on' if w.k_smooth else 'off'}, "
-                               f"Q-smoothing {'on' if w.q_smooth else 'off'}, 64x64 blocks"
+                               f"Q-smoothing {'on' if w.q_smooth else 'off'}, {bq}x{bkv} blocks"
                                f"{', tensors [B,N,H,d]' if a.token_major else ''}",
                    "work_convention": "fwd 4*BH*N^2*d + bwd 10*BH*N^2*d ops, x0.5 causal",
                    "step": "sagebwd_fwd then sagebwd_bwd on one workspace, pre-passes included; "

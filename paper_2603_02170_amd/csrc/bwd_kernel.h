@@ -55,6 +55,7 @@ struct BwdArgs {
   int8_t* dSq;         // psi(dS) tiles [heads, N/64, ds_pitch, 4096]: the four quadrant fragments as phase Q forms them
   int ds_pitch;        // tiles per Q-block row of that array (>= N/64)
   float* sdS;          // their scales [heads, N/64, ds_pitch]
+  float* tmax;         // numerics blocks other than 64 x 64: (max P, max |dS|) per tile [heads, N/64, ds_pitch][2], see kBwdMode
   int bh0;             // first head of this launch (the scratch above is indexed from it)
   unsigned short* dK;  // bf16 [BH, N, D]
   unsigned short* dV;
@@ -135,8 +136,25 @@ __device__ __forceinline__ void bwd_quadrant(const v16i& sacc, const v16f& dp, c
 // software-pipelined over the workgroup's ONE barrier per tile: interval t runs Q of tile t-1,
 // A of tile t and B of tile t-2, so every phase finds its cross-wave inputs complete and the
 // matrix work of one tile runs under the vector work of its neighbours.
-template <int D, bool CAUSAL, bool QSMOOTH>
+//
+// MODE.  psi(P) and psi(dS) share one scale per numerics block of B_q queries x B_kv keys (Algorithm 2 lines
+// 6 and 9).  With 64 x 64 blocks (kBwdFused) that is the tile this kernel walks, and the maxima come from the
+// tile's own phase A.  With blocks of 128 the maxima of up to four tiles must be known before any of them is
+// quantised, two of which this workgroup only reaches one interval later, with no registers or LDS left to
+// hold a tile back.  The kernel then runs twice: kBwdMaxOnly does phase A alone and stores each tile's two
+// maxima to args.tmax; a small kernel (tile_max_blocks_kernel) replaces every entry by the max over its
+// numerics block; kBwdGivenMax is the full kernel again with phase Q reading its tile's entry (staged into
+// LDS one interval ahead) instead of the maxima found in LDS.  P and dS are recomputed bit for bit, so the
+// maxima are exactly those of the values quantised.
+constexpr int kBwdFused = 0, kBwdMaxOnly = 1, kBwdGivenMax = 2;
+
+// KV128 (with kBwdFused): numerics blocks of 64 queries x 128 keys.  The block is the two tiles the workgroup's
+// two groups hold in the same interval, so phase Q takes the maxima over both groups' phase A (a group whose
+// tile does not exist in an interval, above the diagonal or past the last KV block, contributes zeros) and
+// the kernel still runs once.
+template <int D, bool CAUSAL, bool QSMOOTH, int MODE = kBwdFused, bool KV128 = false>
 __global__ void __launch_bounds__(512, 1) sage_bwd_kernel(BwdArgs args) {
+  static_assert(!KV128 || MODE == kBwdFused, "the two-group maxima belong to the single-pass kernel");
   constexpr int KS = D / 32;     // INT8 k-steps over d; channel blocks
   constexpr int KB = D / 16;     // bf16 k-steps over d
   constexpr int NPB = KS / 2;    // 32-row blocks per wave in phase B (2 for D=128, 1 for D=64)
@@ -152,6 +170,7 @@ __global__ void __launch_bounds__(512, 1) sage_bwd_kernel(BwdArgs args) {
     int8_t vst[2][2 * D * 64];                      // [group]: bf16 V_j as B fragments (key block, 16-channel step)
     unsigned red[2][2][4][2];                       // [group][tile parity][wave][max P, max |dS|] as bit patterns
     float csum[QSMOOTH ? 2 * 3 * 2 * 64 : 1];       // [group][tile % 3][q half][key]: column sums of dS
+    float tmx[MODE == kBwdGivenMax ? 2 * 2 * 64 : 1];   // [tile parity][group][even lanes: max P, odd lanes: max |dS|]
   };
   __shared__ __attribute__((aligned(16))) Lds L;
   auto& stA = L.stA;
@@ -160,6 +179,7 @@ __global__ void __launch_bounds__(512, 1) sage_bwd_kernel(BwdArgs args) {
   auto& vst = L.vst;
   auto& red = L.red;
   auto& csum = L.csum;
+  auto& tmx = L.tmx;
 
   const int gidx = blockIdx.x;
   const int N = args.N;
@@ -307,7 +327,7 @@ __global__ void __launch_bounds__(512, 1) sage_bwd_kernel(BwdArgs args) {
     const int ib = nqblk - 1 - (t - 2);        // Q blocks of the three tiles in flight
     const int iq = nqblk - 1 - (t - 1);
     const int ia = nqblk - 1 - t;
-    const bool act_b = STEADY || (t >= 2 && gvalid && (!CAUSAL || ib + sb >= j));
+    const bool act_b = MODE != kBwdMaxOnly && (STEADY || (t >= 2 && gvalid && (!CAUSAL || ib + sb >= j)));
     const bool act_q = STEADY || (t >= 1 && t - 1 < T && gvalid && (!CAUSAL || iq + sb >= j));
     const bool act_a = STEADY || (t < T && gvalid && (!CAUSAL || ia + sb >= j));
 
@@ -321,9 +341,30 @@ __global__ void __launch_bounds__(512, 1) sage_bwd_kernel(BwdArgs args) {
       BwdExchange& X = xch[grp][(t - 1) & 1];
       // (the maxima are non-negative floats: they order like their bit patterns, and integer maxima
       // need no NaN canonicalisation of the loaded values)
-      const unsigned(&R)[4][2] = red[grp][(t - 1) & 1];
-      const float pm = __uint_as_float(max(max(R[0][0], R[1][0]), max(R[2][0], R[3][0])));
-      const float dm = __uint_as_float(max(max(R[0][1], R[1][1]), max(R[2][1], R[3][1])));
+      float pm, dm;
+      if constexpr (MODE == kBwdGivenMax) {
+        const float* tm = tmx + (((t - 1) & 1) * 2 + grp) * 64;
+        pm = tm[0];
+        dm = tm[1];
+      } else {
+        const unsigned(&R)[4][2] = red[grp][(t - 1) & 1];
+        unsigned pu = max(max(R[0][0], R[1][0]), max(R[2][0], R[3][0]));
+        unsigned du = max(max(R[0][1], R[1][1]), max(R[2][1], R[3][1]));
+        if constexpr (KV128) {
+          const unsigned(&R2)[4][2] = red[grp ^ 1][(t - 1) & 1];
+          pu = max(pu, max(max(R2[0][0], R2[1][0]), max(R2[2][0], R2[3][0])));
+          du = max(du, max(max(R2[0][1], R2[1][1]), max(R2[2][1], R2[3][1])));
+        }
+        pm = __uint_as_float(pu);
+        dm = __uint_as_float(du);
+      }
+      if constexpr (MODE == kBwdMaxOnly) {
+        // this tile's two maxima, for the pass over the numerics blocks; nothing is quantised in this mode
+        if (w4 == 0 && lane == 0) {
+          const size_t tile = ((size_t)hl * nqblk + iq) * args.ds_pitch + j;
+          *(v2f*)(args.tmax + 2 * tile) = v2f{pm, dm};
+        }
+      } else {
       // the per-tile scales of P and dS are internal (never stored bit-exactly): 127/a via rcp
       const float rP = pm > 0.f ? 127.0f * __builtin_amdgcn_rcpf(pm) : 0.f;
       const float rS = dm > 0.f ? 127.0f * __builtin_amdgcn_rcpf(dm) : 0.f;
@@ -356,8 +397,19 @@ __global__ void __launch_bounds__(512, 1) sage_bwd_kernel(BwdArgs args) {
         *(v4i*)(args.dSq + tile * 4096 + ((qb * 2 + kb) * 64 + lane) * 16) = df;
         args.sdS[tile] = sS_q;   // the same value from every lane: no branch
       }
+      }
     }
-    if (STEADY || (t >= 1 && t - 1 < T)) load_B(iq, stB[(t - 1) & 1]);
+    if constexpr (MODE != kBwdMaxOnly) {
+      if (STEADY || (t >= 1 && t - 1 < T)) load_B(iq, stB[(t - 1) & 1]);
+    }
+    if constexpr (MODE == kBwdGivenMax) {
+      // the block maxima of tile t (phase Q in the next interval): each wave copies its group's pair, even
+      // lanes max P, odd lanes max |dS| (an idle group or a tile above the diagonal copies an entry nobody reads)
+      if (STEADY || t < T) {
+        const size_t tile = ((size_t)hl * nqblk + ia) * args.ds_pitch + jc;
+        async_copy_4(args.tmax + 2 * tile + (lane & 1), tmx + ((t & 1) * 2 + grp) * 64);
+      }
+    }
 
     __builtin_amdgcn_sched_barrier(0);
     // The two waves of a SIMD are wave w (first group) and w + 4 (second group); the arbiter favours the
@@ -427,6 +479,10 @@ __global__ void __launch_bounds__(512, 1) sage_bwd_kernel(BwdArgs args) {
         cs = half_swap_sum_f32(cs);
         if (h == 0) csum[((grp * 3 + t % 3) * 2 + qb) * 64 + 32 * kb + ll] = cs;
       }
+    } else if constexpr (KV128) {
+      // no tile for this group in this interval: nothing for the other group's block maxima
+      red[grp][t & 1][w4][0] = 0u;
+      red[grp][t & 1][w4][1] = 0u;
     }
 
     __builtin_amdgcn_sched_barrier(0);
@@ -507,6 +563,30 @@ __global__ void __launch_bounds__(512, 1) sage_bwd_kernel(BwdArgs args) {
       }
     }
   }
+}
+
+// ---------------------------------------------------------------------------------
+// Numerics blocks of 128: every tile's (max P, max |dS|) as kBwdMaxOnly left them in `raw` -> the maxima over
+// the tiles of its numerics block (sub_q x sub_k tiles; only tiles that exist and lie on or below the
+// diagonal were written and are combined) in `out`, which kBwdGivenMax then quantises against.
+// One thread per tile; causal_shift < 0: no mask, else tile (i, j) exists iff j <= i + causal_shift.
+__global__ void tile_max_blocks_kernel(const float* __restrict__ raw, float* __restrict__ out, int heads, int nqblk,
+                                       int nkblk, int pitch, int sub_q, int sub_k, int causal_shift) {
+  const size_t idx = blockIdx.x * (size_t)blockDim.x + threadIdx.x;
+  if (idx >= (size_t)heads * nqblk * nkblk) return;
+  const int j = (int)(idx % nkblk), i = (int)((idx / nkblk) % nqblk), hl = (int)(idx / ((size_t)nkblk * nqblk));
+  auto exists = [&](int ii, int jj) { return ii < nqblk && jj < nkblk && (causal_shift < 0 || jj <= ii + causal_shift); };
+  if (!exists(i, j)) return;
+  const int i0 = i / sub_q * sub_q, j0 = j / sub_k * sub_k;
+  float pm = 0.f, dm = 0.f;
+  for (int ii = i0; ii < i0 + sub_q; ii++)
+    for (int jj = j0; jj < j0 + sub_k; jj++)
+      if (exists(ii, jj)) {
+        const v2f m = *(const v2f*)(raw + 2 * (((size_t)hl * nqblk + ii) * pitch + jj));
+        pm = fmaxf(pm, m[0]);
+        dm = fmaxf(dm, m[1]);
+      }
+  *(v2f*)(out + 2 * (((size_t)hl * nqblk + i) * pitch + j)) = v2f{pm, dm};
 }
 
 // ---------------------------------------------------------------------------------

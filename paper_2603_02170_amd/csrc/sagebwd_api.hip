@@ -87,6 +87,7 @@ struct Workspace {
   size_t sdS;               // their scales [heads_per_group, N/64, ds_pitch]
   int heads_per_group;      // the backward runs in groups of heads that share the dS scratch
   int ds_pitch;             // tiles per Q-block row of the dS scratch
+  size_t tmax_raw, tmax;    // numerics blocks of 128: (max P, max |dS|) per tile, as found and per numerics block
   size_t total;
   int nchunk, chunk_rows;   // K-mean reduction: chunks per head, rows per chunk
 };
@@ -135,6 +136,9 @@ Workspace make_layout(const sagebwd_params& p) {
   w.heads_per_group = (int)hpg;
   w.dSq = take(hpg * ds_head);
   w.sdS = take(hpg * nqblk * (size_t)w.ds_pitch * 4);
+  const size_t tm = big_blocks(p) ? hpg * nqblk * (size_t)w.ds_pitch * 8 : 0;
+  w.tmax_raw = take(tm);
+  w.tmax = take(tm);
   w.total = off;
   return w;
 }
@@ -362,18 +366,18 @@ int launch_fwd(const FwdArgs& a, bool causal, bool qs, bool kv128, hipStream_t s
   return qs ? launch_fwd_nw<D, false, true>(a, nw, kv128, st) : launch_fwd_nw<D, false, false>(a, nw, kv128, st);
 }
 
-template <int D>
+template <int D, int MODE, bool KV128 = false>
 int launch_bwd(const BwdArgs& a, bool causal, bool qs, hipStream_t st) {
   const int npair = (a.N / 64 + 1) / 2;     // one workgroup per pair of KV blocks
   BwdArgs args = a;
   args.head_set = head_set_for(npair, a.BH);
   const int grid = grid_for(a.BH, npair);
   if (causal) {
-    if (qs) sage_bwd_kernel<D, true, true><<<grid, 512, 0, st>>>(args);
-    else sage_bwd_kernel<D, true, false><<<grid, 512, 0, st>>>(args);
+    if (qs) sage_bwd_kernel<D, true, true, MODE, KV128><<<grid, 512, 0, st>>>(args);
+    else sage_bwd_kernel<D, true, false, MODE, KV128><<<grid, 512, 0, st>>>(args);
   } else {
-    if (qs) sage_bwd_kernel<D, false, true><<<grid, 512, 0, st>>>(args);
-    else sage_bwd_kernel<D, false, false><<<grid, 512, 0, st>>>(args);
+    if (qs) sage_bwd_kernel<D, false, true, MODE, KV128><<<grid, 512, 0, st>>>(args);
+    else sage_bwd_kernel<D, false, false, MODE, KV128><<<grid, 512, 0, st>>>(args);
   }
   SAGE_LAUNCH_CHECK();
   return SAGEBWD_OK;
@@ -609,7 +613,6 @@ int sagebwd_bwd(const void* Q, const void* K, const void* V, const void* O, cons
   if (Q == nullptr || K == nullptr || V == nullptr || O == nullptr || dO == nullptr || LSE == nullptr ||
       dQ == nullptr || dK == nullptr || dV == nullptr || workspace == nullptr)
     return SAGEBWD_INVALID_ARG;
-  if (big_blocks(*params)) return SAGEBWD_UNSUPPORTED_SHAPE;   // the backward implements 64 x 64 numerics blocks only
   const Workspace w = make_layout(*params);
   if (workspace_bytes < w.total) return SAGEBWD_WORKSPACE_TOO_SMALL;
   hipStream_t st = (hipStream_t)stream;
@@ -644,6 +647,8 @@ int sagebwd_bwd(const void* Q, const void* K, const void* V, const void* O, cons
   a.dSq = (int8_t*)(ws + w.dSq);
   a.ds_pitch = w.ds_pitch;
   a.sdS = (float*)(ws + w.sdS);
+  a.tmax = nullptr;
+  const bool big = big_blocks(*params);
   a.dK = (unsigned short*)dK;
   a.dV = (unsigned short*)dV;
   a.N = Nkp;
@@ -672,8 +677,29 @@ int sagebwd_bwd(const void* Q, const void* K, const void* V, const void* O, cons
     a.BH = q.BH = nh;
     {
       ScopedTimer tm(SAGEBWD_KERNEL_BWD, st);
-      rc = d == 64 ? launch_bwd<64>(a, params->causal != 0, qs, st) : launch_bwd<128>(a, params->causal != 0, qs, st);
-      if (rc != SAGEBWD_OK) return rc;
+      const bool causal = params->causal != 0;
+      if (!big) {
+        rc = d == 64 ? launch_bwd<64, kBwdFused>(a, causal, qs, st) : launch_bwd<128, kBwdFused>(a, causal, qs, st);
+        if (rc != SAGEBWD_OK) return rc;
+      } else if (block_q(*params) == 64) {
+        // 64 x 128: the numerics block is the pair of tiles a workgroup holds at once
+        rc = d == 64 ? launch_bwd<64, kBwdFused, true>(a, causal, qs, st) : launch_bwd<128, kBwdFused, true>(a, causal, qs, st);
+        if (rc != SAGEBWD_OK) return rc;
+      } else {
+        // 128-row Q blocks: phase A alone for every tile's maxima, the maxima per numerics block, then the
+        // full kernel quantising against those (see the modes in bwd_kernel.h)
+        a.tmax = (float*)(ws + w.tmax_raw);
+        rc = d == 64 ? launch_bwd<64, kBwdMaxOnly>(a, causal, qs, st) : launch_bwd<128, kBwdMaxOnly>(a, causal, qs, st);
+        if (rc != SAGEBWD_OK) return rc;
+        const size_t n = (size_t)nh * (Nqp / 64) * (Nkp / 64);
+        tile_max_blocks_kernel<<<(unsigned)((n + 255) / 256), 256, 0, st>>>(
+            (const float*)(ws + w.tmax_raw), (float*)(ws + w.tmax), nh, Nqp / 64, Nkp / 64, w.ds_pitch,
+            block_q(*params) / 64, block_kv(*params) / 64, causal ? shift_blocks : -1);
+        SAGE_LAUNCH_CHECK();
+        a.tmax = (float*)(ws + w.tmax);
+        rc = d == 64 ? launch_bwd<64, kBwdGivenMax>(a, causal, qs, st) : launch_bwd<128, kBwdGivenMax>(a, causal, qs, st);
+        if (rc != SAGEBWD_OK) return rc;
+      }
     }
     {
       ScopedTimer tm(SAGEBWD_KERNEL_BWD_DQ, st);

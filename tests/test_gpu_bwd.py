@@ -26,7 +26,7 @@ def _bwd_case(Q, K, V, dO, p, heads=None):
     todo = [(b, h) for b in range(B) for h in range(H)] if heads is None else heads
     for b, h in todo:
         On[b, h], Ln[b, h] = oracle.forward_head(Qn[b, h], Kn[b, h], Vn[b, h], p.causal, p.k_smooth, p.q_smooth,
-                                                 p.sm_scale or None)
+                                                 p.sm_scale or None, bq=p.bq or 64, bkv=p.bkv or 64)
     Od = torch.from_numpy(On).to(torch.bfloat16).cuda()
     Ld = torch.from_numpy(Ln).cuda()
     dQ, dK, dV = binding.sagebwd_bwd(Q.cuda(), K.cuda(), V.cuda(), Od, dO.cuda(), Ld, p)
@@ -34,7 +34,7 @@ def _bwd_case(Q, K, V, dO, p, heads=None):
     dQ, dK, dV = to_np(dQ), to_np(dK), to_np(dV)
     for b, h in todo:
         rQ, rK, rV = oracle.backward_head(Qn[b, h], Kn[b, h], Vn[b, h], On[b, h], dOn[b, h], Ln[b, h], p.causal,
-                                          p.k_smooth, p.q_smooth, p.sm_scale or None)
+                                          p.k_smooth, p.q_smooth, p.sm_scale or None, bq=p.bq or 64, bkv=p.bkv or 64)
         check_close(f"dV[{b},{h}]", dV[b, h], rV)
         check_close(f"dQ[{b},{h}]", dQ[b, h], rQ)
         check_close(f"dK[{b},{h}]", dK[b, h], rK)
@@ -334,3 +334,58 @@ def test_bwd_non_square_q_smoothing_sharing_and_head_groups():
     assert torch.equal(O, Os) and torch.equal(L, Ls)
     for a, b in zip(ref, got):
         assert torch.equal(a, b)
+
+
+BIG_BLOCKS = [(128, 64), (64, 128), (128, 128)]
+
+
+@pytest.mark.parametrize("bq,bkv", BIG_BLOCKS)
+@pytest.mark.parametrize("N,d,causal", [(128, 64, True), (256, 128, True), (320, 64, False), (448, 128, True), (576, 64, True),
+                                        (640, 128, False), (100, 128, True), (333, 64, False), (200, 64, True)])
+def test_bwd_numerics_blocks_of_128(bq, bkv, N, d, causal):
+    """B_q, B_kv of 128: psi(P) and psi(dS) share one scale per B_q x B_kv block (the maxima over up to four of the
+    kernel's tiles, those on or below the diagonal), psi(dO) and psi(Q) one per B_q rows, psi(K) one per B_kv."""
+    Q, K, V, dO = synth.gaussian_inputs(N, d, sigma_qk=1.5, seed=N + d + bkv, heads=3)
+    _bwd_case(Q, K, V, dO, binding.SageParams(1, 3, N, d, causal=causal, bq=bq, bkv=bkv))
+
+
+@pytest.mark.parametrize("bq,bkv", BIG_BLOCKS)
+def test_bwd_numerics_blocks_of_128_q_smoothing_non_square_head_groups(bq, bkv):
+    from test_gpu_fwd import non_square_inputs
+    Q, K, V, dO = non_square_inputs(192, 448, 128, seed=79, heads=4, q_offset=True)
+    _bwd_case(Q, K, V, dO, binding.SageParams(1, 4, 192, 128, causal=True, q_smooth=True, Nkv=448, bq=bq, bkv=bkv))
+    _bwd_case(Q, K, V, dO, binding.SageParams(1, 4, 192, 128, causal=False, q_smooth=True, Nkv=448, bq=bq, bkv=bkv,
+                                              scratch_budget=2 * 192 * (448 + 192)))
+    Q, K, V, dO = non_square_inputs(100, 300, 64, seed=80, heads=2)
+    _bwd_case(Q, K, V, dO, binding.SageParams(1, 2, 100, 64, causal=False, k_smooth=False, Nkv=300, bq=bq, bkv=bkv))
+
+
+@pytest.mark.parametrize("bq,bkv", BIG_BLOCKS)
+def test_bwd_numerics_blocks_of_128_stored_ds_codes_and_scales(bq, bkv):
+    """The stored psi(dS): one scale per numerics block (stored once per 64 x 64 tile), codes within one step
+    of the oracle's."""
+    N, d = 256, 64
+    Q, K, V, dO = synth.gaussian_inputs(N, d, sigma_qk=1.5, seed=91, heads=1)
+    p = binding.SageParams(1, 1, N, d, causal=True, bq=bq, bkv=bkv)
+    Qn, Kn, Vn, dOn = (to_np(t)[0, 0] for t in (Q, K, V, dO))
+    On, Ln = oracle.forward_head(Qn, Kn, Vn, True, bq=bq, bkv=bkv)
+    inter = {}
+    oracle.backward_head(Qn, Kn, Vn, On, dOn, Ln, True, intermediates=inter, bq=bq, bkv=bkv)
+    ws = binding.alloc_workspace(p)
+    Od = torch.from_numpy(On)[None, None].to(torch.bfloat16).cuda()
+    Ld = torch.from_numpy(Ln)[None, None].cuda()
+    binding.sagebwd_bwd(Q.cuda(), K.cuda(), V.cuda(), Od, dO.cuda(), Ld, p, ws)
+    ds, sc = binding.sagebwd_export_ds(p, ws, 0)
+    torch.cuda.synchronize()
+    ds, sc = ds.cpu().numpy().astype(np.int32), sc.cpu().numpy()
+    # every 64 x 64 tile of a numerics block on or below the diagonal carries the block's scale
+    ref, rsc = inter["dSh"].astype(np.int32), inter["sdS"]
+    nb = N // 64
+    for i in range(nb):
+        for j in range(i + 1):
+            want = rsc[i // (bq // 64), j // (bkv // 64)]
+            assert abs(sc[i, j] / want - 1) < 5e-6, (i, j, sc[i, j], want)
+    assert ref.shape == ds.shape
+    diff = np.abs(ds - ref)
+    assert diff.max() <= 1, diff.max()
+    assert (diff == 0).mean() > 0.999, (diff == 0).mean()

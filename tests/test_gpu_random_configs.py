@@ -2,7 +2,7 @@
 
 The other GPU tests cover each option on shapes chosen for it; this one draws whole configurations at random
 (batch, heads, N_q, N_kv, head dimension, mask, the two smoothings, layout, fused QK-norm, sharing of the
-quantised operands, a small dS scratch budget, a custom scale), so that options meet in combinations nobody
+quantised operands, a small dS scratch budget, a custom scale, numerics blocks of 64 or 128), so that options meet in combinations nobody
 wrote down: e.g. token-major tensors with a partial last block, Q-smoothing, a shifted diagonal and heads
 processed in groups.  The forward is compared with the oracle's forward; the backward is fed the oracle's O and L
 (as in the backward tests) and compared with the oracle's backward, head by head."""
@@ -47,15 +47,17 @@ def _draw(rng):
                share=bool(rng.integers(0, 2)), small_budget=bool(rng.integers(0, 3) == 0),
                sm_scale=0.0 if rng.integers(0, 3) else float(rng.uniform(0.05, 0.2)),
                sigma=float(rng.choice([1.0, 2.0, 4.0])), offset=bool(rng.integers(0, 2)))
+    # numerics blocks (drawn last: the earlier fields keep their values): 64 x 64 in half of the configurations
+    cfg["bq"], cfg["bkv"] = ((64, 64), (64, 64), (128, 64), (64, 128), (128, 128), (128, 128))[int(rng.integers(0, 6))]
     return cfg
 
 
-CONFIGS = [_draw(np.random.default_rng(7000 + i)) for i in range(40)]
+CONFIGS = [_draw(np.random.default_rng(7000 + i)) for i in range(48)]
 
 
 def _id(c):
     bits = "".join(k[0] for k in ("causal", "k_smooth", "q_smooth", "token_major", "qk_norm", "share", "small_budget") if c[k])
-    return f"B{c['B']}H{c['H']}N{c['N']}k{c['Nkv']}d{c['d']}-{bits}"
+    return f"B{c['B']}H{c['H']}N{c['N']}k{c['Nkv']}d{c['d']}b{c['bq']}x{c['bkv']}-{bits}"
 
 
 @pytest.mark.parametrize("c", CONFIGS, ids=_id)
@@ -81,7 +83,8 @@ def test_random_configuration_against_the_oracle(c):
         pq, pk = binding.padded_rows(N), binding.padded_rows(Nk)
         kw["scratch_budget"] = int(np.random.default_rng(seed).integers(1, 3)) * pq * (pk + 192)
     p = binding.SageParams(B, H, N, d, causal=c["causal"], k_smooth=c["k_smooth"], q_smooth=c["q_smooth"],
-                           sm_scale=c["sm_scale"], token_major=c["token_major"], share_quantized=c["share"], Nkv=c["Nkv"], **kw)
+                           sm_scale=c["sm_scale"], token_major=c["token_major"], share_quantized=c["share"], Nkv=c["Nkv"],
+                           bq=c["bq"], bkv=c["bkv"], **kw)
     print(_id(c), p, flush=True)
 
     # what the oracle sees: the normalised tensors when the pre-pass normalises
@@ -90,7 +93,7 @@ def test_random_configuration_against_the_oracle(c):
         Qn = np.stack([[oracle.qk_norm(Qn[b, h], gq.numpy(), 1e-6) for h in range(H)] for b in range(B)])
         Kn = np.stack([[oracle.qk_norm(Kn[b, h], gk.numpy(), 1e-6) for h in range(H)] for b in range(B)])
     scale = c["sm_scale"] or None
-    okw = dict(causal=c["causal"], k_smooth=c["k_smooth"], q_smooth=c["q_smooth"], sm_scale=scale)
+    okw = dict(causal=c["causal"], k_smooth=c["k_smooth"], q_smooth=c["q_smooth"], sm_scale=scale, bq=c["bq"], bkv=c["bkv"])
     On = np.zeros((B, H, N, d), np.float32)
     Ln = np.zeros((B, H, N), np.float32)
     for b in range(B):
