@@ -49,7 +49,7 @@ extern "C" {
 typedef enum sagebwd_status {
   SAGEBWD_OK = 0,
   SAGEBWD_INVALID_ARG = -1,        /* null pointer, non-positive size, unknown selector */
-  SAGEBWD_UNSUPPORTED_SHAPE = -2,  /* d not in {64,128}, blocks other than 64 x 64, sizes beyond the stated limits */
+  SAGEBWD_UNSUPPORTED_SHAPE = -2,  /* d not in {64,128}, numerics blocks other than 64 or 128, sizes beyond the stated limits */
   SAGEBWD_WORKSPACE_TOO_SMALL = -3,
   SAGEBWD_HIP_ERROR = -4,          /* a HIP runtime call or launch failed */
   SAGEBWD_STATIC_SCRATCH_TOO_SMALL = -5 /* sagebwd_fwd_static: the forward's workspace exceeds the built-in scratch */
@@ -92,7 +92,14 @@ typedef struct sagebwd_params {
   int32_t smooth;  /* OR of SAGEBWD_SMOOTH_* ; the paper's default is SAGEBWD_SMOOTH_K */
   float sm_scale;  /* logit scale; 0 selects 1/sqrt(d) (paper Sec. 4: S = Q K^T / sqrt(d)) */
   int32_t layout;  /* SAGEBWD_LAYOUT_*: how the caller holds Q, K, V, O, dO, dQ, dK, dV */
-  int32_t bq, bkv; /* numerics block sizes B_q, B_kv (Algorithm 1, input line); 0 selects 64 */
+  int32_t bq, bkv; /* numerics block sizes B_q, B_kv (Algorithm 1, input line): 0 (= 64), 64 or 128 each.
+                      Q and dO share one psi scale (and Q its smoothing mean) per B_q rows, K and V per B_kv
+                      rows, psi(P~) of the forward its row max per B_kv keys, psi(P) and psi(dS) of the backward
+                      one scale per B_q x B_kv block; blocks start at row / key 0.  The kernels' tiles stay
+                      64 x 64: every stored or exported scale, mean and bias row is kept once per 64-row block
+                      (the value of the numerics block it lies in).  64 x 64 is the fast path: B_kv = 128
+                      costs the forward about a tenth, B_q = 128 a second sweep of the backward (see
+                      sagebwd_bwd).  Forward and backward must be given the same sizes. */
   int32_t flags;   /* OR of SAGEBWD_FLAG_* */
   int32_t Nkv;     /* rows of K, V, dK, dV; 0 selects N (square attention).  With causal = 1 the last
                       query is aligned with the last key (query i sees keys k <= i + Nkv - N), which needs
@@ -175,7 +182,8 @@ int sagebwd_export_stats(const sagebwd_params* params, const void* workspace,
  * Copy the quantised score gradient psi(dS) (Algorithm 2, the dS line and its quantisation) that the
  * last sagebwd_bwd on this workspace left in its scratch, for one head = b * H + h:
  *   ds_out     int8    [Np, Nkp] row-major (query, key); tiles above the causal diagonal are zero
- *   scale_out  float32 [Np/64, Nkp/64], one scale per 64x64 tile (dS ~ scale * code)
+ *   scale_out  float32 [Np/64, Nkp/64], one scale per 64x64 tile (dS ~ scale * code; with larger numerics
+ *              blocks the tiles of a block carry the same scale)
  * Np, Nkp = N, Nkv rounded up to a multiple of 64.  Either output may be NULL.  Only defined when the backward
  * ran all heads in one group (B*H*Np*(Np+192) bytes within params->scratch_budget), otherwise
  * SAGEBWD_UNSUPPORTED_SHAPE.  A test / inspection hook: the in-loop quantisers depend on the
@@ -231,6 +239,10 @@ int sagebwd_fwd_static(const void* Q, const void* K, const void* V, void* O, flo
  * The quantised dS tiles are staged in the workspace (Np*(Np+192) bytes per head, at most
  * params->scratch_budget at a time: larger problems are processed in groups of heads) and dQ is
  * formed from them by a second kernel, so all three gradients are deterministic (no atomics).
+ * Numerics blocks (params->bq, bkv): psi(P) and psi(dS) take one scale per B_q x B_kv block, over the entries
+ * on or below the causal diagonal.  64 x 64 and 64 x 128 run in one sweep; with B_q = 128 the maxima of a block
+ * span tiles the kernel reaches in different iterations, so it first sweeps S, dP, P, dS for the maxima alone and
+ * then runs in full against them (about 1.6 x the time of the 64 x 64 backward).
  */
 int sagebwd_bwd(const void* Q, const void* K, const void* V, const void* O, const void* dO,
                 const float* LSE, void* dQ, void* dK, void* dV, const sagebwd_params* params,

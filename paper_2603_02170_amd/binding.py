@@ -53,7 +53,7 @@ class SageParams:
     token_major: bool = False   # the bf16 tensors are [B, N, H, d] instead of [B, H, N, d]
     share_quantized: bool = False   # the backward takes psi(Q), psi(K) from the forward's workspace
     scratch_budget: int = 0     # bytes of dS scratch the backward holds at once; 0 selects 8 GiB
-    bq: int = 0                 # numerics block sizes; 0 selects 64
+    bq: int = 0                 # numerics block sizes B_q, B_kv: 0 (= 64), 64 or 128
     bkv: int = 0
     Nkv: int = 0                # rows of K, V, dK, dV; 0 selects N
     qk_gamma_q: object = None   # QK-norm fused into the pre-pass: float32 cuda tensors [d] (both or neither);

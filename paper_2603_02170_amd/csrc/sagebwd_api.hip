@@ -780,7 +780,7 @@ const char* sagebwd_strerror(int status) {
   switch (status) {
     case SAGEBWD_OK: return "ok";
     case SAGEBWD_INVALID_ARG: return "invalid argument (null pointer, bad flag or size)";
-    case SAGEBWD_UNSUPPORTED_SHAPE: return "unsupported shape (need d in {64,128}, 64 x 64 numerics blocks, sizes within the stated limits)";
+    case SAGEBWD_UNSUPPORTED_SHAPE: return "unsupported shape (need d in {64,128}, numerics blocks of 64 or 128, sizes within the stated limits)";
     case SAGEBWD_WORKSPACE_TOO_SMALL: return "workspace too small (see sagebwd_workspace_bytes)";
     case SAGEBWD_HIP_ERROR: return "HIP runtime error";
     case SAGEBWD_STATIC_SCRATCH_TOO_SMALL:

@@ -46,11 +46,12 @@ def test_headline_shape_fwd_bwd_sampled_heads():
         assert (t.float().abs().amax(dim=(2, 3)) > 0).all()
 
 
-def _full_launch_sampled_heads(w, sample, k_smooth=None):
+def _full_launch_sampled_heads(w, sample, k_smooth=None, blocks=(64, 64)):
     """The whole batch of workload `w` runs on the GPU in its own launch configuration (the
     workgroup-to-head mapping depends on B*H and N); the (b, h) pairs in `sample` are compared end to
     end with the oracle.  The backward is given the oracle's O and L on the sampled heads."""
-    p = params_for(w) if k_smooth is None else params_for(w, k_smooth=k_smooth)
+    bq, bkv = blocks
+    p = params_for(w, bq=bq, bkv=bkv) if k_smooth is None else params_for(w, k_smooth=k_smooth, bq=bq, bkv=bkv)
     Q, K, V, dO = synth.make_inputs(w)
     Qd, Kd, Vd, dOd = (t.cuda() for t in (Q, K, V, dO))
     ws = binding.alloc_workspace(p)
@@ -58,7 +59,7 @@ def _full_launch_sampled_heads(w, sample, k_smooth=None):
     On, Ln = {}, {}
     for b, h in sample:
         q, k, v = (to_np(t[b, h]) for t in (Q, K, V))
-        On[b, h], Ln[b, h] = oracle.forward_head(q, k, v, causal=w.causal, k_smooth=p.k_smooth)
+        On[b, h], Ln[b, h] = oracle.forward_head(q, k, v, causal=w.causal, k_smooth=p.k_smooth, bq=bq, bkv=bkv)
         check_close(f"O[{b},{h}]", to_np(O[b, h]), On[b, h])
         check_lse(f"LSE[{b},{h}]", to_np(L[b, h]), Ln[b, h])
     O2, L2 = O.clone(), L.clone()
@@ -69,7 +70,7 @@ def _full_launch_sampled_heads(w, sample, k_smooth=None):
     torch.cuda.synchronize()
     for b, h in sample:
         q, k, v, do = (to_np(t[b, h]) for t in (Q, K, V, dO))
-        rQ, rK, rV = oracle.backward_head(q, k, v, On[b, h], do, Ln[b, h], causal=w.causal, k_smooth=p.k_smooth)
+        rQ, rK, rV = oracle.backward_head(q, k, v, On[b, h], do, Ln[b, h], causal=w.causal, k_smooth=p.k_smooth, bq=bq, bkv=bkv)
         check_close(f"dV[{b},{h}]", to_np(dV[b, h]), rV)
         check_close(f"dQ[{b},{h}]", to_np(dQ[b, h]), rQ)
         check_close(f"dK[{b},{h}]", to_np(dK[b, h]), rK)
@@ -190,3 +191,10 @@ def test_very_long_causal_sequence_sampled_blocks():
     check_close("dV rows", to_np(dV[0, 0])[krows], rV[krows])
     for t in (O, dQ, dK, dV):
         assert torch.isfinite(t.float()).all()
+
+
+@pytest.mark.parametrize("blocks", [(128, 128), (128, 64), (64, 128)])
+def test_headline_shape_numerics_blocks_of_128_sampled_head(blocks):
+    """The headline shape with B_q, B_kv of 128, in the launch configuration `bench.py --blocks` times: one
+    head end to end against the oracle run with the same block sizes."""
+    _full_launch_sampled_heads(synth.WORKLOADS["headline"], [(1, 17)], blocks=blocks)
