@@ -241,8 +241,8 @@ int sagebwd_fwd_static(const void* Q, const void* K, const void* V, void* O, flo
  * formed from them by a second kernel, so all three gradients are deterministic (no atomics).
  * Numerics blocks (params->bq, bkv): psi(P) and psi(dS) take one scale per B_q x B_kv block, over the entries
  * on or below the causal diagonal.  64 x 64 and 64 x 128 run in one sweep; with B_q = 128 the maxima of a block
- * span tiles the kernel reaches in different iterations, so it first sweeps S, dP, P, dS for the maxima alone and
- * then runs in full against them (about 1.6 x the time of the 64 x 64 backward).
+ * span tiles the kernel reaches in different iterations, so it first sweeps S, dP, P, dS of every second Q block
+ * for the maxima alone and then runs in full against them (about 1.3 x the time of the 64 x 64 backward).
  */
 int sagebwd_bwd(const void* Q, const void* K, const void* V, const void* O, const void* dO,
                 const float* LSE, void* dQ, void* dK, void* dV, const sagebwd_params* params,

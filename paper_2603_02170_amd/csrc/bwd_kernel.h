@@ -55,7 +55,7 @@ struct BwdArgs {
   int8_t* dSq;         // psi(dS) tiles [heads, N/64, ds_pitch, 4096]: the four quadrant fragments as phase Q forms them
   int ds_pitch;        // tiles per Q-block row of that array (>= N/64)
   float* sdS;          // their scales [heads, N/64, ds_pitch]
-  float* tmax;         // numerics blocks other than 64 x 64: (max P, max |dS|) per tile [heads, N/64, ds_pitch][2], see kBwdMode
+  float* tmax;         // B_q = 128: (max P, max |dS|) of the tiles of the even Q blocks [heads, N/64, ds_pitch][2], see MODE
   int bh0;             // first head of this launch (the scratch above is indexed from it)
   unsigned short* dK;  // bf16 [BH, N, D]
   unsigned short* dV;
@@ -138,23 +138,24 @@ __device__ __forceinline__ void bwd_quadrant(const v16i& sacc, const v16f& dp, c
 // matrix work of one tile runs under the vector work of its neighbours.
 //
 // MODE.  psi(P) and psi(dS) share one scale per numerics block of B_q queries x B_kv keys (Algorithm 2 lines
-// 6 and 9).  With 64 x 64 blocks (kBwdFused) that is the tile this kernel walks, and the maxima come from the
-// tile's own phase A.  With blocks of 128 the maxima of up to four tiles must be known before any of them is
-// quantised, two of which this workgroup only reaches one interval later, with no registers or LDS left to
-// hold a tile back.  The kernel then runs twice: kBwdMaxOnly does phase A alone and stores each tile's two
-// maxima to args.tmax; a small kernel (tile_max_blocks_kernel) replaces every entry by the max over its
-// numerics block; kBwdGivenMax is the full kernel again with phase Q reading its tile's entry (staged into
-// LDS one interval ahead) instead of the maxima found in LDS.  P and dS are recomputed bit for bit, so the
-// maxima are exactly those of the values quantised.
-constexpr int kBwdFused = 0, kBwdMaxOnly = 1, kBwdGivenMax = 2;
+// 6 and 9).  With B_q = 64 (kBwdFused) the block lies inside one interval of this kernel and the maxima come
+// from the interval's own phase A.  With B_q = 128 a block spans two consecutive Q blocks (2m + 1, which the
+// walk meets first, and 2m), one interval apart, with no registers or LDS left to hold a tile back.  The tile
+// of Q block 2m finds its partner's maxima in the previous interval's; the tile of 2m + 1 needs maxima the
+// walk has not reached.  So the kernel runs twice: kBwdMaxOnly visits the EVEN Q blocks only, does phase A
+// alone and stores each tile's two maxima to args.tmax; kBwdPairedRows is the full kernel, whose phase Q
+// combines its own maxima with the stored ones of the tile below (odd Q blocks; staged into LDS one interval
+// ahead) or with the previous interval's (even Q blocks).  P and dS are recomputed bit for bit, so the maxima
+// are exactly those of the values quantised.
+constexpr int kBwdFused = 0, kBwdMaxOnly = 1, kBwdPairedRows = 2;
 
-// KV128 (with kBwdFused): numerics blocks of 64 queries x 128 keys.  The block is the two tiles the workgroup's
+// KV128: numerics blocks of 128 keys.  In that direction the block is the two tiles the workgroup's
 // two groups hold in the same interval, so phase Q takes the maxima over both groups' phase A (a group whose
-// tile does not exist in an interval, above the diagonal or past the last KV block, contributes zeros) and
-// the kernel still runs once.
+// tile does not exist in an interval, above the diagonal or past the last KV block, contributes zeros); 64 x 128
+// blocks therefore need one sweep only.
 template <int D, bool CAUSAL, bool QSMOOTH, int MODE = kBwdFused, bool KV128 = false>
 __global__ void __launch_bounds__(512, 1) sage_bwd_kernel(BwdArgs args) {
-  static_assert(!KV128 || MODE == kBwdFused, "the two-group maxima belong to the single-pass kernel");
+  constexpr int ISTEP = MODE == kBwdMaxOnly ? 2 : 1;     // Q blocks between two tiles of the walk
   constexpr int KS = D / 32;     // INT8 k-steps over d; channel blocks
   constexpr int KB = D / 16;     // bf16 k-steps over d
   constexpr int NPB = KS / 2;    // 32-row blocks per wave in phase B (2 for D=128, 1 for D=64)
@@ -170,7 +171,7 @@ __global__ void __launch_bounds__(512, 1) sage_bwd_kernel(BwdArgs args) {
     int8_t vst[2][2 * D * 64];                      // [group]: bf16 V_j as B fragments (key block, 16-channel step)
     unsigned red[2][2][4][2];                       // [group][tile parity][wave][max P, max |dS|] as bit patterns
     float csum[QSMOOTH ? 2 * 3 * 2 * 64 : 1];       // [group][tile % 3][q half][key]: column sums of dS
-    float tmx[MODE == kBwdGivenMax ? 2 * 2 * 64 : 1];   // [tile parity][group][even lanes: max P, odd lanes: max |dS|]
+    float tmx[MODE == kBwdPairedRows ? 2 * 2 * 64 : 1];   // [tile parity][group][even lanes: max P, odd lanes: max |dS|]
   };
   __shared__ __attribute__((aligned(16))) Lds L;
   auto& stA = L.stA;
@@ -247,7 +248,9 @@ __global__ void __launch_bounds__(512, 1) sage_bwd_kernel(BwdArgs args) {
     }
 
   const int i_first = CAUSAL ? max(2 * jp - sb, 0) : 0;
-  const int T = nqblk - i_first;                // tile rows of this workgroup; tile t is Q block nqblk-1-t
+  // tile t of this workgroup is Q block itop - ISTEP * t, down to i_first (kBwdMaxOnly: the even blocks only)
+  const int itop = MODE == kBwdMaxOnly ? ((nqblk - 1) & ~1) : nqblk - 1;
+  const int T = itop >= i_first ? (itop - i_first) / ISTEP + 1 : 0;
   // Asynchronous staging (global -> LDS, no registers) of the phase-A operands of Q block i.
   // Written without branches where the fragment counts divide evenly among the 8 waves (d = 128):
   // which array a wave copies from is a compile-time fact per copy, and the small vectors are
@@ -313,27 +316,28 @@ __global__ void __launch_bounds__(512, 1) sage_bwd_kernel(BwdArgs args) {
     }
   };
 
-  load_A(nqblk - 1, stA[0], std::true_type{});
+  load_A(itop, stA[0], std::true_type{});
   barrier_all_memory();
 
   float p[16], ds[16];           // P and dS of the tile between its phases A and Q
   float sP_q = 0.f, sS_q = 0.f;  // tile scales found by the last phase Q
+  unsigned prev_p = 0u, prev_d = 0u;   // kBwdPairedRows: the maxima (bit patterns) of the tile the last phase Q handled
   // One interval.  STEADY = all three phases are active and tile t is not on the diagonal: the
   // body is then free of branches, one basic block in which the compiler interleaves the three
   // independent phases (the LDS and MFMA latencies of one hide under the vector work of the others).
   auto interval = [&](const int t, auto steady_tag) __attribute__((always_inline)) {
     constexpr bool STEADY = decltype(steady_tag)::value;
     const float sP_b = sP_q, sS_b = sS_q;      // scales of tile t - 2 (its phase Q ran in the last interval)
-    const int ib = nqblk - 1 - (t - 2);        // Q blocks of the three tiles in flight
-    const int iq = nqblk - 1 - (t - 1);
-    const int ia = nqblk - 1 - t;
+    const int ib = itop - ISTEP * (t - 2);     // Q blocks of the three tiles in flight
+    const int iq = itop - ISTEP * (t - 1);
+    const int ia = itop - ISTEP * t;
     const bool act_b = MODE != kBwdMaxOnly && (STEADY || (t >= 2 && gvalid && (!CAUSAL || ib + sb >= j)));
     const bool act_q = STEADY || (t >= 1 && t - 1 < T && gvalid && (!CAUSAL || iq + sb >= j));
     const bool act_a = STEADY || (t < T && gvalid && (!CAUSAL || ia + sb >= j));
 
     // operands of the coming intervals; the copies are issued in two batches so that the eight
     // waves do not queue up behind each other at the memory pipeline
-    if (STEADY || t + 1 < T) load_A(ia - 1, stA[(t + 1) & 1], std::false_type{});
+    if (STEADY || t + 1 < T) load_A(ia - ISTEP, stA[(t + 1) & 1], std::false_type{});
 
     __builtin_amdgcn_sched_barrier(0);
     // ---------------- phase Q of tile t - 1 ----------------
@@ -341,23 +345,42 @@ __global__ void __launch_bounds__(512, 1) sage_bwd_kernel(BwdArgs args) {
       BwdExchange& X = xch[grp][(t - 1) & 1];
       // (the maxima are non-negative floats: they order like their bit patterns, and integer maxima
       // need no NaN canonicalisation of the loaded values)
-      float pm, dm;
-      if constexpr (MODE == kBwdGivenMax) {
-        const float* tm = tmx + (((t - 1) & 1) * 2 + grp) * 64;
-        pm = tm[0];
-        dm = tm[1];
-      } else {
-        const unsigned(&R)[4][2] = red[grp][(t - 1) & 1];
-        unsigned pu = max(max(R[0][0], R[1][0]), max(R[2][0], R[3][0]));
-        unsigned du = max(max(R[0][1], R[1][1]), max(R[2][1], R[3][1]));
-        if constexpr (KV128) {
-          const unsigned(&R2)[4][2] = red[grp ^ 1][(t - 1) & 1];
-          pu = max(pu, max(max(R2[0][0], R2[1][0]), max(R2[2][0], R2[3][0])));
-          du = max(du, max(max(R2[0][1], R2[1][1]), max(R2[2][1], R2[3][1])));
-        }
-        pm = __uint_as_float(pu);
-        dm = __uint_as_float(du);
+      const unsigned(&R)[4][2] = red[grp][(t - 1) & 1];
+      unsigned pu = max(max(R[0][0], R[1][0]), max(R[2][0], R[3][0]));
+      unsigned du = max(max(R[0][1], R[1][1]), max(R[2][1], R[3][1]));
+      if constexpr (KV128) {
+        const unsigned(&R2)[4][2] = red[grp ^ 1][(t - 1) & 1];
+        pu = max(pu, max(max(R2[0][0], R2[1][0]), max(R2[2][0], R2[3][0])));
+        du = max(du, max(max(R2[0][1], R2[1][1]), max(R2[2][1], R2[3][1])));
       }
+      if constexpr (MODE == kBwdPairedRows) {
+        // the other Q block of the numerics block: below (iq odd: the stored maxima of tile (iq - 1, j), and of
+        // its neighbour in the 128-key block, where those tiles exist) or above (iq even: the last interval's)
+        const unsigned own_p = pu, own_d = du;
+        if (iq & 1) {
+          const unsigned* tm = (const unsigned*)(tmx + (((t - 1) & 1) * 2 + grp) * 64);
+          if constexpr (KV128) {
+            const int j0 = j & ~1;
+            if (!CAUSAL || j0 <= iq - 1 + sb) {
+              pu = max(pu, tm[0]);
+              du = max(du, tm[1]);
+            }
+            if (j0 + 1 < nblk && (!CAUSAL || j0 + 1 <= iq - 1 + sb)) {
+              pu = max(pu, tm[2]);
+              du = max(du, tm[3]);
+            }
+          } else if (!CAUSAL || j <= iq - 1 + sb) {
+            pu = max(pu, tm[0]);
+            du = max(du, tm[1]);
+          }
+        } else if (iq + 1 < nqblk) {
+          pu = max(pu, prev_p);
+          du = max(du, prev_d);
+        }
+        prev_p = own_p;
+        prev_d = own_d;
+      }
+      const float pm = __uint_as_float(pu), dm = __uint_as_float(du);
       if constexpr (MODE == kBwdMaxOnly) {
         // this tile's two maxima, for the pass over the numerics blocks; nothing is quantised in this mode
         if (w4 == 0 && lane == 0) {
@@ -402,12 +425,14 @@ __global__ void __launch_bounds__(512, 1) sage_bwd_kernel(BwdArgs args) {
     if constexpr (MODE != kBwdMaxOnly) {
       if (STEADY || (t >= 1 && t - 1 < T)) load_B(iq, stB[(t - 1) & 1]);
     }
-    if constexpr (MODE == kBwdGivenMax) {
-      // the block maxima of tile t (phase Q in the next interval): each wave copies its group's pair, even
-      // lanes max P, odd lanes max |dS| (an idle group or a tile above the diagonal copies an entry nobody reads)
-      if (STEADY || t < T) {
-        const size_t tile = ((size_t)hl * nqblk + ia) * args.ds_pitch + jc;
-        async_copy_4(args.tmax + 2 * tile + (lane & 1), tmx + ((t & 1) * 2 + grp) * 64);
+    if constexpr (MODE == kBwdPairedRows) {
+      // tile t has its phase Q in the next interval: if its Q block is odd, the stored maxima of the tile below
+      // it (and, with 128-key blocks, of that tile's neighbour: entries j0 and j0 + 1 are adjacent; the rows of
+      // the table are three entries longer than a row of tiles).  Each wave copies its group's two or four
+      // floats: lanes 0, 1 (, 2, 3) = max P, max |dS| (, of the neighbour); the other lanes repeat them.
+      if ((STEADY || t < T) && (ia & 1)) {
+        const size_t tile = ((size_t)hl * nqblk + ia - 1) * args.ds_pitch + (KV128 ? (jc & ~1) : jc);
+        async_copy_4(args.tmax + 2 * tile + (lane & (KV128 ? 3 : 1)), tmx + ((t & 1) * 2 + grp) * 64);
       }
     }
 
@@ -533,7 +558,8 @@ __global__ void __launch_bounds__(512, 1) sage_bwd_kernel(BwdArgs args) {
   };
   // steady intervals: t >= 2 (all three tiles exist), tile t above the diagonal and not the last row
   // (a KV block with keys that do not exist masks them in every tile: no branch-free intervals for its group)
-  const int t_steady_end = (!gvalid || kvalid < 64) ? 0 : (CAUSAL ? min(nqblk - 1 + sb - j, T - 1) : T - 1);
+  // (under the mask: while Q block itop - ISTEP * t lies above the group's diagonal block j - sb)
+  const int t_steady_end = (!gvalid || kvalid < 64) ? 0 : (CAUSAL ? min((itop + sb - j + ISTEP - 1) / ISTEP, T - 1) : T - 1);
   int t = 0;
   for (; t < 2 && t < T + 2; t++) interval(t, std::false_type{});
   for (; t < t_steady_end; t++) interval(t, std::true_type{});
@@ -563,30 +589,6 @@ __global__ void __launch_bounds__(512, 1) sage_bwd_kernel(BwdArgs args) {
       }
     }
   }
-}
-
-// ---------------------------------------------------------------------------------
-// Numerics blocks of 128: every tile's (max P, max |dS|) as kBwdMaxOnly left them in `raw` -> the maxima over
-// the tiles of its numerics block (sub_q x sub_k tiles; only tiles that exist and lie on or below the
-// diagonal were written and are combined) in `out`, which kBwdGivenMax then quantises against.
-// One thread per tile; causal_shift < 0: no mask, else tile (i, j) exists iff j <= i + causal_shift.
-__global__ void tile_max_blocks_kernel(const float* __restrict__ raw, float* __restrict__ out, int heads, int nqblk,
-                                       int nkblk, int pitch, int sub_q, int sub_k, int causal_shift) {
-  const size_t idx = blockIdx.x * (size_t)blockDim.x + threadIdx.x;
-  if (idx >= (size_t)heads * nqblk * nkblk) return;
-  const int j = (int)(idx % nkblk), i = (int)((idx / nkblk) % nqblk), hl = (int)(idx / ((size_t)nkblk * nqblk));
-  auto exists = [&](int ii, int jj) { return ii < nqblk && jj < nkblk && (causal_shift < 0 || jj <= ii + causal_shift); };
-  if (!exists(i, j)) return;
-  const int i0 = i / sub_q * sub_q, j0 = j / sub_k * sub_k;
-  float pm = 0.f, dm = 0.f;
-  for (int ii = i0; ii < i0 + sub_q; ii++)
-    for (int jj = j0; jj < j0 + sub_k; jj++)
-      if (exists(ii, jj)) {
-        const v2f m = *(const v2f*)(raw + 2 * (((size_t)hl * nqblk + ii) * pitch + jj));
-        pm = fmaxf(pm, m[0]);
-        dm = fmaxf(dm, m[1]);
-      }
-  *(v2f*)(out + 2 * (((size_t)hl * nqblk + i) * pitch + j)) = v2f{pm, dm};
 }
 
 // ---------------------------------------------------------------------------------

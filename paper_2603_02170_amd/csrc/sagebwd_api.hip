@@ -87,7 +87,7 @@ struct Workspace {
   size_t sdS;               // their scales [heads_per_group, N/64, ds_pitch]
   int heads_per_group;      // the backward runs in groups of heads that share the dS scratch
   int ds_pitch;             // tiles per Q-block row of the dS scratch
-  size_t tmax_raw, tmax;    // numerics blocks of 128: (max P, max |dS|) per tile, as found and per numerics block
+  size_t tmax;              // B_q = 128: (max P, max |dS|) per tile of the even Q blocks, from the backward's first sweep
   size_t total;
   int nchunk, chunk_rows;   // K-mean reduction: chunks per head, rows per chunk
 };
@@ -136,9 +136,7 @@ Workspace make_layout(const sagebwd_params& p) {
   w.heads_per_group = (int)hpg;
   w.dSq = take(hpg * ds_head);
   w.sdS = take(hpg * nqblk * (size_t)w.ds_pitch * 4);
-  const size_t tm = big_blocks(p) ? hpg * nqblk * (size_t)w.ds_pitch * 8 : 0;
-  w.tmax_raw = take(tm);
-  w.tmax = take(tm);
+  w.tmax = take(block_q(p) == 128 ? hpg * nqblk * (size_t)w.ds_pitch * 8 : 0);
   w.total = off;
   return w;
 }
@@ -686,18 +684,15 @@ int sagebwd_bwd(const void* Q, const void* K, const void* V, const void* O, cons
         rc = d == 64 ? launch_bwd<64, kBwdFused, true>(a, causal, qs, st) : launch_bwd<128, kBwdFused, true>(a, causal, qs, st);
         if (rc != SAGEBWD_OK) return rc;
       } else {
-        // 128-row Q blocks: phase A alone for every tile's maxima, the maxima per numerics block, then the
-        // full kernel quantising against those (see the modes in bwd_kernel.h)
-        a.tmax = (float*)(ws + w.tmax_raw);
+        // 128-row Q blocks: phase A alone on the even Q blocks for their tiles' maxima, then the full kernel,
+        // which pairs every Q block with its neighbour (see the modes in bwd_kernel.h)
+        a.tmax = (float*)(ws + w.tmax);
         rc = d == 64 ? launch_bwd<64, kBwdMaxOnly>(a, causal, qs, st) : launch_bwd<128, kBwdMaxOnly>(a, causal, qs, st);
         if (rc != SAGEBWD_OK) return rc;
-        const size_t n = (size_t)nh * (Nqp / 64) * (Nkp / 64);
-        tile_max_blocks_kernel<<<(unsigned)((n + 255) / 256), 256, 0, st>>>(
-            (const float*)(ws + w.tmax_raw), (float*)(ws + w.tmax), nh, Nqp / 64, Nkp / 64, w.ds_pitch,
-            block_q(*params) / 64, block_kv(*params) / 64, causal ? shift_blocks : -1);
-        SAGE_LAUNCH_CHECK();
-        a.tmax = (float*)(ws + w.tmax);
-        rc = d == 64 ? launch_bwd<64, kBwdGivenMax>(a, causal, qs, st) : launch_bwd<128, kBwdGivenMax>(a, causal, qs, st);
+        if (block_kv(*params) == 128)
+          rc = d == 64 ? launch_bwd<64, kBwdPairedRows, true>(a, causal, qs, st) : launch_bwd<128, kBwdPairedRows, true>(a, causal, qs, st);
+        else
+          rc = d == 64 ? launch_bwd<64, kBwdPairedRows>(a, causal, qs, st) : launch_bwd<128, kBwdPairedRows>(a, causal, qs, st);
         if (rc != SAGEBWD_OK) return rc;
       }
     }
