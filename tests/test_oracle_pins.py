@@ -623,7 +623,7 @@ def test_non_square_zero_queries_closed_form_and_tiled_formulation(causal):
 
 
 # ------------------------------------------- other numerics block sizes (Algorithm 1 leaves B_q, B_kv free)
-@pytest.mark.parametrize("bq,bkv", [(128, 64), (128, 128)])
+@pytest.mark.parametrize("bq,bkv", [(128, 64), (128, 128), (64, 128)])
 def test_larger_blocks_quantiser_and_prepass(bq, bkv):
     rng = np.random.default_rng(70)
     X = _bf(rng.standard_normal((256, 16)) * 2)
@@ -643,7 +643,7 @@ def test_larger_blocks_quantiser_and_prepass(bq, bkv):
     assert np.array_equal(pp["sK"], s64.reshape(-1, bkv // 64).max(axis=1))
 
 
-@pytest.mark.parametrize("bq,bkv", [(128, 64), (128, 128)])
+@pytest.mark.parametrize("bq,bkv", [(128, 64), (128, 128), (64, 128)])
 @pytest.mark.parametrize("causal", [True, False])
 def test_larger_blocks_close_to_exact_attention_and_closed_forms(bq, bkv, causal):
     N, d = 256, 64
