@@ -249,12 +249,16 @@ int sagebwd_bwd(const void* Q, const void* K, const void* V, const void* O, cons
                 void* workspace, size_t workspace_bytes, void* stream);
 
 /* ---- benchmark hooks (not calls of the method; the only process-wide state of the library) ----
- * Per-kernel device timing.  When enabled, every entry point brackets each kernel
- * it launches with HIP events on the caller's stream.  sagebwd_read_timing waits for
- * the recorded events of `kernel`, returns their summed milliseconds and the launch
- * count since the last read, and resets both.  The switch and the recorded events are shared by
- * all threads of the process (guarded by a mutex); do not enable it under stream capture. */
-int sagebwd_set_timing(int enable);
+ * Per-kernel device timing.  `kernels` is a mask (bit k = sagebwd_kernel k, SAGEBWD_TIMING_ALL = all,
+ * 0 = off): every entry point brackets the selected kernels it launches with HIP events on the caller's
+ * stream.  An event between two kernels keeps the second from starting until the first has drained
+ * (about 10 us on an MI355X), so a benchmark that wants the step undisturbed selects the one kernel it
+ * prices.  sagebwd_read_timing waits for the recorded events of `kernel`, returns their summed
+ * milliseconds and the launch count since the last read, and resets both.  The mask and the recorded
+ * events are shared by all threads of the process (guarded by a mutex); do not enable it under stream
+ * capture. */
+#define SAGEBWD_TIMING_ALL 31
+int sagebwd_set_timing(int kernels);
 int sagebwd_read_timing(int kernel /* sagebwd_kernel */, double* total_ms, int* launches);
 
 /* Machine probes (not calls of the method): what this GPU sustains, under the clocks and the power

@@ -281,8 +281,13 @@ def sagebwd_bwd(Q, K, V, O, dO, LSE, p: SageParams, workspace=None, dQ=None, dK=
     return tuple(outs)
 
 
-def set_timing(enable: bool):
-    _check(load_library().sagebwd_set_timing(int(enable)), "sagebwd_set_timing")
+TIMING_ALL = 31
+
+
+def set_timing(kernels):
+    """kernels: True / False (all / none) or a mask with bit k set for kernel k (KERNEL_*)."""
+    mask = (TIMING_ALL if kernels else 0) if isinstance(kernels, bool) else int(kernels)
+    _check(load_library().sagebwd_set_timing(mask), "sagebwd_set_timing")
 
 
 def read_timing(kernel: int):

@@ -181,7 +181,7 @@ struct TimedSpan {
 };
 // Benchmark hook: the only process-wide state of the library, guarded by one mutex.
 std::mutex g_timing_mutex;
-bool g_timing = false;
+int g_timing = 0;   // bit k set: bracket kernel k (sagebwd_kernel) with events
 std::vector<TimedSpan> g_spans[SAGEBWD_KERNEL_COUNT];
 std::vector<TimedSpan> g_pool;
 
@@ -192,7 +192,7 @@ struct ScopedTimer {
   bool on;
   ScopedTimer(int kernel, hipStream_t s) : k(kernel), st(s), on(false) {
     std::lock_guard<std::mutex> lock(g_timing_mutex);
-    on = g_timing;
+    on = ((g_timing >> kernel) & 1) != 0;
     if (!on) return;
     if (!g_pool.empty()) {
       span = g_pool.back();
@@ -705,9 +705,10 @@ int sagebwd_bwd(const void* Q, const void* K, const void* V, const void* O, cons
   return rc;
 }
 
-int sagebwd_set_timing(int enable) {
+int sagebwd_set_timing(int kernels) {
+  if (kernels < 0 || kernels > SAGEBWD_TIMING_ALL) return SAGEBWD_INVALID_ARG;
   std::lock_guard<std::mutex> lock(g_timing_mutex);
-  g_timing = enable != 0;
+  g_timing = kernels;
   return SAGEBWD_OK;
 }
 

@@ -133,6 +133,7 @@ def test_entry_points_reject_bad_arguments_on_the_host(lib):
     assert lib.sagebwd_fwd(one, one, one, one, one, ctypes.byref(bad), one, 1 << 30, null) == -1
     tot, cnt = ctypes.c_double(0), ctypes.c_int(0)
     assert lib.sagebwd_read_timing(99, ctypes.byref(tot), ctypes.byref(cnt)) == -1
+    assert lib.sagebwd_set_timing(32) == -1 and lib.sagebwd_set_timing(-1) == -1 and lib.sagebwd_set_timing(0) == 0
 
 
 def test_probes_reject_bad_arguments_on_the_host(lib):
